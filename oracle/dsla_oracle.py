@@ -1,0 +1,90 @@
+"""ctypes front end of the C oracle (oracle/dsla_oracle.c).
+
+Test infrastructure only.  Inputs are numpy arrays of any float dtype; they are
+widened to fp64 exactly and every result is fp64.
+
+Layouts follow the layer statement of Section 4.1 of the paper:
+  q, k, g1, g2 : [B, T, H, dk]   (g = natural log of the forget gate, <= 0)
+  v, o         : [B, T, H, dv]
+  S1, S2       : [B, H, dk, dv]  (history, recency)
+"""
+import ctypes
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        path = _build.build(force=False)
+        lib = ctypes.CDLL(path)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ci = ctypes.c_int
+        lib.dsla_oracle_recurrent.argtypes = [ci] * 5 + [dp] * 6 + [ctypes.c_double, dp, dp, dp]
+        lib.dsla_oracle_recurrent.restype = None
+        lib.dsla_oracle_unrolled.argtypes = [ci] * 5 + [dp] * 6 + [ctypes.c_double, dp]
+        lib.dsla_oracle_unrolled.restype = None
+        lib.dsla_oracle_threads.argtypes = []
+        lib.dsla_oracle_threads.restype = ci
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    """Number of host threads the oracle's (batch, head) loop uses."""
+    return int(_load().dsla_oracle_threads())
+
+
+def _f64(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.float64))
+
+
+def _ptr(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _gamma_vec(gamma, H):
+    g = np.asarray(gamma, dtype=np.float64)
+    if g.ndim == 0:
+        g = np.full((H,), float(g), dtype=np.float64)
+    assert g.shape == (H,)
+    return np.ascontiguousarray(g)
+
+
+def recurrent(q, k, v, g1, g2, gamma, scale=1.0, S1=None, S2=None):
+    """Token-by-token DSLA recurrence (Section 4.1, state-update and read-out equations).
+
+    Returns (o, S1_final, S2_final), all fp64.  S1/S2 default to zeros; when given
+    they are the carried-in states and are not modified (copies are returned).
+    A decode step is the call with T == 1.
+    """
+    q, k, v, g1, g2 = map(_f64, (q, k, v, g1, g2))
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    assert k.shape == (B, T, H, dk) and g1.shape == (B, T, H, dk) and g2.shape == (B, T, H, dk)
+    assert v.shape == (B, T, H, dv)
+    gm = _gamma_vec(gamma, H)
+    S1 = np.zeros((B, H, dk, dv)) if S1 is None else _f64(S1).copy()
+    S2 = np.zeros((B, H, dk, dv)) if S2 is None else _f64(S2).copy()
+    assert S1.shape == (B, H, dk, dv) and S2.shape == (B, H, dk, dv)
+    o = np.zeros((B, T, H, dv), dtype=np.float64)
+    _load().dsla_oracle_recurrent(B, T, H, dk, dv, _ptr(q), _ptr(k), _ptr(v), _ptr(g1), _ptr(g2),
+                                  _ptr(gm), float(scale), _ptr(S1), _ptr(S2), _ptr(o))
+    return o, S1, S2
+
+
+def unrolled(q, k, v, g1, g2, gamma, scale=1.0):
+    """O(T^2) attention-score form with zero initial states (Section 4.1, last display,
+    applied to every query position).  Returns o (fp64)."""
+    q, k, v, g1, g2 = map(_f64, (q, k, v, g1, g2))
+    B, T, H, dk = q.shape
+    dv = v.shape[-1]
+    gm = _gamma_vec(gamma, H)
+    o = np.zeros((B, T, H, dv), dtype=np.float64)
+    _load().dsla_oracle_unrolled(B, T, H, dk, dv, _ptr(q), _ptr(k), _ptr(v), _ptr(g1), _ptr(g2),
+                                 _ptr(gm), float(scale), _ptr(o))
+    return o

@@ -1,0 +1,289 @@
+"""Pins of the CPU oracle against what the paper's equations and the mathematics fix.
+
+None of these call the GPU library.  Each check is chosen so that a plausible mistake
+in oracle/dsla_oracle.c (dropped term, wrong gate on a state, transposed operand,
+read-out before the update, off-by-one in the gate product) fails at least one.
+"""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import dsla_oracle as orc
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def rnd(seed, *shape):
+    return np.random.default_rng(seed).standard_normal(shape)
+
+
+def rand_case(seed, B=2, T=13, H=3, dk=5, dv=4, strong=False):
+    q, k = rnd(seed, B, T, H, dk), rnd(seed + 1, B, T, H, dk)
+    v = rnd(seed + 2, B, T, H, dv)
+    lo = 3.0 if strong else 0.3
+    g1 = -np.random.default_rng(seed + 3).uniform(0.0, lo, (B, T, H, dk))
+    g2 = -np.random.default_rng(seed + 4).uniform(0.0, 3 * lo, (B, T, H, dk))
+    return q, k, v, g1, g2
+
+
+def test_hand_example_d1():
+    rows = np.loadtxt(os.path.join(GOLD, "hand_example_d1.txt"))
+    T = rows.shape[0]
+    one = np.ones((1, T, 1, 1))
+    g1 = np.full((1, T, 1, 1), np.log(0.5))
+    g2 = np.zeros((1, T, 1, 1))
+    o, S1, S2 = orc.recurrent(one, one, one, g1, g2, 0.5)
+    np.testing.assert_allclose(o.ravel(), rows[:, 3], rtol=0, atol=1e-15)
+    assert S1.ravel()[0] == pytest.approx(rows[-1, 1], abs=1e-15)
+    assert S2.ravel()[0] == pytest.approx(rows[-1, 2], abs=1e-15)
+    # every prefix, through the state returned by a shorter call
+    for t in range(T):
+        _, s1, s2 = orc.recurrent(one[:, :t + 1], one[:, :t + 1], one[:, :t + 1], g1[:, :t + 1], g2[:, :t + 1], 0.5)
+        assert s1.ravel()[0] == pytest.approx(rows[t, 1], abs=1e-15)
+        assert s2.ravel()[0] == pytest.approx(rows[t, 2], abs=1e-15)
+    np.testing.assert_allclose(orc.unrolled(one, one, one, g1, g2, 0.5).ravel(), rows[:, 3], atol=1e-15)
+
+
+def test_hand_example_d2():
+    rows = np.loadtxt(os.path.join(GOLD, "hand_example_d2.txt"))
+    q = np.array([[1, 2], [2, -1]], float).reshape(1, 2, 1, 2)
+    k = np.array([[1, 0], [2, 1]], float).reshape(1, 2, 1, 2)
+    v = np.array([[3, 5], [1, -1]], float).reshape(1, 2, 1, 2)
+    g1 = np.log(np.array([[0.5, 0.25], [0.5, 0.25]])).reshape(1, 2, 1, 2)
+    g2 = np.log(np.array([[1.0, 0.5], [1.0, 0.5]])).reshape(1, 2, 1, 2)
+    o, S1, S2 = orc.recurrent(q, k, v, g1, g2, 0.25)
+    np.testing.assert_allclose(o.reshape(2, 2), rows[0:2], atol=1e-14)
+    np.testing.assert_allclose(S1.reshape(2, 2), rows[2:4], atol=1e-14)
+    np.testing.assert_allclose(S2.reshape(2, 2), rows[4:6], atol=1e-14)
+    np.testing.assert_allclose(orc.unrolled(q, k, v, g1, g2, 0.25).reshape(2, 2), rows[0:2], atol=1e-14)
+
+
+def test_ungated_is_causal_linear_attention():
+    """log-gate 0 (alpha = 1): o = tril(Q K^T) V and S_T = K^T V, by library matmul."""
+    B, T, H, dk, dv = 2, 17, 3, 6, 5
+    q, k, v = rnd(1, B, T, H, dk), rnd(2, B, T, H, dk), rnd(3, B, T, H, dv)
+    z = np.zeros((B, T, H, dk))
+    o, S1, S2 = orc.recurrent(q, k, v, z, z, 0.3, scale=0.7)
+    ou = orc.unrolled(q, k, v, z, z, 0.3, scale=0.7)
+    for b in range(B):
+        for h in range(H):
+            Q, K, V = q[b, :, h], k[b, :, h], v[b, :, h]
+            ref = 0.7 * np.tril(Q @ K.T) @ V
+            np.testing.assert_allclose(o[b, :, h], ref, rtol=1e-12, atol=1e-12)
+            np.testing.assert_allclose(ou[b, :, h], ref, rtol=1e-12, atol=1e-12)
+            np.testing.assert_allclose(S1[b, h], K.T @ V, rtol=1e-12, atol=1e-12)
+            np.testing.assert_allclose(S2[b, h], K.T @ V, rtol=1e-12, atol=1e-12)
+
+
+def test_scalar_gate_is_decay_masked_matmul():
+    """A gate that is the same for every feature: o = ((Q K^T) * D) V with
+    D[t,s] = prod_{tau=s+1..t} a_tau for s <= t; the two states blend linearly."""
+    B, T, H, dk, dv = 1, 19, 2, 4, 3
+    q, k, v = rnd(4, B, T, H, dk), rnd(5, B, T, H, dk), rnd(6, B, T, H, dv)
+    a1 = np.random.default_rng(7).uniform(0.5, 1.0, (B, T, H))
+    a2 = np.random.default_rng(8).uniform(0.05, 0.9, (B, T, H))
+    g1 = np.repeat(np.log(a1)[..., None], dk, -1)
+    g2 = np.repeat(np.log(a2)[..., None], dk, -1)
+    gam = 0.35
+    o, _, _ = orc.recurrent(q, k, v, g1, g2, gam)
+    for h in range(H):
+        Q, K, V = q[0, :, h], k[0, :, h], v[0, :, h]
+
+        def D(a):
+            M = np.zeros((T, T))
+            for t in range(T):
+                for s in range(t + 1):
+                    M[t, s] = np.prod(a[s + 1:t + 1])
+            return M
+        ref = ((Q @ K.T) * (gam * D(a1[0, :, h]) + (1 - gam) * D(a2[0, :, h]))) @ V
+        np.testing.assert_allclose(o[0, :, h], ref, rtol=1e-11, atol=1e-12)
+
+
+def test_geometric_closed_form():
+    """Constant per-feature gate, constant k and v: S_T[d,:] = (1-a_d^T)/(1-a_d) k_d v."""
+    T, dk, dv = 40, 4, 3
+    a1 = np.array([0.9, 0.5, 1.0, 0.99])
+    a2 = np.array([0.1, 0.7, 0.3, 1.0])
+    kk, vv, qq = np.array([1.0, -2.0, 0.5, 3.0]), np.array([2.0, -1.0, 0.25]), np.array([0.3, 0.1, -0.7, 1.1])
+
+    def tile(x):
+        return np.broadcast_to(x, (1, T, 1, x.size)).copy()
+    with np.errstate(divide="ignore"):
+        o, S1, S2 = orc.recurrent(tile(qq), tile(kk), tile(vv), tile(np.log(a1)), tile(np.log(a2)), 0.6)
+
+    def geo(a, n):
+        return np.where(a == 1.0, float(n), (1 - a ** n) / np.where(a == 1.0, 1.0, 1 - a))
+    np.testing.assert_allclose(S1[0, 0], (geo(a1, T) * kk)[:, None] * vv[None, :], rtol=1e-12)
+    np.testing.assert_allclose(S2[0, 0], (geo(a2, T) * kk)[:, None] * vv[None, :], rtol=1e-12)
+    for t in (0, 1, 7, T - 1):
+        mix = 0.6 * geo(a1, t + 1) + 0.4 * geo(a2, t + 1)
+        np.testing.assert_allclose(o[0, t, 0], np.sum(qq * kk * mix) * vv, rtol=1e-12)
+
+
+def test_closed_gate_keeps_only_current_token():
+    """alpha -> 0: S_t = k_t^T v_t and o_t = (q_t . k_t) v_t (read-out after the update,
+    current token undecayed)."""
+    B, T, H, dk, dv = 1, 6, 2, 3, 4
+    q, k, v = rnd(9, B, T, H, dk), rnd(10, B, T, H, dk), rnd(11, B, T, H, dv)
+    g = np.full((B, T, H, dk), -1.0e4)
+    o, S1, S2 = orc.recurrent(q, k, v, g, g, 0.2)
+    ref = np.einsum("bthd,bthd->bth", q, k)[..., None] * v
+    np.testing.assert_allclose(o, ref, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(S1[0, 1], np.outer(k[0, -1, 1], v[0, -1, 1]), rtol=1e-13)
+    np.testing.assert_allclose(orc.unrolled(q, k, v, g, g, 0.2), ref, rtol=1e-13, atol=1e-13)
+
+
+def test_recurrence_equals_unrolled_form():
+    for seed, strong in ((100, False), (200, True)):
+        q, k, v, g1, g2 = rand_case(seed, B=2, T=33, H=2, dk=7, dv=5, strong=strong)
+        gam = np.array([0.3, 0.8])
+        o, _, _ = orc.recurrent(q, k, v, g1, g2, gam, scale=1.3)
+        ou = orc.unrolled(q, k, v, g1, g2, gam, scale=1.3)
+        np.testing.assert_allclose(o, ou, rtol=1e-11, atol=1e-12)
+
+
+def test_brute_force_python_loops_tiny():
+    """Quadruple loop over (t, s, d, j) with explicit gate products, tiny sizes."""
+    q, k, v, g1, g2 = rand_case(300, B=1, T=6, H=1, dk=3, dv=2, strong=True)
+    gam = 0.45
+    o, _, _ = orc.recurrent(q, k, v, g1, g2, gam)
+    a1, a2 = np.exp(g1), np.exp(g2)
+    ref = np.zeros_like(o)
+    for t in range(6):
+        for s in range(t + 1):
+            for d in range(3):
+                p1 = p2 = 1.0
+                for tau in range(s + 1, t + 1):
+                    p1 *= a1[0, tau, 0, d]
+                    p2 *= a2[0, tau, 0, d]
+                for j in range(2):
+                    ref[0, t, 0, j] += q[0, t, 0, d] * k[0, s, 0, d] * (gam * p1 + (1 - gam) * p2) * v[0, s, 0, j]
+    np.testing.assert_allclose(o, ref, rtol=1e-12, atol=1e-13)
+
+
+def test_state_disabling_and_equal_gates():
+    q, k, v, g1, g2 = rand_case(400)
+    junk = -np.abs(rnd(401, *g1.shape))
+    # gamma = 1: only the history state and its gate matter
+    o1, S1a, _ = orc.recurrent(q, k, v, g1, g2, 1.0)
+    o1b, S1b, _ = orc.recurrent(q, k, v, g1, junk, 1.0)
+    np.testing.assert_allclose(o1, o1b, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(S1a, S1b, rtol=0, atol=0)
+    # gamma = 0: only the recency state and its gate matter
+    o0, _, _ = orc.recurrent(q, k, v, g1, g2, 0.0)
+    o0b, _, _ = orc.recurrent(q, k, v, junk, g2, 0.0)
+    np.testing.assert_allclose(o0, o0b, rtol=1e-13, atol=1e-13)
+    assert np.max(np.abs(o1 - o0)) > 1e-3  # the two single-state outputs do differ
+    # single-state output with gate g equals gamma=1 with g1=g and gamma=0 with g2=g
+    oa, _, _ = orc.recurrent(q, k, v, g1, junk, 1.0)
+    ob, _, _ = orc.recurrent(q, k, v, junk, g1, 0.0)
+    np.testing.assert_allclose(oa, ob, rtol=1e-13, atol=1e-13)
+    # equal gates: output does not depend on gamma
+    oc, _, _ = orc.recurrent(q, k, v, g1, g1, 0.15)
+    od, _, _ = orc.recurrent(q, k, v, g1, g1, 0.9)
+    np.testing.assert_allclose(oc, od, rtol=1e-12, atol=1e-12)
+    # general gamma is the blend of the two single-state outputs
+    og, _, _ = orc.recurrent(q, k, v, g1, g2, 0.37)
+    np.testing.assert_allclose(og, 0.37 * o1 + 0.63 * o0, rtol=1e-12, atol=1e-12)
+
+
+def test_linearity():
+    q, k, v, g1, g2 = rand_case(500)
+    v2, q2 = rnd(501, *v.shape), rnd(502, *q.shape)
+    o, S1, S2 = orc.recurrent(q, k, v, g1, g2, 0.4)
+    ov, S1v, _ = orc.recurrent(q, k, 2.0 * v - 3.0 * v2, g1, g2, 0.4)
+    o2, S12, _ = orc.recurrent(q, k, v2, g1, g2, 0.4)
+    np.testing.assert_allclose(ov, 2 * o - 3 * o2, rtol=1e-11, atol=1e-11)
+    np.testing.assert_allclose(S1v, 2 * S1 - 3 * S12, rtol=1e-11, atol=1e-11)
+    oq, _, _ = orc.recurrent(q + q2, k, v, g1, g2, 0.4)
+    oq2, _, _ = orc.recurrent(q2, k, v, g1, g2, 0.4)
+    np.testing.assert_allclose(oq, o + oq2, rtol=1e-11, atol=1e-11)
+    ok, S1k, _ = orc.recurrent(q, -1.5 * k, v, g1, g2, 0.4)
+    np.testing.assert_allclose(ok, -1.5 * o, rtol=1e-11, atol=1e-11)
+    np.testing.assert_allclose(S1k, -1.5 * S1, rtol=1e-11, atol=1e-11)
+    osc, _, _ = orc.recurrent(q, k, v, g1, g2, 0.4, scale=0.125)
+    np.testing.assert_allclose(osc, 0.125 * o, rtol=1e-13, atol=1e-13)
+
+
+def test_continuation_and_decode_steps():
+    q, k, v, g1, g2 = rand_case(600, T=21)
+    o, S1, S2 = orc.recurrent(q, k, v, g1, g2, 0.55)
+    T1 = 8
+    oa, s1, s2 = orc.recurrent(q[:, :T1], k[:, :T1], v[:, :T1], g1[:, :T1], g2[:, :T1], 0.55)
+    outs = [oa]
+    for t in range(T1, 21):  # decode: one token at a time on the carried states
+        ot, s1, s2 = orc.recurrent(q[:, t:t + 1], k[:, t:t + 1], v[:, t:t + 1], g1[:, t:t + 1], g2[:, t:t + 1],
+                                   0.55, S1=s1, S2=s2)
+        outs.append(ot)
+    np.testing.assert_allclose(np.concatenate(outs, 1), o, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(s1, S1, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(s2, S2, rtol=1e-13, atol=1e-13)
+
+
+def test_initial_state_pure_decay():
+    """k = 0: the carried-in state only decays, S_T = diag(prod alpha) S_0, o_t = q_t S_t."""
+    B, T, H, dk, dv = 1, 9, 2, 4, 3
+    q, _, _, g1, g2 = rand_case(700, B=B, T=T, H=H, dk=dk, dv=dv)
+    S10, S20 = rnd(701, B, H, dk, dv), rnd(702, B, H, dk, dv)
+    zk, zv = np.zeros((B, T, H, dk)), np.zeros((B, T, H, dv))
+    o, S1, S2 = orc.recurrent(q, zk, zv, g1, g2, 0.25, S1=S10, S2=S20)
+    c1, c2 = np.exp(np.cumsum(g1, 1)), np.exp(np.cumsum(g2, 1))  # [B,T,H,dk]
+    np.testing.assert_allclose(S1[0], c1[0, -1][:, :, None] * S10[0], rtol=1e-12)
+    np.testing.assert_allclose(S2[0], c2[0, -1][:, :, None] * S20[0], rtol=1e-12)
+    for t in (0, 4, T - 1):
+        for h in range(H):
+            mix = 0.25 * c1[0, t, h][:, None] * S10[0, h] + 0.75 * c2[0, t, h][:, None] * S20[0, h]
+            np.testing.assert_allclose(o[0, t, h], q[0, t, h] @ mix, rtol=1e-12, atol=1e-13)
+
+
+def test_batch_head_independence_and_permutation():
+    q, k, v, g1, g2 = rand_case(800, B=3, H=4)
+    gam = np.array([0.1, 0.4, 0.7, 0.95])
+    o, S1, S2 = orc.recurrent(q, k, v, g1, g2, gam)
+    pb, ph = [2, 0, 1], [3, 1, 0, 2]
+
+    def perm(x):
+        return x[pb][:, :, ph]
+    op, S1p, _ = orc.recurrent(perm(q), perm(k), perm(v), perm(g1), perm(g2), gam[ph])
+    np.testing.assert_array_equal(op, perm(o))
+    np.testing.assert_array_equal(S1p, S1[pb][:, ph])
+    # one (b, h) on its own gives the same numbers
+    b, h = 1, 2
+    o1, s1, _ = orc.recurrent(q[b:b + 1, :, h:h + 1], k[b:b + 1, :, h:h + 1], v[b:b + 1, :, h:h + 1],
+                              g1[b:b + 1, :, h:h + 1], g2[b:b + 1, :, h:h + 1], gam[h])
+    np.testing.assert_array_equal(o1[0, :, 0], o[b, :, h])
+    np.testing.assert_array_equal(s1[0, 0], S1[b, h])
+
+
+def test_planted_mistakes_are_caught():
+    """The pins above would notice the usual slips: emulate each slip in numpy and check
+    that it differs from the oracle on the data of a pin."""
+    q, k, v, g1, g2 = rand_case(900, B=1, T=8, H=1, dk=3, dv=2, strong=True)
+    o, _, _ = orc.recurrent(q, k, v, g1, g2, 0.3)
+
+    def emulate(read_before_update=False, swap_gates=False, decay_current=False):
+        S1 = np.zeros((3, 2))
+        S2 = np.zeros((3, 2))
+        out = []
+        for t in range(8):
+            a1, a2 = np.exp(g1[0, t, 0]), np.exp(g2[0, t, 0])
+            if swap_gates:
+                a1, a2 = a2, a1
+            kv = np.outer(k[0, t, 0], v[0, t, 0])
+            if read_before_update:
+                out.append(q[0, t, 0] @ (0.3 * S1 + 0.7 * S2))
+            if decay_current:
+                S1, S2 = a1[:, None] * (S1 + kv), a2[:, None] * (S2 + kv)
+            else:
+                S1, S2 = a1[:, None] * S1 + kv, a2[:, None] * S2 + kv
+            if not read_before_update:
+                out.append(q[0, t, 0] @ (0.3 * S1 + 0.7 * S2))
+        return np.array(out)
+    np.testing.assert_allclose(emulate(), o[0, :, 0], rtol=1e-12, atol=1e-13)
+    for kw in (dict(read_before_update=True), dict(swap_gates=True), dict(decay_current=True)):
+        assert np.max(np.abs(emulate(**kw) - o[0, :, 0])) > 1e-3
+
+
+def test_oracle_threads_reported():
+    assert orc.threads() >= 1
