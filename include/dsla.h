@@ -1,0 +1,160 @@
+/*
+ * dsla.h - C ABI of the MI355X (gfx950) dual-state linear attention (DSLA) layer forward.
+ *
+ * What the layer computes (paper Section 4.1 "Dual-State Linear Attention"), for every
+ * (batch, head) pair independently, with row vectors q_t, k_t of length d_k and v_t, o_t
+ * of length d_v, two d_k x d_v states S1 (history) and S2 (recency), forget gates
+ * alpha1_t, alpha2_t in (0,1]^{d_k} (one value per token per feature, broadcast along
+ * d_v) and a blend coefficient gamma:
+ *
+ *     S^i_t = diag(alpha^i_t) S^i_{t-1} + k_t^T v_t          i = 1, 2   (state update)
+ *     o_t   = scale * q_t ( gamma S^1_t + (1 - gamma) S^2_t )            (read-out)
+ *
+ * The read-out uses the states after the update of the same token.  No feature map,
+ * normaliser or output gate is applied.  Gates cross this boundary as natural
+ * logarithms g^i_t = log alpha^i_t <= 0, never as alpha itself: a bf16 alpha close to one
+ * would lose the decay rate.
+ *
+ * Conventions
+ *  - Every pointer is a DEVICE pointer unless marked HOST.  The caller owns every
+ *    buffer; the library allocates and frees no device memory and never synchronises:
+ *    work is enqueued on the HIP stream passed as `stream` (a hipStream_t cast to void*,
+ *    NULL = the default stream) and the call returns.
+ *  - Layouts are contiguous with the last index fastest:
+ *        q, k, g1, g2 : [B][T][H][d_k]        v, o : [B][T][H][d_v]
+ *        S1, S2       : [B][H][d_k][d_v]  always fp32, updated in place
+ *    (decode tensors are the same with the T index dropped).
+ *    q, k, v, o have element type io_dtype; g1, g2 have element type gate_dtype.
+ *    Pointers must be aligned to 16 bytes.
+ *  - Errors: argument checks run on the host before anything is enqueued, so a call that
+ *    returns an error other than DSLA_ERR_HIP has done nothing.  DSLA_ERR_HIP reports a
+ *    failed launch (hipGetLastError text available through dsla_last_hip_error()).
+ *  - Same inputs give bit-identical outputs (no atomics, fixed reduction order).
+ *  - Supported shapes: d_k = d_v in {64, 128}; chunk in {0 (library default), 32, 64} subject
+ *    to the table in dsla_prefill(); B, H, T >= 1 (T == 0 is accepted and does nothing).
+ *  - Supported gate domain for dsla_prefill: within any one chunk of `chunk` consecutive
+ *    tokens the sum of |g| over the tokens must stay below 80 for every feature (the
+ *    chunk-local factorisation forms exp(+|sum g|)).  dsla_decode has no such limit.
+ */
+#ifndef DSLA_H
+#define DSLA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Exported with default visibility; everything else in the library is hidden. */
+#define DSLA_API __attribute__((visibility("default")))
+
+typedef enum {
+    DSLA_OK = 0,
+    DSLA_ERR_NULL = 1,        /* a required pointer is NULL                          */
+    DSLA_ERR_SHAPE = 2,       /* non-positive size, misaligned pointer                */
+    DSLA_ERR_UNSUPPORTED = 3, /* head size, chunk or dtype combination not built      */
+    DSLA_ERR_WORKSPACE = 4,   /* workspace NULL or smaller than the query says        */
+    DSLA_ERR_HIP = 5          /* a HIP call failed                                    */
+} dsla_status;
+
+typedef enum { DSLA_F32 = 0, DSLA_BF16 = 1 } dsla_dtype;
+
+/* Layer descriptor (HOST memory, read during the call only). */
+typedef struct {
+    int32_t B;          /* sequences in the batch                                       */
+    int32_t H;          /* heads                                                        */
+    int32_t d_k;        /* width of q, k and the gates; rows of a state                 */
+    int32_t d_v;        /* width of v, o; columns of a state                            */
+    int32_t chunk;      /* prefill chunk length C; 0 = library default; decode ignores  */
+    int32_t segments;   /* prefill: 0 = choose automatically; > 0 = split every sequence
+                           into this many segments processed in parallel (tuning/tests);
+                           the result does not depend on it beyond rounding             */
+    int32_t io_dtype;   /* dsla_dtype of q, k, v, o                                     */
+    int32_t gate_dtype; /* dsla_dtype of g1, g2                                         */
+    float gamma;        /* blend coefficient of the layer (read-out equation); any real */
+    float scale;        /* multiplies q (e.g. d_k^-1/2); 1.0 = the paper's plain form   */
+    const float *gamma_per_head; /* optional DEVICE array [H] overriding gamma; or NULL */
+} dsla_desc;
+
+/*
+ * dsla_state_init - set both states to zero, the initial condition implied by the
+ * unrolled form of Section 4.1 (no term from before the first token).
+ * S1, S2: [B][H][d_k][d_v] fp32, written.
+ */
+DSLA_API dsla_status dsla_state_init(const dsla_desc *desc, float *S1, float *S2, void *stream);
+
+/*
+ * dsla_prefill_workspace_bytes - size in bytes of the scratch buffer dsla_prefill needs
+ * for this descriptor and sequence length (0 when none is needed).  Returns 0 for an
+ * invalid descriptor as well; dsla_prefill reports the actual error.
+ */
+DSLA_API size_t dsla_prefill_workspace_bytes(const dsla_desc *desc, int64_t T);
+
+/*
+ * dsla_prefill - the layer over T tokens per sequence, in chunks of C tokens: within a
+ * chunk the state update and read-out of Section 4.1 are evaluated as dense
+ * contractions, and the two states are carried from chunk to chunk.  The result equals
+ * the token-by-token recurrence up to rounding for every T >= 1 (a ragged last chunk is
+ * masked).
+ *
+ *   q, k, v, g1, g2 : inputs, layouts above          o : output, [B][T][H][d_v]
+ *   S1, S2          : states before the first token on entry, after the last on return;
+ *                     calling again with the next T' tokens continues the sequence
+ *   workspace       : at least dsla_prefill_workspace_bytes(desc, T) bytes, 256-byte
+ *                     aligned; contents are scratch (undefined before and after)
+ * Built combinations: io bf16: (d=128, C in {32, 64}), (d=64, C in {32, 64});
+ *                     io f32 : (d=64, C in {32, 64}), (d=128, C=32).
+ *                     chunk = 0 selects 64 when built for the shape, else 32.
+ * io f32 uses fp32 arithmetic throughout; io bf16 rounds contraction operands to bf16
+ * and accumulates in fp32; states are fp32 in both.
+ */
+DSLA_API dsla_status dsla_prefill(const dsla_desc *desc, int64_t T,
+                         const void *q, const void *k, const void *v,
+                         const void *g1, const void *g2,
+                         float *S1, float *S2, void *o,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * dsla_decode - one token per sequence: the state update and read-out of Section 4.1
+ * applied once, fused so that each state is read from and written to memory exactly once.
+ *   q, k, g1, g2 : [B][H][d_k]     v : [B][H][d_v]     o : [B][H][d_v] (written)
+ *   S1, S2       : updated in place
+ */
+DSLA_API dsla_status dsla_decode(const dsla_desc *desc,
+                        const void *q, const void *k, const void *v,
+                        const void *g1, const void *g2,
+                        float *S1, float *S2, void *o, void *stream);
+
+/* Text for a status code (static storage). */
+DSLA_API const char *dsla_status_string(dsla_status s);
+
+/* Text of the last HIP error seen by this thread's calls into the library (static). */
+DSLA_API const char *dsla_last_hip_error(void);
+
+/*
+ * Kernel timing for benchmarks.  While enabled, every kernel the library launches is
+ * bracketed by two HIP events recorded on the launch stream (events come from a pool
+ * created by dsla_profile_enable, so the launch path still allocates nothing).
+ * Kernel ids: 0 state_init, 1 prefill_segment_state, 2 prefill_segment_scan,
+ * 3 prefill_chunk_loop, 4 decode.
+ */
+#define DSLA_KERNEL_STATE_INIT 0
+#define DSLA_KERNEL_PREFILL_SEGMENT_STATE 1
+#define DSLA_KERNEL_PREFILL_SEGMENT_SCAN 2
+#define DSLA_KERNEL_PREFILL_CHUNK_LOOP 3
+#define DSLA_KERNEL_DECODE 4
+#define DSLA_KERNEL_COUNT 5
+
+/* enable != 0: create the event pool (max_records launches can be recorded between two
+ * collects) and start recording; enable == 0: stop and destroy the pool. */
+DSLA_API dsla_status dsla_profile_enable(int enable, int max_records);
+/* Waits for the recorded events, adds up elapsed milliseconds and launch counts per
+ * kernel id into the HOST arrays total_ms[DSLA_KERNEL_COUNT], launches[DSLA_KERNEL_COUNT],
+ * and clears the records. */
+DSLA_API dsla_status dsla_profile_collect(double *total_ms, int64_t *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DSLA_H */

@@ -1,0 +1,9 @@
+"""MI355X-native dual-state linear attention (DSLA) layer forward.
+
+The compute lives in a C-ABI shared library built from csrc/ (hand-written gfx950 HIP
+kernels); `binding` is a thin ctypes layer with the same entry-point names.  Importing
+the package does not load the library; the first call does, and fails loudly if the
+library has not been built.
+"""
+from .binding import (DslaDesc, DslaError, dsla_decode, dsla_prefill, dsla_prefill_workspace_bytes,  # noqa: F401
+                      dsla_state_init, library_path, load_library, make_desc, profile_collect, profile_enable)

@@ -1,0 +1,139 @@
+"""ctypes binding of libdsla.so: same entry-point names as include/dsla.h, argument
+marshalling only.  Tensors are torch tensors on the GPU; their data pointers and the
+current torch HIP stream are handed to the library.  No computation happens here, and
+there is no fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libdsla.so")
+_lib = None
+
+DSLA_F32, DSLA_BF16 = 0, 1
+KERNEL_NAMES = ("state_init", "prefill_segment_state", "prefill_segment_scan", "prefill_chunk_loop", "decode")
+EXPORTS = ("dsla_state_init", "dsla_prefill_workspace_bytes", "dsla_prefill", "dsla_decode",
+           "dsla_status_string", "dsla_last_hip_error", "dsla_profile_enable", "dsla_profile_collect")
+
+
+class DslaDesc(ctypes.Structure):
+    """Mirror of `dsla_desc` in include/dsla.h."""
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d_k", ctypes.c_int32), ("d_v", ctypes.c_int32),
+                ("chunk", ctypes.c_int32), ("segments", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
+                ("gate_dtype", ctypes.c_int32), ("gamma", ctypes.c_float), ("scale", ctypes.c_float),
+                ("gamma_per_head", ctypes.c_void_p)]
+
+
+class DslaError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"dsla status {status}: {text}")
+        self.status = status
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads libdsla.so (built by paper_2506_09316_amd/build.py).  Raises if it is absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(f"{_LIB_PATH} is not built; run `python -m paper_2506_09316_amd.build` "
+                                "(or __graft_entry__.build())")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, dp = ctypes.c_void_p, ctypes.POINTER(DslaDesc)
+    lib.dsla_state_init.argtypes = [dp, vp, vp, vp]
+    lib.dsla_state_init.restype = ctypes.c_int
+    lib.dsla_prefill_workspace_bytes.argtypes = [dp, ctypes.c_int64]
+    lib.dsla_prefill_workspace_bytes.restype = ctypes.c_size_t
+    lib.dsla_prefill.argtypes = [dp, ctypes.c_int64] + [vp] * 9 + [ctypes.c_size_t, vp]
+    lib.dsla_prefill.restype = ctypes.c_int
+    lib.dsla_decode.argtypes = [dp] + [vp] * 9
+    lib.dsla_decode.restype = ctypes.c_int
+    lib.dsla_status_string.argtypes = [ctypes.c_int]
+    lib.dsla_status_string.restype = ctypes.c_char_p
+    lib.dsla_last_hip_error.argtypes = []
+    lib.dsla_last_hip_error.restype = ctypes.c_char_p
+    lib.dsla_profile_enable.argtypes = [ctypes.c_int, ctypes.c_int]
+    lib.dsla_profile_enable.restype = ctypes.c_int
+    lib.dsla_profile_collect.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    lib.dsla_profile_collect.restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _check(status: int):
+    if status != 0:
+        lib = load_library()
+        text = lib.dsla_status_string(status).decode()
+        if status == 5:
+            text += ": " + lib.dsla_last_hip_error().decode()
+        raise DslaError(status, text)
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.bfloat16:
+        return DSLA_BF16
+    if t.dtype == torch.float32:
+        return DSLA_F32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "tensors must be contiguous GPU tensors"
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_desc(B, H, d_k, d_v, *, io_dtype, gate_dtype, gamma=0.5, scale=1.0, chunk=0, segments=0,
+              gamma_per_head=None) -> DslaDesc:
+    gp = ctypes.c_void_p(gamma_per_head.data_ptr()) if gamma_per_head is not None else None
+    return DslaDesc(int(B), int(H), int(d_k), int(d_v), int(chunk), int(segments), int(io_dtype), int(gate_dtype),
+                    float(gamma), float(scale), gp)
+
+
+def dsla_state_init(desc: DslaDesc, S1, S2):
+    """Zero both states (include/dsla.h: dsla_state_init)."""
+    _check(load_library().dsla_state_init(ctypes.byref(desc), _ptr(S1), _ptr(S2), _stream()))
+
+
+def dsla_prefill_workspace_bytes(desc: DslaDesc, T: int) -> int:
+    return int(load_library().dsla_prefill_workspace_bytes(ctypes.byref(desc), int(T)))
+
+
+def dsla_prefill(desc: DslaDesc, T, q, k, v, g1, g2, S1, S2, o, workspace=None):
+    """Chunked prefill over T tokens (include/dsla.h: dsla_prefill).  `workspace` is a uint8 GPU
+    tensor of at least dsla_prefill_workspace_bytes(desc, T) bytes, or None when that is zero."""
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().dsla_prefill(ctypes.byref(desc), int(T), _ptr(q), _ptr(k), _ptr(v), _ptr(g1), _ptr(g2),
+                                       _ptr(S1), _ptr(S2), _ptr(o), _ptr(workspace), wbytes, _stream()))
+
+
+def dsla_decode(desc: DslaDesc, q, k, v, g1, g2, S1, S2, o):
+    """One fused decode step (include/dsla.h: dsla_decode)."""
+    _check(load_library().dsla_decode(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g1), _ptr(g2),
+                                      _ptr(S1), _ptr(S2), _ptr(o), _stream()))
+
+
+def profile_enable(enable: bool, max_records: int = 4096):
+    _check(load_library().dsla_profile_enable(1 if enable else 0, int(max_records)))
+
+
+def profile_collect() -> dict:
+    """Returns {kernel name: (total milliseconds, launches)} since the last collect."""
+    n = len(KERNEL_NAMES)
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_int64 * n)()
+    _check(load_library().dsla_profile_collect(ms, cnt))
+    return {KERNEL_NAMES[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}

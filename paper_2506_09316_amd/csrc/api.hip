@@ -1,0 +1,191 @@
+// C ABI of libdsla: argument checks, planning and dispatch.  Declarations and the contract
+// of every entry point are in include/dsla.h.
+#include <mutex>
+#include <vector>
+
+#include "dsla_internal.h"
+
+namespace dsla {
+namespace {
+
+thread_local const char *g_last_hip_error = "";
+
+dsla_status hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return DSLA_OK;
+    g_last_hip_error = hipGetErrorString(e);
+    return DSLA_ERR_HIP;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+dsla_status check_desc(const dsla_desc *d)
+{
+    if (!d) return DSLA_ERR_NULL;
+    if (d->B <= 0 || d->H <= 0 || d->d_k <= 0 || d->d_v <= 0) return DSLA_ERR_SHAPE;
+    if (d->chunk < 0 || d->segments < 0) return DSLA_ERR_SHAPE;
+    if ((d->io_dtype != DSLA_F32 && d->io_dtype != DSLA_BF16) ||
+        (d->gate_dtype != DSLA_F32 && d->gate_dtype != DSLA_BF16))
+        return DSLA_ERR_UNSUPPORTED;
+    if (static_cast<int64_t>(d->B) * d->H > 0x7fffffffLL / 8) return DSLA_ERR_SHAPE;
+    if (!decode_supported(*d)) return DSLA_ERR_UNSUPPORTED;  // d_k = d_v in {64, 128}
+    return DSLA_OK;
+}
+
+// ---- kernel timing --------------------------------------------------------------------------
+struct Profiler {
+    std::mutex mu;
+    bool enabled = false;
+    std::vector<hipEvent_t> ev;  // 2 per record
+    std::vector<int> ids;
+    int max_records = 0;
+    bool open = false;  // a "before" without its "after"
+} g_prof;
+
+}  // namespace
+
+void profile_before(int kernel_id, hipStream_t stream)
+{
+    if (!g_prof.enabled) return;
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    if (static_cast<int>(g_prof.ids.size()) >= g_prof.max_records) return;
+    const size_t r = g_prof.ids.size();
+    (void)hipEventRecord(g_prof.ev[2 * r], stream);
+    g_prof.ids.push_back(kernel_id);
+    g_prof.open = true;
+}
+
+void profile_after(int, hipStream_t stream)
+{
+    if (!g_prof.enabled) return;
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    if (!g_prof.open) return;
+    const size_t r = g_prof.ids.size() - 1;
+    (void)hipEventRecord(g_prof.ev[2 * r + 1], stream);
+    g_prof.open = false;
+}
+
+}  // namespace dsla
+
+using namespace dsla;
+
+extern "C" {
+
+const char *dsla_status_string(dsla_status s)
+{
+    switch (s) {
+    case DSLA_OK: return "ok";
+    case DSLA_ERR_NULL: return "required pointer is NULL";
+    case DSLA_ERR_SHAPE: return "bad size or misaligned pointer";
+    case DSLA_ERR_UNSUPPORTED: return "shape, chunk or dtype combination not supported";
+    case DSLA_ERR_WORKSPACE: return "workspace missing or too small";
+    case DSLA_ERR_HIP: return "HIP call failed";
+    }
+    return "unknown status";
+}
+
+const char *dsla_last_hip_error(void) { return g_last_hip_error; }
+
+dsla_status dsla_state_init(const dsla_desc *desc, float *S1, float *S2, void *stream)
+{
+    dsla_status st = check_desc(desc);
+    if (st != DSLA_OK) return st;
+    if (!S1 || !S2) return DSLA_ERR_NULL;
+    if (!aligned16(S1) || !aligned16(S2)) return DSLA_ERR_SHAPE;
+    const size_t n = static_cast<size_t>(desc->B) * desc->H * desc->d_k * desc->d_v;
+    return hip_status(launch_state_init(S1, S2, n, static_cast<hipStream_t>(stream)));
+}
+
+size_t dsla_prefill_workspace_bytes(const dsla_desc *desc, int64_t T)
+{
+    if (check_desc(desc) != DSLA_OK || T <= 0) return 0;
+    PrefillPlan plan;
+    if (!prefill_plan(*desc, T, &plan)) return 0;
+    return plan.ws_total_bytes;
+}
+
+dsla_status dsla_prefill(const dsla_desc *desc, int64_t T, const void *q, const void *k, const void *v,
+                         const void *g1, const void *g2, float *S1, float *S2, void *o, void *workspace,
+                         size_t workspace_bytes, void *stream)
+{
+    dsla_status st = check_desc(desc);
+    if (st != DSLA_OK) return st;
+    if (T < 0) return DSLA_ERR_SHAPE;
+    if (!S1 || !S2) return DSLA_ERR_NULL;
+    if (T == 0) return DSLA_OK;
+    if (!q || !k || !v || !g1 || !g2 || !o) return DSLA_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g1) || !aligned16(g2) || !aligned16(o) ||
+        !aligned16(S1) || !aligned16(S2))
+        return DSLA_ERR_SHAPE;
+    if (T > (int64_t(1) << 40)) return DSLA_ERR_SHAPE;
+    PrefillPlan plan;
+    if (!prefill_plan(*desc, T, &plan)) return DSLA_ERR_UNSUPPORTED;
+    if (plan.ws_total_bytes > 0) {
+        if (!workspace || workspace_bytes < plan.ws_total_bytes) return DSLA_ERR_WORKSPACE;
+        if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return DSLA_ERR_SHAPE;
+    }
+    return hip_status(launch_prefill(*desc, plan, T, q, k, v, g1, g2, S1, S2, o, workspace,
+                                     static_cast<hipStream_t>(stream)));
+}
+
+dsla_status dsla_decode(const dsla_desc *desc, const void *q, const void *k, const void *v, const void *g1,
+                        const void *g2, float *S1, float *S2, void *o, void *stream)
+{
+    dsla_status st = check_desc(desc);
+    if (st != DSLA_OK) return st;
+    if (!q || !k || !v || !g1 || !g2 || !S1 || !S2 || !o) return DSLA_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g1) || !aligned16(g2) || !aligned16(o) ||
+        !aligned16(S1) || !aligned16(S2))
+        return DSLA_ERR_SHAPE;
+    return hip_status(launch_decode(*desc, q, k, v, g1, g2, S1, S2, o, static_cast<hipStream_t>(stream)));
+}
+
+dsla_status dsla_profile_enable(int enable, int max_records)
+{
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    for (hipEvent_t e : g_prof.ev) (void)hipEventDestroy(e);
+    g_prof.ev.clear();
+    g_prof.ids.clear();
+    g_prof.enabled = false;
+    g_prof.open = false;
+    g_prof.max_records = 0;
+    if (!enable) return DSLA_OK;
+    if (max_records <= 0) return DSLA_ERR_SHAPE;
+    g_prof.ev.resize(2 * static_cast<size_t>(max_records));
+    for (auto &e : g_prof.ev) {
+        hipError_t err = hipEventCreate(&e);
+        if (err != hipSuccess) return hip_status(err);
+    }
+    g_prof.ids.reserve(max_records);
+    g_prof.max_records = max_records;
+    g_prof.enabled = true;
+    return DSLA_OK;
+}
+
+dsla_status dsla_profile_collect(double *total_ms, int64_t *launches)
+{
+    if (!total_ms || !launches) return DSLA_ERR_NULL;
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    for (int i = 0; i < DSLA_KERNEL_COUNT; ++i) {
+        total_ms[i] = 0.0;
+        launches[i] = 0;
+    }
+    const size_t n = g_prof.ids.size() - (g_prof.open ? 1 : 0);
+    for (size_t r = 0; r < n; ++r) {
+        hipError_t err = hipEventSynchronize(g_prof.ev[2 * r + 1]);
+        if (err != hipSuccess) return hip_status(err);
+        float ms = 0.f;
+        err = hipEventElapsedTime(&ms, g_prof.ev[2 * r], g_prof.ev[2 * r + 1]);
+        if (err != hipSuccess) return hip_status(err);
+        const int id = g_prof.ids[r];
+        if (id >= 0 && id < DSLA_KERNEL_COUNT) {
+            total_ms[id] += ms;
+            launches[id] += 1;
+        }
+    }
+    g_prof.ids.clear();
+    g_prof.open = false;
+    return DSLA_OK;
+}
+
+}  // extern "C"

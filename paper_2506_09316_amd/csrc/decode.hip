@@ -1,0 +1,166 @@
+// Fused DSLA decode step (paper Section 4.1: state-update equation and blended read-out,
+// applied to one token per sequence).
+//
+// Bandwidth-bound: per (batch, head) the two fp32 states (2 * d_k * d_v * 4 bytes) are read
+// once and written once; everything else is a few hundred bytes.  One workgroup of 256
+// threads streams one (batch, head) pair.  A thread owns four adjacent state columns
+// (one 16-byte access) in every ROWG-th row, so a wavefront access covers whole rows and is
+// fully coalesced.  All state loads are issued before anything else so that the maximum
+// number of bytes is in flight; the small per-token vectors go through LDS meanwhile.
+#include "dsla_internal.h"
+
+namespace dsla {
+namespace {
+
+constexpr int kDecodeThreads = 256;
+
+template <int DK, int DV, class TIO, class TG>
+__global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
+    const TIO *__restrict__ q, const TIO *__restrict__ k, const TIO *__restrict__ v, const TG *__restrict__ g1,
+    const TG *__restrict__ g2, float *__restrict__ S1, float *__restrict__ S2, TIO *__restrict__ o, int H,
+    float gamma, const float *__restrict__ gamma_per_head, float scale)
+{
+    constexpr int COLG = DV / 4;                  // threads across a state row (float4 each)
+    constexpr int ROWG = kDecodeThreads / COLG;   // row groups
+    constexpr int ROWS = DK / ROWG;               // rows per thread
+    static_assert(kDecodeThreads % COLG == 0 && DK % ROWG == 0, "shape");
+    static_assert(COLG <= 64 && 64 % COLG == 0, "a wavefront must hold whole row groups");
+
+    __shared__ float s_q[DK], s_k[DK], s_a1[DK], s_a2[DK];
+    __shared__ float4 s_red[kDecodeThreads / 64][COLG];
+
+    const int bh = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int cg = tid % COLG;
+    const int rg = tid / COLG;
+    const size_t sbase = static_cast<size_t>(bh) * DK * DV;
+    float4 *p1 = reinterpret_cast<float4 *>(S1 + sbase) + cg;
+    float4 *p2 = reinterpret_cast<float4 *>(S2 + sbase) + cg;
+
+    // 1. all state loads in flight
+    float4 a[ROWS], b[ROWS];
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+        const int row = rg + j * ROWG;
+        a[j] = p1[static_cast<size_t>(row) * COLG];
+        b[j] = p2[static_cast<size_t>(row) * COLG];
+    }
+
+    // 2. per-token vectors -> LDS (gates exponentiated once per row)
+    const float gm = gamma_per_head ? gamma_per_head[bh % H] : gamma;
+    const size_t kb = static_cast<size_t>(bh) * DK;
+    for (int d = tid; d < DK; d += kDecodeThreads) {
+        s_q[d] = scale * to_f32(q[kb + d]);
+        s_k[d] = to_f32(k[kb + d]);
+        s_a1[d] = __expf(to_f32(g1[kb + d]));
+        s_a2[d] = __expf(to_f32(g2[kb + d]));
+    }
+    const TIO *vp = v + static_cast<size_t>(bh) * DV + cg * 4;
+    const float v0 = to_f32(vp[0]), v1 = to_f32(vp[1]), v2 = to_f32(vp[2]), v3 = to_f32(vp[3]);
+    __syncthreads();
+
+    // 3. update both states, accumulate the read-out, store
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    const float gm2 = 1.0f - gm;
+#pragma unroll
+    for (int j = 0; j < ROWS; ++j) {
+        const int row = rg + j * ROWG;
+        const float a1 = s_a1[row], a2 = s_a2[row], kd = s_k[row], qd = s_q[row];
+        float4 x = a[j], y = b[j];
+        x.x = fmaf(a1, x.x, kd * v0); x.y = fmaf(a1, x.y, kd * v1);
+        x.z = fmaf(a1, x.z, kd * v2); x.w = fmaf(a1, x.w, kd * v3);
+        y.x = fmaf(a2, y.x, kd * v0); y.y = fmaf(a2, y.y, kd * v1);
+        y.z = fmaf(a2, y.z, kd * v2); y.w = fmaf(a2, y.w, kd * v3);
+        p1[static_cast<size_t>(row) * COLG] = x;
+        p2[static_cast<size_t>(row) * COLG] = y;
+        const float qa = qd * gm, qb = qd * gm2;
+        acc.x = fmaf(qa, x.x, fmaf(qb, y.x, acc.x));
+        acc.y = fmaf(qa, x.y, fmaf(qb, y.y, acc.y));
+        acc.z = fmaf(qa, x.z, fmaf(qb, y.z, acc.z));
+        acc.w = fmaf(qa, x.w, fmaf(qb, y.w, acc.w));
+    }
+
+    // 4. reduce the read-out over row groups: inside a wavefront by shuffles, across by LDS
+#pragma unroll
+    for (int off = 32; off >= COLG; off >>= 1) {
+        acc.x += __shfl_xor(acc.x, off);
+        acc.y += __shfl_xor(acc.y, off);
+        acc.z += __shfl_xor(acc.z, off);
+        acc.w += __shfl_xor(acc.w, off);
+    }
+    const int wave = tid / 64, lane = tid % 64;
+    if (lane < COLG) s_red[wave][lane] = acc;
+    __syncthreads();
+    if (tid < COLG) {
+        float4 r = s_red[0][tid];
+#pragma unroll
+        for (int w = 1; w < kDecodeThreads / 64; ++w) {
+            const float4 t = s_red[w][tid];
+            r.x += t.x; r.y += t.y; r.z += t.z; r.w += t.w;
+        }
+        TIO *op = o + static_cast<size_t>(bh) * DV + tid * 4;
+        op[0] = from_f32<TIO>(r.x);
+        op[1] = from_f32<TIO>(r.y);
+        op[2] = from_f32<TIO>(r.z);
+        op[3] = from_f32<TIO>(r.w);
+    }
+}
+
+__global__ __launch_bounds__(256) void state_init_kernel(float4 *__restrict__ S1, float4 *__restrict__ S2, size_t n4)
+{
+    const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n4;
+         i += static_cast<size_t>(gridDim.x) * blockDim.x) {
+        S1[i] = z;
+        S2[i] = z;
+    }
+}
+
+template <int D, class TIO, class TG>
+hipError_t launch_decode_t(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
+                           const void *g2, float *S1, float *S2, void *o, hipStream_t stream)
+{
+    const unsigned grid = static_cast<unsigned>(d.B) * static_cast<unsigned>(d.H);
+    ProfileScope ps(DSLA_KERNEL_DECODE, stream);
+    hipLaunchKernelGGL((decode_kernel<D, D, TIO, TG>), dim3(grid), dim3(kDecodeThreads), 0, stream,
+                       static_cast<const TIO *>(q), static_cast<const TIO *>(k), static_cast<const TIO *>(v),
+                       static_cast<const TG *>(g1), static_cast<const TG *>(g2), S1, S2, static_cast<TIO *>(o), d.H,
+                       d.gamma, d.gamma_per_head, d.scale);
+    return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_decode_d(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
+                           const void *g2, float *S1, float *S2, void *o, hipStream_t stream)
+{
+    const bool io16 = d.io_dtype == DSLA_BF16, g16 = d.gate_dtype == DSLA_BF16;
+    if (io16 && g16) return launch_decode_t<D, bf16_t, bf16_t>(d, q, k, v, g1, g2, S1, S2, o, stream);
+    if (io16 && !g16) return launch_decode_t<D, bf16_t, float>(d, q, k, v, g1, g2, S1, S2, o, stream);
+    if (!io16 && g16) return launch_decode_t<D, float, bf16_t>(d, q, k, v, g1, g2, S1, S2, o, stream);
+    return launch_decode_t<D, float, float>(d, q, k, v, g1, g2, S1, S2, o, stream);
+}
+
+}  // namespace
+
+bool decode_supported(const dsla_desc &d) { return d.d_k == d.d_v && (d.d_k == 64 || d.d_k == 128); }
+
+hipError_t launch_decode(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
+                         const void *g2, float *S1, float *S2, void *o, hipStream_t stream)
+{
+    if (d.d_k == 128) return launch_decode_d<128>(d, q, k, v, g1, g2, S1, S2, o, stream);
+    return launch_decode_d<64>(d, q, k, v, g1, g2, S1, S2, o, stream);
+}
+
+hipError_t launch_state_init(float *S1, float *S2, size_t elems_per_state, hipStream_t stream)
+{
+    const size_t n4 = elems_per_state / 4;  // d_k*d_v is a multiple of 4 for every supported shape
+    size_t blocks = (n4 + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    if (blocks == 0) blocks = 1;
+    ProfileScope ps(DSLA_KERNEL_STATE_INIT, stream);
+    hipLaunchKernelGGL(state_init_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream,
+                       reinterpret_cast<float4 *>(S1), reinterpret_cast<float4 *>(S2), n4);
+    return hipGetLastError();
+}
+
+}  // namespace dsla

@@ -1,0 +1,66 @@
+// Internal declarations shared by the translation units of libdsla (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "dsla.h"
+
+namespace dsla {
+
+// ---- storage element types -------------------------------------------------------------
+struct bf16_t {
+    uint16_t bits;
+};
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float(static_cast<uint32_t>(x.bits) << 16); }
+
+// fp32 -> bf16, round to nearest even (the hardware conversion of gfx950 does the same).
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f)
+{
+    __bf16 h = static_cast<__bf16>(f);
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+template <class T>
+__device__ __forceinline__ T from_f32(float f);
+template <>
+__device__ __forceinline__ float from_f32<float>(float f) { return f; }
+template <>
+__device__ __forceinline__ bf16_t from_f32<bf16_t>(float f) { return bf16_t{f32_to_bf16_bits(f)}; }
+
+// ---- profiling hooks (api.hip) -----------------------------------------------------------
+void profile_before(int kernel_id, hipStream_t stream);
+void profile_after(int kernel_id, hipStream_t stream);
+
+struct ProfileScope {
+    int id;
+    hipStream_t s;
+    ProfileScope(int kernel_id, hipStream_t stream) : id(kernel_id), s(stream) { profile_before(id, s); }
+    ~ProfileScope() { profile_after(id, s); }
+};
+
+// ---- launchers (one per kernel family; each returns the launch error) ------------------------
+hipError_t launch_state_init(float *S1, float *S2, size_t elems_per_state, hipStream_t stream);
+
+hipError_t launch_decode(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
+                         const void *g2, float *S1, float *S2, void *o, hipStream_t stream);
+bool decode_supported(const dsla_desc &d);
+
+// Prefill plan: how a sequence is cut into segments and chunks.
+struct PrefillPlan {
+    int chunk;               // C
+    int segments;            // P >= 1
+    int64_t segment_tokens;  // tokens per segment (multiple of C), last segment may be shorter
+    size_t state_elems;      // B*H*d_k*d_v
+    size_t ws_state_bytes;   // P slots of both states (fp32) when P > 1
+    size_t ws_decay_bytes;   // P-1 slots of both segment decays (fp32 log2) when P > 1
+    size_t ws_total_bytes;
+};
+bool prefill_plan(const dsla_desc &d, int64_t T, PrefillPlan *plan);  // false: unsupported combination
+hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T, const void *q, const void *k,
+                          const void *v, const void *g1, const void *g2, float *S1, float *S2, void *o,
+                          void *workspace, hipStream_t stream);
+
+}  // namespace dsla

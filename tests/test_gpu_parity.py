@@ -1,0 +1,185 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU oracle, element by element.
+
+Tolerances (norm: max |x - ref| / max |ref| per tensor):
+  fp32 I/O : 1e-4          bf16 I/O : 2e-2 against the fp64 oracle fed the same bf16-rounded inputs
+"""
+import numpy as np
+import pytest
+
+from oracle import dsla_oracle as orc
+from paper_2506_09316_amd import workloads as wl
+from tests.util import GpuLayer, max_rel_err, slice_t
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+def check(name, got, ref, tol):
+    err = max_rel_err(got, ref)
+    print(f"    {name}: max rel err {err:.3e} (tol {tol:g})", flush=True)
+    assert np.all(np.isfinite(got)), f"{name} has non-finite values"
+    assert err <= tol, f"{name}: {err} > {tol}"
+
+
+def run_prefill_case(B, T, H, d, io, gd, *, chunk=0, segments=0, gamma=0.5, scale=1.0, tau=16.0, seed=1,
+                     qk_scale=1.0, init=False, gph=None):
+    print(f"  prefill B={B} T={T} H={H} d={d} io={io} gates={gd} chunk={chunk} segments={segments} "
+          f"gamma={gamma} scale={scale} tau={tau} init={init}", flush=True)
+    x = wl.layer_inputs(seed, B, T, H, d, d, io_dtype=io, gate_dtype=gd, tau=tau, qk_scale=qk_scale)
+    layer = GpuLayer(B, H, d, io, gd, gamma=gamma, scale=scale, chunk=chunk, segments=segments, gamma_per_head=gph)
+    S10 = S20 = None
+    if init:
+        S10, S20 = wl.initial_states(seed, B, H, d, d, amplitude=2.0)
+        layer.set_states(S10, S20)
+    o = layer.prefill(x)
+    S1, S2 = layer.states()
+    g = gph if gph is not None else gamma
+    ro, rS1, rS2 = orc.recurrent(x["q"], x["k"], x["v"], x["g1"], x["g2"], g, scale, S1=S10, S2=S20)
+    tol = TOL[io]
+    check("o", o, ro, tol)
+    check("S1", S1, rS1, tol)
+    check("S2", S2, rS2, tol)
+
+
+# ---------------------------------------------------------------- decode
+@pytest.mark.parametrize("io,gd,d", [("f32", "f32", 64), ("bf16", "bf16", 128), ("bf16", "f32", 64), ("f32", "bf16", 128)])
+def test_decode_steps(io, gd, d):
+    B, H, steps = 3, 5, 6
+    x = wl.layer_inputs(77, B, steps, H, d, d, io_dtype=io, gate_dtype=gd, tau=4.0)
+    S10, S20 = wl.initial_states(78, B, H, d, d)
+    gph = np.linspace(0.1, 0.9, H)
+    layer = GpuLayer(B, H, d, io, gd, scale=0.5, gamma_per_head=gph)
+    layer.set_states(S10, S20)
+    s1, s2 = S10.astype(np.float64), S20.astype(np.float64)
+    for t in range(steps):
+        xt = slice_t(x, t, t + 1)
+        o = layer.decode(xt)
+        ro, s1, s2 = orc.recurrent(xt["q"], xt["k"], xt["v"], xt["g1"], xt["g2"], gph, 0.5, S1=s1, S2=s2)
+        # o is rounded to the I/O dtype on the way out: one bf16 ulp is 2^-8 relative
+        check(f"o[{t}]", o, ro, TOL[io])
+    S1, S2 = layer.states()
+    check("S1", S1, s1, 1e-5)
+    check("S2", S2, s2, 1e-5)
+
+
+# ---------------------------------------------------------------- prefill, fp32 (tight check of the algebra)
+def test_prefill_cfg1_fp32():
+    c = wl.CONFIGS["cfg1"]
+    for gamma, tau in ((0.5, 16.0), (0.3, 16.0), (0.5, 1.0)):
+        run_prefill_case(c["B"], c["T"], c["H"], c["dk"], "f32", "f32", chunk=c["chunk"], gamma=gamma, tau=tau,
+                         seed=c["seed"])
+
+
+@pytest.mark.parametrize("chunk,segments,T", [(64, 1, 256), (64, 2, 256), (64, 4, 256), (32, 1, 256), (32, 3, 224),
+                                              (64, 1, 200), (64, 3, 333), (32, 2, 37), (64, 1, 1), (32, 1, 31),
+                                              (64, 0, 2048)])
+def test_prefill_fp32_shapes(chunk, segments, T):
+    run_prefill_case(2, T, 3, 64, "f32", "f32", chunk=chunk, segments=segments, gamma=0.35, scale=0.7, seed=5,
+                     init=True, gph=None)
+
+
+def test_prefill_fp32_d128_chunk32_per_head_gamma():
+    run_prefill_case(1, 150, 2, 128, "f32", "bf16", chunk=32, segments=2, seed=9, init=True, gph=np.array([0.2, 0.9]),
+                     qk_scale=128 ** -0.5)
+
+
+def test_prefill_fp32_gamma_extremes():
+    for gamma in (0.0, 1.0, 1.5):
+        run_prefill_case(1, 130, 2, 64, "f32", "f32", chunk=64, segments=2, gamma=gamma, seed=11, init=True)
+
+
+# ---------------------------------------------------------------- prefill, bf16
+@pytest.mark.parametrize("d,chunk,segments,T,gd", [(128, 64, 1, 512, "bf16"), (128, 64, 3, 500, "f32"),
+                                                   (128, 32, 2, 257, "bf16"), (64, 64, 2, 384, "bf16"),
+                                                   (64, 32, 1, 100, "f32"), (128, 64, 0, 1024, "bf16")])
+def test_prefill_bf16_shapes(d, chunk, segments, T, gd):
+    run_prefill_case(2, T, 3, d, "bf16", gd, chunk=chunk, segments=segments, gamma=0.4, seed=21, init=True,
+                     qk_scale=d ** -0.5)
+
+
+def test_prefill_bf16_strong_decay_tau1():
+    run_prefill_case(1, 512, 4, 128, "bf16", "f32", chunk=64, segments=2, gamma=0.5, tau=1.0, seed=31,
+                     qk_scale=128 ** -0.5)
+
+
+# ---------------------------------------------------------------- invariants on the GPU path
+def test_continuation_prefill_prefill_decode():
+    """prefill(T1) -> prefill(T2) -> n decode steps equals the oracle over T1 + T2 + n tokens."""
+    B, H, d, T1, T2, n = 1, 4, 64, 100, 156, 16
+    c = wl.CONFIGS["cfg1"]
+    x = wl.layer_inputs(c["seed"] + 7, B, T1 + T2 + n, H, d, d, io_dtype="f32", gate_dtype="f32")
+    layer = GpuLayer(B, H, d, "f32", "f32", gamma=0.5, chunk=64)
+    outs = [layer.prefill(slice_t(x, 0, T1)), layer.prefill(slice_t(x, T1, T1 + T2))]
+    for t in range(T1 + T2, T1 + T2 + n):
+        outs.append(layer.decode(slice_t(x, t, t + 1)))
+    o = np.concatenate(outs, 1)
+    S1, S2 = layer.states()
+    ro, rS1, rS2 = orc.recurrent(x["q"], x["k"], x["v"], x["g1"], x["g2"], 0.5)
+    check("o", o, ro, 1e-4)
+    check("S1", S1, rS1, 1e-4)
+    check("S2", S2, rS2, 1e-4)
+
+
+def test_chunk_and_segment_invariance_and_determinism():
+    B, T, H, d = 1, 512, 2, 128
+    x = wl.layer_inputs(41, B, T, H, d, d, io_dtype="bf16", gate_dtype="bf16", qk_scale=d ** -0.5)
+    outs = []
+    for chunk, seg in ((64, 1), (64, 1), (64, 4), (32, 2)):
+        layer = GpuLayer(B, H, d, "bf16", "bf16", chunk=chunk, segments=seg)
+        outs.append((layer.prefill(x),) + layer.states())
+    for a, b in zip(outs[0], outs[1]):
+        assert np.array_equal(a, b), "same call twice must be bit-identical"
+    for other in outs[2:]:
+        for a, b in zip(outs[0], other):
+            assert max_rel_err(b, a) < 2e-2
+
+
+# ---------------------------------------------------------------- full-size configurations, sampled heads
+def _sampled_heads_check(cfg_name, heads, segments=0):
+    c = wl.CONFIGS[cfg_name]
+    B, T, H, d = c["B"], c["T"], c["H"], c["dk"]
+    print(f"  {cfg_name}: B={B} T={T} H={H} d={d} chunk={c['chunk']}", flush=True)
+    x = wl.layer_inputs(c["seed"], B, T, H, d, d, io_dtype=c["io_dtype"], gate_dtype=c["gate_dtype"],
+                        qk_scale=c["qk_scale"])
+    layer = GpuLayer(B, H, d, c["io_dtype"], c["gate_dtype"], gamma=0.5, chunk=c["chunk"], segments=segments)
+    o = layer.prefill(x)
+    S1, S2 = layer.states()
+    assert np.all(np.isfinite(o))
+    for h in heads:
+        xs = {n: x[n][:, :, h:h + 1] for n in x}
+        ro, rS1, rS2 = orc.recurrent(xs["q"], xs["k"], xs["v"], xs["g1"], xs["g2"], 0.5)
+        check(f"o[h={h}]", o[:, :, h:h + 1], ro, 2e-2)
+        check(f"S1[h={h}]", S1[:, h:h + 1], rS1, 2e-2)
+        check(f"S2[h={h}]", S2[:, h:h + 1], rS2, 2e-2)
+
+
+def test_cfg2_full_size_sampled_heads():
+    _sampled_heads_check("cfg2", heads=(0, 13, 31))
+
+
+def test_cfg3_16k_full_size_sampled_heads():
+    _sampled_heads_check("cfg3_16k", heads=(5, 30))
+
+
+# ---------------------------------------------------------------- boundary behaviour
+def test_state_init_zeroes():
+    layer = GpuLayer(2, 3, 64, "bf16", "bf16")
+    S1, S2 = layer.states()
+    assert not S1.any() and not S2.any()
+
+
+def test_T0_is_noop_and_errors_do_nothing():
+    import torch
+    import paper_2506_09316_amd as dsla
+    layer = GpuLayer(1, 2, 64, "f32", "f32")
+    S10, S20 = wl.initial_states(3, 1, 2, 64, 64)
+    layer.set_states(S10, S20)
+    dsla.dsla_prefill(layer.desc, 0, None, None, None, None, None, layer.S1, layer.S2, None, None)
+    with pytest.raises(dsla.DslaError) as e:
+        q = torch.zeros(1, 8, 2, 64, device="cuda")
+        dsla.dsla_prefill(layer.desc, 8, q, q, q, q, None, layer.S1, layer.S2, q, None)
+    assert e.value.status == 1
+    torch.cuda.synchronize()
+    S1, S2 = layer.states()
+    assert np.array_equal(S1, S10) and np.array_equal(S2, S20)

@@ -1,0 +1,75 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header
+declares, and its host-side argument checks return the documented codes without a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2506_09316_amd as dsla
+from paper_2506_09316_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(dsla.library_path()):
+        from paper_2506_09316_amd import build
+        build.build()
+    return dsla.load_library()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "dsla.h")).read()
+    return sorted(set(re.findall(r"DSLA_API[^;(]*?\b(dsla_\w+)\s*\(", text)))
+
+
+def test_header_symbols_exported(lib):
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(lib):
+    for s in range(6):
+        assert lib.dsla_status_string(s)
+
+
+def test_argument_checks_need_no_gpu(lib):
+    d = dsla.make_desc(1, 2, 64, 64, io_dtype=0, gate_dtype=0)
+    fake = ctypes.c_void_p(4096)
+    # NULL state pointer
+    assert lib.dsla_state_init(ctypes.byref(d), None, fake, None) == 1
+    # unsupported head size
+    bad = dsla.make_desc(1, 2, 48, 48, io_dtype=0, gate_dtype=0)
+    assert lib.dsla_state_init(ctypes.byref(bad), fake, fake, None) == 3
+    # non-positive batch
+    bad = dsla.make_desc(0, 2, 64, 64, io_dtype=0, gate_dtype=0)
+    assert lib.dsla_decode(ctypes.byref(bad), *([fake] * 9)) == 2
+    # misaligned pointer
+    odd = ctypes.c_void_p(4100)
+    assert lib.dsla_decode(ctypes.byref(d), odd, *([fake] * 8)) == 2
+    # fp32 with d=128 has no chunk-64 build
+    big = dsla.make_desc(1, 2, 128, 128, io_dtype=0, gate_dtype=0, chunk=64)
+    assert lib.dsla_prefill(ctypes.byref(big), 128, *([fake] * 8), None, 0, None) == 3
+    # missing workspace when the plan needs one
+    seg = dsla.make_desc(1, 2, 64, 64, io_dtype=0, gate_dtype=0, chunk=64, segments=4)
+    need = lib.dsla_prefill_workspace_bytes(ctypes.byref(seg), 1024)
+    assert need > 0
+    assert lib.dsla_prefill(ctypes.byref(seg), 1024, *([fake] * 8), None, 0, None) == 4
+    assert lib.dsla_prefill(ctypes.byref(seg), 1024, *([fake] * 8), fake, need - 1, None) == 4
+    # T = 0 does nothing and needs no tensors
+    assert lib.dsla_prefill(ctypes.byref(d), 0, None, None, None, None, None, fake, fake, None, None, 0, None) == 0
+    assert lib.dsla_prefill(ctypes.byref(d), -1, *([fake] * 8), None, 0, None) == 2
+
+
+def test_workspace_plan(lib):
+    # one segment: no workspace
+    d = dsla.make_desc(8, 32, 128, 128, io_dtype=1, gate_dtype=1, chunk=64)
+    assert lib.dsla_prefill_workspace_bytes(ctypes.byref(d), 8192) == 0
+    # B*H = 32 at T = 16384: 8 segments of both fp32 states plus the decay vectors
+    d = dsla.make_desc(1, 32, 128, 128, io_dtype=1, gate_dtype=1, chunk=64)
+    n = lib.dsla_prefill_workspace_bytes(ctypes.byref(d), 16384)
+    assert n == 8 * 32 * 2 * 128 * 128 * 4 + 7 * 32 * 2 * 128 * 4
