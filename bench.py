@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the DSLA layer forward on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+Prints ONE JSON line.  Headline (`value`): prefill throughput in tokens/s of one
+Llama-2-7B-shaped DSLA layer (B=1, H=32, d_k=d_v=128, bf16 I/O, fp32 states, chunk 64)
+at T=16384; a step is dsla_state_init + dsla_prefill over the whole sequence with the
+inputs already resident in HBM.  The same line carries the batched-decode measurement
+(B=64, 256 single-token steps rotating over 8 independent state sets so that the
+256 MB last-level cache cannot hold the states), the roofline objects of the dominant
+kernels (durations from HIP events recorded by the library around each kernel launch,
+inside the timed region) and the CPU oracle timed on the host cores as a baseline.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
+
+
+def read_traffic(kernel: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), as recorded in
+    profiles/hbm_traffic.txt by hand from the counter runs; None when not recorded."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        m = re.match(r"\s*%s\s+bytes_per_launch\s*=\s*([0-9.eE+]+)" % re.escape(kernel), line)
+        if m:
+            return float(m.group(1))
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--T", type=int, default=16384, help="prefill length (default: the headline 16384)")
+    ap.add_argument("--segments", type=int, default=0)
+    ap.add_argument("--chunk", type=int, default=64)
+    ap.add_argument("--decode-steps", type=int, default=256)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (no collectives); use --gpus 1")
+
+    import numpy as np
+    import torch
+    import paper_2506_09316_amd as dsla
+    from paper_2506_09316_amd import workloads as wl
+    from paper_2506_09316_amd.binding import DSLA_BF16
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dsla.load_library()
+    dev = "cuda"
+
+    # ------------------------------------------------------------------ prefill
+    c = dict(wl.CONFIGS["cfg3_16k"])
+    B, H, D, T = c["B"], c["H"], c["dk"], args.T
+    x = wl.layer_inputs(c["seed"], B, T, H, D, D, io_dtype="bf16", gate_dtype="bf16", qk_scale=c["qk_scale"])
+    xg = {n: torch.from_numpy(a).to(dev).to(torch.bfloat16).contiguous() for n, a in x.items()}
+    desc = dsla.make_desc(B, H, D, D, io_dtype=DSLA_BF16, gate_dtype=DSLA_BF16, gamma=0.5, scale=1.0,
+                          chunk=args.chunk, segments=args.segments)
+    S1 = torch.empty(B, H, D, D, device=dev, dtype=torch.float32)
+    S2 = torch.empty_like(S1)
+    o = torch.empty_like(xg["v"])
+    nws = dsla.dsla_prefill_workspace_bytes(desc, T)
+    ws = torch.empty(max(nws, 256), dtype=torch.uint8, device=dev)
+
+    def prefill_step():
+        dsla.dsla_state_init(desc, S1, S2)
+        dsla.dsla_prefill(desc, T, xg["q"], xg["k"], xg["v"], xg["g1"], xg["g2"], S1, S2, o, ws if nws else None)
+
+    for _ in range(args.warmup):
+        prefill_step()
+    torch.cuda.synchronize()
+    dsla.profile_enable(True, 8 * (args.steps + 8))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        prefill_step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = dsla.profile_collect()
+    dsla.profile_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = B * T / (ms_per_step * 1e-3)
+
+    kern_ms = {k: (v[0] / v[1] if v[1] else None) for k, v in prof.items()}
+    loop_ms = kern_ms["prefill_chunk_loop"]
+    token_heads = B * T * H
+    alg_bytes = 6 * D * 2 * token_heads                    # q k v g1 g2 in, o out, bf16
+    C = args.chunk
+    alg_flops = (2 * D * (C + 1) + D * (C + 1) + 8 * D * D) * token_heads
+    roofline = {
+        "kernel": "prefill_chunk_loop", "bound": "hbm",
+        "achieved": alg_bytes / (loop_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "traffic": read_traffic("prefill_chunk_loop"),
+        "avg_kernel_ms": loop_ms,
+        "mfma_tflops_algorithmic": alg_flops / (loop_ms * 1e-3) / 1e12,
+        "mfma_frac_of_bf16_peak": alg_flops / (loop_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+    }
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+
+    out = {
+        "metric": "DSLA layer prefill tokens/s (Llama-2-7B shape, T=%d)" % T,
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg3 prefill: B=1 H=32 d_k=d_v=128 T=%d chunk=%d bf16 io, bf16 log-gates, "
+                               "fp32 states; step = state_init + prefill" % (T, C),
+                   "segments": args.segments, "workspace_bytes": nws},
+        "roofline": roofline,
+        "kernel_ms": {k: v for k, v in kern_ms.items() if v is not None},
+        "end_to_end_hbm_frac": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+    }
+
+    # ------------------------------------------------------------------ batched decode
+    del xg, o, ws
+    if not args.no_decode:
+        c4 = wl.CONFIGS["cfg4"]
+        Bd, Hd, Dd, Tp = c4["B"], c4["H"], c4["dk"], c4["T"]
+        NSETS = 8
+        ddesc = dsla.make_desc(Bd, Hd, Dd, Dd, io_dtype=DSLA_BF16, gate_dtype=DSLA_BF16, gamma=0.5, scale=1.0,
+                               chunk=64)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(c4["seed"])
+
+        def rnd(shape, scale=1.0, mean=0.0):
+            return torch.randn(shape, device=dev, generator=gen, dtype=torch.float32) * scale + mean
+
+        def gates(shape):
+            return (-torch.nn.functional.softplus(-rnd(shape, 1.0, 2.0)) / 16.0).to(torch.bfloat16)
+
+        sets = []
+        # states pre-populated by a T=2048 prefill per sequence (same value distribution as cfg3)
+        pq = rnd((Bd, Tp, Hd, Dd), c4["qk_scale"]).to(torch.bfloat16)
+        pk = rnd((Bd, Tp, Hd, Dd), c4["qk_scale"]).to(torch.bfloat16)
+        pv = rnd((Bd, Tp, Hd, Dd), c4["qk_scale"]).to(torch.bfloat16)
+        pg1, pg2 = gates((Bd, Tp, Hd, Dd)), gates((Bd, Tp, Hd, Dd))
+        po = torch.empty_like(pv)
+        pws_n = dsla.dsla_prefill_workspace_bytes(ddesc, Tp)
+        pws = torch.empty(max(pws_n, 256), dtype=torch.uint8, device=dev)
+        for s in range(NSETS):
+            a = torch.empty(Bd, Hd, Dd, Dd, device=dev, dtype=torch.float32)
+            b = torch.empty_like(a)
+            dsla.dsla_state_init(ddesc, a, b)
+            # a different roll of the same tokens per set keeps the sets distinct without 8x the inputs
+            dsla.dsla_prefill(ddesc, Tp, pq.roll(s, 0), pk.roll(s, 1), pv, pg1, pg2, a, b, po, pws if pws_n else None)
+            sets.append((a, b))
+        torch.cuda.synchronize()
+        t_pre0 = time.perf_counter()
+        dsla.dsla_prefill(ddesc, Tp, pq, pk, pv, pg1, pg2, sets[0][0], sets[0][1], po, pws if pws_n else None)
+        torch.cuda.synchronize()
+        batched_prefill_ms = (time.perf_counter() - t_pre0) * 1e3
+        del pq, pk, pv, pg1, pg2, po, pws
+        dq = [rnd((Bd, Hd, Dd), c4["qk_scale"]).to(torch.bfloat16) for _ in range(NSETS)]
+        dk = [rnd((Bd, Hd, Dd), c4["qk_scale"]).to(torch.bfloat16) for _ in range(NSETS)]
+        dv = [rnd((Bd, Hd, Dd), c4["qk_scale"]).to(torch.bfloat16) for _ in range(NSETS)]
+        dg1 = [gates((Bd, Hd, Dd)) for _ in range(NSETS)]
+        dg2 = [gates((Bd, Hd, Dd)) for _ in range(NSETS)]
+        do = torch.empty(Bd, Hd, Dd, device=dev, dtype=torch.bfloat16)
+
+        def decode_steps(n):
+            for i in range(n):
+                s = i % NSETS
+                dsla.dsla_decode(ddesc, dq[s], dk[s], dv[s], dg1[s], dg2[s], sets[s][0], sets[s][1], do)
+
+        decode_steps(16)
+        torch.cuda.synchronize()
+        nd = args.decode_steps
+        dsla.profile_enable(True, nd + 8)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        decode_steps(nd)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        dprof = dsla.profile_collect()
+        dsla.profile_enable(False)
+        dec_ms = dprof["decode"][0] / max(dprof["decode"][1], 1)
+        dec_bytes = Bd * Hd * (2 * Dd * Dd * 4 * 2 + (4 * Dd + 2 * Dd) * 2)
+        out["decode"] = {
+            "workload": "cfg4 decode: B=64 H=32 d=128, %d steps rotating over %d state sets" % (nd, NSETS),
+            "value": Bd * nd / (t1 - t0), "unit": "tokens/s", "ms_per_step": (t1 - t0) * 1e3 / nd,
+            "roofline": {"kernel": "decode", "bound": "hbm", "achieved": dec_bytes / (dec_ms * 1e-3) / 1e9,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": dec_bytes / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "traffic": read_traffic("decode"), "avg_kernel_ms": dec_ms},
+            "batched_prefill_B64_T2048_ms": batched_prefill_ms,
+            "batched_prefill_tokens_per_s": Bd * Tp / (batched_prefill_ms * 1e-3),
+        }
+        del sets
+
+    # ------------------------------------------------------------------ CPU oracle baseline
+    if not args.no_cpu_baseline:
+        from oracle import dsla_oracle as orc
+        Ts = min(T, 16384)
+        xs = {n: a[:, :Ts] for n, a in x.items()}
+        t0 = time.perf_counter()
+        orc.recurrent(xs["q"], xs["k"], xs["v"], xs["g1"], xs["g2"], 0.5)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": B * Ts / dt, "unit": "tokens/s", "cores": orc.threads(), "kind": "oracle",
+                               "sample": "prefill workload, first %d tokens of the same inputs, all %d heads, "
+                                         "fp64 token-by-token recurrence, %.1f s" % (Ts, H, dt)}
+        if not args.no_decode:
+            rng = np.random.default_rng(7)
+            nds = 16
+            dx = {n: rng.standard_normal((64, nds, 32, 128), dtype=np.float32) * 0.088 for n in ("q", "k", "v")}
+            dgs = {n: -np.abs(rng.standard_normal((64, nds, 32, 128), dtype=np.float32)) * 0.01 for n in ("g1", "g2")}
+            t0 = time.perf_counter()
+            orc.recurrent(dx["q"], dx["k"], dx["v"], dgs["g1"], dgs["g2"], 0.5)
+            dt = time.perf_counter() - t0
+            out["decode"]["cpu_baseline"] = {"value": 64 * nds / dt, "unit": "tokens/s", "cores": orc.threads(),
+                                             "kind": "oracle",
+                                             "sample": "%d decode steps at B=64 H=32 d=128, %.1f s" % (nds, dt)}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -37,6 +37,10 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() would also wait for the global
+// loads of the next chunk that are deliberately left in flight across the contraction phases.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // ---------------------------------------------------------------------------------------------
 // Arithmetic-type policies: how a contraction operand is stored in LDS and fed to MFMA.
 // A "fragment" is the 8 contraction-index values one lane supplies for a block of 16 contraction
@@ -185,9 +189,48 @@ struct PrefillArgs {
     float gamma, scale;
 };
 
-// Position of contraction index d inside a row of the "row layout" operands: bits 2 and 3 swapped, so
-// that 8 consecutive positions hold the features an accumulator-derived fragment holds (see header).
-__device__ __forceinline__ int perm_pos(int d) { return (d & ~12) | ((d & 4) << 1) | ((d & 8) >> 1); }
+// Transposed store of V: element e of RPT consecutive tokens -> RPT adjacent LDS elements.
+// bf16 data is moved with byte permutes (no conversion); fp32 data is stored as is.
+template <int RPT>
+__device__ __forceinline__ void store_v_tokens(uint16_t *dst, const Raw8<bf16_t> (&v)[RPT], int e)
+{
+    const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+    auto word = [&](const uint4 &u) -> uint32_t {
+        switch (e >> 1) {
+        case 0: return u.x;
+        case 1: return u.y;
+        case 2: return u.z;
+        default: return u.w;
+        }
+    };
+    const uint32_t lo = __builtin_amdgcn_perm(word(v[1].u), word(v[0].u), sel);
+    if (RPT == 4) {
+        const uint32_t hi = __builtin_amdgcn_perm(word(v[3].u), word(v[2].u), sel);
+        *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi);
+    } else {
+        *reinterpret_cast<uint32_t *>(dst) = lo;
+    }
+}
+template <int RPT>
+__device__ __forceinline__ void store_v_tokens(float *dst, const Raw8<float> (&v)[RPT], int e)
+{
+    auto pick = [&](const Raw8<float> &r) -> float {
+        switch (e) {
+        case 0: return r.a.x;
+        case 1: return r.a.y;
+        case 2: return r.a.z;
+        case 3: return r.a.w;
+        case 4: return r.b.x;
+        case 5: return r.b.y;
+        case 6: return r.b.z;
+        default: return r.b.w;
+        }
+    };
+    if (RPT == 4)
+        *reinterpret_cast<float4 *>(dst) = make_float4(pick(v[0]), pick(v[1]), pick(v[2]), pick(v[3]));
+    else
+        *reinterpret_cast<float2 *>(dst) = make_float2(pick(v[0]), pick(v[1]));
+}
 
 template <int D, int C, class TIO, class TG, bool kFull>
 struct Kern {
@@ -215,7 +258,7 @@ struct Kern {
         elem Kt[2 * D * TP];            // [i*D + d][token]        k 2^{bC - b}   (column groups swizzled)
         elem Vt[D * TP];                // [column][token]         v              (column groups swizzled)
         elem As[kFull ? C * TP : 8];    // [query token][key token] blended, masked scores
-        float cs[SG * 2 * D];           // gate scan scratch: per token-group totals -> exclusive prefixes
+        float cs[SG * 2 * D];           // gate scan scratch: per token-group totals -> exclusive prefixes (ln)
         float bC[2 * D];                // log2 decay of the whole chunk, per (state, feature)
         float dec[2 * D];               // 2^{bC}
     };
@@ -231,71 +274,87 @@ struct Kern {
         Raw8<TG> g1[RPT], g2[RPT];
     };
 
-    // Loads the rows of one chunk this thread owns; rows at or beyond t_end read as zero.
-    static __device__ __forceinline__ void load_chunk(RawChunk &rc, const PrefillArgs &a, size_t row0_elem,
-                                                      int64_t t_chunk, int64_t t_end, int sg, int dg)
+    // Per-thread global pointers at (first token this thread owns in the current chunk, feature group).
+    struct Ptrs {
+        const TIO *q, *k, *v;
+        const TG *g1, *g2;
+    };
+
+    // Loads the tokens of one chunk this thread owns; tokens at or beyond `valid` read as zero
+    // (zero log-gate = no decay, zero k and v = no contribution).
+    static __device__ __forceinline__ void load_chunk(RawChunk &rc, const Ptrs &p, size_t rs, int valid, int sg)
     {
-        const size_t rs = static_cast<size_t>(a.H) * D;
+        if (valid >= C) {
 #pragma unroll
-        for (int j = 0; j < RPT; ++j) {
-            const int64_t t = t_chunk + sg * RPT + j;
-            if (t < t_end) {
-                const size_t off = row0_elem + static_cast<size_t>(t) * rs + dg * 8;
-                if (kFull) rc.q[j].load(static_cast<const TIO *>(a.q) + off);
-                rc.k[j].load(static_cast<const TIO *>(a.k) + off);
-                rc.v[j].load(static_cast<const TIO *>(a.v) + off);
-                rc.g1[j].load(static_cast<const TG *>(a.g1) + off);
-                rc.g2[j].load(static_cast<const TG *>(a.g2) + off);
-            } else {
-                if (kFull) rc.q[j].zero();
-                rc.k[j].zero();
-                rc.v[j].zero();
-                rc.g1[j].zero();
-                rc.g2[j].zero();
+            for (int j = 0; j < RPT; ++j) {
+                if (kFull) rc.q[j].load(p.q + j * rs);
+                rc.k[j].load(p.k + j * rs);
+                rc.v[j].load(p.v + j * rs);
+                rc.g1[j].load(p.g1 + j * rs);
+                rc.g2[j].load(p.g2 + j * rs);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < RPT; ++j) {
+                if (sg * RPT + j < valid) {
+                    if (kFull) rc.q[j].load(p.q + j * rs);
+                    rc.k[j].load(p.k + j * rs);
+                    rc.v[j].load(p.v + j * rs);
+                    rc.g1[j].load(p.g1 + j * rs);
+                    rc.g2[j].load(p.g2 + j * rs);
+                } else {
+                    if (kFull) rc.q[j].zero();
+                    rc.k[j].zero();
+                    rc.v[j].zero();
+                    rc.g1[j].zero();
+                    rc.g2[j].zero();
+                }
             }
         }
     }
 
     // Gate scan and operand preparation for one chunk (all threads).  Ends with the operands in LDS;
-    // the caller places the barrier.
-    static __device__ __forceinline__ void prepare(Smem &sm, const RawChunk &rc, float gs1, float gs2, int tid,
-                                                   float &seg_log2_decay)
+    // the caller places the barrier.  lg[i] = log2|gamma_i scale|, neg[i] = gamma_i scale < 0.
+    static __device__ __forceinline__ void prepare(Smem &sm, const RawChunk &rc, const float (&lg)[2],
+                                                   const bool (&neg)[2], int tid, float &seg_log2_decay)
     {
         const int dg = tid % DG, sg = tid / DG;
-        float b[2][RPT][8];
-        // inclusive cumulative log2-gates over this thread's tokens
+        float bl[2][RPT][8];  // cumulative natural-log gates over this thread's tokens
 #pragma unroll
         for (int j = 0; j < RPT; ++j) {
             float g[8];
             rc.g1[j].unpack(g);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) b[0][j][e] = g[e] * kLog2e + (j ? b[0][j - 1][e] : 0.f);
+            for (int e = 0; e < 8; ++e) bl[0][j][e] = j ? bl[0][j - 1][e] + g[e] : g[e];
             rc.g2[j].unpack(g);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) b[1][j][e] = g[e] * kLog2e + (j ? b[1][j - 1][e] : 0.f);
+            for (int e = 0; e < 8; ++e) bl[1][j][e] = j ? bl[1][j - 1][e] + g[e] : g[e];
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             float *dst = &sm.cs[sg * 2 * D + i * D + dg * 8];
             *reinterpret_cast<float4 *>(dst) =
-                make_float4(b[i][RPT - 1][0], b[i][RPT - 1][1], b[i][RPT - 1][2], b[i][RPT - 1][3]);
+                make_float4(bl[i][RPT - 1][0], bl[i][RPT - 1][1], bl[i][RPT - 1][2], bl[i][RPT - 1][3]);
             *reinterpret_cast<float4 *>(dst + 4) =
-                make_float4(b[i][RPT - 1][4], b[i][RPT - 1][5], b[i][RPT - 1][6], b[i][RPT - 1][7]);
+                make_float4(bl[i][RPT - 1][4], bl[i][RPT - 1][5], bl[i][RPT - 1][6], bl[i][RPT - 1][7]);
         }
-        __syncthreads();
+        lds_barrier();
         {   // thread c scans column c = (state, feature) over the token groups
+            float t[SG];
+#pragma unroll
+            for (int s = 0; s < SG; ++s) t[s] = sm.cs[s * 2 * D + tid];
             float run = 0.f;
 #pragma unroll
             for (int s = 0; s < SG; ++s) {
-                const float t = sm.cs[s * 2 * D + tid];
                 sm.cs[s * 2 * D + tid] = run;
-                run += t;
+                run += t[s];
             }
-            sm.bC[tid] = run;
-            sm.dec[tid] = __builtin_amdgcn_exp2f(run);
-            seg_log2_decay += run;
+            const float run2 = run * kLog2e;
+            sm.bC[tid] = run2;
+            sm.dec[tid] = __builtin_amdgcn_exp2f(run2);
+            seg_log2_decay += run2;
         }
-        __syncthreads();
+        lds_barrier();
 
         float kf[RPT][8];
 #pragma unroll
@@ -303,29 +362,30 @@ struct Kern {
 
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-            float pre[8], bc[8];
+            float aq[8], ak[8], einv[8];
             {
                 const float *src = &sm.cs[sg * 2 * D + i * D + dg * 8];
                 const float4 p0 = *reinterpret_cast<const float4 *>(src);
                 const float4 p1 = *reinterpret_cast<const float4 *>(src + 4);
-                pre[0] = p0.x; pre[1] = p0.y; pre[2] = p0.z; pre[3] = p0.w;
-                pre[4] = p1.x; pre[5] = p1.y; pre[6] = p1.z; pre[7] = p1.w;
                 const float *sb = &sm.bC[i * D + dg * 8];
                 const float4 c0 = *reinterpret_cast<const float4 *>(sb);
                 const float4 c1 = *reinterpret_cast<const float4 *>(sb + 4);
-                bc[0] = c0.x; bc[1] = c0.y; bc[2] = c0.z; bc[3] = c0.w;
-                bc[4] = c1.x; bc[5] = c1.y; bc[6] = c1.z; bc[7] = c1.w;
+                const float pre[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+                const float bc[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float p2 = pre[e] * kLog2e;
+                    aq[e] = p2 + lg[i];    // exponent of gamma_i scale 2^{b}: add the local part
+                    ak[e] = bc[e] - p2;    // exponent of 2^{bC - b}: subtract the local part
+                    if (kFull) einv[e] = __builtin_amdgcn_exp2f(-bc[e]);
+                }
             }
             float khat[RPT][8];
 #pragma unroll
-            for (int j = 0; j < RPT; ++j) {
+            for (int j = 0; j < RPT; ++j)
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float bb = b[i][j][e] + pre[e];
-                    b[i][j][e] = bb;
-                    khat[j][e] = kf[j][e] * __builtin_amdgcn_exp2f(bc[e] - bb);
-                }
-            }
+                for (int e = 0; e < 8; ++e)
+                    khat[j][e] = kf[j][e] * __builtin_amdgcn_exp2f(fmaf(bl[i][j][e], -kLog2e, ak[e]));
             // K^ transposed: row = i*D + feature, RPT consecutive tokens per store
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
@@ -337,12 +397,8 @@ struct Kern {
                     A::store2(dst, khat[0][e], khat[1][e]);
             }
             if (kFull) {
-                const float gs = i ? gs2 : gs1;
                 // position of this thread's 8 features inside a permuted row: two groups of 4
                 const int p0 = i * D + (dg >> 1) * 16 + (dg & 1) * 4;
-                float einv[8];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) einv[e] = __builtin_amdgcn_exp2f(-bc[e]);
 #pragma unroll
                 for (int j = 0; j < RPT; ++j) {
                     float qf[8];
@@ -350,7 +406,9 @@ struct Kern {
                     float qt[8], kt[8];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        qt[e] = gs * qf[e] * __builtin_amdgcn_exp2f(b[i][j][e]);
+                        float eq = __builtin_amdgcn_exp2f(fmaf(bl[i][j][e], kLog2e, aq[e]));
+                        if (neg[i]) eq = -eq;
+                        qt[e] = qf[e] * eq;
                         kt[e] = khat[j][e] * einv[e];
                     }
                     const int row = sg * RPT + j;
@@ -362,19 +420,10 @@ struct Kern {
             }
         }
         // V transposed
-        {
-            float vf[RPT][8];
 #pragma unroll
-            for (int j = 0; j < RPT; ++j) rc.v[j].unpack(vf[j]);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int row = dg * 8 + e;
-                elem *dst = &sm.Vt[row * TP + tcol(row, sg * RPT)];
-                if (RPT == 4)
-                    A::store4(dst, vf[0][e], vf[1][e], vf[2][e], vf[3][e]);
-                else
-                    A::store2(dst, vf[0][e], vf[1][e]);
-            }
+        for (int e = 0; e < 8; ++e) {
+            const int row = dg * 8 + e;
+            store_v_tokens<RPT>(&sm.Vt[row * TP + tcol(row, sg * RPT)], rc.v, e);
         }
     }
 
@@ -396,11 +445,15 @@ struct Kern {
 
         const int64_t t0 = static_cast<int64_t>(p) * a.seg_tokens;
         const int64_t t1 = (t0 + a.seg_tokens < a.T) ? t0 + a.seg_tokens : a.T;
-        const size_t row0 = (static_cast<size_t>(bidx) * a.T * a.H + h) * D;  // element offset of (b, t=0, h, 0)
         const size_t rs = static_cast<size_t>(a.H) * D;
+        // element offset of (b, first token this thread owns, h, feature group)
+        const size_t off0 = (static_cast<size_t>(bidx) * a.T * a.H + h) * D +
+                            static_cast<size_t>(t0 + sg * RPT) * rs + dg * 8;
 
         const float gm = a.gamma_per_head ? a.gamma_per_head[h] : a.gamma;
-        const float gs1 = gm * a.scale, gs2 = (1.0f - gm) * a.scale;
+        const float gsv[2] = {gm * a.scale, (1.0f - gm) * a.scale};
+        const float lg[2] = {__builtin_amdgcn_logf(fabsf(gsv[0])), __builtin_amdgcn_logf(fabsf(gsv[1]))};
+        const bool neg[2] = {gsv[0] < 0.f, gsv[1] < 0.f};
 
         // ---- state accumulators: tile (i, dt) covers rows 32dt..32dt+31 of state i, columns 32*wave.. ----
         f32x16 acc[2][DT];
@@ -426,14 +479,31 @@ struct Kern {
         }
 
         float seg_decay = 0.f;  // thread tid: log2 of the segment decay of (state, feature) column tid
+        Ptrs ptr;
+        ptr.q = static_cast<const TIO *>(a.q) + off0;
+        ptr.k = static_cast<const TIO *>(a.k) + off0;
+        ptr.v = static_cast<const TIO *>(a.v) + off0;
+        ptr.g1 = static_cast<const TG *>(a.g1) + off0;
+        ptr.g2 = static_cast<const TG *>(a.g2) + off0;
+        TIO *optr = static_cast<TIO *>(a.o) + off0;
+        const size_t cstep = static_cast<size_t>(C) * rs;
+
         RawChunk rc;
-        load_chunk(rc, a, row0, t0, t1, sg, dg);
+        {
+            const int64_t left = t1 - t0;
+            load_chunk(rc, ptr, rs, left >= C ? C : static_cast<int>(left), sg);
+        }
 
         for (int64_t tc = t0; tc < t1; tc += C) {
-            prepare(sm, rc, gs1, gs2, tid, seg_decay);
-            if (tc + C < t1) load_chunk(rc, a, row0, tc + C, t1, sg, dg);  // in flight during the contractions
-            __syncthreads();
+            prepare(sm, rc, lg, neg, tid, seg_decay);
+            ptr.q += cstep; ptr.k += cstep; ptr.v += cstep; ptr.g1 += cstep; ptr.g2 += cstep;
+            if (tc + C < t1) {  // next chunk: in flight during the contractions
+                const int64_t left = t1 - (tc + C);
+                load_chunk(rc, ptr, rs, left >= C ? C : static_cast<int>(left), sg);
+            }
+            lds_barrier();
 
+            Frag sfr[kFull ? 2 : 1][kFull ? DT : 1][2];
             if (kFull) {
                 // ---- scores, transposed: tile (ts, tr) holds S^T[s][r] for key tile ts <= query tile tr ----
                 constexpr int NTILE = RT * (RT + 1) / 2;
@@ -464,8 +534,26 @@ struct Kern {
                         A::store4(&sm.As[r * TP + s0], x[0], x[1], x[2], x[3]);
                     }
                 }
-                __syncthreads();
             }
+            // ---- carried state: take its input fragments for the read-out, then decay its rows ----
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    if (kFull) {
+                        sfr[i][dt][0] = A::from_acc(acc[i][dt], 0);
+                        sfr[i][dt][1] = A::from_acc(acc[i][dt], 1);
+                    }
+#pragma unroll
+                    for (int jb = 0; jb < 4; ++jb) {
+                        const float4 dd = *reinterpret_cast<const float4 *>(&sm.dec[i * D + 32 * dt + 8 * jb + 4 * g]);
+                        acc[i][dt][4 * jb + 0] *= dd.x;
+                        acc[i][dt][4 * jb + 1] *= dd.y;
+                        acc[i][dt][4 * jb + 2] *= dd.z;
+                        acc[i][dt][4 * jb + 3] *= dd.w;
+                    }
+                }
+            if (kFull) lds_barrier();
 
             // ---- V fragments of this wavefront's columns (input of both the output and the update) ----
             Frag vf[KB];
@@ -491,19 +579,18 @@ struct Kern {
                         const Frag fb = A::load_frag(&sm.As[(32 * tr + ln) * TP + 16 * kb + 8 * g]);
                         A::mma(oacc[tr], vf[kb], fb);
                     }
-                // carried state: accumulators act as the input fragment
+                // carried state: the fragments taken from the accumulators are the other input
 #pragma unroll
                 for (int i = 0; i < 2; ++i)
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                         for (int half = 0; half < 2; ++half) {
-                            const Frag fa = A::from_acc(acc[i][dt], half);
                             const int kpos = i * D + 32 * dt + 16 * half + 8 * g;
 #pragma unroll
                             for (int tr = 0; tr < RT; ++tr) {
                                 const Frag fb = A::load_frag(&sm.Qs[(32 * tr + ln) * QP + kpos]);
-                                A::mma(oacc[tr], fa, fb);
+                                A::mma(oacc[tr], sfr[i][dt][half], fb);
                             }
                         }
                 // stage o (Ks is free since the scores barrier): Os[token][column], pitch D + 8
@@ -518,43 +605,32 @@ struct Kern {
                     }
             }
 
-            // ---- state update: decay the rows, add K^^T V ----
+            // ---- state update: add K^^T V to the decayed state ----
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
+                for (int i = 0; i < 2; ++i)
 #pragma unroll
-                    for (int jb = 0; jb < 4; ++jb) {
-                        const float4 dd = *reinterpret_cast<const float4 *>(&sm.dec[i * D + 32 * dt + 8 * jb + 4 * g]);
-                        acc[i][dt][4 * jb + 0] *= dd.x;
-                        acc[i][dt][4 * jb + 1] *= dd.y;
-                        acc[i][dt][4 * jb + 2] *= dd.z;
-                        acc[i][dt][4 * jb + 3] *= dd.w;
-                    }
-                    const int row = i * D + 32 * dt + ln;
-#pragma unroll
-                    for (int kb = 0; kb < KB; ++kb) {
+                    for (int dt = 0; dt < DT; ++dt) {
+                        const int row = i * D + 32 * dt + ln;
                         const Frag fa = A::load_frag(&sm.Kt[row * TP + tcol(row, 16 * kb + 8 * g)]);
                         A::mma(acc[i][dt], fa, vf[kb]);
                     }
-                }
-            __syncthreads();
 
             if (kFull) {
+                lds_barrier();
                 // ---- coalesced store of the staged output rows ----
                 const elem *Os = sm.Ks;
+                const int64_t left = t1 - tc;
 #pragma unroll
                 for (int j = 0; j < RPT; ++j) {
                     const int r = sg * RPT + j;
-                    const int64_t t = tc + r;
-                    if (t < t1) {
-                        TIO *dst = static_cast<TIO *>(a.o) + row0 + static_cast<size_t>(t) * rs + dg * 8;
-                        store8_global(dst, &Os[r * (D + 8) + dg * 8]);
-                    }
+                    if (r < left) store8_global(optr + j * rs, &Os[r * (D + 8) + dg * 8]);
                 }
+                optr += cstep;
             }
-            // the next prepare() writes Ks/Qs/Kt/Vt only after its two scan barriers, which every thread
-            // reaches after finishing the reads above
+            // The next prepare() writes Qs/Ks/Kt/Vt/dec only after its first scan barrier, which no
+            // wavefront passes before every wavefront has finished the LDS reads above.
         }
 
         // ---- write the state out ----
