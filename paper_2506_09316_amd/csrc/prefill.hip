@@ -23,6 +23,7 @@
 // those accumulators are fed back as the input fragment of the carried read-out without passing
 // through LDS; the partner operand is stored in LDS with the matching order of the contraction
 // index (bits 2 and 3 of the feature index swapped).
+#include <cstdio>
 #include <type_traits>
 
 #include "dsla_internal.h"
@@ -39,7 +40,72 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() would also wait for the global
 // loads of the next chunk that are deliberately left in flight across the contraction phases.
-__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_sched_barrier(0);   // phases are not interleaved by the instruction scheduler
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
+// Development aid, compiled out unless DSLA_PHASE_CLOCKS is defined: one lane of workgroup 0 adds up the
+// shader clock spent between phase marks and the launcher prints the totals.
+#ifdef DSLA_PHASE_CLOCKS
+struct PhaseClock {
+    long long acc[12];
+    long long last;
+    __device__ __forceinline__ void start()
+    {
+        for (int n = 0; n < 12; ++n) acc[n] = 0;
+        last = __builtin_amdgcn_s_memtime();
+    }
+    __device__ __forceinline__ void mark(int n)
+    {
+        const long long now = __builtin_amdgcn_s_memtime();
+        acc[n] += now - last;
+        last = now;
+    }
+    __device__ __forceinline__ void flush(long long *dbg) const
+    {
+        if (blockIdx.x == 0 && (threadIdx.x & 63) == 0 && dbg)
+            for (int n = 0; n < 12; ++n) dbg[(threadIdx.x >> 6) * 12 + n] = acc[n];
+    }
+};
+#else
+struct PhaseClock {
+    __device__ __forceinline__ void start() {}
+    __device__ __forceinline__ void mark(int) {}
+};
+#endif
+
+// ---------------------------------------------------------------------------------------------
+// LDS access by byte address.  Every LDS address below is "per-lane base register + compile-time
+// constant"; the bases are computed once and passed through opaque() so that the compiler keeps them
+// as they are instead of materialising one register per (base, constant) pair.
+// ---------------------------------------------------------------------------------------------
+#define DSLA_LDS __attribute__((address_space(3)))
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint32_t lds_addr_of(const void *p)
+{
+    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((DSLA_LDS const char *)p));
+}
+__device__ __forceinline__ uint32_t opaque(uint32_t x)
+{
+    asm volatile("" : "+v"(x));
+    return x;
+}
+template <class T>
+__device__ __forceinline__ T lds_ld(uint32_t a)
+{
+    return *(DSLA_LDS const T *)a;
+}
+template <class T>
+__device__ __forceinline__ void lds_st(uint32_t a, T v)
+{
+    *(DSLA_LDS T *)a = v;
+}
 
 // ---------------------------------------------------------------------------------------------
 // Arithmetic-type policies: how a contraction operand is stored in LDS and fed to MFMA.
@@ -47,18 +113,17 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 // indices (lane group g = lane/32 supplies indices 8g..8g+7 of the block).
 // ---------------------------------------------------------------------------------------------
 struct ArithBf16 {
-    using elem = uint16_t;  // LDS storage
+    static constexpr int ESZ = 2;  // bytes per LDS element
     struct Frag {
         bf16x8 v;
     };
-    struct Pack4 {
-        uint2 v;
+    struct Row8 {   // 8 operand values of one token, packed
+        u32x4 u;
     };
-    static __device__ __forceinline__ Frag load_frag(const elem *p)
+    static __device__ __forceinline__ Frag load_frag(uint32_t a)
     {
-        const uint4 u = *reinterpret_cast<const uint4 *>(p);
         Frag f;
-        f.v = __builtin_bit_cast(bf16x8, u);
+        f.v = __builtin_bit_cast(bf16x8, lds_ld<u32x4>(a));
         return f;
     }
     static __device__ __forceinline__ uint32_t pack2(float a, float b)
@@ -67,21 +132,34 @@ struct ArithBf16 {
         bf16x2 y = __builtin_convertvector(x, bf16x2);
         return __builtin_bit_cast(uint32_t, y);
     }
-    static __device__ __forceinline__ void store4(elem *p, float a, float b, float c, float d)
+    static __device__ __forceinline__ Row8 pack_row(const float (&x)[8])
     {
-        *reinterpret_cast<uint2 *>(p) = make_uint2(pack2(a, b), pack2(c, d));
+        Row8 r;
+        r.u = u32x4{pack2(x[0], x[1]), pack2(x[2], x[3]), pack2(x[4], x[5]), pack2(x[6], x[7])};
+        return r;
     }
-    static __device__ __forceinline__ void store2(elem *p, float a, float b)
+    static __device__ __forceinline__ void store_row(uint32_t a, const Row8 &r) { lds_st<u32x4>(a, r.u); }
+    // element e of RPT consecutive tokens -> RPT adjacent LDS elements
+    template <int RPT>
+    static __device__ __forceinline__ void store_tokens(uint32_t a, const Row8 (&r)[RPT], int e)
     {
-        *reinterpret_cast<uint32_t *>(p) = pack2(a, b);
+        const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+        const uint32_t lo = __builtin_amdgcn_perm(r[1].u[e >> 1], r[0].u[e >> 1], sel);
+        if constexpr (RPT == 4) {
+            const uint32_t hi = __builtin_amdgcn_perm(r[3].u[e >> 1], r[2].u[e >> 1], sel);
+            lds_st<u32x2>(a, u32x2{lo, hi});
+        } else {
+            lds_st<uint32_t>(a, lo);
+        }
+    }
+    static __device__ __forceinline__ void store4(uint32_t a, float x0, float x1, float x2, float x3)
+    {
+        lds_st<u32x2>(a, u32x2{pack2(x0, x1), pack2(x2, x3)});
     }
     static __device__ __forceinline__ Frag from_acc(const f32x16 &acc, int half)
     {
-        uint4 u;
-        u.x = pack2(acc[8 * half + 0], acc[8 * half + 1]);
-        u.y = pack2(acc[8 * half + 2], acc[8 * half + 3]);
-        u.z = pack2(acc[8 * half + 4], acc[8 * half + 5]);
-        u.w = pack2(acc[8 * half + 6], acc[8 * half + 7]);
+        const u32x4 u = {pack2(acc[8 * half + 0], acc[8 * half + 1]), pack2(acc[8 * half + 2], acc[8 * half + 3]),
+                         pack2(acc[8 * half + 4], acc[8 * half + 5]), pack2(acc[8 * half + 6], acc[8 * half + 7])};
         Frag f;
         f.v = __builtin_bit_cast(bf16x8, u);
         return f;
@@ -93,26 +171,44 @@ struct ArithBf16 {
 };
 
 struct ArithF32 {
-    using elem = float;
+    static constexpr int ESZ = 4;
     struct Frag {
         float v[8];
     };
-    static __device__ __forceinline__ Frag load_frag(const elem *p)
+    struct Row8 {
+        float x[8];
+    };
+    static __device__ __forceinline__ Frag load_frag(uint32_t a)
     {
-        const float4 a = *reinterpret_cast<const float4 *>(p);
-        const float4 b = *reinterpret_cast<const float4 *>(p + 4);
+        const f32x4 lo = lds_ld<f32x4>(a), hi = lds_ld<f32x4>(a + 16);
         Frag f;
-        f.v[0] = a.x; f.v[1] = a.y; f.v[2] = a.z; f.v[3] = a.w;
-        f.v[4] = b.x; f.v[5] = b.y; f.v[6] = b.z; f.v[7] = b.w;
+        f.v[0] = lo[0]; f.v[1] = lo[1]; f.v[2] = lo[2]; f.v[3] = lo[3];
+        f.v[4] = hi[0]; f.v[5] = hi[1]; f.v[6] = hi[2]; f.v[7] = hi[3];
         return f;
     }
-    static __device__ __forceinline__ void store4(elem *p, float a, float b, float c, float d)
+    static __device__ __forceinline__ Row8 pack_row(const float (&x)[8])
     {
-        *reinterpret_cast<float4 *>(p) = make_float4(a, b, c, d);
+        Row8 r;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r.x[e] = x[e];
+        return r;
     }
-    static __device__ __forceinline__ void store2(elem *p, float a, float b)
+    static __device__ __forceinline__ void store_row(uint32_t a, const Row8 &r)
     {
-        *reinterpret_cast<float2 *>(p) = make_float2(a, b);
+        lds_st<f32x4>(a, f32x4{r.x[0], r.x[1], r.x[2], r.x[3]});
+        lds_st<f32x4>(a + 16, f32x4{r.x[4], r.x[5], r.x[6], r.x[7]});
+    }
+    template <int RPT>
+    static __device__ __forceinline__ void store_tokens(uint32_t a, const Row8 (&r)[RPT], int e)
+    {
+        if constexpr (RPT == 4)
+            lds_st<f32x4>(a, f32x4{r[0].x[e], r[1].x[e], r[2].x[e], r[3].x[e]});
+        else
+            lds_st<f32x2>(a, f32x2{r[0].x[e], r[1].x[e]});
+    }
+    static __device__ __forceinline__ void store4(uint32_t a, float x0, float x1, float x2, float x3)
+    {
+        lds_st<f32x4>(a, f32x4{x0, x1, x2, x3});
     }
     static __device__ __forceinline__ Frag from_acc(const f32x16 &acc, int half)
     {
@@ -132,46 +228,115 @@ struct ArithF32 {
 template <class TIO>
 using ArithOf = typename std::conditional<std::is_same<TIO, bf16_t>::value, ArithBf16, ArithF32>::type;
 
-// ---- raw 8-element global loads (kept unconverted while in flight) ----------------------------------
+// ---- raw global loads (kept unconverted while in flight); address = uniform base + 32-bit lane offset ----
 template <class T>
 struct Raw8;
 template <>
 struct Raw8<bf16_t> {
-    uint4 u;
-    __device__ __forceinline__ void load(const bf16_t *p) { u = *reinterpret_cast<const uint4 *>(p); }
-    __device__ __forceinline__ void zero() { u = make_uint4(0, 0, 0, 0); }
-    __device__ __forceinline__ void unpack(float *f) const
+    u32x4 u;
+    __device__ __forceinline__ void load(const bf16_t *base, uint32_t elem_off)
     {
-        f[0] = __uint_as_float(u.x << 16); f[1] = __uint_as_float(u.x & 0xffff0000u);
-        f[2] = __uint_as_float(u.y << 16); f[3] = __uint_as_float(u.y & 0xffff0000u);
-        f[4] = __uint_as_float(u.z << 16); f[5] = __uint_as_float(u.z & 0xffff0000u);
-        f[6] = __uint_as_float(u.w << 16); f[7] = __uint_as_float(u.w & 0xffff0000u);
+        u = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(base) + elem_off * 2u);
+    }
+    __device__ __forceinline__ void zero() { u = u32x4{0, 0, 0, 0}; }
+    __device__ __forceinline__ void unpack(float (&f)[8]) const
+    {
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            f[2 * w] = __uint_as_float(u[w] << 16);
+            f[2 * w + 1] = __uint_as_float(u[w] & 0xffff0000u);
+        }
     }
 };
 template <>
 struct Raw8<float> {
-    float4 a, b;
-    __device__ __forceinline__ void load(const float *p)
+    f32x4 a, b;
+    __device__ __forceinline__ void load(const float *base, uint32_t elem_off)
     {
-        a = *reinterpret_cast<const float4 *>(p);
-        b = *reinterpret_cast<const float4 *>(p + 4);
+        const char *p = reinterpret_cast<const char *>(base) + elem_off * 4u;
+        a = *reinterpret_cast<const f32x4 *>(p);
+        b = *reinterpret_cast<const f32x4 *>(p + 16);
     }
-    __device__ __forceinline__ void zero() { a = b = make_float4(0.f, 0.f, 0.f, 0.f); }
-    __device__ __forceinline__ void unpack(float *f) const
+    __device__ __forceinline__ void zero() { a = b = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    __device__ __forceinline__ void unpack(float (&f)[8]) const
     {
-        f[0] = a.x; f[1] = a.y; f[2] = a.z; f[3] = a.w;
-        f[4] = b.x; f[5] = b.y; f[6] = b.z; f[7] = b.w;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            f[w] = a[w];
+            f[4 + w] = b[w];
+        }
     }
 };
+template <class T>
+struct Raw4;
+template <>
+struct Raw4<bf16_t> {
+    u32x2 u;
+    __device__ __forceinline__ void load(const bf16_t *base, uint32_t elem_off)
+    {
+        u = *reinterpret_cast<const u32x2 *>(reinterpret_cast<const char *>(base) + elem_off * 2u);
+    }
+    __device__ __forceinline__ void zero() { u = u32x2{0, 0}; }
+};
+template <>
+struct Raw4<float> {
+    f32x4 a;
+    __device__ __forceinline__ void load(const float *base, uint32_t elem_off)
+    {
+        a = *reinterpret_cast<const f32x4 *>(reinterpret_cast<const char *>(base) + elem_off * 4u);
+    }
+    __device__ __forceinline__ void zero() { a = f32x4{0.f, 0.f, 0.f, 0.f}; }
+};
 
-__device__ __forceinline__ void store8_global(bf16_t *p, const uint16_t *lds8)
+// Transposed store of V: element e (0..3) of RPT consecutive tokens -> RPT adjacent LDS elements.
+// bf16 data is moved with byte permutes (no conversion); fp32 data is stored as is.
+template <int RPT>
+__device__ __forceinline__ void store_v_tokens(uint32_t a, const Raw4<bf16_t> (&v)[RPT], int e)
 {
-    *reinterpret_cast<uint4 *>(p) = *reinterpret_cast<const uint4 *>(lds8);
+    const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+    const uint32_t lo = __builtin_amdgcn_perm(v[1].u[e >> 1], v[0].u[e >> 1], sel);
+    if constexpr (RPT == 4) {
+        const uint32_t hi = __builtin_amdgcn_perm(v[3].u[e >> 1], v[2].u[e >> 1], sel);
+        lds_st<u32x2>(a, u32x2{lo, hi});
+    } else {
+        lds_st<uint32_t>(a, lo);
+    }
 }
-__device__ __forceinline__ void store8_global(float *p, const float *lds8)
+template <int RPT>
+__device__ __forceinline__ void store_v_tokens(uint32_t a, const Raw4<float> (&v)[RPT], int e)
 {
-    *reinterpret_cast<float4 *>(p) = *reinterpret_cast<const float4 *>(lds8);
-    *reinterpret_cast<float4 *>(p + 4) = *reinterpret_cast<const float4 *>(lds8 + 4);
+    if constexpr (RPT == 4)
+        lds_st<f32x4>(a, f32x4{v[0].a[e], v[1].a[e], v[2].a[e], v[3].a[e]});
+    else
+        lds_st<f32x2>(a, f32x2{v[0].a[e], v[1].a[e]});
+}
+
+// staged output row (8 elements in LDS) -> global, uniform base + 32-bit lane offset
+__device__ __forceinline__ void store8_global(bf16_t *base, uint32_t elem_off, uint32_t lds8)
+{
+    *reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(base) + elem_off * 2u) = lds_ld<u32x4>(lds8);
+}
+__device__ __forceinline__ void store8_global(float *base, uint32_t elem_off, uint32_t lds8)
+{
+    char *p = reinterpret_cast<char *>(base) + elem_off * 4u;
+    *reinterpret_cast<f32x4 *>(p) = lds_ld<f32x4>(lds8);
+    *reinterpret_cast<f32x4 *>(p + 16) = lds_ld<f32x4>(lds8 + 16);
+}
+
+// Software-pipelined sequence of N steps: the LDS fragment of step s + DEPTH is requested before the
+// MFMA of step s is issued, so that LDS latency overlaps DEPTH matrix instructions.  Fully unrolled.
+template <int N, int DEPTH, class ARITH, class AddrF, class StepF>
+__device__ __forceinline__ void pipelined_steps(AddrF addr, StepF step)
+{
+    typename ARITH::Frag buf[DEPTH];
+#pragma unroll
+    for (int i = 0; i < DEPTH && i < N; ++i) buf[i] = ARITH::load_frag(addr(i));
+#pragma unroll
+    for (int s = 0; s < N; ++s) {
+        const typename ARITH::Frag cur = buf[s % DEPTH];
+        if (s + DEPTH < N) buf[s % DEPTH] = ARITH::load_frag(addr(s + DEPTH));
+        step(s, cur);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -187,255 +352,275 @@ struct PrefillArgs {
     int H;
     int P;
     float gamma, scale;
+#ifdef DSLA_PHASE_CLOCKS
+    long long *dbg;
+#endif
 };
 
-// Transposed store of V: element e of RPT consecutive tokens -> RPT adjacent LDS elements.
-// bf16 data is moved with byte permutes (no conversion); fp32 data is stored as is.
-template <int RPT>
-__device__ __forceinline__ void store_v_tokens(uint16_t *dst, const Raw8<bf16_t> (&v)[RPT], int e)
-{
-    const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
-    auto word = [&](const uint4 &u) -> uint32_t {
-        switch (e >> 1) {
-        case 0: return u.x;
-        case 1: return u.y;
-        case 2: return u.z;
-        default: return u.w;
-        }
-    };
-    const uint32_t lo = __builtin_amdgcn_perm(word(v[1].u), word(v[0].u), sel);
-    if (RPT == 4) {
-        const uint32_t hi = __builtin_amdgcn_perm(word(v[3].u), word(v[2].u), sel);
-        *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi);
-    } else {
-        *reinterpret_cast<uint32_t *>(dst) = lo;
-    }
-}
-template <int RPT>
-__device__ __forceinline__ void store_v_tokens(float *dst, const Raw8<float> (&v)[RPT], int e)
-{
-    auto pick = [&](const Raw8<float> &r) -> float {
-        switch (e) {
-        case 0: return r.a.x;
-        case 1: return r.a.y;
-        case 2: return r.a.z;
-        case 3: return r.a.w;
-        case 4: return r.b.x;
-        case 5: return r.b.y;
-        case 6: return r.b.z;
-        default: return r.b.w;
-        }
-    };
-    if (RPT == 4)
-        *reinterpret_cast<float4 *>(dst) = make_float4(pick(v[0]), pick(v[1]), pick(v[2]), pick(v[3]));
-    else
-        *reinterpret_cast<float2 *>(dst) = make_float2(pick(v[0]), pick(v[1]));
-}
-
+// Workgroup layout.  4 D threads = D/8 wavefronts in two groups; group i (wavefronts i*D/32 ...)
+// prepares the operands of state i and owns state i in the contractions; inside a group, wavefront ct
+// owns state columns [32 ct, 32 ct + 32).
 template <int D, int C, class TIO, class TG, bool kFull>
 struct Kern {
     using A = ArithOf<TIO>;
-    using elem = typename A::elem;
     using Frag = typename A::Frag;
+    using Row8 = typename A::Row8;
+    static constexpr int ESZ = A::ESZ;
 
-    static constexpr int NW = D / 32;       // wavefronts
-    static constexpr int NT = 64 * NW;      // threads (= 2 D)
+    static constexpr int CT = D / 32;       // column tiles = wavefronts per group
+    static constexpr int NW = 2 * CT;       // wavefronts
+    static constexpr int NT = 64 * NW;      // threads (= 4 D)
+    static constexpr int GT = NT / 2;       // threads per group (= 2 D)
     static constexpr int DG = D / 8;        // feature groups of 8
-    static constexpr int SG = NT / DG;      // token groups (16)
+    static constexpr int SG = GT / DG;      // token groups (16)
     static constexpr int RPT = C / SG;      // tokens per thread
     static constexpr int QP = 2 * D + 8;    // pitch of row-layout operands (elements)
     static constexpr int TP = C + 8;        // pitch of token-contiguous operands (elements)
+    static constexpr int OP = D + 8;        // pitch of the output staging tile
     static constexpr int NC16 = C / 8;      // 8-element column groups in a token-contiguous row
     static constexpr int RT = C / 32;       // 32-token tiles in a chunk
     static constexpr int KB = C / 16;       // contraction blocks over tokens
     static constexpr int DT = D / 32;       // 32-row tiles of a state
+    static constexpr int NTILE = RT * (RT + 1) / 2;  // score tiles on or below the diagonal
+    static constexpr int XS = (RT == 2) ? NW : CT;   // exchange slots: all wavefronts send (RT = 2) or group 1 only
     static_assert(SG == 16 && (RPT == 2 || RPT == 4), "chunk must be 32 or 64");
-    static_assert(NT == 2 * D, "one thread per (state, feature) column in the gate scan");
+    static_assert(NTILE <= NW, "one score tile per wavefront");
 
-    struct Smem {
-        elem Qs[kFull ? C * QP : 8];    // [token][perm(i*D + d)]  gamma_i scale q 2^{b}
-        elem Ks[kFull ? C * QP : 8];    // [token][perm(i*D + d)]  k 2^{-b}; reused as the o staging tile
-        elem Kt[2 * D * TP];            // [i*D + d][token]        k 2^{bC - b}   (column groups swizzled)
-        elem Vt[D * TP];                // [column][token]         v              (column groups swizzled)
-        elem As[kFull ? C * TP : 8];    // [query token][key token] blended, masked scores
-        float cs[SG * 2 * D];           // gate scan scratch: per token-group totals -> exclusive prefixes (ln)
-        float bC[2 * D];                // log2 decay of the whole chunk, per (state, feature)
-        float dec[2 * D];               // 2^{bC}
-    };
+    // LDS map (byte offsets from the start of the block's LDS allocation)
+    static constexpr uint32_t QS = 0;                                             // [token][i*D + d]  gamma_i scale q 2^{b}
+    static constexpr uint32_t KS = QS + (kFull ? C * QP * ESZ : 0);               // [token][i*D + d]  k 2^{-b}
+    static constexpr uint32_t KT = KS + (kFull ? C * QP * ESZ : 0);               // [i*D + rho(d)][token]  k 2^{bC-b}
+    static constexpr uint32_t VT = KT + 2 * D * TP * ESZ;                         // [column][token]  v
+    static constexpr uint32_t AS = VT + D * TP * ESZ;                             // [query][key] blended masked scores
+    static constexpr uint32_t CS = AS + (kFull ? C * TP * ESZ : 0);               // float [i][token group][d] gate scan
+    static constexpr uint32_t BC = CS + 2 * SG * D * 4;                           // float [2D] log2 chunk decay
+    static constexpr uint32_t DEC = BC + 2 * D * 4;                               // float [2D] 2^{bC}
+    static constexpr uint32_t LDS_BYTES = DEC + 2 * D * 4;
+    static constexpr uint32_t XB = KS;   // partial-output exchange (float4 [XS][4][64]) reuses Ks after the scores
+    static constexpr uint32_t OS = QS;   // output staging tile [token][OP] reuses Qs after the read-out
+    static_assert(!kFull || XS * 4096 <= C * QP * ESZ, "exchange buffer fits in Ks");
+    static_assert(!kFull || C * OP <= C * QP, "staging tile fits in Qs");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 compute unit");
 
     // swizzled offset inside a token-contiguous row: 8-element column group XOR (row / 8)
-    static __device__ __forceinline__ int tcol(int row, int s)
+    static __device__ __forceinline__ uint32_t tcol(uint32_t row, uint32_t s)
     {
         return ((((s >> 3) ^ (row >> 3)) & (NC16 - 1)) << 3) | (s & 7);
     }
+    // Kt row order: feature d sits in row rho(d) (bits 2 and 3 of d swapped).  With this order, accumulator
+    // register j of lane group g in a 32-row state tile holds feature 16*(j/8) + 8*g + (j%8) of the tile:
+    // the 8 registers of one half of the tile are 8 consecutive features, exactly one MFMA input fragment.
 
-    struct RawChunk {
-        Raw8<TIO> q[kFull ? RPT : 1], k[RPT], v[RPT];
-        Raw8<TG> g1[RPT], g2[RPT];
+    // Inputs of one chunk as loaded (unconverted).  The gates of the next chunk are loaded into registers
+    // one phase ahead (they are needed first); q, k and v of the next chunk are only touched (one 4-byte
+    // read per 128-byte line) so that they wait in L2, and are loaded for real when the preparation starts:
+    // holding all of them in registers across the contraction phases costs more registers than there are.
+    struct RawG {
+        Raw8<TG> g[RPT];
     };
-
-    // Per-thread global pointers at (first token this thread owns in the current chunk, feature group).
-    struct Ptrs {
+    struct RawQKV {
+        Raw8<TIO> q[kFull ? RPT : 1], k[RPT];
+        Raw4<TIO> v[RPT];
+    };
+    struct Ptrs {   // uniform base pointers of the current chunk
         const TIO *q, *k, *v;
-        const TG *g1, *g2;
+        const TG *g;
+    };
+    struct PrepAddr {   // per-lane LDS byte addresses used by prepare()
+        uint32_t cs_w, cs_c, bc_w, bc_r, kt_w0, kt_w1, vt_w, qs_w;
     };
 
-    // Loads the tokens of one chunk this thread owns; tokens at or beyond `valid` read as zero
-    // (zero log-gate = no decay, zero k and v = no contribution).
-    static __device__ __forceinline__ void load_chunk(RawChunk &rc, const Ptrs &p, size_t rs, int valid, int sg)
+    // Tokens at or beyond `valid` read as zero (zero log-gate = no decay, zero k and v = no contribution).
+    static __device__ __forceinline__ void load_gates(RawG &rg, const TG *gp, uint32_t rs, int valid, int sg,
+                                                      uint32_t off)
     {
-        if (valid >= C) {
 #pragma unroll
-            for (int j = 0; j < RPT; ++j) {
-                if (kFull) rc.q[j].load(p.q + j * rs);
-                rc.k[j].load(p.k + j * rs);
-                rc.v[j].load(p.v + j * rs);
-                rc.g1[j].load(p.g1 + j * rs);
-                rc.g2[j].load(p.g2 + j * rs);
-            }
-        } else {
+        for (int j = 0; j < RPT; ++j) {
+            if (valid >= C || sg * RPT + j < valid)
+                rg.g[j].load(gp + j * rs, off);
+            else
+                rg.g[j].zero();
+        }
+    }
+    static __device__ __forceinline__ void load_qkv(RawQKV &rc, const Ptrs &p, uint32_t rs, int valid, int sg,
+                                                    uint32_t off, uint32_t voff)
+    {
 #pragma unroll
-            for (int j = 0; j < RPT; ++j) {
-                if (sg * RPT + j < valid) {
-                    if (kFull) rc.q[j].load(p.q + j * rs);
-                    rc.k[j].load(p.k + j * rs);
-                    rc.v[j].load(p.v + j * rs);
-                    rc.g1[j].load(p.g1 + j * rs);
-                    rc.g2[j].load(p.g2 + j * rs);
-                } else {
-                    if (kFull) rc.q[j].zero();
-                    rc.k[j].zero();
-                    rc.v[j].zero();
-                    rc.g1[j].zero();
-                    rc.g2[j].zero();
-                }
+        for (int j = 0; j < RPT; ++j) {
+            if (valid >= C || sg * RPT + j < valid) {
+                rc.k[j].load(p.k + j * rs, off);
+                if (kFull) rc.q[j].load(p.q + j * rs, off);
+                rc.v[j].load(p.v + j * rs, voff);
+            } else {
+                rc.k[j].zero();
+                if (kFull) rc.q[j].zero();
+                rc.v[j].zero();
             }
         }
     }
-
-    // Gate scan and operand preparation for one chunk (all threads).  Ends with the operands in LDS;
-    // the caller places the barrier.  lg[i] = log2|gamma_i scale|, neg[i] = gamma_i scale < 0.
-    static __device__ __forceinline__ void prepare(Smem &sm, const RawChunk &rc, const float (&lg)[2],
-                                                   const bool (&neg)[2], int tid, float &seg_log2_decay)
+    // One 4-byte read per 128-byte line of the q, k, v rows of a chunk (rows below `valid` only).  The
+    // value is returned so that the caller can keep it "in use" until the real loads have been issued.
+    static constexpr int TOUCH_LPR = D * static_cast<int>(sizeof(TIO)) / 128;   // 128-byte lines per token row
+    static constexpr int TOUCH_LPT = C * TOUCH_LPR;                             // lines per tensor and chunk
+    static constexpr int TOUCH_NTEN = kFull ? 3 : 2;
+    static constexpr int TOUCH_N = TOUCH_NTEN * ((TOUCH_LPT + NT - 1) / NT);    // touches per thread
+    struct Touched {
+        uint32_t x[TOUCH_N];
+    };
+    static __device__ __forceinline__ void touch_qkv(Touched &t, const Ptrs &p, uint32_t rs, int valid, int tid)
     {
-        const int dg = tid % DG, sg = tid / DG;
-        float bl[2][RPT][8];  // cumulative natural-log gates over this thread's tokens
+        constexpr int PASSES = (TOUCH_LPT + NT - 1) / NT;
+#pragma unroll
+        for (int ten = 0; ten < TOUCH_NTEN; ++ten) {
+            const TIO *tp = (ten == 0) ? p.k : (ten == 1) ? p.v : p.q;
+#pragma unroll
+            for (int ps = 0; ps < PASSES; ++ps) {
+                // thread tid of pass ps touches line (ps * NT + tid) of every tensor
+                const int l = ps * NT + tid;
+                const int row = l / TOUCH_LPR, part = l % TOUCH_LPR;
+                uint32_t x = 0;
+                if (l < TOUCH_LPT && row < valid) {
+                    const uint32_t boff = (static_cast<uint32_t>(row) * rs) * static_cast<uint32_t>(sizeof(TIO)) + part * 128;
+                    x = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(tp) + boff);
+                }
+                t.x[ten * PASSES + ps] = x;
+            }
+        }
+    }
+    static __device__ __forceinline__ void touch_use(const Touched &t)
+    {
+#pragma unroll
+        for (int i = 0; i < TOUCH_N; ++i) asm volatile("" ::"v"(t.x[i]));
+    }
+
+    // Gate scan and operand preparation for one chunk.  Thread (ip, dg, sg) handles state ip, features
+    // 8dg..8dg+7, tokens RPT*sg.. of q, k and the gate, and columns ip*D/2 + 4dg.. of v.  Ends with the
+    // operands in LDS; the caller places the barrier.  lg = log2|gamma_ip scale|, neg = its sign.
+    // Per-lane LDS byte addresses of prepare().  They are derived inside the chunk loop from an opaque copy
+    // of the thread index: a few integer operations per chunk instead of registers that would stay
+    // occupied during the contraction phases.
+    static __device__ __forceinline__ PrepAddr prep_addr(uint32_t sm, int ip, uint32_t u)
+    {
+        const uint32_t dg = u % DG, sg = u / DG;
+        PrepAddr pa;
+        pa.cs_w = sm + CS + ((ip * SG + sg) * D + dg * 8) * 4;
+        pa.cs_c = sm + CS + (ip * SG * D + u) * 4;
+        pa.bc_w = sm + BC + (ip * D + u) * 4;
+        pa.bc_r = sm + BC + (ip * D + dg * 8) * 4;
+        const uint32_t r0 = ip * D + 16 * (dg >> 1) + 4 * (dg & 1), r1 = r0 + 8;
+        pa.kt_w0 = sm + KT + (r0 * TP + tcol(r0, sg * RPT)) * ESZ;
+        pa.kt_w1 = sm + KT + (r1 * TP + tcol(r1, sg * RPT)) * ESZ;
+        const uint32_t rv = ip * (D / 2) + dg * 4;
+        pa.vt_w = sm + VT + (rv * TP + tcol(rv, sg * RPT)) * ESZ;
+        pa.qs_w = sm + QS + ((sg * RPT) * QP + ip * D + dg * 8) * ESZ;
+        return pa;
+    }
+
+    static __device__ __forceinline__ void prepare(const PrepAddr &pa, const RawG &rg, const RawQKV &rc, float lg,
+                                                   bool neg, bool scans, float &seg_log2_decay, PhaseClock &clk)
+    {
+        float bl[RPT][8];  // cumulative natural-log gates over this thread's tokens
 #pragma unroll
         for (int j = 0; j < RPT; ++j) {
             float g[8];
-            rc.g1[j].unpack(g);
+            rg.g[j].unpack(g);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) bl[0][j][e] = j ? bl[0][j - 1][e] + g[e] : g[e];
-            rc.g2[j].unpack(g);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) bl[1][j][e] = j ? bl[1][j - 1][e] + g[e] : g[e];
+            for (int e = 0; e < 8; ++e) bl[j][e] = j ? bl[j - 1][e] + g[e] : g[e];
         }
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            float *dst = &sm.cs[sg * 2 * D + i * D + dg * 8];
-            *reinterpret_cast<float4 *>(dst) =
-                make_float4(bl[i][RPT - 1][0], bl[i][RPT - 1][1], bl[i][RPT - 1][2], bl[i][RPT - 1][3]);
-            *reinterpret_cast<float4 *>(dst + 4) =
-                make_float4(bl[i][RPT - 1][4], bl[i][RPT - 1][5], bl[i][RPT - 1][6], bl[i][RPT - 1][7]);
-        }
+        lds_st<f32x4>(pa.cs_w, f32x4{bl[RPT - 1][0], bl[RPT - 1][1], bl[RPT - 1][2], bl[RPT - 1][3]});
+        lds_st<f32x4>(pa.cs_w + 16, f32x4{bl[RPT - 1][4], bl[RPT - 1][5], bl[RPT - 1][6], bl[RPT - 1][7]});
+        clk.mark(0);
         lds_barrier();
-        {   // thread c scans column c = (state, feature) over the token groups
+        clk.mark(1);
+        if (scans) {   // thread u < D of a group scans feature u of its state over the token groups
             float t[SG];
 #pragma unroll
-            for (int s = 0; s < SG; ++s) t[s] = sm.cs[s * 2 * D + tid];
+            for (int s = 0; s < SG; ++s) t[s] = lds_ld<float>(pa.cs_c + s * D * 4);
             float run = 0.f;
 #pragma unroll
             for (int s = 0; s < SG; ++s) {
-                sm.cs[s * 2 * D + tid] = run;
+                lds_st<float>(pa.cs_c + s * D * 4, run);
                 run += t[s];
             }
             const float run2 = run * kLog2e;
-            sm.bC[tid] = run2;
-            sm.dec[tid] = __builtin_amdgcn_exp2f(run2);
+            lds_st<float>(pa.bc_w, run2);
+            lds_st<float>(pa.bc_w + (DEC - BC), __builtin_amdgcn_exp2f(run2));
             seg_log2_decay += run2;
         }
         lds_barrier();
+        clk.mark(2);
 
-        float kf[RPT][8];
+        float pre2[8], bc[8];
+        {
+            const f32x4 p0 = lds_ld<f32x4>(pa.cs_w), p1 = lds_ld<f32x4>(pa.cs_w + 16);
+            const f32x4 c0 = lds_ld<f32x4>(pa.bc_r), c1 = lds_ld<f32x4>(pa.bc_r + 16);
 #pragma unroll
-        for (int j = 0; j < RPT; ++j) rc.k[j].unpack(kf[j]);
-
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            float aq[8], ak[8], einv[8];
-            {
-                const float *src = &sm.cs[sg * 2 * D + i * D + dg * 8];
-                const float4 p0 = *reinterpret_cast<const float4 *>(src);
-                const float4 p1 = *reinterpret_cast<const float4 *>(src + 4);
-                const float *sb = &sm.bC[i * D + dg * 8];
-                const float4 c0 = *reinterpret_cast<const float4 *>(sb);
-                const float4 c1 = *reinterpret_cast<const float4 *>(sb + 4);
-                const float pre[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
-                const float bc[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float p2 = pre[e] * kLog2e;
-                    aq[e] = p2 + lg[i];    // exponent of gamma_i scale 2^{b}: add the local part
-                    ak[e] = bc[e] - p2;    // exponent of 2^{bC - b}: subtract the local part
-                    if (kFull) einv[e] = __builtin_amdgcn_exp2f(-bc[e]);
-                }
+            for (int e = 0; e < 4; ++e) {
+                pre2[e] = p0[e] * kLog2e;   // log2 decay accumulated before this thread's first token
+                pre2[4 + e] = p1[e] * kLog2e;
+                bc[e] = c0[e];
+                bc[4 + e] = c1[e];
             }
-            float khat[RPT][8];
-#pragma unroll
-            for (int j = 0; j < RPT; ++j)
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    khat[j][e] = kf[j][e] * __builtin_amdgcn_exp2f(fmaf(bl[i][j][e], -kLog2e, ak[e]));
-            // K^ transposed: row = i*D + feature, RPT consecutive tokens per store
+        }
+        {   // ---- k: K^ = k 2^{bC - b} (token-contiguous) and K~ = K^ 2^{-bC} (row layout) ----
+            float ak[8], einv[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int row = i * D + dg * 8 + e;
-                elem *dst = &sm.Kt[row * TP + tcol(row, sg * RPT)];
-                if (RPT == 4)
-                    A::store4(dst, khat[0][e], khat[1][e], khat[2][e], khat[3][e]);
-                else
-                    A::store2(dst, khat[0][e], khat[1][e]);
+                ak[e] = bc[e] - pre2[e];
+                if (kFull) einv[e] = __builtin_amdgcn_exp2f(-bc[e]);
             }
-            if (kFull) {
-                // position of this thread's 8 features inside a permuted row: two groups of 4
-                const int p0 = i * D + (dg >> 1) * 16 + (dg & 1) * 4;
+            Row8 khat[RPT];
 #pragma unroll
-                for (int j = 0; j < RPT; ++j) {
-                    float qf[8];
-                    rc.q[j].unpack(qf);
-                    float qt[8], kt[8];
+            for (int j = 0; j < RPT; ++j) {
+                float kf[8], kh[8];
+                rc.k[j].unpack(kf);
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        float eq = __builtin_amdgcn_exp2f(fmaf(bl[i][j][e], kLog2e, aq[e]));
-                        if (neg[i]) eq = -eq;
-                        qt[e] = qf[e] * eq;
-                        kt[e] = khat[j][e] * einv[e];
-                    }
-                    const int row = sg * RPT + j;
-                    A::store4(&sm.Qs[row * QP + p0], qt[0], qt[1], qt[2], qt[3]);
-                    A::store4(&sm.Qs[row * QP + p0 + 8], qt[4], qt[5], qt[6], qt[7]);
-                    A::store4(&sm.Ks[row * QP + p0], kt[0], kt[1], kt[2], kt[3]);
-                    A::store4(&sm.Ks[row * QP + p0 + 8], kt[4], kt[5], kt[6], kt[7]);
+                for (int e = 0; e < 8; ++e) kh[e] = kf[e] * __builtin_amdgcn_exp2f(fmaf(bl[j][e], -kLog2e, ak[e]));
+                khat[j] = A::pack_row(kh);
+                if (kFull) {
+                    float kt[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) kt[e] = kh[e] * einv[e];
+                    A::store_row(pa.qs_w + (KS - QS) + j * QP * ESZ, A::pack_row(kt));
                 }
+                __builtin_amdgcn_sched_barrier(0);   // one token at a time: keeps the temporaries of a token short-lived
+            }
+            // rows rho(feature): e = 0..3 -> kt_w0 + e rows, e = 4..7 -> kt_w1 + (e - 4) rows
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                A::template store_tokens<RPT>((e < 4 ? pa.kt_w0 : pa.kt_w1) + (e & 3) * TP * ESZ, khat, e);
+        }
+        if (kFull) {   // ---- q: Q~ = gamma_i scale q 2^{b} (row layout) ----
+#pragma unroll
+            for (int j = 0; j < RPT; ++j) {
+                float qf[8], qt[8];
+                rc.q[j].unpack(qf);
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    qt[e] = qf[e] * __builtin_amdgcn_exp2f(fmaf(bl[j][e], kLog2e, pre2[e] + lg));
+                if (neg) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) qt[e] = -qt[e];
+                }
+                A::store_row(pa.qs_w + j * QP * ESZ, A::pack_row(qt));
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
-        // V transposed
+        // V transposed: columns ip*D/2 + 4dg .. + 3
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int row = dg * 8 + e;
-            store_v_tokens<RPT>(&sm.Vt[row * TP + tcol(row, sg * RPT)], rc.v, e);
-        }
+        for (int e = 0; e < 4; ++e) store_v_tokens<RPT>(pa.vt_w + e * TP * ESZ, rc.v, e);
     }
 
-    // accumulator register j of a 32x32 tile holds tile row 8*(j/4) + 4*g + (j%4), tile column lane%32
-    static __device__ __forceinline__ int acc_row(int j, int g) { return 8 * (j >> 2) + 4 * g + (j & 3); }
-
-    static __device__ void run(const PrefillArgs &a, Smem &sm)
+    static __device__ void run(const PrefillArgs &a, uint32_t sm)
     {
         const int tid = threadIdx.x;
-        const int lane = tid & 63, wave = tid >> 6;
+        const int lane = tid & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform, kept in scalar registers
         const int ln = lane & 31, g = lane >> 5;
-        const int dg = tid % DG, sg = tid / DG;
+        const int ip = wave / CT;                // state this wavefront prepares and owns
+        const int ct = wave % CT;                // column tile it owns in the contractions
+        const int u = tid - ip * GT;             // index inside the group
+        const int dg = u % DG, sg = u / DG;
 
         const int nseg = kFull ? a.P : a.P - 1;
         const int bh = blockIdx.x / nseg;
@@ -445,231 +630,321 @@ struct Kern {
 
         const int64_t t0 = static_cast<int64_t>(p) * a.seg_tokens;
         const int64_t t1 = (t0 + a.seg_tokens < a.T) ? t0 + a.seg_tokens : a.T;
-        const size_t rs = static_cast<size_t>(a.H) * D;
-        // element offset of (b, first token this thread owns, h, feature group)
-        const size_t off0 = (static_cast<size_t>(bidx) * a.T * a.H + h) * D +
-                            static_cast<size_t>(t0 + sg * RPT) * rs + dg * 8;
+        const uint32_t rs = static_cast<uint32_t>(a.H) * D;   // elements between consecutive tokens
+        // uniform element offset of (b, t0, h, 0); per-lane offsets are 32-bit
+        const size_t seg0 = (static_cast<size_t>(bidx) * a.T * a.H + h) * D + static_cast<size_t>(t0) * rs;
+        // per-lane element offsets of the global accesses; evaluated from an opaque copy of the thread index
+        // where they are used, so that they do not stay in registers across the other phases
+        auto lane_off = [&](uint32_t uo) -> uint32_t { return (uo / DG) * RPT * rs + (uo % DG) * 8; };
+        auto lane_voff = [&](uint32_t uo) -> uint32_t { return (uo / DG) * RPT * rs + ip * (D / 2) + (uo % DG) * 4; };
 
         const float gm = a.gamma_per_head ? a.gamma_per_head[h] : a.gamma;
-        const float gsv[2] = {gm * a.scale, (1.0f - gm) * a.scale};
-        const float lg[2] = {__builtin_amdgcn_logf(fabsf(gsv[0])), __builtin_amdgcn_logf(fabsf(gsv[1]))};
-        const bool neg[2] = {gsv[0] < 0.f, gsv[1] < 0.f};
+        const float gsv = (ip ? 1.0f - gm : gm) * a.scale;
+        const float lg = __builtin_amdgcn_logf(fabsf(gsv));
+        const bool neg = gsv < 0.f;
 
-        // ---- state accumulators: tile (i, dt) covers rows 32dt..32dt+31 of state i, columns 32*wave.. ----
-        f32x16 acc[2][DT];
-        const int col = 32 * wave + ln;
+        // ---- state accumulators: tile dt covers Kt rows 32dt..32dt+31 of state ip, columns 32*ct.. ----
+        // register j of lane (ln, g) holds state element (feature 32dt + 16(j/8) + 8g + j%8, column 32ct + ln)
+        f32x16 acc[DT];
+        const uint32_t sbase = static_cast<uint32_t>(8 * g) * D + 32 * ct + ln;  // lane part of the state offset
         if (kFull) {
-            const float *src1 = (a.P > 1) ? a.ws_state + ((static_cast<size_t>(p) * BH + bh) * 2 + 0) * D * D
-                                          : a.S1 + static_cast<size_t>(bh) * D * D;
-            const float *src2 = (a.P > 1) ? a.ws_state + ((static_cast<size_t>(p) * BH + bh) * 2 + 1) * D * D
-                                          : a.S2 + static_cast<size_t>(bh) * D * D;
+            const float *src = (a.P > 1) ? a.ws_state + ((static_cast<size_t>(p) * BH + bh) * 2 + ip) * D * D
+                                         : (ip ? a.S2 : a.S1) + static_cast<size_t>(bh) * D * D;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int row = 32 * dt + acc_row(j, g);
-                    acc[0][dt][j] = src1[static_cast<size_t>(row) * D + col];
-                    acc[1][dt][j] = src2[static_cast<size_t>(row) * D + col];
-                }
+                for (int j = 0; j < 16; ++j) acc[dt][j] = src[sbase + (32 * dt + 16 * (j >> 3) + (j & 7)) * D];
         } else {
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) acc[0][dt][j] = acc[1][dt][j] = 0.f;
+                for (int j = 0; j < 16; ++j) acc[dt][j] = 0.f;
         }
 
-        float seg_decay = 0.f;  // thread tid: log2 of the segment decay of (state, feature) column tid
+        const int own = (RT == 2) ? ip : 0;   // query tile this wavefront finishes
+        // score tile of wavefronts 0..NTILE-1: RT = 1: (0,0); RT = 2: 0 -> (0,0), 1 -> (0,1), 2 -> (1,1)
+        const int sc_ts = (RT == 2 && wave == 2) ? 1 : 0;
+        const int sc_tr = (RT == 2 && wave >= 1) ? 1 : 0;
+
+        float seg_decay = 0.f;  // threads u < D: log2 of the segment decay of feature u of state ip
         Ptrs ptr;
-        ptr.q = static_cast<const TIO *>(a.q) + off0;
-        ptr.k = static_cast<const TIO *>(a.k) + off0;
-        ptr.v = static_cast<const TIO *>(a.v) + off0;
-        ptr.g1 = static_cast<const TG *>(a.g1) + off0;
-        ptr.g2 = static_cast<const TG *>(a.g2) + off0;
-        TIO *optr = static_cast<TIO *>(a.o) + off0;
+        ptr.q = static_cast<const TIO *>(a.q) + seg0;
+        ptr.k = static_cast<const TIO *>(a.k) + seg0;
+        ptr.g = static_cast<const TG *>(ip ? a.g2 : a.g1) + seg0;
+        ptr.v = static_cast<const TIO *>(a.v) + seg0;
+        TIO *optr = static_cast<TIO *>(a.o) + seg0;
         const size_t cstep = static_cast<size_t>(C) * rs;
 
-        RawChunk rc;
-        {
-            const int64_t left = t1 - t0;
-            load_chunk(rc, ptr, rs, left >= C ? C : static_cast<int>(left), sg);
+        if (kFull && RT == 2) {
+            // scores of keys 32..63 against queries 0..31 are in the future of every query: that block of As is
+            // never computed; it is cleared once so that the read-out can run over all key blocks unconditionally
+            for (int i = tid; i < 32 * 32 / 8; i += NT) {
+                const int r = i / 4, c8 = i % 4;
+                const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                A::store_row(sm + AS + (r * TP + 32 + 8 * c8) * ESZ, A::pack_row(z));
+            }
         }
+        RawG rg;
+        int valid = (t1 - t0 >= C) ? C : static_cast<int>(t1 - t0);   // tokens of the current chunk
+        load_gates(rg, ptr.g, rs, valid, sg, lane_off(u));
+        Touched touched;
+#pragma unroll
+        for (int i = 0; i < TOUCH_N; ++i) touched.x[i] = 0;
+        PhaseClock clk;
+        clk.start();
 
         for (int64_t tc = t0; tc < t1; tc += C) {
-            prepare(sm, rc, lg, neg, tid, seg_decay);
-            ptr.q += cstep; ptr.k += cstep; ptr.v += cstep; ptr.g1 += cstep; ptr.g2 += cstep;
-            if (tc + C < t1) {  // next chunk: in flight during the contractions
-                const int64_t left = t1 - (tc + C);
-                load_chunk(rc, ptr, rs, left >= C ? C : static_cast<int>(left), sg);
+            {
+                RawQKV rc;
+                const uint32_t uo = opaque(static_cast<uint32_t>(u));
+                load_qkv(rc, ptr, rs, valid, sg, lane_off(uo), lane_voff(uo));
+                touch_use(touched);   // the touches of this chunk's lines were issued before these loads
+                const PrepAddr pa = prep_addr(sm, ip, opaque(static_cast<uint32_t>(u)));
+                prepare(pa, rg, rc, lg, neg, u < D, seg_decay, clk);
             }
+            clk.mark(3);
             lds_barrier();
+            clk.mark(4);
 
-            Frag sfr[kFull ? 2 : 1][kFull ? DT : 1][2];
-            if (kFull) {
+            // ---- per-lane LDS addresses of the contraction phases (derived per chunk, see prep_addr) ----
+            const uint32_t lq = opaque(static_cast<uint32_t>(lane));
+            const uint32_t lnq = lq & 31, gq = lq >> 5;
+            const uint32_t q_own = sm + QS + ((32 * own + lnq) * QP + ip * D + 8 * gq) * ESZ;
+            const uint32_t q_oth = sm + QS + ((32 * (RT - 1 - own) + lnq) * QP + ip * D + 8 * gq) * ESZ;
+            const uint32_t a_own = sm + AS + ((32 * own + lnq) * TP + 8 * gq) * ESZ;
+            uint32_t vt_r[KB], kt_r[KB];   // swizzled token blocks of this lane's Vt row / first Kt row
+            {
+                const uint32_t vrow = 32 * ct + lnq, krow = ip * D + lnq;
+#pragma unroll
+                for (int kb = 0; kb < KB; ++kb) {
+                    vt_r[kb] = sm + VT + (vrow * TP + tcol(vrow, 16 * kb + 8 * gq)) * ESZ;
+                    kt_r[kb] = sm + KT + (krow * TP + tcol(krow, 16 * kb + 8 * gq)) * ESZ;
+                }
+            }
+            const uint32_t dec_r = sm + DEC + (ip * D + 8 * gq) * 4;
+
+            Frag sfr[kFull ? DT : 1][2];
+            if (kFull && wave < NTILE) {
                 // ---- scores, transposed: tile (ts, tr) holds S^T[s][r] for key tile ts <= query tile tr ----
-                constexpr int NTILE = RT * (RT + 1) / 2;
+                f32x16 sc;
 #pragma unroll
-                for (int tt = 0; tt < NTILE; ++tt) {
-                    if (tt % NW != wave) continue;
-                    // enumerate (ts, tr), ts <= tr: RT = 1: (0,0); RT = 2: (0,0) (0,1) (1,1)
-                    const int ts = (RT == 2 && tt == 2) ? 1 : 0;
-                    const int tr = (RT == 2 && tt >= 1) ? 1 : 0;
-                    f32x16 sc;
+                for (int j = 0; j < 16; ++j) sc[j] = 0.f;
+                constexpr int NK = 2 * D / 16;
+                // addresses used once per chunk are derived here from a per-iteration opaque copy of the lane
+                // id, so that they do not occupy registers for the whole loop
+                const uint32_t l2 = opaque(static_cast<uint32_t>(lane));
+                const uint32_t lrow = (l2 & 31) * (QP * ESZ) + (l2 >> 5) * (8 * ESZ);
+                const uint32_t sc_k = sm + KS + 32 * sc_ts * QP * ESZ + lrow;
+                const uint32_t sc_q = sm + QS + 32 * sc_tr * QP * ESZ + lrow;
+                const uint32_t sc_w =
+                    sm + AS + (32 * sc_tr * TP + 32 * sc_ts) * ESZ + (l2 & 31) * (TP * ESZ) + (l2 >> 5) * (4 * ESZ);
+                {
+                    Frag held;   // the Ks fragment of a step waits here for its Qs partner
+                    pipelined_steps<2 * NK, 8, A>(
+                        [&](int s) -> uint32_t { return ((s & 1) ? sc_q : sc_k) + 16 * (s >> 1) * ESZ; },
+                        [&](int s, const Frag &f) {
+                            if ((s & 1) == 0)
+                                held = f;
+                            else
+                                A::mma(sc, held, f);
+                        });
+                    // requested order: the fragment pairs of 4 steps are read ahead of the MFMAs
+                    constexpr int RD = ESZ == 2 ? 1 : 2, MM = ESZ == 2 ? 1 : 8;
+                    __builtin_amdgcn_sched_group_barrier(0x100, 8 * RD, 0);
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) sc[j] = 0.f;
-                    const elem *kp = &sm.Ks[(32 * ts + ln) * QP + 8 * g];
-                    const elem *qp = &sm.Qs[(32 * tr + ln) * QP + 8 * g];
-#pragma unroll
-                    for (int kb = 0; kb < 2 * D / 16; ++kb) {
-                        const Frag fa = A::load_frag(kp + 16 * kb);
-                        const Frag fb = A::load_frag(qp + 16 * kb);
-                        A::mma(sc, fa, fb);
+                    for (int i = 0; i < NK - 4; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, MM, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 2 * RD, 0);
                     }
-                    const int r = 32 * tr + ln;
+                    __builtin_amdgcn_sched_group_barrier(0x008, 4 * MM, 0);
+                }
+                // keep key <= query: key = 32 ts + 8 jb + 4 g + e, query = 32 tr + ln
+                const int dq = 32 * (sc_tr - sc_ts) + ln - 4 * g;
 #pragma unroll
-                    for (int jb = 0; jb < 4; ++jb) {
-                        const int s0 = 32 * ts + 8 * jb + 4 * g;
-                        float x[4];
+                for (int jb = 0; jb < 4; ++jb) {
+                    float x[4];
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) x[e] = (s0 + e <= r) ? sc[4 * jb + e] : 0.f;
-                        A::store4(&sm.As[r * TP + s0], x[0], x[1], x[2], x[3]);
-                    }
+                    for (int e = 0; e < 4; ++e) x[e] = (8 * jb + e <= dq) ? sc[4 * jb + e] : 0.f;
+                    A::store4(sc_w + 8 * jb * ESZ, x[0], x[1], x[2], x[3]);
                 }
             }
             // ---- carried state: take its input fragments for the read-out, then decay its rows ----
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    if (kFull) {
-                        sfr[i][dt][0] = A::from_acc(acc[i][dt], 0);
-                        sfr[i][dt][1] = A::from_acc(acc[i][dt], 1);
-                    }
-#pragma unroll
-                    for (int jb = 0; jb < 4; ++jb) {
-                        const float4 dd = *reinterpret_cast<const float4 *>(&sm.dec[i * D + 32 * dt + 8 * jb + 4 * g]);
-                        acc[i][dt][4 * jb + 0] *= dd.x;
-                        acc[i][dt][4 * jb + 1] *= dd.y;
-                        acc[i][dt][4 * jb + 2] *= dd.z;
-                        acc[i][dt][4 * jb + 3] *= dd.w;
-                    }
+            for (int dt = 0; dt < DT; ++dt) {
+                if (kFull) {
+                    sfr[dt][0] = A::from_acc(acc[dt], 0);
+                    sfr[dt][1] = A::from_acc(acc[dt], 1);
                 }
+#pragma unroll
+                for (int jb = 0; jb < 4; ++jb) {
+                    const f32x4 dd = lds_ld<f32x4>(dec_r + (32 * dt + 16 * (jb >> 1) + 4 * (jb & 1)) * 4);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc[dt][4 * jb + e] *= dd[e];
+                }
+            }
+            clk.mark(5);
             if (kFull) lds_barrier();
+            clk.mark(6);
 
             // ---- V fragments of this wavefront's columns (input of both the output and the update) ----
             Frag vf[KB];
-            {
-                const int row = 32 * wave + ln;
 #pragma unroll
-                for (int kb = 0; kb < KB; ++kb) vf[kb] = A::load_frag(&sm.Vt[row * TP + tcol(row, 16 * kb + 8 * g)]);
-            }
+            for (int kb = 0; kb < KB; ++kb) vf[kb] = A::load_frag(vt_r[kb]);
 
+            // o_own: the query tile this wavefront finishes; o_oth: the tile the other group finishes (RT = 2)
+            f32x16 o_own, o_oth;
             if (kFull) {
-                // ---- output, transposed: tile tr holds o^T[column][query token] ----
-                f32x16 oacc[RT];
+                // ---- partial output, transposed (o^T[column][query token]), summed over the features of
+                //      state ip; the other group adds its state ----
 #pragma unroll
-                for (int tr = 0; tr < RT; ++tr)
+                for (int j = 0; j < 16; ++j) o_own[j] = o_oth[j] = 0.f;
+                {
+                    constexpr int NS = DT * 2;   // steps over (dt, half): 16 features each
+                    Frag f1 = A::load_frag(q_own), f2;
+                    if (RT == 2) f2 = A::load_frag(q_oth);
 #pragma unroll
-                    for (int j = 0; j < 16; ++j) oacc[tr][j] = 0.f;
-                // inside the chunk: sum over key tokens (blocks wholly in the future of a query tile are zero)
-#pragma unroll
-                for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                    for (int tr = 0; tr < RT; ++tr) {
-                        if (16 * kb > 32 * tr + 31) continue;
-                        const Frag fb = A::load_frag(&sm.As[(32 * tr + ln) * TP + 16 * kb + 8 * g]);
-                        A::mma(oacc[tr], vf[kb], fb);
-                    }
-                // carried state: the fragments taken from the accumulators are the other input
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                        for (int half = 0; half < 2; ++half) {
-                            const int kpos = i * D + 32 * dt + 16 * half + 8 * g;
-#pragma unroll
-                            for (int tr = 0; tr < RT; ++tr) {
-                                const Frag fb = A::load_frag(&sm.Qs[(32 * tr + ln) * QP + kpos]);
-                                A::mma(oacc[tr], sfr[i][dt][half], fb);
-                            }
+                    for (int s = 0; s < NS; ++s) {
+                        const Frag c1 = f1, c2 = f2;
+                        if (s + 1 < NS) {
+                            f1 = A::load_frag(q_own + 16 * (s + 1) * ESZ);
+                            if (RT == 2) f2 = A::load_frag(q_oth + 16 * (s + 1) * ESZ);
                         }
-                // stage o (Ks is free since the scores barrier): Os[token][column], pitch D + 8
-                elem *Os = sm.Ks;
-#pragma unroll
-                for (int tr = 0; tr < RT; ++tr)
-#pragma unroll
-                    for (int jb = 0; jb < 4; ++jb) {
-                        const int c0 = 32 * wave + 8 * jb + 4 * g;
-                        A::store4(&Os[(32 * tr + ln) * (D + 8) + c0], oacc[tr][4 * jb + 0], oacc[tr][4 * jb + 1],
-                                  oacc[tr][4 * jb + 2], oacc[tr][4 * jb + 3]);
+                        A::mma(o_own, sfr[s >> 1][s & 1], c1);
+                        if (RT == 2) A::mma(o_oth, sfr[s >> 1][s & 1], c2);
                     }
+                }
+                // inside the chunk (key blocks in the future of the own query tile hold zeros)
+                if (RT == 2 || ip == 0) {
+#pragma unroll
+                    for (int kb = 0; kb < KB; ++kb) A::mma(o_own, vf[kb], A::load_frag(a_own + 16 * kb * ESZ));
+                }
+                // hand over what the other group finishes: X[slot][jb][lane] (float4 units), in Ks
+                const uint32_t x_w = sm + XB + (RT == 2 ? wave : ct) * 4096 + opaque(static_cast<uint32_t>(lane)) * 16;
+                if (RT == 2) {
+#pragma unroll
+                    for (int jb = 0; jb < 4; ++jb)
+                        lds_st<f32x4>(x_w + jb * 1024,
+                                      f32x4{o_oth[4 * jb], o_oth[4 * jb + 1], o_oth[4 * jb + 2], o_oth[4 * jb + 3]});
+                } else if (ip == 1) {
+#pragma unroll
+                    for (int jb = 0; jb < 4; ++jb)
+                        lds_st<f32x4>(x_w + jb * 1024,
+                                      f32x4{o_own[4 * jb], o_own[4 * jb + 1], o_own[4 * jb + 2], o_own[4 * jb + 3]});
+                }
+                if (RT == 2) {
+                    // requested order for this region: LDS reads run 6 fragments ahead of the MFMAs
+                    constexpr int RD = ESZ == 2 ? 1 : 2, MM = ESZ == 2 ? 1 : 8;
+                    constexpr int NRD = KB + DT * 2 * RT + KB, NMM = DT * 2 * RT + KB;
+                    __builtin_amdgcn_sched_group_barrier(0x100, 6 * RD, 0);
+#pragma unroll
+                    for (int i = 0; i < NRD - 6; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, MM, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, (NMM - (NRD - 6)) * MM, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x200, 4, 0);
+                }
             }
 
-            // ---- state update: add K^^T V to the decayed state ----
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) {
-                        const int row = i * D + 32 * dt + ln;
-                        const Frag fa = A::load_frag(&sm.Kt[row * TP + tcol(row, 16 * kb + 8 * g)]);
-                        A::mma(acc[i][dt], fa, vf[kb]);
-                    }
-
+            clk.mark(7);
             if (kFull) {
                 lds_barrier();
-                // ---- coalesced store of the staged output rows ----
-                const elem *Os = sm.Ks;
+                clk.mark(8);
+                // ---- finish the own output tile: own part + the other group's, staged in Qs ----
+                if (RT == 2 || ip == 0) {
+                    const uint32_t l2 = opaque(static_cast<uint32_t>(lane));
+                    const uint32_t x_r = sm + XB + (RT == 2 ? (1 - ip) * CT + ct : ct) * 4096 + l2 * 16;
+                    const uint32_t os_w =
+                        sm + OS + (32 * own * OP + 32 * ct) * ESZ + (l2 & 31) * (OP * ESZ) + (l2 >> 5) * (4 * ESZ);
+#pragma unroll
+                    for (int jb = 0; jb < 4; ++jb) {
+                        const f32x4 x = lds_ld<f32x4>(x_r + jb * 1024);
+                        A::store4(os_w + 8 * jb * ESZ, o_own[4 * jb] + x[0], o_own[4 * jb + 1] + x[1],
+                                  o_own[4 * jb + 2] + x[2], o_own[4 * jb + 3] + x[3]);
+                    }
+                }
+            }
+            clk.mark(9);
+            // ---- next chunk's inputs: gates into registers, q/k/v lines into L2; in flight during the update
+            //      and the output store ----
+            ptr.q += cstep; ptr.k += cstep; ptr.v += cstep; ptr.g += cstep;
+            if (tc + C < t1) {
+                const int64_t left = t1 - (tc + C);
+                valid = left >= C ? C : static_cast<int>(left);
+                load_gates(rg, ptr.g, rs, valid, sg, lane_off(opaque(static_cast<uint32_t>(u))));
+                touch_qkv(touched, ptr, rs, valid, opaque(static_cast<uint32_t>(tid)));
+            }
+            // ---- state update: add K^^T V to the decayed state.  Tile dt starts 32 dt rows further; the
+            //      swizzle of odd tiles is that of even tiles with token blocks kb and kb^2 exchanged ----
+            {
+                constexpr int NS = KB * DT;
+                auto kaddr = [&](int s) -> uint32_t {
+                    const int dt = s % DT, kb = s / DT;
+                    const int sw = (NC16 == 8) ? (kb ^ (2 * (dt & 1))) : kb;
+                    return kt_r[sw] + 32 * dt * TP * ESZ;
+                };
+                pipelined_steps<NS, 4, A>(kaddr, [&](int s, const Frag &f) { A::mma(acc[s % DT], f, vf[s / DT]); });
+                // requested instruction order for this region: LDS reads run 4 fragments ahead of the MFMAs
+                constexpr int RD = ESZ == 2 ? 1 : 2;   // ds_read_b128 per fragment
+                constexpr int MM = ESZ == 2 ? 1 : 8;   // MFMA instructions per fragment pair
+                __builtin_amdgcn_sched_group_barrier(0x100, 4 * RD, 0);
+#pragma unroll
+                for (int s = 0; s < NS - 4; ++s) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, MM, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 4 * MM, 0);
+            }
+            clk.mark(10);
+            if (kFull) {
+                lds_barrier();
+                // ---- coalesced store of the staged output rows, 32 rows per pass ----
+                const uint32_t t2 = opaque(static_cast<uint32_t>(tid));
+                const uint32_t os_r = sm + OS + (t2 / DG) * (OP * ESZ) + (t2 % DG) * (8 * ESZ);
+                const uint32_t ooff = (t2 / DG) * rs + (t2 % DG) * 8;   // 32 rows per pass
                 const int64_t left = t1 - tc;
 #pragma unroll
-                for (int j = 0; j < RPT; ++j) {
-                    const int r = sg * RPT + j;
-                    if (r < left) store8_global(optr + j * rs, &Os[r * (D + 8) + dg * 8]);
+                for (int ps = 0; ps < RT; ++ps) {
+                    if (32 * ps + static_cast<int>(t2 / DG) < left)
+                        store8_global(optr + static_cast<size_t>(32 * ps) * rs, ooff, os_r + 32 * ps * OP * ESZ);
                 }
                 optr += cstep;
+                clk.mark(11);
             }
             // The next prepare() writes Qs/Ks/Kt/Vt/dec only after its first scan barrier, which no
             // wavefront passes before every wavefront has finished the LDS reads above.
         }
 
+#ifdef DSLA_PHASE_CLOCKS
+        if (kFull) clk.flush(a.dbg);
+#endif
         // ---- write the state out ----
+        float *dst = nullptr;
         if (kFull) {
-            if (p == a.P - 1) {
-                float *d1 = a.S1 + static_cast<size_t>(bh) * D * D;
-                float *d2 = a.S2 + static_cast<size_t>(bh) * D * D;
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                    for (int j = 0; j < 16; ++j) {
-                        const int row = 32 * dt + acc_row(j, g);
-                        d1[static_cast<size_t>(row) * D + col] = acc[0][dt][j];
-                        d2[static_cast<size_t>(row) * D + col] = acc[1][dt][j];
-                    }
-            }
+            if (p == a.P - 1) dst = (ip ? a.S2 : a.S1) + static_cast<size_t>(bh) * D * D;
         } else {
             // contribution of segment p goes to state slot p+1; its log2 decay to decay slot p
-            float *d1 = a.ws_state + ((static_cast<size_t>(p + 1) * BH + bh) * 2 + 0) * D * D;
-            float *d2 = d1 + static_cast<size_t>(D) * D;
+            dst = a.ws_state + ((static_cast<size_t>(p + 1) * BH + bh) * 2 + ip) * D * D;
+            if (u < D) a.ws_decay[(static_cast<size_t>(p) * BH + bh) * 2 * D + ip * D + u] = seg_decay;
+        }
+        if (dst) {
+            // recomputed on purpose (opaque): keeping the 16 DT offsets of the initial load alive across the
+            // chunk loop would cost that many registers
+            const uint32_t sb = opaque(static_cast<uint32_t>(8 * g) * D + 32 * ct + ln);
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int row = 32 * dt + acc_row(j, g);
-                    d1[static_cast<size_t>(row) * D + col] = acc[0][dt][j];
-                    d2[static_cast<size_t>(row) * D + col] = acc[1][dt][j];
-                }
-            a.ws_decay[(static_cast<size_t>(p) * BH + bh) * 2 * D + tid] = seg_decay;
+                for (int j = 0; j < 16; ++j) dst[sb + (32 * dt + 16 * (j >> 3) + (j & 7)) * D] = acc[dt][j];
         }
     }
 };
 
 template <int D, int C, class TIO, class TG, bool kFull>
-__global__ __launch_bounds__(2 * D) void prefill_kernel(PrefillArgs a)
+__global__ __launch_bounds__(4 * D) void prefill_kernel(PrefillArgs a)
 {
     using K = Kern<D, C, TIO, TG, kFull>;
-    __shared__ __attribute__((aligned(16))) typename K::Smem sm;
-    K::run(a, sm);
+    __shared__ __attribute__((aligned(16))) char smem[K::LDS_BYTES];
+    K::run(a, lds_addr_of(smem));
 }
 
 // Elementwise scan over segments: slot 0 <- caller's state; slot p+1 <- 2^{decay_p} * slot p + U_p,
@@ -714,7 +989,7 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
     if (plan.segments > 1) {
         {
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_STATE, stream);
-            hipLaunchKernelGGL((prefill_kernel<D, C, TIO, TG, false>), dim3(BH * (plan.segments - 1)), dim3(2 * D), 0,
+            hipLaunchKernelGGL((prefill_kernel<D, C, TIO, TG, false>), dim3(BH * (plan.segments - 1)), dim3(4 * D), 0,
                                stream, a);
             err = hipGetLastError();
         }
@@ -728,9 +1003,34 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
         }
         if (err != hipSuccess) return err;
     }
-    ProfileScope ps(DSLA_KERNEL_PREFILL_CHUNK_LOOP, stream);
-    hipLaunchKernelGGL((prefill_kernel<D, C, TIO, TG, true>), dim3(BH * plan.segments), dim3(2 * D), 0, stream, a);
-    return hipGetLastError();
+#ifdef DSLA_PHASE_CLOCKS
+    static long long *dbg = nullptr;
+    if (!dbg) (void)hipMalloc(&dbg, 16 * 12 * sizeof(long long));
+    (void)hipMemsetAsync(dbg, 0, 16 * 12 * sizeof(long long), stream);
+    a.dbg = dbg;
+#endif
+    {
+        ProfileScope ps(DSLA_KERNEL_PREFILL_CHUNK_LOOP, stream);
+        hipLaunchKernelGGL((prefill_kernel<D, C, TIO, TG, true>), dim3(BH * plan.segments), dim3(4 * D), 0, stream, a);
+    }
+    err = hipGetLastError();
+#ifdef DSLA_PHASE_CLOCKS
+    {
+        long long h[16 * 12];
+        (void)hipStreamSynchronize(stream);
+        (void)hipMemcpy(h, dbg, sizeof(h), hipMemcpyDeviceToHost);
+        static const char *names[12] = {"prep:cumsum", "prep:B1", "prep:scan+B2", "prep:operands", "loads+B3", "scores+state",
+                                        "B4", "output", "B5", "finish", "loads+update", "B6+store"};
+        for (int w = 0; w < 4 * D / 64; ++w) {
+            long long tot = 0;
+            for (int n = 0; n < 12; ++n) tot += h[w * 12 + n];
+            fprintf(stderr, "[phase clocks] wave %d total %lld:", w, tot);
+            for (int n = 0; n < 12; ++n) fprintf(stderr, " %s=%lld", names[n], h[w * 12 + n]);
+            fprintf(stderr, "\n");
+        }
+    }
+#endif
+    return err;
 }
 
 template <int D, int C, class TIO>
