@@ -493,9 +493,6 @@ struct Kern {
         for (int i = 0; i < TOUCH_N; ++i) asm volatile("" ::"v"(t.x[i]));
     }
 
-    // Gate scan and operand preparation for one chunk.  Thread (ip, dg, sg) handles state ip, features
-    // 8dg..8dg+7, tokens RPT*sg.. of q, k and the gate, and columns ip*D/2 + 4dg.. of v.  Ends with the
-    // operands in LDS; the caller places the barrier.  lg = log2|gamma_ip scale|, neg = its sign.
     // Per-lane LDS byte addresses of prepare().  They are derived inside the chunk loop from an opaque copy
     // of the thread index: a few integer operations per chunk instead of registers that would stay
     // occupied during the contraction phases.
@@ -516,10 +513,11 @@ struct Kern {
         return pa;
     }
 
-    static __device__ __forceinline__ void prepare(const PrepAddr &pa, const RawG &rg, const RawQKV &rc, float lg,
-                                                   bool neg, bool scans, float &seg_log2_decay, PhaseClock &clk)
+    // Cumulative natural-log gates over this thread's tokens, and the thread's total into the scan scratch.
+    // Runs at the end of the previous chunk's iteration (before its output store), so that the gate
+    // registers are consumed there and no load is waited for behind a store at the top of the loop.
+    static __device__ __forceinline__ void gate_sums(float (&bl)[RPT][8], const RawG &rg, uint32_t cs_w)
     {
-        float bl[RPT][8];  // cumulative natural-log gates over this thread's tokens
 #pragma unroll
         for (int j = 0; j < RPT; ++j) {
             float g[8];
@@ -527,8 +525,17 @@ struct Kern {
 #pragma unroll
             for (int e = 0; e < 8; ++e) bl[j][e] = j ? bl[j - 1][e] + g[e] : g[e];
         }
-        lds_st<f32x4>(pa.cs_w, f32x4{bl[RPT - 1][0], bl[RPT - 1][1], bl[RPT - 1][2], bl[RPT - 1][3]});
-        lds_st<f32x4>(pa.cs_w + 16, f32x4{bl[RPT - 1][4], bl[RPT - 1][5], bl[RPT - 1][6], bl[RPT - 1][7]});
+        lds_st<f32x4>(cs_w, f32x4{bl[RPT - 1][0], bl[RPT - 1][1], bl[RPT - 1][2], bl[RPT - 1][3]});
+        lds_st<f32x4>(cs_w + 16, f32x4{bl[RPT - 1][4], bl[RPT - 1][5], bl[RPT - 1][6], bl[RPT - 1][7]});
+    }
+
+    // Gate scan and operand preparation for one chunk.  Thread (ip, dg, sg) handles state ip, features
+    // 8dg..8dg+7, tokens RPT*sg.. of q, k and the gate, and columns ip*D/2 + 4dg.. of v.  Ends with the
+    // operands in LDS; the caller places the barrier.  lg = log2|gamma_ip scale|, neg = its sign.
+    static __device__ __forceinline__ void prepare(const PrepAddr &pa, const float (&bl)[RPT][8], const RawQKV &rc,
+                                                   float lg, bool neg, bool scans, float &seg_log2_decay,
+                                                   PhaseClock &clk)
+    {
         clk.mark(0);
         lds_barrier();
         clk.mark(1);
@@ -690,21 +697,35 @@ struct Kern {
         Touched touched;
 #pragma unroll
         for (int i = 0; i < TOUCH_N; ++i) touched.x[i] = 0;
+        float bl[RPT][8];   // cumulative log-gates of the current chunk (computed one iteration ahead)
+        gate_sums(bl, rg, sm + CS + ((ip * SG + sg) * D + dg * 8) * 4);
         PhaseClock clk;
         clk.start();
 
         for (int64_t tc = t0; tc < t1; tc += C) {
+            const bool has_next = tc + C < t1;
+            const int64_t left_next = t1 - (tc + C);
+            const int valid_next = has_next ? (left_next >= C ? C : static_cast<int>(left_next)) : 0;
             {
+                // ---- this chunk's q/k/v: their lines wait in L2; first needed after the gate scan ----
                 RawQKV rc;
                 const uint32_t uo = opaque(static_cast<uint32_t>(u));
                 load_qkv(rc, ptr, rs, valid, sg, lane_off(uo), lane_voff(uo));
-                touch_use(touched);   // the touches of this chunk's lines were issued before these loads
-                const PrepAddr pa = prep_addr(sm, ip, opaque(static_cast<uint32_t>(u)));
-                prepare(pa, rg, rc, lg, neg, u < D, seg_decay, clk);
+                const PrepAddr pa = prep_addr(sm, ip, uo);
+                prepare(pa, bl, rc, lg, neg, u < D, seg_decay, clk);
             }
             clk.mark(3);
             lds_barrier();
             clk.mark(4);
+            {
+                // ---- next chunk: gates into registers (used at the end of this iteration) and one touch per
+                //      line of its q/k/v rows, issued here where the memory pipeline is otherwise idle.  Past
+                //      the end of the segment valid_next is 0: nothing is read and the gates become zeros. ----
+                ptr.q += cstep; ptr.k += cstep; ptr.v += cstep; ptr.g += cstep;
+                load_gates(rg, ptr.g, rs, valid_next, sg, lane_off(opaque(static_cast<uint32_t>(u))));
+                touch_qkv(touched, ptr, rs, valid_next, opaque(static_cast<uint32_t>(tid)));
+                valid = valid_next;
+            }
 
             // ---- per-lane LDS addresses of the contraction phases (derived per chunk, see prep_addr) ----
             const uint32_t lq = opaque(static_cast<uint32_t>(lane));
@@ -865,15 +886,6 @@ struct Kern {
                 }
             }
             clk.mark(9);
-            // ---- next chunk's inputs: gates into registers, q/k/v lines into L2; in flight during the update
-            //      and the output store ----
-            ptr.q += cstep; ptr.k += cstep; ptr.v += cstep; ptr.g += cstep;
-            if (tc + C < t1) {
-                const int64_t left = t1 - (tc + C);
-                valid = left >= C ? C : static_cast<int>(left);
-                load_gates(rg, ptr.g, rs, valid, sg, lane_off(opaque(static_cast<uint32_t>(u))));
-                touch_qkv(touched, ptr, rs, valid, opaque(static_cast<uint32_t>(tid)));
-            }
             // ---- state update: add K^^T V to the decayed state.  Tile dt starts 32 dt rows further; the
             //      swizzle of odd tiles is that of even tiles with token blocks kb and kb^2 exchanged ----
             {
@@ -894,6 +906,13 @@ struct Kern {
                     __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
                 }
                 __builtin_amdgcn_sched_group_barrier(0x008, 4 * MM, 0);
+            }
+            // ---- next chunk's gate sums: consumes the gates loaded at the top of this iteration, before the
+            //      output store is issued (a wait for a load would otherwise also wait for the stores) ----
+            {
+                const uint32_t uo = opaque(static_cast<uint32_t>(u));
+                gate_sums(bl, rg, sm + CS + ((ip * SG + uo / DG) * D + (uo % DG) * 8) * 4);
+                touch_use(touched);
             }
             clk.mark(10);
             if (kFull) {
@@ -916,7 +935,7 @@ struct Kern {
         }
 
 #ifdef DSLA_PHASE_CLOCKS
-        if (kFull) clk.flush(a.dbg);
+        clk.flush(a.dbg);
 #endif
         // ---- write the state out ----
         float *dst = nullptr;
@@ -987,6 +1006,12 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
     const int BH = d.B * d.H;
     hipError_t err;
     if (plan.segments > 1) {
+#ifdef DSLA_PHASE_CLOCKS
+        static long long *dbg1 = nullptr;
+        if (!dbg1) (void)hipMalloc(&dbg1, 16 * 12 * sizeof(long long));
+        (void)hipMemsetAsync(dbg1, 0, 16 * 12 * sizeof(long long), stream);
+        a.dbg = dbg1;
+#endif
         {
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_STATE, stream);
             hipLaunchKernelGGL((prefill_kernel<D, C, TIO, TG, false>), dim3(BH * (plan.segments - 1)), dim3(4 * D), 0,
@@ -994,6 +1019,20 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
             err = hipGetLastError();
         }
         if (err != hipSuccess) return err;
+#ifdef DSLA_PHASE_CLOCKS
+        {
+            long long h[16 * 12];
+            (void)hipStreamSynchronize(stream);
+            (void)hipMemcpy(h, dbg1, sizeof(h), hipMemcpyDeviceToHost);
+            for (int w = 0; w < 4 * D / 64; w += 4) {
+                long long tot = 0;
+                for (int n = 0; n < 12; ++n) tot += h[w * 12 + n];
+                fprintf(stderr, "[segment_state clocks] wave %d total %lld:", w, tot);
+                for (int n = 0; n < 12; ++n) fprintf(stderr, " %d=%lld", n, h[w * 12 + n]);
+                fprintf(stderr, "\n");
+            }
+        }
+#endif
         {
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_SCAN, stream);
             const size_t n4 = static_cast<size_t>(BH) * 2 * D * (D / 4);
