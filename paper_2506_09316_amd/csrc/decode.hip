@@ -2,25 +2,45 @@
 // applied to one token per sequence).
 //
 // Bandwidth-bound: per (batch, head) the two fp32 states (2 * d_k * d_v * 4 bytes) are read
-// once and written once; everything else is a few hundred bytes.  One workgroup of 256
-// threads streams one (batch, head) pair.  A thread owns four adjacent state columns
+// once and written once; everything else is a few hundred bytes.  SPLIT workgroups of 256
+// threads stream one (batch, head) pair, each a slice of the columns (the read-out of a column
+// needs no other column).  A thread owns four adjacent state columns
 // (one 16-byte access) in every ROWG-th row, so a wavefront access covers whole rows and is
 // fully coalesced.  All state loads are issued before anything else so that the maximum
 // number of bytes is in flight; the small per-token vectors go through LDS meanwhile.
+#include <cstdlib>
+
 #include "dsla_internal.h"
 
 namespace dsla {
 namespace {
 
 constexpr int kDecodeThreads = 256;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-template <int DK, int DV, class TIO, class TG>
+__device__ __forceinline__ float4 load_f4(const float4 *p, bool nt)
+{
+    const f32x4 *q = reinterpret_cast<const f32x4 *>(p);
+    const f32x4 x = nt ? __builtin_nontemporal_load(q) : *q;
+    return make_float4(x[0], x[1], x[2], x[3]);
+}
+__device__ __forceinline__ void store_f4(float4 *p, const float4 &v, bool nt)
+{
+    f32x4 *q = reinterpret_cast<f32x4 *>(p);
+    const f32x4 x = {v.x, v.y, v.z, v.w};
+    if (nt)
+        __builtin_nontemporal_store(x, q);
+    else
+        *q = x;
+}
+
+template <int DK, int DV, int SPLIT, bool NT, class TIO, class TG>
 __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
     const TIO *__restrict__ q, const TIO *__restrict__ k, const TIO *__restrict__ v, const TG *__restrict__ g1,
     const TG *__restrict__ g2, float *__restrict__ S1, float *__restrict__ S2, TIO *__restrict__ o, int H,
     float gamma, const float *__restrict__ gamma_per_head, float scale)
 {
-    constexpr int COLG = DV / 4;                  // threads across a state row (float4 each)
+    constexpr int COLG = DV / 4 / SPLIT;          // threads across this workgroup's part of a state row (float4 each)
     constexpr int ROWG = kDecodeThreads / COLG;   // row groups
     constexpr int ROWS = DK / ROWG;               // rows per thread
     static_assert(kDecodeThreads % COLG == 0 && DK % ROWG == 0, "shape");
@@ -29,21 +49,23 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
     __shared__ float s_q[DK], s_k[DK], s_a1[DK], s_a2[DK];
     __shared__ float4 s_red[kDecodeThreads / 64][COLG];
 
-    const int bh = blockIdx.x;
+    const int bh = blockIdx.x / SPLIT;
+    const int part = blockIdx.x % SPLIT;          // which slice of the columns
     const int tid = threadIdx.x;
     const int cg = tid % COLG;
     const int rg = tid / COLG;
+    constexpr int ROWF4 = DV / 4;                 // float4 per state row
     const size_t sbase = static_cast<size_t>(bh) * DK * DV;
-    float4 *p1 = reinterpret_cast<float4 *>(S1 + sbase) + cg;
-    float4 *p2 = reinterpret_cast<float4 *>(S2 + sbase) + cg;
+    float4 *p1 = reinterpret_cast<float4 *>(S1 + sbase) + part * COLG + cg;
+    float4 *p2 = reinterpret_cast<float4 *>(S2 + sbase) + part * COLG + cg;
 
     // 1. all state loads in flight
     float4 a[ROWS], b[ROWS];
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
         const int row = rg + j * ROWG;
-        a[j] = p1[static_cast<size_t>(row) * COLG];
-        b[j] = p2[static_cast<size_t>(row) * COLG];
+        a[j] = load_f4(&p1[static_cast<size_t>(row) * ROWF4], NT);
+        b[j] = load_f4(&p2[static_cast<size_t>(row) * ROWF4], NT);
     }
 
     // 2. per-token vectors -> LDS (gates exponentiated once per row)
@@ -55,7 +77,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
         s_a1[d] = __expf(to_f32(g1[kb + d]));
         s_a2[d] = __expf(to_f32(g2[kb + d]));
     }
-    const TIO *vp = v + static_cast<size_t>(bh) * DV + cg * 4;
+    const TIO *vp = v + static_cast<size_t>(bh) * DV + (part * COLG + cg) * 4;
     const float v0 = to_f32(vp[0]), v1 = to_f32(vp[1]), v2 = to_f32(vp[2]), v3 = to_f32(vp[3]);
     __syncthreads();
 
@@ -71,8 +93,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
         x.z = fmaf(a1, x.z, kd * v2); x.w = fmaf(a1, x.w, kd * v3);
         y.x = fmaf(a2, y.x, kd * v0); y.y = fmaf(a2, y.y, kd * v1);
         y.z = fmaf(a2, y.z, kd * v2); y.w = fmaf(a2, y.w, kd * v3);
-        p1[static_cast<size_t>(row) * COLG] = x;
-        p2[static_cast<size_t>(row) * COLG] = y;
+        store_f4(&p1[static_cast<size_t>(row) * ROWF4], x, NT);
+        store_f4(&p2[static_cast<size_t>(row) * ROWF4], y, NT);
         const float qa = qd * gm, qb = qd * gm2;
         acc.x = fmaf(qa, x.x, fmaf(qb, y.x, acc.x));
         acc.y = fmaf(qa, x.y, fmaf(qb, y.y, acc.y));
@@ -98,7 +120,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
             const float4 t = s_red[w][tid];
             r.x += t.x; r.y += t.y; r.z += t.z; r.w += t.w;
         }
-        TIO *op = o + static_cast<size_t>(bh) * DV + tid * 4;
+        TIO *op = o + static_cast<size_t>(bh) * DV + (part * COLG + tid) * 4;
         op[0] = from_f32<TIO>(r.x);
         op[1] = from_f32<TIO>(r.y);
         op[2] = from_f32<TIO>(r.z);
@@ -116,17 +138,55 @@ __global__ __launch_bounds__(256) void state_init_kernel(float4 *__restrict__ S1
     }
 }
 
-template <int D, class TIO, class TG>
-hipError_t launch_decode_t(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
+// Development switch (environment variable DSLA_DECODE_VARIANT, read once): column split and
+// non-temporal hint of the decode kernel.  Default "2x": two workgroups per (batch, head) (measured
+// fastest on MI355X: 5.07 TB/s against 4.80 with one and 4.91 with four; the hint makes no difference).
+struct DecodeVariant {
+    int split;
+    bool nt;
+};
+inline DecodeVariant decode_variant()
+{
+    static const DecodeVariant v = [] {
+        DecodeVariant d{2, false};
+        if (const char *e = getenv("DSLA_DECODE_VARIANT")) {
+            if (e[0] == '1' || e[0] == '2' || e[0] == '4') d.split = e[0] - '0';
+            d.nt = (e[1] == 'n');
+        }
+        return d;
+    }();
+    return v;
+}
+
+template <int D, int SPLIT, bool NT, class TIO, class TG>
+hipError_t launch_decode_v(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
                            const void *g2, float *S1, float *S2, void *o, hipStream_t stream)
 {
-    const unsigned grid = static_cast<unsigned>(d.B) * static_cast<unsigned>(d.H);
+    const unsigned grid = static_cast<unsigned>(d.B) * static_cast<unsigned>(d.H) * SPLIT;
     ProfileScope ps(DSLA_KERNEL_DECODE, stream);
-    hipLaunchKernelGGL((decode_kernel<D, D, TIO, TG>), dim3(grid), dim3(kDecodeThreads), 0, stream,
+    hipLaunchKernelGGL((decode_kernel<D, D, SPLIT, NT, TIO, TG>), dim3(grid), dim3(kDecodeThreads), 0, stream,
                        static_cast<const TIO *>(q), static_cast<const TIO *>(k), static_cast<const TIO *>(v),
                        static_cast<const TG *>(g1), static_cast<const TG *>(g2), S1, S2, static_cast<TIO *>(o), d.H,
                        d.gamma, d.gamma_per_head, d.scale);
     return hipGetLastError();
+}
+
+template <int D, class TIO, class TG>
+hipError_t launch_decode_t(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
+                           const void *g2, float *S1, float *S2, void *o, hipStream_t stream)
+{
+    const DecodeVariant var = decode_variant();
+#define DSLA_DECODE_CASE(SP, N)                                                                          \
+    if (var.split == SP && var.nt == N)                                                                  \
+        return launch_decode_v<D, SP, N, TIO, TG>(d, q, k, v, g1, g2, S1, S2, o, stream)
+    DSLA_DECODE_CASE(1, false);
+    DSLA_DECODE_CASE(1, true);
+    DSLA_DECODE_CASE(2, false);
+    DSLA_DECODE_CASE(2, true);
+    DSLA_DECODE_CASE(4, false);
+    DSLA_DECODE_CASE(4, true);
+#undef DSLA_DECODE_CASE
+    return hipErrorInvalidValue;
 }
 
 template <int D>

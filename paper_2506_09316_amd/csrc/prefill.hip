@@ -97,14 +97,18 @@ __device__ __forceinline__ uint32_t opaque(uint32_t x)
     return x;
 }
 template <class T>
+struct LdsPtr {
+    typedef T DSLA_LDS *type;   // pointer into LDS (32-bit)
+};
+template <class T>
 __device__ __forceinline__ T lds_ld(uint32_t a)
 {
-    return *(DSLA_LDS const T *)a;
+    return *reinterpret_cast<typename LdsPtr<const T>::type>(static_cast<uintptr_t>(a));
 }
 template <class T>
 __device__ __forceinline__ void lds_st(uint32_t a, T v)
 {
-    *(DSLA_LDS T *)a = v;
+    *reinterpret_cast<typename LdsPtr<T>::type>(static_cast<uintptr_t>(a)) = v;
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -183,3 +183,48 @@ def test_T0_is_noop_and_errors_do_nothing():
     torch.cuda.synchronize()
     S1, S2 = layer.states()
     assert np.array_equal(S1, S10) and np.array_equal(S2, S20)
+
+
+# ---------------------------------------------------------------- batched decode at full size (cfg4)
+def test_cfg4_batched_decode_full_size_sampled_pairs():
+    """B=64, H=32, d=128: states from a T=2048 prefill, then 256 fused decode steps on the full batch, in the
+    launch configuration bench.py times.  The prefill tokens of sequence b are those of base sequence b % 4 (four
+    seeded base sequences keep host generation small); decode inputs are distinct for all 64 sequences.  Sampled
+    (batch, head) pairs are checked element by element against the oracle run over prefill + decode tokens."""
+    import torch
+    import paper_2506_09316_amd as dsla
+    from tests.util import code, to_gpu
+    c = wl.CONFIGS["cfg4"]
+    B, T, H, d, steps, NB = c["B"], c["T"], c["H"], c["dk"], c["decode_steps"], 4
+    base = wl.layer_inputs(c["seed"], NB, T, H, d, d, io_dtype="bf16", gate_dtype="bf16", qk_scale=c["qk_scale"])
+    dec = wl.layer_inputs(c["seed"] + 50, B, steps, H, d, d, io_dtype="bf16", gate_dtype="bf16", qk_scale=c["qk_scale"])
+    desc = dsla.make_desc(B, H, d, d, io_dtype=code("bf16"), gate_dtype=code("bf16"), gamma=0.5, chunk=c["chunk"])
+    S1 = torch.empty(B, H, d, d, device="cuda")
+    S2 = torch.empty_like(S1)
+    dsla.dsla_state_init(desc, S1, S2)
+    xg = {n: to_gpu(base[n], "bf16").repeat(B // NB, 1, 1, 1).contiguous() for n in base}  # sequence b <- base b % 4
+    o = torch.empty_like(xg["v"])
+    assert dsla.dsla_prefill_workspace_bytes(desc, T) == 0
+    dsla.dsla_prefill(desc, T, xg["q"], xg["k"], xg["v"], xg["g1"], xg["g2"], S1, S2, o, None)
+    torch.cuda.synchronize()
+    pairs = ((0, 0), (5, 17), (34, 3), (63, 31), (22, 9))
+    o_pre = {(b, h): o[b, :, h].float().cpu().numpy() for b, h in pairs}
+    assert bool(torch.isfinite(o.float()).all())
+    del xg, o
+    dg = {n: to_gpu(dec[n], "bf16") for n in dec}   # [B, steps, H, d]
+    outs = torch.empty(steps, B, H, d, device="cuda", dtype=torch.bfloat16)
+    for t in range(steps):
+        dsla.dsla_decode(desc, dg["q"][:, t].contiguous(), dg["k"][:, t].contiguous(), dg["v"][:, t].contiguous(),
+                         dg["g1"][:, t].contiguous(), dg["g2"][:, t].contiguous(), S1, S2, outs[t])
+    torch.cuda.synchronize()
+    o_dec = outs.float().cpu().numpy()           # [steps, B, H, d]
+    S1h, S2h = S1.cpu().numpy(), S2.cpu().numpy()
+    assert np.all(np.isfinite(o_dec))
+    for b, h in pairs:
+        x = {n: np.concatenate([base[n][b % NB:b % NB + 1, :, h:h + 1], dec[n][b:b + 1, :, h:h + 1]], 1) for n in base}
+        ro, rS1, rS2 = orc.recurrent(x["q"], x["k"], x["v"], x["g1"], x["g2"], 0.5)
+        print(f"  pair (b={b}, h={h})", flush=True)
+        check("o prefill", o_pre[(b, h)], ro[0, :T, 0], 2e-2)
+        check("o decode", o_dec[:, b, h], ro[0, T:, 0], 2e-2)
+        check("S1", S1h[b, h], rS1[0, 0], 2e-2)
+        check("S2", S2h[b, h], rS2[0, 0], 2e-2)
