@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--no-calibration-copy", action="store_true",
+                    help="skip the plain 256 MiB device copy that gives counter runs a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (no collectives); use --gpus 1")
@@ -65,6 +67,15 @@ def main():
     torch.cuda.set_device(0)
     dsla.load_library()
     dev = "cuda"
+
+    if not args.no_calibration_copy:
+        # a plain copy of known size (256 MiB read + 256 MiB written): FETCH_SIZE / WRITE_SIZE of rocprofv3
+        # counter runs are scaled by what they report for this kernel
+        src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ------------------------------------------------------------------ prefill
     c = dict(wl.CONFIGS["cfg3_16k"])
