@@ -126,12 +126,13 @@ def main():
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
 
     out = {
-        "metric": "DSLA layer prefill tokens/s (Llama-2-7B shape, T=%d)" % T,
+        "metric": "DSLA layer tokens/s (prefill 7B-shape T=16k; decode B=64); % of roofline",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "cfg3 prefill: B=1 H=32 d_k=d_v=128 T=%d chunk=%d bf16 io, bf16 log-gates, "
-                               "fp32 states; step = state_init + prefill" % (T, C),
+        "config": {"workload": "value = prefill tokens/s of cfg3: B=1 H=32 d_k=d_v=128 T=%d chunk=%d bf16 io, bf16 "
+                               "log-gates, fp32 states; step = state_init + prefill; the decode part of the "
+                               "metric (cfg4, B=64) is under \"decode\"" % (T, C),
                    "segments": args.segments, "workspace_bytes": nws},
         "roofline": roofline,
         "kernel_ms": {k: v for k, v in kern_ms.items() if v is not None},
