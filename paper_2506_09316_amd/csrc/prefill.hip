@@ -243,6 +243,8 @@ struct Raw8<bf16_t> {
         u = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(base) + elem_off * 2u);
     }
     __device__ __forceinline__ void zero() { u = u32x4{0, 0, 0, 0}; }
+    // orders every later use of the loaded value after `dep` has been computed (no instruction is emitted)
+    __device__ __forceinline__ void pin_after(float dep) { asm volatile("" : "+v"(u) : "v"(dep)); }
     __device__ __forceinline__ void unpack(float (&f)[8]) const
     {
 #pragma unroll
@@ -262,6 +264,7 @@ struct Raw8<float> {
         b = *reinterpret_cast<const f32x4 *>(p + 16);
     }
     __device__ __forceinline__ void zero() { a = b = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    __device__ __forceinline__ void pin_after(float dep) { asm volatile("" : "+v"(a), "+v"(b) : "v"(dep)); }
     __device__ __forceinline__ void unpack(float (&f)[8]) const
     {
 #pragma unroll
@@ -315,6 +318,28 @@ __device__ __forceinline__ void store_v_tokens(uint32_t a, const Raw4<float> (&v
         lds_st<f32x2>(a, f32x2{v[0].a[e], v[1].a[e]});
 }
 
+template <int RPT>
+__device__ __forceinline__ void store_v_tokens(uint32_t a, const Raw8<bf16_t> (&v)[RPT], int e)
+{
+    const uint32_t sel = (e & 1) ? 0x07060302u : 0x05040100u;
+    const uint32_t lo = __builtin_amdgcn_perm(v[1].u[e >> 1], v[0].u[e >> 1], sel);
+    if constexpr (RPT == 4) {
+        const uint32_t hi = __builtin_amdgcn_perm(v[3].u[e >> 1], v[2].u[e >> 1], sel);
+        lds_st<u32x2>(a, u32x2{lo, hi});
+    } else {
+        lds_st<uint32_t>(a, lo);
+    }
+}
+template <int RPT>
+__device__ __forceinline__ void store_v_tokens(uint32_t a, const Raw8<float> (&v)[RPT], int e)
+{
+    auto pick = [&](const Raw8<float> &r) -> float { return e < 4 ? r.a[e & 3] : r.b[e & 3]; };
+    if constexpr (RPT == 4)
+        lds_st<f32x4>(a, f32x4{pick(v[0]), pick(v[1]), pick(v[2]), pick(v[3])});
+    else
+        lds_st<f32x2>(a, f32x2{pick(v[0]), pick(v[1])});
+}
+
 // staged output row (8 elements in LDS) -> global, uniform base + 32-bit lane offset
 __device__ __forceinline__ void store8_global(bf16_t *base, uint32_t elem_off, uint32_t lds8)
 {
@@ -361,9 +386,11 @@ struct PrefillArgs {
 #endif
 };
 
-// Workgroup layout.  4 D threads = D/8 wavefronts in two groups; group i (wavefronts i*D/32 ...)
-// prepares the operands of state i and owns state i in the contractions; inside a group, wavefront ct
-// owns state columns [32 ct, 32 ct + 32).
+// Workgroup layout.  A group of 2 D threads (D/32 wavefronts) prepares the operands of one state and owns
+// that state in the contractions; inside a group, wavefront ct owns state columns [32 ct, 32 ct + 32).
+// The chunk loop (kFull) runs both states in one workgroup of two groups, because the read-out blends
+// them.  The segment pre-pass (!kFull) needs no blend: one state per workgroup of one group, so that
+// several small workgroups share a compute unit and overlap each other's phases.
 template <int D, int C, class TIO, class TG, bool kFull>
 struct Kern {
     using A = ArithOf<TIO>;
@@ -372,9 +399,11 @@ struct Kern {
     static constexpr int ESZ = A::ESZ;
 
     static constexpr int CT = D / 32;       // column tiles = wavefronts per group
-    static constexpr int NW = 2 * CT;       // wavefronts
-    static constexpr int NT = 64 * NW;      // threads (= 4 D)
-    static constexpr int GT = NT / 2;       // threads per group (= 2 D)
+    static constexpr int GROUPS = kFull ? 2 : 1;   // wavefront groups = states handled by one workgroup
+    static constexpr int NW = GROUPS * CT;  // wavefronts
+    static constexpr int NT = 64 * NW;      // threads (4 D with both states, 2 D with one)
+    static constexpr int GT = 2 * D;        // threads per group
+    static constexpr int VW = kFull ? 4 : 8;   // v columns per thread (a group covers D/2 or all D columns)
     static constexpr int DG = D / 8;        // feature groups of 8
     static constexpr int SG = GT / DG;      // token groups (16)
     static constexpr int RPT = C / SG;      // tokens per thread
@@ -388,18 +417,18 @@ struct Kern {
     static constexpr int NTILE = RT * (RT + 1) / 2;  // score tiles on or below the diagonal
     static constexpr int XS = (RT == 2) ? NW : CT;   // exchange slots: all wavefronts send (RT = 2) or group 1 only
     static_assert(SG == 16 && (RPT == 2 || RPT == 4), "chunk must be 32 or 64");
-    static_assert(NTILE <= NW, "one score tile per wavefront");
+    static_assert(!kFull || NTILE <= NW, "one score tile per wavefront");
 
     // LDS map (byte offsets from the start of the block's LDS allocation)
     static constexpr uint32_t QS = 0;                                             // [token][i*D + d]  gamma_i scale q 2^{b}
     static constexpr uint32_t KS = QS + (kFull ? C * QP * ESZ : 0);               // [token][i*D + d]  k 2^{-b}
     static constexpr uint32_t KT = KS + (kFull ? C * QP * ESZ : 0);               // [i*D + rho(d)][token]  k 2^{bC-b}
-    static constexpr uint32_t VT = KT + 2 * D * TP * ESZ;                         // [column][token]  v
+    static constexpr uint32_t VT = KT + GROUPS * D * TP * ESZ;                    // [column][token]  v
     static constexpr uint32_t AS = VT + D * TP * ESZ;                             // [query][key] blended masked scores
     static constexpr uint32_t CS = AS + (kFull ? C * TP * ESZ : 0);               // float [i][token group][d] gate scan
-    static constexpr uint32_t BC = CS + 2 * SG * D * 4;                           // float [2D] log2 chunk decay
-    static constexpr uint32_t DEC = BC + 2 * D * 4;                               // float [2D] 2^{bC}
-    static constexpr uint32_t LDS_BYTES = DEC + 2 * D * 4;
+    static constexpr uint32_t BC = CS + GROUPS * SG * D * 4;                      // float [GROUPS D] log2 chunk decay
+    static constexpr uint32_t DEC = BC + GROUPS * D * 4;                          // float [GROUPS D] 2^{bC}
+    static constexpr uint32_t LDS_BYTES = DEC + GROUPS * D * 4;
     static constexpr uint32_t XB = KS;   // partial-output exchange (float4 [XS][4][64]) reuses Ks after the scores
     static constexpr uint32_t OS = QS;   // output staging tile [token][OP] reuses Qs after the read-out
     static_assert(!kFull || XS * 4096 <= C * QP * ESZ, "exchange buffer fits in Ks");
@@ -422,9 +451,10 @@ struct Kern {
     struct RawG {
         Raw8<TG> g[RPT];
     };
+    using RawV = typename std::conditional<kFull, Raw4<TIO>, Raw8<TIO>>::type;
     struct RawQKV {
         Raw8<TIO> q[kFull ? RPT : 1], k[RPT];
-        Raw4<TIO> v[RPT];
+        RawV v[RPT];
     };
     struct Ptrs {   // uniform base pointers of the current chunk
         const TIO *q, *k, *v;
@@ -435,30 +465,45 @@ struct Kern {
     };
 
     // Tokens at or beyond `valid` read as zero (zero log-gate = no decay, zero k and v = no contribution).
+    // A full chunk (valid == C, a workgroup-uniform condition) takes the branch without per-token tests.
     static __device__ __forceinline__ void load_gates(RawG &rg, const TG *gp, uint32_t rs, int valid, int sg,
                                                       uint32_t off)
     {
+        if (valid >= C) {
 #pragma unroll
-        for (int j = 0; j < RPT; ++j) {
-            if (valid >= C || sg * RPT + j < valid)
-                rg.g[j].load(gp + j * rs, off);
-            else
-                rg.g[j].zero();
+            for (int j = 0; j < RPT; ++j) rg.g[j].load(gp + j * rs, off);
+        } else {
+#pragma unroll
+            for (int j = 0; j < RPT; ++j) {
+                if (sg * RPT + j < valid)
+                    rg.g[j].load(gp + j * rs, off);
+                else
+                    rg.g[j].zero();
+            }
         }
     }
     static __device__ __forceinline__ void load_qkv(RawQKV &rc, const Ptrs &p, uint32_t rs, int valid, int sg,
                                                     uint32_t off, uint32_t voff)
     {
+        if (valid >= C) {
 #pragma unroll
-        for (int j = 0; j < RPT; ++j) {
-            if (valid >= C || sg * RPT + j < valid) {
+            for (int j = 0; j < RPT; ++j) {
                 rc.k[j].load(p.k + j * rs, off);
                 if (kFull) rc.q[j].load(p.q + j * rs, off);
                 rc.v[j].load(p.v + j * rs, voff);
-            } else {
-                rc.k[j].zero();
-                if (kFull) rc.q[j].zero();
-                rc.v[j].zero();
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < RPT; ++j) {
+                if (sg * RPT + j < valid) {
+                    rc.k[j].load(p.k + j * rs, off);
+                    if (kFull) rc.q[j].load(p.q + j * rs, off);
+                    rc.v[j].load(p.v + j * rs, voff);
+                } else {
+                    rc.k[j].zero();
+                    if (kFull) rc.q[j].zero();
+                    rc.v[j].zero();
+                }
             }
         }
     }
@@ -483,7 +528,7 @@ struct Kern {
                 const int l = ps * NT + tid;
                 const int row = l / TOUCH_LPR, part = l % TOUCH_LPR;
                 uint32_t x = 0;
-                if (l < TOUCH_LPT && row < valid) {
+                if (l < TOUCH_LPT && (valid >= C || row < valid)) {
                     const uint32_t boff = (static_cast<uint32_t>(row) * rs) * static_cast<uint32_t>(sizeof(TIO)) + part * 128;
                     x = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(tp) + boff);
                 }
@@ -500,7 +545,7 @@ struct Kern {
     // Per-lane LDS byte addresses of prepare().  They are derived inside the chunk loop from an opaque copy
     // of the thread index: a few integer operations per chunk instead of registers that would stay
     // occupied during the contraction phases.
-    static __device__ __forceinline__ PrepAddr prep_addr(uint32_t sm, int ip, uint32_t u)
+    static __device__ __forceinline__ PrepAddr prep_addr(uint32_t sm, int ip, uint32_t u)   // ip: group index
     {
         const uint32_t dg = u % DG, sg = u / DG;
         PrepAddr pa;
@@ -511,7 +556,7 @@ struct Kern {
         const uint32_t r0 = ip * D + 16 * (dg >> 1) + 4 * (dg & 1), r1 = r0 + 8;
         pa.kt_w0 = sm + KT + (r0 * TP + tcol(r0, sg * RPT)) * ESZ;
         pa.kt_w1 = sm + KT + (r1 * TP + tcol(r1, sg * RPT)) * ESZ;
-        const uint32_t rv = ip * (D / 2) + dg * 4;
+        const uint32_t rv = ip * (D / 2) + dg * VW;
         pa.vt_w = sm + VT + (rv * TP + tcol(rv, sg * RPT)) * ESZ;
         pa.qs_w = sm + QS + ((sg * RPT) * QP + ip * D + dg * 8) * ESZ;
         return pa;
@@ -617,9 +662,9 @@ struct Kern {
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        // V transposed: columns ip*D/2 + 4dg .. + 3
+        // V transposed: this thread's VW columns (rows of Vt), RPT tokens each
 #pragma unroll
-        for (int e = 0; e < 4; ++e) store_v_tokens<RPT>(pa.vt_w + e * TP * ESZ, rc.v, e);
+        for (int e = 0; e < VW; ++e) store_v_tokens<RPT>(pa.vt_w + e * TP * ESZ, rc.v, e);
     }
 
     static __device__ void run(const PrefillArgs &a, uint32_t sm)
@@ -628,16 +673,35 @@ struct Kern {
         const int lane = tid & 63;
         const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform, kept in scalar registers
         const int ln = lane & 31, g = lane >> 5;
-        const int ip = wave / CT;                // state this wavefront prepares and owns
-        const int ct = wave % CT;                // column tile it owns in the contractions
-        const int u = tid - ip * GT;             // index inside the group
+        const int ct = wave % CT;                // column tile this wavefront owns in the contractions
+        // Work item of the workgroup and state of this wavefront.  Chunk loop: block = (bh, segment), state =
+        // wavefront group.  Pre-pass: block = (bh, segment, state); blocks 8 apart (same XCD, hence same L2
+        // under round-robin dispatch) handle the two states of one (bh, segment) and share its k and v lines.
+        const int nseg = kFull ? a.P : a.P - 1;
+        int unit, ip;
+        if (kFull) {
+            unit = blockIdx.x;
+            ip = wave / CT;
+        } else {
+            const int pairs = gridDim.x / 2;                      // (bh, segment) items
+            const int blk = blockIdx.x, grp16 = blk / 16, in16 = blk % 16;
+            if ((grp16 + 1) * 8 <= pairs) {                       // full 16-block group: 8 items x 2 states
+                unit = grp16 * 8 + in16 % 8;
+                ip = in16 / 8;
+            } else {                                              // tail: adjacent blocks pair up
+                const int rest = blk - grp16 * 16;
+                unit = grp16 * 8 + rest / 2;
+                ip = rest % 2;
+            }
+        }
+        const int ipl = kFull ? ip : 0;          // group index inside the workgroup (LDS layout)
+        const int u = tid - ipl * GT;            // index inside the group
         const int dg = u % DG, sg = u / DG;
 
-        const int nseg = kFull ? a.P : a.P - 1;
-        const int bh = blockIdx.x / nseg;
-        const int p = blockIdx.x % nseg;
+        const int bh = unit / nseg;
+        const int p = unit % nseg;
         const int bidx = bh / a.H, h = bh % a.H;
-        const int BH = gridDim.x / nseg;
+        const int BH = (kFull ? gridDim.x : gridDim.x / 2) / nseg;
 
         const int64_t t0 = static_cast<int64_t>(p) * a.seg_tokens;
         const int64_t t1 = (t0 + a.seg_tokens < a.T) ? t0 + a.seg_tokens : a.T;
@@ -647,7 +711,7 @@ struct Kern {
         // per-lane element offsets of the global accesses; evaluated from an opaque copy of the thread index
         // where they are used, so that they do not stay in registers across the other phases
         auto lane_off = [&](uint32_t uo) -> uint32_t { return (uo / DG) * RPT * rs + (uo % DG) * 8; };
-        auto lane_voff = [&](uint32_t uo) -> uint32_t { return (uo / DG) * RPT * rs + ip * (D / 2) + (uo % DG) * 4; };
+        auto lane_voff = [&](uint32_t uo) -> uint32_t { return (uo / DG) * RPT * rs + ipl * (D / 2) + (uo % DG) * VW; };
 
         const float gm = a.gamma_per_head ? a.gamma_per_head[h] : a.gamma;
         const float gsv = (ip ? 1.0f - gm : gm) * a.scale;
@@ -702,7 +766,7 @@ struct Kern {
 #pragma unroll
         for (int i = 0; i < TOUCH_N; ++i) touched.x[i] = 0;
         float bl[RPT][8];   // cumulative log-gates of the current chunk (computed one iteration ahead)
-        gate_sums(bl, rg, sm + CS + ((ip * SG + sg) * D + dg * 8) * 4);
+        gate_sums(bl, rg, sm + CS + ((ipl * SG + sg) * D + dg * 8) * 4);
         PhaseClock clk;
         clk.start();
 
@@ -715,7 +779,7 @@ struct Kern {
                 RawQKV rc;
                 const uint32_t uo = opaque(static_cast<uint32_t>(u));
                 load_qkv(rc, ptr, rs, valid, sg, lane_off(uo), lane_voff(uo));
-                const PrepAddr pa = prep_addr(sm, ip, uo);
+                const PrepAddr pa = prep_addr(sm, ipl, uo);
                 prepare(pa, bl, rc, lg, neg, u < D, seg_decay, clk);
             }
             clk.mark(3);
@@ -727,26 +791,28 @@ struct Kern {
                 //      the end of the segment valid_next is 0: nothing is read and the gates become zeros. ----
                 ptr.q += cstep; ptr.k += cstep; ptr.v += cstep; ptr.g += cstep;
                 load_gates(rg, ptr.g, rs, valid_next, sg, lane_off(opaque(static_cast<uint32_t>(u))));
+                if (!kFull) clk.mark(6);
                 touch_qkv(touched, ptr, rs, valid_next, opaque(static_cast<uint32_t>(tid)));
+                if (!kFull) clk.mark(8);
                 valid = valid_next;
             }
 
             // ---- per-lane LDS addresses of the contraction phases (derived per chunk, see prep_addr) ----
             const uint32_t lq = opaque(static_cast<uint32_t>(lane));
             const uint32_t lnq = lq & 31, gq = lq >> 5;
-            const uint32_t q_own = sm + QS + ((32 * own + lnq) * QP + ip * D + 8 * gq) * ESZ;
-            const uint32_t q_oth = sm + QS + ((32 * (RT - 1 - own) + lnq) * QP + ip * D + 8 * gq) * ESZ;
+            const uint32_t q_own = sm + QS + ((32 * own + lnq) * QP + ipl * D + 8 * gq) * ESZ;
+            const uint32_t q_oth = sm + QS + ((32 * (RT - 1 - own) + lnq) * QP + ipl * D + 8 * gq) * ESZ;
             const uint32_t a_own = sm + AS + ((32 * own + lnq) * TP + 8 * gq) * ESZ;
             uint32_t vt_r[KB], kt_r[KB];   // swizzled token blocks of this lane's Vt row / first Kt row
             {
-                const uint32_t vrow = 32 * ct + lnq, krow = ip * D + lnq;
+                const uint32_t vrow = 32 * ct + lnq, krow = ipl * D + lnq;
 #pragma unroll
                 for (int kb = 0; kb < KB; ++kb) {
                     vt_r[kb] = sm + VT + (vrow * TP + tcol(vrow, 16 * kb + 8 * gq)) * ESZ;
                     kt_r[kb] = sm + KT + (krow * TP + tcol(krow, 16 * kb + 8 * gq)) * ESZ;
                 }
             }
-            const uint32_t dec_r = sm + DEC + (ip * D + 8 * gq) * 4;
+            const uint32_t dec_r = sm + DEC + (ipl * D + 8 * gq) * 4;
 
             Frag sfr[kFull ? DT : 1][2];
             if (kFull && wave < NTILE) {
@@ -793,18 +859,34 @@ struct Kern {
                     A::store4(sc_w + 8 * jb * ESZ, x[0], x[1], x[2], x[3]);
                 }
             }
-            // ---- carried state: take its input fragments for the read-out, then decay its rows ----
+            // ---- carried state: take its input fragments for the read-out, then decay its rows.  The decay
+            //      factors of two tiles (8 LDS reads) are requested together, ahead of the multiplies. ----
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                if (kFull) {
-                    sfr[dt][0] = A::from_acc(acc[dt], 0);
-                    sfr[dt][1] = A::from_acc(acc[dt], 1);
-                }
+            for (int dt2 = 0; dt2 < DT; dt2 += 2) {
+                constexpr int NTL = (DT >= 2) ? 2 : 1;   // tiles per batch
+                f32x4 dd[NTL][4];
 #pragma unroll
-                for (int jb = 0; jb < 4; ++jb) {
-                    const f32x4 dd = lds_ld<f32x4>(dec_r + (32 * dt + 16 * (jb >> 1) + 4 * (jb & 1)) * 4);
+                for (int t = 0; t < NTL; ++t)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) acc[dt][4 * jb + e] *= dd[e];
+                    for (int jb = 0; jb < 4; ++jb)
+                        dd[t][jb] = lds_ld<f32x4>(dec_r + (32 * (dt2 + t) + 16 * (jb >> 1) + 4 * (jb & 1)) * 4);
+                // all reads of the batch are in flight before the first one is consumed
+                if constexpr (NTL == 2)
+                    asm volatile("" : "+v"(dd[0][0]), "+v"(dd[0][1]), "+v"(dd[0][2]), "+v"(dd[0][3]), "+v"(dd[1][0]),
+                                 "+v"(dd[1][1]), "+v"(dd[1][2]), "+v"(dd[1][3]));
+                else
+                    asm volatile("" : "+v"(dd[0][0]), "+v"(dd[0][1]), "+v"(dd[0][2]), "+v"(dd[0][3]));
+#pragma unroll
+                for (int t = 0; t < NTL; ++t) {
+                    const int dt = dt2 + t;
+                    if (kFull) {
+                        sfr[dt][0] = A::from_acc(acc[dt], 0);
+                        sfr[dt][1] = A::from_acc(acc[dt], 1);
+                    }
+#pragma unroll
+                    for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[dt][4 * jb + e] *= dd[t][jb][e];
                 }
             }
             clk.mark(5);
@@ -914,8 +996,12 @@ struct Kern {
             // ---- next chunk's gate sums: consumes the gates loaded at the top of this iteration, before the
             //      output store is issued (a wait for a load would otherwise also wait for the stores) ----
             {
+                // The gates must not be consumed earlier than here (their load would be waited for right after it
+                // was issued): the empty asm ties their registers to the last result of the update.
+#pragma unroll
+                for (int j = 0; j < RPT; ++j) rg.g[j].pin_after(acc[DT - 1][15]);
                 const uint32_t uo = opaque(static_cast<uint32_t>(u));
-                gate_sums(bl, rg, sm + CS + ((ip * SG + uo / DG) * D + (uo % DG) * 8) * 4);
+                gate_sums(bl, rg, sm + CS + ((ipl * SG + uo / DG) * D + (uo % DG) * 8) * 4);
                 touch_use(touched);
             }
             clk.mark(10);
@@ -963,7 +1049,7 @@ struct Kern {
 };
 
 template <int D, int C, class TIO, class TG, bool kFull>
-__global__ __launch_bounds__(4 * D) void prefill_kernel(PrefillArgs a)
+__global__ __launch_bounds__(kFull ? 4 * D : 2 * D, kFull ? 2 : 3) void prefill_kernel(PrefillArgs a)
 {
     using K = Kern<D, C, TIO, TG, kFull>;
     __shared__ __attribute__((aligned(16))) char smem[K::LDS_BYTES];
@@ -1018,8 +1104,8 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
 #endif
         {
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_STATE, stream);
-            hipLaunchKernelGGL((prefill_kernel<D, C, TIO, TG, false>), dim3(BH * (plan.segments - 1)), dim3(4 * D), 0,
-                               stream, a);
+            hipLaunchKernelGGL((prefill_kernel<D, C, TIO, TG, false>), dim3(BH * (plan.segments - 1) * 2), dim3(2 * D),
+                               0, stream, a);
             err = hipGetLastError();
         }
         if (err != hipSuccess) return err;
