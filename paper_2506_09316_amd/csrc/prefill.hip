@@ -25,6 +25,7 @@
 // index (bits 2 and 3 of the feature index swapped).
 #include <cstdio>
 #include <type_traits>
+#include <utility>
 
 #include "dsla_internal.h"
 
@@ -340,6 +341,16 @@ __device__ __forceinline__ void store_v_tokens(uint32_t a, const Raw8<float> (&v
         lds_st<f32x2>(a, f32x2{pick(v[0]), pick(v[1])});
 }
 
+// four adjacent output elements -> global
+__device__ __forceinline__ void store4_global(bf16_t *p, float a, float b, float c, float d)
+{
+    *reinterpret_cast<u32x2 *>(p) = u32x2{ArithBf16::pack2(a, b), ArithBf16::pack2(c, d)};
+}
+__device__ __forceinline__ void store4_global(float *p, float a, float b, float c, float d)
+{
+    *reinterpret_cast<f32x4 *>(p) = f32x4{a, b, c, d};
+}
+
 // staged output row (8 elements in LDS) -> global, uniform base + 32-bit lane offset
 __device__ __forceinline__ void store8_global(bf16_t *base, uint32_t elem_off, uint32_t lds8)
 {
@@ -386,285 +397,351 @@ struct PrefillArgs {
 #endif
 };
 
-// Workgroup layout.  A group of 2 D threads (D/32 wavefronts) prepares the operands of one state and owns
-// that state in the contractions; inside a group, wavefront ct owns state columns [32 ct, 32 ct + 32).
-// The chunk loop (kFull) runs both states in one workgroup of two groups, because the read-out blends
-// them.  The segment pre-pass (!kFull) needs no blend: one state per workgroup of one group, so that
-// several small workgroups share a compute unit and overlap each other's phases.
-template <int D, int C, class TIO, class TG, bool kFull>
+// Workgroup layout: producer / consumer wavefronts.  4 D threads = D/8 wavefronts.  The first D/32
+// wavefronts are CONSUMERS: wavefront ct owns columns [32 ct, 32 ct + 32) of BOTH states for all d_k rows as fp32
+// MFMA accumulators and runs every contraction of a step.  The other D/32 wavefronts are PRODUCERS: they load
+// the inputs of later steps, run the gate scan and write the contraction operands of the NEXT step into the
+// other half of a double-buffered LDS.  One workgroup barrier per step hands a finished operand set from the
+// producers to the consumers.  Each SIMD hosts one consumer and one producer wavefront, so the VALU-bound
+// preparation and the MFMA-bound contractions of neighbouring steps overlap.  A step is S = 32 tokens (a chunk
+// of 64 is two steps): two operand sets of 32 tokens fit in the 160 KB LDS, two sets of 64 do not.
+//
+// Step algebra (Section 4.1 unrolled over the S tokens of a step; b_s = log2 of the gate product from the first
+// token of the step up to and including token s, bS = b of the last token, all per state and feature):
+//     Q' = gamma_i scale q 2^{b - bS}        K^ = k 2^{bS - b}          (|K^| <= |k|, |Q'| <= |q| 2^{|bS|})
+//     state  <- diag(2^{bS}) state                                       (decay over the whole step, done first)
+//     o      =  Q' state  +  mask_{key <= query}(Q' K^^T) V              (both states in one contraction of width 2 d_k)
+//     state  <- state + K^^T V
+template <int D, class TIO, class TG, bool kFull>
 struct Kern {
     using A = ArithOf<TIO>;
     using Frag = typename A::Frag;
     using Row8 = typename A::Row8;
     static constexpr int ESZ = A::ESZ;
 
-    static constexpr int CT = D / 32;       // column tiles = wavefronts per group
-    static constexpr int GROUPS = kFull ? 2 : 1;   // wavefront groups = states handled by one workgroup
-    static constexpr int NW = GROUPS * CT;  // wavefronts
-    static constexpr int NT = 64 * NW;      // threads (4 D with both states, 2 D with one)
-    static constexpr int GT = 2 * D;        // threads per group
-    static constexpr int VW = kFull ? 4 : 8;   // v columns per thread (a group covers D/2 or all D columns)
-    static constexpr int DG = D / 8;        // feature groups of 8
-    static constexpr int SG = GT / DG;      // token groups (16)
-    static constexpr int RPT = C / SG;      // tokens per thread
+    static constexpr int S = 32;            // tokens per step
+    static constexpr int CT = D / 32;       // column tiles = consumer wavefronts = producer wavefronts
+    static constexpr int NW = 2 * CT;       // wavefronts
+    static constexpr int NT = 64 * NW;      // threads (= 4 D)
+    static constexpr int SGN = 16;          // token pairs per step
+    static constexpr int RPT = 2;           // tokens per producer thread
     static constexpr int QP = 2 * D + 8;    // pitch of row-layout operands (elements)
-    static constexpr int TP = C + 8;        // pitch of token-contiguous operands (elements)
-    static constexpr int OP = D + 8;        // pitch of the output staging tile
-    static constexpr int NC16 = C / 8;      // 8-element column groups in a token-contiguous row
-    static constexpr int RT = C / 32;       // 32-token tiles in a chunk
-    static constexpr int KB = C / 16;       // contraction blocks over tokens
+    static constexpr int TP = S + 8;        // pitch of token-contiguous operands (elements)
     static constexpr int DT = D / 32;       // 32-row tiles of a state
-    static constexpr int NTILE = RT * (RT + 1) / 2;  // score tiles on or below the diagonal
-    static constexpr int XS = (RT == 2) ? NW : CT;   // exchange slots: all wavefronts send (RT = 2) or group 1 only
-    static_assert(SG == 16 && (RPT == 2 || RPT == 4), "chunk must be 32 or 64");
-    static_assert(!kFull || NTILE <= NW, "one score tile per wavefront");
+    static constexpr int KB = S / 16;       // contraction blocks over tokens
+    static constexpr int NK = 2 * D / 16;   // contraction blocks over the 2 d_k features
 
-    // LDS map (byte offsets from the start of the block's LDS allocation)
-    static constexpr uint32_t QS = 0;                                             // [token][i*D + d]  gamma_i scale q 2^{b}
-    static constexpr uint32_t KS = QS + (kFull ? C * QP * ESZ : 0);               // [token][i*D + d]  k 2^{-b}
-    static constexpr uint32_t KT = KS + (kFull ? C * QP * ESZ : 0);               // [i*D + rho(d)][token]  k 2^{bC-b}
-    static constexpr uint32_t VT = KT + GROUPS * D * TP * ESZ;                    // [column][token]  v
-    static constexpr uint32_t AS = VT + D * TP * ESZ;                             // [query][key] blended masked scores
-    static constexpr uint32_t CS = AS + (kFull ? C * TP * ESZ : 0);               // float [i][token group][d] gate scan
-    static constexpr uint32_t BC = CS + GROUPS * SG * D * 4;                      // float [GROUPS D] log2 chunk decay
-    static constexpr uint32_t DEC = BC + GROUPS * D * 4;                          // float [GROUPS D] 2^{bC}
-    static constexpr uint32_t LDS_BYTES = DEC + GROUPS * D * 4;
-    static constexpr uint32_t XB = KS;   // partial-output exchange (float4 [XS][4][64]) reuses Ks after the scores
-    static constexpr uint32_t OS = QS;   // output staging tile [token][OP] reuses Qs after the read-out
-    static_assert(!kFull || XS * 4096 <= C * QP * ESZ, "exchange buffer fits in Ks");
-    static_assert(!kFull || C * OP <= C * QP, "staging tile fits in Qs");
-    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget of a gfx950 compute unit");
+    // LDS map (bytes).  Two operand sets; per set:
+    static constexpr uint32_t O_QS = 0;                                        // [token][i*D + d]            Q'
+    static constexpr uint32_t O_KS = O_QS + (kFull ? S * QP * ESZ : 0);        // [token][i*D + d]            K^
+    static constexpr uint32_t O_KT = O_KS + (kFull ? S * QP * ESZ : 0);        // [i*D + rho(d)][rho(token)]  K^
+    static constexpr uint32_t O_VT = O_KT + 2 * D * TP * ESZ;                  // [column][rho(token)]        v
+    static constexpr uint32_t O_DEC = O_VT + D * TP * ESZ;                     // float [2D]  2^{bS}
+    static constexpr uint32_t SET_BYTES = O_DEC + 2 * D * 4;
+    static constexpr uint32_t LDS_MAX = 160 * 1024;                            // LDS of a gfx950 compute unit
+    // Two operand sets where they fit (the producers then run a whole step ahead of the consumers); one set
+    // otherwise (fp32 at d = 128): the producers then only load ahead and prepare between two barriers.
+    static constexpr int SETS = (2 * SET_BYTES + CT * 4096 <= LDS_MAX) ? 2 : 1;
+    static constexpr uint32_t O_CS = SETS * SET_BYTES;                         // per producer wavefront: float [2][16][32]
+    static constexpr uint32_t LDS_BYTES = O_CS + CT * 4096;
+    static_assert(LDS_BYTES <= LDS_MAX, "LDS budget");
 
-    // swizzled offset inside a token-contiguous row: 8-element column group XOR (row / 8)
-    static __device__ __forceinline__ uint32_t tcol(uint32_t row, uint32_t s)
+    // rho: bits 2 and 3 of an index swapped.  Features are stored in Kt rows in rho order and tokens in Kt / Vt
+    // columns in rho order.  With this order the 8 accumulator registers of one half of a 32x32 MFMA result tile
+    // (lane group g holds tile rows 8a + 4g + b) are exactly the 8 contraction indices lane group g supplies in an
+    // MFMA input fragment read from 8 consecutive positions, so results are fed back as inputs without LDS.
+    static __device__ __forceinline__ uint32_t rho(uint32_t x) { return (x & ~12u) | ((x & 4u) << 1) | ((x & 8u) >> 1); }
+
+    struct RawStep {   // inputs of one step as loaded (unconverted): this thread's 2 tokens x 8 features
+        Raw8<TIO> q[RPT], k[RPT], v[RPT];
+        Raw8<TG> g1[RPT], g2[RPT];
+    };
+    // Where a producer lane reads a step from.  Loads are never predicated (the number of loads in flight stays
+    // a compile-time fact, so waiting for the oldest never waits for the newest): a step past the end of the
+    // segment re-reads the last one and a token past the end re-reads the last token; produce() zeroes those.
+    struct StepSrc {
+        const TIO *q, *k, *v;   // uniform: first token of the step, this (batch, head)
+        const TG *g1, *g2;
+        uint32_t off[RPT];      // per lane: element offset of token 2 sg + j, features 32 pw + 8 dgl ..
+    };
+    static constexpr int N_LOADS = (kFull ? 5 : 4) * RPT;
+    template <int IDX>
+    static __device__ __forceinline__ void load_one(RawStep &r, const StepSrc &s)
     {
-        return ((((s >> 3) ^ (row >> 3)) & (NC16 - 1)) << 3) | (s & 7);
+        constexpr int j = IDX % RPT, ten = IDX / RPT;
+        if (ten == 0) r.g1[j].load(s.g1, s.off[j]);
+        if (ten == 1) r.g2[j].load(s.g2, s.off[j]);
+        if (ten == 2) r.k[j].load(s.k, s.off[j]);
+        if (ten == 3) r.v[j].load(s.v, s.off[j]);
+        if (ten == 4) r.q[j].load(s.q, s.off[j]);
     }
-    // Kt row order: feature d sits in row rho(d) (bits 2 and 3 of d swapped).  With this order, accumulator
-    // register j of lane group g in a 32-row state tile holds feature 16*(j/8) + 8*g + (j%8) of the tile:
-    // the 8 registers of one half of the tile are 8 consecutive features, exactly one MFMA input fragment.
-
-    // Inputs of one chunk as loaded (unconverted).  The gates of the next chunk are loaded into registers
-    // one phase ahead (they are needed first); q, k and v of the next chunk are only touched (one 4-byte
-    // read per 128-byte line) so that they wait in L2, and are loaded for real when the preparation starts:
-    // holding all of them in registers across the contraction phases costs more registers than there are.
-    struct RawG {
-        Raw8<TG> g[RPT];
-    };
-    using RawV = typename std::conditional<kFull, Raw4<TIO>, Raw8<TIO>>::type;
-    struct RawQKV {
-        Raw8<TIO> q[kFull ? RPT : 1], k[RPT];
-        RawV v[RPT];
-    };
-    struct Ptrs {   // uniform base pointers of the current chunk
-        const TIO *q, *k, *v;
-        const TG *g;
-    };
-    struct PrepAddr {   // per-lane LDS byte addresses used by prepare()
-        uint32_t cs_w, cs_c, bc_w, bc_r, kt_w0, kt_w1, vt_w, qs_w;
-    };
-
-    // Tokens at or beyond `valid` read as zero (zero log-gate = no decay, zero k and v = no contribution).
-    // A full chunk (valid == C, a workgroup-uniform condition) takes the branch without per-token tests.
-    static __device__ __forceinline__ void load_gates(RawG &rg, const TG *gp, uint32_t rs, int valid, int sg,
-                                                      uint32_t off)
+    template <int... I>
+    static __device__ __forceinline__ void load_all(RawStep &r, const StepSrc &s, std::integer_sequence<int, I...>)
     {
-        if (valid >= C) {
-#pragma unroll
-            for (int j = 0; j < RPT; ++j) rg.g[j].load(gp + j * rs, off);
-        } else {
-#pragma unroll
-            for (int j = 0; j < RPT; ++j) {
-                if (sg * RPT + j < valid)
-                    rg.g[j].load(gp + j * rs, off);
-                else
-                    rg.g[j].zero();
-            }
+        (load_one<I>(r, s), ...);
+    }
+    struct NoLoads {
+        __device__ __forceinline__ void at(int) const {}
+    };
+    struct NextLoads {   // the loads of a later step, issued one at a time between the stages of produce()
+        RawStep &r;
+        const StepSrc &s;
+        template <int... I>
+        __device__ __forceinline__ void pick(int idx, std::integer_sequence<int, I...>) const
+        {
+            ((idx == I ? (load_one<I>(r, s), 0) : 0), ...);
         }
-    }
-    static __device__ __forceinline__ void load_qkv(RawQKV &rc, const Ptrs &p, uint32_t rs, int valid, int sg,
-                                                    uint32_t off, uint32_t voff)
-    {
-        if (valid >= C) {
-#pragma unroll
-            for (int j = 0; j < RPT; ++j) {
-                rc.k[j].load(p.k + j * rs, off);
-                if (kFull) rc.q[j].load(p.q + j * rs, off);
-                rc.v[j].load(p.v + j * rs, voff);
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < RPT; ++j) {
-                if (sg * RPT + j < valid) {
-                    rc.k[j].load(p.k + j * rs, off);
-                    if (kFull) rc.q[j].load(p.q + j * rs, off);
-                    rc.v[j].load(p.v + j * rs, voff);
-                } else {
-                    rc.k[j].zero();
-                    if (kFull) rc.q[j].zero();
-                    rc.v[j].zero();
-                }
-            }
-        }
-    }
-    // One 4-byte read per 128-byte line of the q, k, v rows of a chunk (rows below `valid` only).  The
-    // value is returned so that the caller can keep it "in use" until the real loads have been issued.
-    static constexpr int TOUCH_LPR = D * static_cast<int>(sizeof(TIO)) / 128;   // 128-byte lines per token row
-    static constexpr int TOUCH_LPT = C * TOUCH_LPR;                             // lines per tensor and chunk
-    static constexpr int TOUCH_NTEN = kFull ? 3 : 2;
-    static constexpr int TOUCH_N = TOUCH_NTEN * ((TOUCH_LPT + NT - 1) / NT);    // touches per thread
-    struct Touched {
-        uint32_t x[TOUCH_N];
+        // idx is a constant after unrolling; slots beyond the loads of a step are empty
+        __device__ __forceinline__ void at(int idx) const { pick(idx, std::make_integer_sequence<int, N_LOADS>{}); }
     };
-    static __device__ __forceinline__ void touch_qkv(Touched &t, const Ptrs &p, uint32_t rs, int valid, int tid)
-    {
-        constexpr int PASSES = (TOUCH_LPT + NT - 1) / NT;
-#pragma unroll
-        for (int ten = 0; ten < TOUCH_NTEN; ++ten) {
-            const TIO *tp = (ten == 0) ? p.k : (ten == 1) ? p.v : p.q;
-#pragma unroll
-            for (int ps = 0; ps < PASSES; ++ps) {
-                // thread tid of pass ps touches line (ps * NT + tid) of every tensor
-                const int l = ps * NT + tid;
-                const int row = l / TOUCH_LPR, part = l % TOUCH_LPR;
-                uint32_t x = 0;
-                if (l < TOUCH_LPT && (valid >= C || row < valid)) {
-                    const uint32_t boff = (static_cast<uint32_t>(row) * rs) * static_cast<uint32_t>(sizeof(TIO)) + part * 128;
-                    x = *reinterpret_cast<const uint32_t *>(reinterpret_cast<const char *>(tp) + boff);
-                }
-                t.x[ten * PASSES + ps] = x;
-            }
-        }
-    }
-    static __device__ __forceinline__ void touch_use(const Touched &t)
-    {
-#pragma unroll
-        for (int i = 0; i < TOUCH_N; ++i) asm volatile("" ::"v"(t.x[i]));
-    }
 
-    // Per-lane LDS byte addresses of prepare().  They are derived inside the chunk loop from an opaque copy
-    // of the thread index: a few integer operations per chunk instead of registers that would stay
-    // occupied during the contraction phases.
-    static __device__ __forceinline__ PrepAddr prep_addr(uint32_t sm, int ip, uint32_t u)   // ip: group index
-    {
-        const uint32_t dg = u % DG, sg = u / DG;
-        PrepAddr pa;
-        pa.cs_w = sm + CS + ((ip * SG + sg) * D + dg * 8) * 4;
-        pa.cs_c = sm + CS + (ip * SG * D + u) * 4;
-        pa.bc_w = sm + BC + (ip * D + u) * 4;
-        pa.bc_r = sm + BC + (ip * D + dg * 8) * 4;
-        const uint32_t r0 = ip * D + 16 * (dg >> 1) + 4 * (dg & 1), r1 = r0 + 8;
-        pa.kt_w0 = sm + KT + (r0 * TP + tcol(r0, sg * RPT)) * ESZ;
-        pa.kt_w1 = sm + KT + (r1 * TP + tcol(r1, sg * RPT)) * ESZ;
-        const uint32_t rv = ip * (D / 2) + dg * VW;
-        pa.vt_w = sm + VT + (rv * TP + tcol(rv, sg * RPT)) * ESZ;
-        pa.qs_w = sm + QS + ((sg * RPT) * QP + ip * D + dg * 8) * ESZ;
-        return pa;
-    }
+    // wavefront-private LDS hand-over: the LDS pipeline runs the requests of one wavefront in order; only the
+    // compiler has to be kept from moving accesses across
+    static __device__ __forceinline__ void wave_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
-    // Cumulative natural-log gates over this thread's tokens, and the thread's total into the scan scratch.
-    // Runs at the end of the previous chunk's iteration (before its output store), so that the gate
-    // registers are consumed there and no load is waited for behind a store at the top of the loop.
-    static __device__ __forceinline__ void gate_sums(float (&bl)[RPT][8], const RawG &rg, uint32_t cs_w)
-    {
-#pragma unroll
-        for (int j = 0; j < RPT; ++j) {
-            float g[8];
-            rg.g[j].unpack(g);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) bl[j][e] = j ? bl[j - 1][e] + g[e] : g[e];
-        }
-        lds_st<f32x4>(cs_w, f32x4{bl[RPT - 1][0], bl[RPT - 1][1], bl[RPT - 1][2], bl[RPT - 1][3]});
-        lds_st<f32x4>(cs_w + 16, f32x4{bl[RPT - 1][4], bl[RPT - 1][5], bl[RPT - 1][6], bl[RPT - 1][7]});
-    }
-
-    // Gate scan and operand preparation for one chunk.  Thread (ip, dg, sg) handles state ip, features
-    // 8dg..8dg+7, tokens RPT*sg.. of q, k and the gate, and columns ip*D/2 + 4dg.. of v.  Ends with the
-    // operands in LDS; the caller places the barrier.  lg = log2|gamma_ip scale|, neg = its sign.
-    static __device__ __forceinline__ void prepare(const PrepAddr &pa, const float (&bl)[RPT][8], const RawQKV &rc,
-                                                   float lg, bool neg, bool scans, float &seg_log2_decay,
-                                                   PhaseClock &clk)
+    // ------------------------------------------------------------------------------------------------------
+    // Producer: gate scan and operand preparation of one step into operand set `set`.
+    // Lane (sg, dgl) of producer wavefront pw handles tokens 2sg, 2sg+1 and features 32 pw + 8 dgl .. + 7 of both
+    // states (and the same columns of v).  All 16 token pairs of a feature live in one wavefront, so the scan of
+    // the gates over the tokens needs no workgroup barrier.  `valid` = tokens of the step that exist (0: the whole
+    // step lies past the end: the operands written are never consumed and the segment decay is not touched).
+    // ------------------------------------------------------------------------------------------------------
+    template <class Loads>
+    static __device__ __forceinline__ void produce(uint32_t sm, uint32_t set, RawStep &r, int valid, int pw, int lane,
+                                                   const float (&lg)[2], const bool (&neg)[2], float &seg_log2_decay,
+                                                   const Loads &next, PhaseClock &clk)
     {
         clk.mark(0);
-        lds_barrier();
-        clk.mark(1);
-        if (scans) {   // thread u < D of a group scans feature u of its state over the token groups
-            float t[SG];
+        const uint32_t lo = opaque(static_cast<uint32_t>(lane));   // per-step copy: derived addresses stay short-lived
+        const uint32_t sg = lo >> 2, dgl = lo & 3;
+        const uint32_t f0 = 32 * pw + 8 * dgl;
+        const uint32_t csw = sm + O_CS + pw * 4096;
+        const uint32_t setb = sm + set * SET_BYTES;
+
+        if (valid < S) {   // ragged tail: tokens past the end act as "no decay, no key, no value"
 #pragma unroll
-            for (int s = 0; s < SG; ++s) t[s] = lds_ld<float>(pa.cs_c + s * D * 4);
+            for (int j = 0; j < RPT; ++j)
+                if (static_cast<int>(sg) * RPT + j >= valid) {
+                    r.g1[j].zero();
+                    r.g2[j].zero();
+                    r.k[j].zero();
+                    r.v[j].zero();
+                }
+        }
+
+        clk.mark(7);
+        float c[2][RPT][8];   // cumulative natural-log gates over this thread's tokens
+        {
+            float g[8];
+#pragma unroll
+            for (int j = 0; j < RPT; ++j) {
+                r.g1[j].unpack(g);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) c[0][j][e] = j ? c[0][j - 1][e] + g[e] : g[e];
+                r.g2[j].unpack(g);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) c[1][j][e] = j ? c[1][j - 1][e] + g[e] : g[e];
+            }
+        }
+        // totals of this token pair -> scan scratch [i][sg][feature in wavefront]
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint32_t a = csw + ((i * SGN + sg) * 32 + 8 * dgl) * 4;
+            lds_st<f32x4>(a, f32x4{c[i][RPT - 1][0], c[i][RPT - 1][1], c[i][RPT - 1][2], c[i][RPT - 1][3]});
+            lds_st<f32x4>(a + 16, f32x4{c[i][RPT - 1][4], c[i][RPT - 1][5], c[i][RPT - 1][6], c[i][RPT - 1][7]});
+        }
+        wave_sync();
+        clk.mark(6);
+        const uint32_t dec_a = setb + O_DEC + ((lo >> 5) * D + 32 * pw + (lo & 31)) * 4;
+        {   // lane l scans column (state l / 32, feature l % 32) over the 16 token pairs
+            const uint32_t col = csw + ((lo >> 5) * SGN * 32 + (lo & 31)) * 4;
+            float t[SGN];
+#pragma unroll
+            for (int s2 = 0; s2 < SGN; ++s2) t[s2] = lds_ld<float>(col + s2 * 32 * 4);
             float run = 0.f;
 #pragma unroll
-            for (int s = 0; s < SG; ++s) {
-                lds_st<float>(pa.cs_c + s * D * 4, run);
-                run += t[s];
+            for (int s2 = 0; s2 < SGN; ++s2) {
+                lds_st<float>(col + s2 * 32 * 4, run);
+                run += t[s2];
             }
             const float run2 = run * kLog2e;
-            lds_st<float>(pa.bc_w, run2);
-            lds_st<float>(pa.bc_w + (DEC - BC), __builtin_amdgcn_exp2f(run2));
-            seg_log2_decay += run2;
+            // log2 decay of the step: parked in the slot of the decay factor until the operands are done
+            lds_st<float>(dec_a, run2);
+            seg_log2_decay += (valid > 0) ? run2 : 0.f;
         }
-        lds_barrier();
-        clk.mark(2);
+        wave_sync();
+        clk.mark(1);
 
-        float pre2[8], bc[8];
-        {
-            const f32x4 p0 = lds_ld<f32x4>(pa.cs_w), p1 = lds_ld<f32x4>(pa.cs_w + 16);
-            const f32x4 c0 = lds_ld<f32x4>(pa.bc_r), c1 = lds_ld<f32x4>(pa.bc_r + 16);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                pre2[e] = p0[e] * kLog2e;   // log2 decay accumulated before this thread's first token
-                pre2[4 + e] = p1[e] * kLog2e;
-                bc[e] = c0[e];
-                bc[4 + e] = c1[e];
-            }
-        }
-        {   // ---- k: K^ = k 2^{bC - b} (token-contiguous) and K~ = K^ 2^{-bC} (row layout) ----
-            float ak[8], einv[8];
+        for (int i = 0; i < 2; ++i) {
+            float ak[8], aq[8];   // exponents (log2) of the K^ and Q' factors before this thread's first token
+            {
+                const uint32_t a = csw + ((i * SGN + sg) * 32 + 8 * dgl) * 4;
+                const f32x4 p0 = lds_ld<f32x4>(a), p1 = lds_ld<f32x4>(a + 16);
+                const uint32_t b = setb + O_DEC + (i * D + f0) * 4;
+                const f32x4 c0 = lds_ld<f32x4>(b), c1 = lds_ld<f32x4>(b + 16);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                ak[e] = bc[e] - pre2[e];
-                if (kFull) einv[e] = __builtin_amdgcn_exp2f(-bc[e]);
+                for (int e = 0; e < 4; ++e) {
+                    ak[e] = fmaf(p0[e], -kLog2e, c0[e]);   // bS - (log2 decay before this thread's first token)
+                    ak[4 + e] = fmaf(p1[e], -kLog2e, c1[e]);
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) aq[e] = lg[i] - ak[e];
             }
             Row8 khat[RPT];
 #pragma unroll
             for (int j = 0; j < RPT; ++j) {
-                float kf[8], kh[8];
-                rc.k[j].unpack(kf);
+                if (i == 0) next.at(4 * j);
+                if (i == 1) next.at(4 * j + 2);
+                {   // ---- K^ = k 2^{bS - b}: row layout for the scores, token-contiguous for the update ----
+                    float kf[8], kh[8];
+                    r.k[j].unpack(kf);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) kh[e] = kf[e] * __builtin_amdgcn_exp2f(fmaf(bl[j][e], -kLog2e, ak[e]));
-                khat[j] = A::pack_row(kh);
-                if (kFull) {
-                    float kt[8];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) kt[e] = kh[e] * einv[e];
-                    A::store_row(pa.qs_w + (KS - QS) + j * QP * ESZ, A::pack_row(kt));
+                    for (int e = 0; e < 8; ++e) kh[e] = kf[e] * __builtin_amdgcn_exp2f(fmaf(c[i][j][e], -kLog2e, ak[e]));
+                    khat[j] = A::pack_row(kh);
+                    if (kFull) A::store_row(setb + O_KS + ((sg * RPT + j) * QP + i * D + f0) * ESZ, khat[j]);
                 }
-                __builtin_amdgcn_sched_barrier(0);   // one token at a time: keeps the temporaries of a token short-lived
+                if (i == 0) next.at(4 * j + 1);
+                if (i == 1) next.at(4 * j + 3);
+                if (kFull) {   // ---- Q' = gamma_i scale q 2^{b - bS} ----
+                    float qf[8], qt[8];
+                    r.q[j].unpack(qf);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) qt[e] = qf[e] * __builtin_amdgcn_exp2f(fmaf(c[i][j][e], kLog2e, aq[e]));
+                    if (neg[i]) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) qt[e] = -qt[e];
+                    }
+                    A::store_row(setb + O_QS + ((sg * RPT + j) * QP + i * D + f0) * ESZ, A::pack_row(qt));
+                }
             }
-            // rows rho(feature): e = 0..3 -> kt_w0 + e rows, e = 4..7 -> kt_w1 + (e - 4) rows
+            // feature 8 dgl + e of the wavefront's 32 goes to row rho(.); the token pair to column rho(2 sg)
+            const uint32_t tcolb = rho(2 * sg) * ESZ;
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                A::template store_tokens<RPT>((e < 4 ? pa.kt_w0 : pa.kt_w1) + (e & 3) * TP * ESZ, khat, e);
-        }
-        if (kFull) {   // ---- q: Q~ = gamma_i scale q 2^{b} (row layout) ----
-#pragma unroll
-            for (int j = 0; j < RPT; ++j) {
-                float qf[8], qt[8];
-                rc.q[j].unpack(qf);
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    qt[e] = qf[e] * __builtin_amdgcn_exp2f(fmaf(bl[j][e], kLog2e, pre2[e] + lg));
-                if (neg) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) qt[e] = -qt[e];
-                }
-                A::store_row(pa.qs_w + j * QP * ESZ, A::pack_row(qt));
-                __builtin_amdgcn_sched_barrier(0);
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t row = i * D + 32 * pw + 16 * (dgl >> 1) + 8 * (e >> 2) + 4 * (dgl & 1) + (e & 3);
+                A::template store_tokens<RPT>(setb + O_KT + row * TP * ESZ + tcolb, khat, e);
             }
         }
-        // V transposed: this thread's VW columns (rows of Vt), RPT tokens each
+        next.at(8);
+        // 2^{bS} for the consumers: the lane that scanned column (i, f) replaces the log by the factor
+        lds_st<float>(dec_a, __builtin_amdgcn_exp2f(lds_ld<float>(dec_a)));
+        next.at(9);
+        // V transposed: columns 32 pw + 8 dgl .. + 7, the token pair at column rho(2 sg)
+        {
+            const uint32_t tcolb = rho(2 * sg) * ESZ;
 #pragma unroll
-        for (int e = 0; e < VW; ++e) store_v_tokens<RPT>(pa.vt_w + e * TP * ESZ, rc.v, e);
+            for (int e = 0; e < 8; ++e) store_v_tokens<RPT>(setb + O_VT + (f0 + e) * TP * ESZ + tcolb, r.v, e);
+        }
+        clk.mark(2);
+    }
+
+    // ------------------------------------------------------------------------------------------------------
+    // Consumer: all contractions of one step from operand set `set`.  acc[i][dt]: rows 32 dt .. of state i (Kt row
+    // order), columns 32 ct ...  Register j of lane (ln, g) holds feature 32 dt + 16 (j / 8) + 8 g + j % 8.
+    // ------------------------------------------------------------------------------------------------------
+    static __device__ __forceinline__ void consume(uint32_t sm, uint32_t set, f32x16 (&acc)[2][DT], int ct, int lane,
+                                                   TIO *orow, uint32_t rs, int valid, PhaseClock &clk)
+    {
+        clk.mark(0);
+        const uint32_t lo = opaque(static_cast<uint32_t>(lane));
+        const uint32_t ln = lo & 31, g = lo >> 5;
+        const uint32_t setb = sm + set * SET_BYTES;
+        const uint32_t vt_r = setb + O_VT + ((32 * ct + ln) * TP + 8 * g) * ESZ;
+        const uint32_t kt_r = setb + O_KT + (ln * TP + 8 * g) * ESZ;
+        const uint32_t dec_r = setb + O_DEC + (8 * g) * 4;
+
+        Frag vf[KB];   // V fragments of this wavefront's columns: input of the output and of the update
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb) vf[kb] = A::load_frag(vt_r + 16 * kb * ESZ);
+
+        // ---- decay the states over the step ----
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int dt2 = 0; dt2 < DT; dt2 += 2) {
+                f32x4 dd[2][4];
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int jb = 0; jb < 4; ++jb)
+                        dd[t][jb] = lds_ld<f32x4>(dec_r + (i * D + 32 * (dt2 + t) + 16 * (jb >> 1) + 4 * (jb & 1)) * 4);
+                asm volatile("" : "+v"(dd[0][0]), "+v"(dd[0][1]), "+v"(dd[0][2]), "+v"(dd[0][3]), "+v"(dd[1][0]),
+                             "+v"(dd[1][1]), "+v"(dd[1][2]), "+v"(dd[1][3]));
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[i][dt2 + t][4 * jb + e] *= dd[t][jb][e];
+            }
+        clk.mark(1);
+
+        if (kFull) {
+            const uint32_t qs_r = setb + O_QS + (ln * QP + 8 * g) * ESZ;
+            const uint32_t ks_r = setb + O_KS + (ln * QP + 8 * g) * ESZ;
+            // One pass over the 2 d_k features, 16 at a time, with the Q' fragment shared by two products:
+            //   sc[j]   = S^T[key 8(j/4) + 4g + j%4][query ln]        (Q' K^^T, both states blended)
+            //   oacc[j] = o^T[column 8(j/4) + 4g + j%4][query ln]     (carried states: the accumulators themselves
+            //                                                          are the input fragments)
+            f32x16 sc, oacc;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) sc[j] = oacc[j] = 0.f;
+            {
+                Frag held;   // the Ks fragment of a block waits here for its Qs partner
+                pipelined_steps<2 * NK, 8, A>(
+                    [&](int s2) -> uint32_t { return ((s2 & 1) ? qs_r : ks_r) + 16 * (s2 >> 1) * ESZ; },
+                    [&](int s2, const Frag &f) {
+                        if ((s2 & 1) == 0) {
+                            held = f;
+                        } else {
+                            const int kb = s2 >> 1, i = kb / (2 * DT), dt = (kb / 2) % DT, half = kb & 1;
+                            A::mma(sc, held, f);
+                            A::mma(oacc, A::from_acc(acc[i][dt], half), f);
+                        }
+                    });
+            }
+            clk.mark(2);
+            // keep key <= query; the two halves of the tile become the score fragments of the two token blocks
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const uint32_t key = 8 * (j >> 2) + 4 * g + (j & 3);
+                sc[j] = (key <= ln) ? sc[j] : 0.f;
+            }
+#pragma unroll
+            for (int kb = 0; kb < KB; ++kb) A::mma(oacc, vf[kb], A::from_acc(sc, kb));
+            // ---- store: lane (ln, g) holds query ln, columns 32 ct + 8 jb + 4 g .. + 3 ----
+            if (static_cast<int>(ln) < valid) {
+                TIO *op = orow + static_cast<size_t>(ln) * rs + 32 * ct + 4 * g;
+#pragma unroll
+                for (int jb = 0; jb < 4; ++jb)
+                    store4_global(op + 8 * jb, oacc[4 * jb], oacc[4 * jb + 1], oacc[4 * jb + 2], oacc[4 * jb + 3]);
+            }
+        }
+        clk.mark(3);
+
+        // ---- add K^^T V ----
+        {
+            constexpr int NS = KB * 2 * DT;   // (token block, state, tile)
+            pipelined_steps<NS, 4, A>(
+                [&](int s2) -> uint32_t {
+                    const int kb = s2 / (2 * DT), i = (s2 / DT) % 2, dt = s2 % DT;
+                    return kt_r + ((i * D + 32 * dt) * TP + 16 * kb) * ESZ;
+                },
+                [&](int s2, const Frag &f) {
+                    const int kb = s2 / (2 * DT), i = (s2 / DT) % 2, dt = s2 % DT;
+                    A::mma(acc[i][dt], f, vf[kb]);
+                });
+            constexpr int RD = ESZ == 2 ? 1 : 2, MM = ESZ == 2 ? 1 : 8;
+            __builtin_amdgcn_sched_group_barrier(0x100, 4 * RD, 0);
+#pragma unroll
+            for (int s2 = 0; s2 < NS - 4; ++s2) {
+                __builtin_amdgcn_sched_group_barrier(0x008, MM, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 4 * MM, 0);
+        }
+        clk.mark(4);
     }
 
     static __device__ void run(const PrefillArgs &a, uint32_t sm)
@@ -672,386 +749,156 @@ struct Kern {
         const int tid = threadIdx.x;
         const int lane = tid & 63;
         const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform, kept in scalar registers
-        const int ln = lane & 31, g = lane >> 5;
-        const int ct = wave % CT;                // column tile this wavefront owns in the contractions
-        // Work item of the workgroup and state of this wavefront.  Chunk loop: block = (bh, segment), state =
-        // wavefront group.  Pre-pass: block = (bh, segment, state); blocks 8 apart (same XCD, hence same L2
-        // under round-robin dispatch) handle the two states of one (bh, segment) and share its k and v lines.
-        const int nseg = kFull ? a.P : a.P - 1;
-        int unit, ip;
-        if (kFull) {
-            unit = blockIdx.x;
-            ip = wave / CT;
-        } else {
-            const int pairs = gridDim.x / 2;                      // (bh, segment) items
-            const int blk = blockIdx.x, grp16 = blk / 16, in16 = blk % 16;
-            if ((grp16 + 1) * 8 <= pairs) {                       // full 16-block group: 8 items x 2 states
-                unit = grp16 * 8 + in16 % 8;
-                ip = in16 / 8;
-            } else {                                              // tail: adjacent blocks pair up
-                const int rest = blk - grp16 * 16;
-                unit = grp16 * 8 + rest / 2;
-                ip = rest % 2;
-            }
-        }
-        const int ipl = kFull ? ip : 0;          // group index inside the workgroup (LDS layout)
-        const int u = tid - ipl * GT;            // index inside the group
-        const int dg = u % DG, sg = u / DG;
-
-        const int bh = unit / nseg;
-        const int p = unit % nseg;
-        const int bidx = bh / a.H, h = bh % a.H;
-        const int BH = (kFull ? gridDim.x : gridDim.x / 2) / nseg;
-
-        const int64_t t0 = static_cast<int64_t>(p) * a.seg_tokens;
-        const int64_t t1 = (t0 + a.seg_tokens < a.T) ? t0 + a.seg_tokens : a.T;
-        const uint32_t rs = static_cast<uint32_t>(a.H) * D;   // elements between consecutive tokens
-        // uniform element offset of (b, t0, h, 0); per-lane offsets are 32-bit
-        const size_t seg0 = (static_cast<size_t>(bidx) * a.T * a.H + h) * D + static_cast<size_t>(t0) * rs;
-        // per-lane element offsets of the global accesses; evaluated from an opaque copy of the thread index
-        // where they are used, so that they do not stay in registers across the other phases
-        auto lane_off = [&](uint32_t uo) -> uint32_t { return (uo / DG) * RPT * rs + (uo % DG) * 8; };
-        auto lane_voff = [&](uint32_t uo) -> uint32_t { return (uo / DG) * RPT * rs + ipl * (D / 2) + (uo % DG) * VW; };
-
-        const float gm = a.gamma_per_head ? a.gamma_per_head[h] : a.gamma;
-        const float gsv = (ip ? 1.0f - gm : gm) * a.scale;
-        const float lg = __builtin_amdgcn_logf(fabsf(gsv));
-        const bool neg = gsv < 0.f;
-
-        // ---- state accumulators: tile dt covers Kt rows 32dt..32dt+31 of state ip, columns 32*ct.. ----
-        // register j of lane (ln, g) holds state element (feature 32dt + 16(j/8) + 8g + j%8, column 32ct + ln)
-        f32x16 acc[DT];
-        const uint32_t sbase = static_cast<uint32_t>(8 * g) * D + 32 * ct + ln;  // lane part of the state offset
-        if (kFull) {
-            const float *src = (a.P > 1) ? a.ws_state + ((static_cast<size_t>(p) * BH + bh) * 2 + ip) * D * D
-                                         : (ip ? a.S2 : a.S1) + static_cast<size_t>(bh) * D * D;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) acc[dt][j] = src[sbase + (32 * dt + 16 * (j >> 3) + (j & 7)) * D];
-        } else {
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) acc[dt][j] = 0.f;
-        }
-
-        const int own = (RT == 2) ? ip : 0;   // query tile this wavefront finishes
-        // score tile of wavefronts 0..NTILE-1: RT = 1: (0,0); RT = 2: 0 -> (0,0), 1 -> (0,1), 2 -> (1,1)
-        const int sc_ts = (RT == 2 && wave == 2) ? 1 : 0;
-        const int sc_tr = (RT == 2 && wave >= 1) ? 1 : 0;
-
-        float seg_decay = 0.f;  // threads u < D: log2 of the segment decay of feature u of state ip
-        Ptrs ptr;
-        ptr.q = static_cast<const TIO *>(a.q) + seg0;
-        ptr.k = static_cast<const TIO *>(a.k) + seg0;
-        ptr.g = static_cast<const TG *>(ip ? a.g2 : a.g1) + seg0;
-        ptr.v = static_cast<const TIO *>(a.v) + seg0;
-        TIO *optr = static_cast<TIO *>(a.o) + seg0;
-        const size_t cstep = static_cast<size_t>(C) * rs;
-
-        if (kFull && RT == 2) {
-            // scores of keys 32..63 against queries 0..31 are in the future of every query: that block of As is
-            // never computed; it is cleared once so that the read-out can run over all key blocks unconditionally
-            for (int i = tid; i < 32 * 32 / 8; i += NT) {
-                const int r = i / 4, c8 = i % 4;
-                const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                A::store_row(sm + AS + (r * TP + 32 + 8 * c8) * ESZ, A::pack_row(z));
-            }
-        }
-        RawG rg;
-        int valid = (t1 - t0 >= C) ? C : static_cast<int>(t1 - t0);   // tokens of the current chunk
-        load_gates(rg, ptr.g, rs, valid, sg, lane_off(u));
-        Touched touched;
-#pragma unroll
-        for (int i = 0; i < TOUCH_N; ++i) touched.x[i] = 0;
-        float bl[RPT][8];   // cumulative log-gates of the current chunk (computed one iteration ahead)
-        gate_sums(bl, rg, sm + CS + ((ipl * SG + sg) * D + dg * 8) * 4);
         PhaseClock clk;
         clk.start();
 
-        for (int64_t tc = t0; tc < t1; tc += C) {
-            const bool has_next = tc + C < t1;
-            const int64_t left_next = t1 - (tc + C);
-            const int valid_next = has_next ? (left_next >= C ? C : static_cast<int>(left_next)) : 0;
-            {
-                // ---- this chunk's q/k/v: their lines wait in L2; first needed after the gate scan ----
-                RawQKV rc;
-                const uint32_t uo = opaque(static_cast<uint32_t>(u));
-                load_qkv(rc, ptr, rs, valid, sg, lane_off(uo), lane_voff(uo));
-                const PrepAddr pa = prep_addr(sm, ipl, uo);
-                prepare(pa, bl, rc, lg, neg, u < D, seg_decay, clk);
-            }
-            clk.mark(3);
-            lds_barrier();
-            clk.mark(4);
-            {
-                // ---- next chunk: gates into registers (used at the end of this iteration) and one touch per
-                //      line of its q/k/v rows, issued here where the memory pipeline is otherwise idle.  Past
-                //      the end of the segment valid_next is 0: nothing is read and the gates become zeros. ----
-                ptr.q += cstep; ptr.k += cstep; ptr.v += cstep; ptr.g += cstep;
-                load_gates(rg, ptr.g, rs, valid_next, sg, lane_off(opaque(static_cast<uint32_t>(u))));
-                if (!kFull) clk.mark(6);
-                touch_qkv(touched, ptr, rs, valid_next, opaque(static_cast<uint32_t>(tid)));
-                if (!kFull) clk.mark(8);
-                valid = valid_next;
-            }
+        const int nseg = kFull ? a.P : a.P - 1;
+        const int bh = blockIdx.x / nseg;
+        const int p = blockIdx.x % nseg;
+        const int bidx = bh / a.H, h = bh % a.H;
+        const int BH = gridDim.x / nseg;
 
-            // ---- per-lane LDS addresses of the contraction phases (derived per chunk, see prep_addr) ----
-            const uint32_t lq = opaque(static_cast<uint32_t>(lane));
-            const uint32_t lnq = lq & 31, gq = lq >> 5;
-            const uint32_t q_own = sm + QS + ((32 * own + lnq) * QP + ipl * D + 8 * gq) * ESZ;
-            const uint32_t q_oth = sm + QS + ((32 * (RT - 1 - own) + lnq) * QP + ipl * D + 8 * gq) * ESZ;
-            const uint32_t a_own = sm + AS + ((32 * own + lnq) * TP + 8 * gq) * ESZ;
-            uint32_t vt_r[KB], kt_r[KB];   // swizzled token blocks of this lane's Vt row / first Kt row
-            {
-                const uint32_t vrow = 32 * ct + lnq, krow = ipl * D + lnq;
-#pragma unroll
-                for (int kb = 0; kb < KB; ++kb) {
-                    vt_r[kb] = sm + VT + (vrow * TP + tcol(vrow, 16 * kb + 8 * gq)) * ESZ;
-                    kt_r[kb] = sm + KT + (krow * TP + tcol(krow, 16 * kb + 8 * gq)) * ESZ;
-                }
-            }
-            const uint32_t dec_r = sm + DEC + (ipl * D + 8 * gq) * 4;
+        const int64_t t0 = static_cast<int64_t>(p) * a.seg_tokens;
+        const int64_t t1 = (t0 + a.seg_tokens < a.T) ? t0 + a.seg_tokens : a.T;
+        const int ntok = static_cast<int>(t1 - t0);               // tokens of this segment (>= 1)
+        const int nsteps = (ntok + S - 1) / S;
+        const uint32_t rs = static_cast<uint32_t>(a.H) * D;       // elements between consecutive tokens
+        // uniform element offset of (b, t0, h, 0); per-lane offsets are 32-bit
+        const size_t seg0 = (static_cast<size_t>(bidx) * a.T * a.H + h) * D + static_cast<size_t>(t0) * rs;
+        const size_t sstep = static_cast<size_t>(S) * rs;
+        auto valid_of = [&](int n) -> int {   // tokens of step n that exist
+            const int left = ntok - n * S;
+            return left >= S ? S : (left > 0 ? left : 0);
+        };
+        // The step loop runs in pairs (set 0, set 1), so both roles pass the same number of barriers:
+        // 1 + 2 * ceil(nsteps / 2) with two sets, twice as many in the loop with one.
 
-            Frag sfr[kFull ? DT : 1][2];
-            if (kFull && wave < NTILE) {
-                // ---- scores, transposed: tile (ts, tr) holds S^T[s][r] for key tile ts <= query tile tr ----
-                f32x16 sc;
-#pragma unroll
-                for (int j = 0; j < 16; ++j) sc[j] = 0.f;
-                constexpr int NK = 2 * D / 16;
-                // addresses used once per chunk are derived here from a per-iteration opaque copy of the lane
-                // id, so that they do not occupy registers for the whole loop
-                const uint32_t l2 = opaque(static_cast<uint32_t>(lane));
-                const uint32_t lrow = (l2 & 31) * (QP * ESZ) + (l2 >> 5) * (8 * ESZ);
-                const uint32_t sc_k = sm + KS + 32 * sc_ts * QP * ESZ + lrow;
-                const uint32_t sc_q = sm + QS + 32 * sc_tr * QP * ESZ + lrow;
-                const uint32_t sc_w =
-                    sm + AS + (32 * sc_tr * TP + 32 * sc_ts) * ESZ + (l2 & 31) * (TP * ESZ) + (l2 >> 5) * (4 * ESZ);
-                {
-                    Frag held;   // the Ks fragment of a step waits here for its Qs partner
-                    pipelined_steps<2 * NK, 8, A>(
-                        [&](int s) -> uint32_t { return ((s & 1) ? sc_q : sc_k) + 16 * (s >> 1) * ESZ; },
-                        [&](int s, const Frag &f) {
-                            if ((s & 1) == 0)
-                                held = f;
-                            else
-                                A::mma(sc, held, f);
-                        });
-                    // requested order: the fragment pairs of 4 steps are read ahead of the MFMAs
-                    constexpr int RD = ESZ == 2 ? 1 : 2, MM = ESZ == 2 ? 1 : 8;
-                    __builtin_amdgcn_sched_group_barrier(0x100, 8 * RD, 0);
-#pragma unroll
-                    for (int i = 0; i < NK - 4; ++i) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, MM, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x100, 2 * RD, 0);
-                    }
-                    __builtin_amdgcn_sched_group_barrier(0x008, 4 * MM, 0);
-                }
-                // keep key <= query: key = 32 ts + 8 jb + 4 g + e, query = 32 tr + ln
-                const int dq = 32 * (sc_tr - sc_ts) + ln - 4 * g;
-#pragma unroll
-                for (int jb = 0; jb < 4; ++jb) {
-                    float x[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) x[e] = (8 * jb + e <= dq) ? sc[4 * jb + e] : 0.f;
-                    A::store4(sc_w + 8 * jb * ESZ, x[0], x[1], x[2], x[3]);
-                }
-            }
-            // ---- carried state: take its input fragments for the read-out, then decay its rows.  The decay
-            //      factors of two tiles (8 LDS reads) are requested together, ahead of the multiplies. ----
-#pragma unroll
-            for (int dt2 = 0; dt2 < DT; dt2 += 2) {
-                constexpr int NTL = (DT >= 2) ? 2 : 1;   // tiles per batch
-                f32x4 dd[NTL][4];
-#pragma unroll
-                for (int t = 0; t < NTL; ++t)
-#pragma unroll
-                    for (int jb = 0; jb < 4; ++jb)
-                        dd[t][jb] = lds_ld<f32x4>(dec_r + (32 * (dt2 + t) + 16 * (jb >> 1) + 4 * (jb & 1)) * 4);
-                // all reads of the batch are in flight before the first one is consumed
-                if constexpr (NTL == 2)
-                    asm volatile("" : "+v"(dd[0][0]), "+v"(dd[0][1]), "+v"(dd[0][2]), "+v"(dd[0][3]), "+v"(dd[1][0]),
-                                 "+v"(dd[1][1]), "+v"(dd[1][2]), "+v"(dd[1][3]));
-                else
-                    asm volatile("" : "+v"(dd[0][0]), "+v"(dd[0][1]), "+v"(dd[0][2]), "+v"(dd[0][3]));
-#pragma unroll
-                for (int t = 0; t < NTL; ++t) {
-                    const int dt = dt2 + t;
-                    if (kFull) {
-                        sfr[dt][0] = A::from_acc(acc[dt], 0);
-                        sfr[dt][1] = A::from_acc(acc[dt], 1);
-                    }
-#pragma unroll
-                    for (int jb = 0; jb < 4; ++jb)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[dt][4 * jb + e] *= dd[t][jb][e];
-                }
-            }
-            clk.mark(5);
-            if (kFull) lds_barrier();
-            clk.mark(6);
-
-            // ---- V fragments of this wavefront's columns (input of both the output and the update) ----
-            Frag vf[KB];
-#pragma unroll
-            for (int kb = 0; kb < KB; ++kb) vf[kb] = A::load_frag(vt_r[kb]);
-
-            // o_own: the query tile this wavefront finishes; o_oth: the tile the other group finishes (RT = 2)
-            f32x16 o_own, o_oth;
+        if (wave < CT) {
+            // =============================== consumer ===============================
+            const int ct = wave;
+            const int ln = lane & 31, g = lane >> 5;
+            f32x16 acc[2][DT];
+            const uint32_t sbase = static_cast<uint32_t>(8 * g) * D + 32 * ct + ln;   // lane part of the state offset
             if (kFull) {
-                // ---- partial output, transposed (o^T[column][query token]), summed over the features of
-                //      state ip; the other group adds its state ----
 #pragma unroll
-                for (int j = 0; j < 16; ++j) o_own[j] = o_oth[j] = 0.f;
-                {
-                    constexpr int NS = DT * 2;   // steps over (dt, half): 16 features each
-                    Frag f1 = A::load_frag(q_own), f2;
-                    if (RT == 2) f2 = A::load_frag(q_oth);
+                for (int i = 0; i < 2; ++i) {
+                    const float *src = (a.P > 1) ? a.ws_state + ((static_cast<size_t>(p) * BH + bh) * 2 + i) * D * D
+                                                 : (i ? a.S2 : a.S1) + static_cast<size_t>(bh) * D * D;
 #pragma unroll
-                    for (int s = 0; s < NS; ++s) {
-                        const Frag c1 = f1, c2 = f2;
-                        if (s + 1 < NS) {
-                            f1 = A::load_frag(q_own + 16 * (s + 1) * ESZ);
-                            if (RT == 2) f2 = A::load_frag(q_oth + 16 * (s + 1) * ESZ);
-                        }
-                        A::mma(o_own, sfr[s >> 1][s & 1], c1);
-                        if (RT == 2) A::mma(o_oth, sfr[s >> 1][s & 1], c2);
-                    }
+                    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) acc[i][dt][j] = src[sbase + (32 * dt + 16 * (j >> 3) + (j & 7)) * D];
                 }
-                // inside the chunk (key blocks in the future of the own query tile hold zeros)
-                if (RT == 2 || ip == 0) {
+            } else {
 #pragma unroll
-                    for (int kb = 0; kb < KB; ++kb) A::mma(o_own, vf[kb], A::load_frag(a_own + 16 * kb * ESZ));
-                }
-                // hand over what the other group finishes: X[slot][jb][lane] (float4 units), in Ks
-                const uint32_t x_w = sm + XB + (RT == 2 ? wave : ct) * 4096 + opaque(static_cast<uint32_t>(lane)) * 16;
-                if (RT == 2) {
+                for (int i = 0; i < 2; ++i)
 #pragma unroll
-                    for (int jb = 0; jb < 4; ++jb)
-                        lds_st<f32x4>(x_w + jb * 1024,
-                                      f32x4{o_oth[4 * jb], o_oth[4 * jb + 1], o_oth[4 * jb + 2], o_oth[4 * jb + 3]});
-                } else if (ip == 1) {
+                    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                    for (int jb = 0; jb < 4; ++jb)
-                        lds_st<f32x4>(x_w + jb * 1024,
-                                      f32x4{o_own[4 * jb], o_own[4 * jb + 1], o_own[4 * jb + 2], o_own[4 * jb + 3]});
-                }
-                if (RT == 2) {
-                    // requested order for this region: LDS reads run 6 fragments ahead of the MFMAs
-                    constexpr int RD = ESZ == 2 ? 1 : 2, MM = ESZ == 2 ? 1 : 8;
-                    constexpr int NRD = KB + DT * 2 * RT + KB, NMM = DT * 2 * RT + KB;
-                    __builtin_amdgcn_sched_group_barrier(0x100, 6 * RD, 0);
-#pragma unroll
-                    for (int i = 0; i < NRD - 6; ++i) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, MM, 0);
-                        __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
-                    }
-                    __builtin_amdgcn_sched_group_barrier(0x008, (NMM - (NRD - 6)) * MM, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x200, 4, 0);
-                }
+                        for (int j = 0; j < 16; ++j) acc[i][dt][j] = 0.f;
             }
-
-            clk.mark(7);
-            if (kFull) {
+            TIO *orow = static_cast<TIO *>(a.o) + seg0;
+            lds_barrier();   // operands of step 0 are ready
+            for (int n = 0; n < nsteps; n += 2) {
+                consume(sm, 0, acc, ct, lane, orow, rs, valid_of(n), clk);
+                orow += sstep;
+                lds_barrier();                    // step n consumed (two sets: and step n+1 ready)
+                if (SETS == 1) lds_barrier();     // one set: step n+1 ready
+                if (n + 1 < nsteps) {
+                    consume(sm, SETS - 1, acc, ct, lane, orow, rs, valid_of(n + 1), clk);
+                    orow += sstep;
+                }
                 lds_barrier();
-                clk.mark(8);
-                // ---- finish the own output tile: own part + the other group's, staged in Qs ----
-                if (RT == 2 || ip == 0) {
-                    const uint32_t l2 = opaque(static_cast<uint32_t>(lane));
-                    const uint32_t x_r = sm + XB + (RT == 2 ? (1 - ip) * CT + ct : ct) * 4096 + l2 * 16;
-                    const uint32_t os_w =
-                        sm + OS + (32 * own * OP + 32 * ct) * ESZ + (l2 & 31) * (OP * ESZ) + (l2 >> 5) * (4 * ESZ);
-#pragma unroll
-                    for (int jb = 0; jb < 4; ++jb) {
-                        const f32x4 x = lds_ld<f32x4>(x_r + jb * 1024);
-                        A::store4(os_w + 8 * jb * ESZ, o_own[4 * jb] + x[0], o_own[4 * jb + 1] + x[1],
-                                  o_own[4 * jb + 2] + x[2], o_own[4 * jb + 3] + x[3]);
-                    }
-                }
+                if (SETS == 1) lds_barrier();
             }
-            clk.mark(9);
-            // ---- state update: add K^^T V to the decayed state.  Tile dt starts 32 dt rows further; the
-            //      swizzle of odd tiles is that of even tiles with token blocks kb and kb^2 exchanged ----
-            {
-                constexpr int NS = KB * DT;
-                auto kaddr = [&](int s) -> uint32_t {
-                    const int dt = s % DT, kb = s / DT;
-                    const int sw = (NC16 == 8) ? (kb ^ (2 * (dt & 1))) : kb;
-                    return kt_r[sw] + 32 * dt * TP * ESZ;
-                };
-                pipelined_steps<NS, 4, A>(kaddr, [&](int s, const Frag &f) { A::mma(acc[s % DT], f, vf[s / DT]); });
-                // requested instruction order for this region: LDS reads run 4 fragments ahead of the MFMAs
-                constexpr int RD = ESZ == 2 ? 1 : 2;   // ds_read_b128 per fragment
-                constexpr int MM = ESZ == 2 ? 1 : 8;   // MFMA instructions per fragment pair
-                __builtin_amdgcn_sched_group_barrier(0x100, 4 * RD, 0);
-#pragma unroll
-                for (int s = 0; s < NS - 4; ++s) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, MM, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
-                }
-                __builtin_amdgcn_sched_group_barrier(0x008, 4 * MM, 0);
-            }
-            // ---- next chunk's gate sums: consumes the gates loaded at the top of this iteration, before the
-            //      output store is issued (a wait for a load would otherwise also wait for the stores) ----
-            {
-                // The gates must not be consumed earlier than here (their load would be waited for right after it
-                // was issued): the empty asm ties their registers to the last result of the update.
-#pragma unroll
-                for (int j = 0; j < RPT; ++j) rg.g[j].pin_after(acc[DT - 1][15]);
-                const uint32_t uo = opaque(static_cast<uint32_t>(u));
-                gate_sums(bl, rg, sm + CS + ((ipl * SG + uo / DG) * D + (uo % DG) * 8) * 4);
-                touch_use(touched);
-            }
-            clk.mark(10);
-            if (kFull) {
-                lds_barrier();
-                // ---- coalesced store of the staged output rows, 32 rows per pass ----
-                const uint32_t t2 = opaque(static_cast<uint32_t>(tid));
-                const uint32_t os_r = sm + OS + (t2 / DG) * (OP * ESZ) + (t2 % DG) * (8 * ESZ);
-                const uint32_t ooff = (t2 / DG) * rs + (t2 % DG) * 8;   // 32 rows per pass
-                const int64_t left = t1 - tc;
-#pragma unroll
-                for (int ps = 0; ps < RT; ++ps) {
-                    if (32 * ps + static_cast<int>(t2 / DG) < left)
-                        store8_global(optr + static_cast<size_t>(32 * ps) * rs, ooff, os_r + 32 * ps * OP * ESZ);
-                }
-                optr += cstep;
-                clk.mark(11);
-            }
-            // The next prepare() writes Qs/Ks/Kt/Vt/dec only after its first scan barrier, which no
-            // wavefront passes before every wavefront has finished the LDS reads above.
-        }
-
 #ifdef DSLA_PHASE_CLOCKS
-        clk.flush(a.dbg);
+            clk.flush(a.dbg);
 #endif
-        // ---- write the state out ----
-        float *dst = nullptr;
-        if (kFull) {
-            if (p == a.P - 1) dst = (ip ? a.S2 : a.S1) + static_cast<size_t>(bh) * D * D;
+            // ---- write the states out ----
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                float *dst = nullptr;
+                if (kFull) {
+                    if (p == a.P - 1) dst = (i ? a.S2 : a.S1) + static_cast<size_t>(bh) * D * D;
+                } else {
+                    // contribution of segment p goes to state slot p+1
+                    dst = a.ws_state + ((static_cast<size_t>(p + 1) * BH + bh) * 2 + i) * D * D;
+                }
+                if (dst) {
+                    const uint32_t sb = opaque(static_cast<uint32_t>(8 * g) * D + 32 * ct + ln);
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) dst[sb + (32 * dt + 16 * (j >> 3) + (j & 7)) * D] = acc[i][dt][j];
+                }
+            }
         } else {
-            // contribution of segment p goes to state slot p+1; its log2 decay to decay slot p
-            dst = a.ws_state + ((static_cast<size_t>(p + 1) * BH + bh) * 2 + ip) * D * D;
-            if (u < D) a.ws_decay[(static_cast<size_t>(p) * BH + bh) * 2 * D + ip * D + u] = seg_decay;
-        }
-        if (dst) {
-            // recomputed on purpose (opaque): keeping the 16 DT offsets of the initial load alive across the
-            // chunk loop would cost that many registers
-            const uint32_t sb = opaque(static_cast<uint32_t>(8 * g) * D + 32 * ct + ln);
+            // =============================== producer ===============================
+            const int pw = wave - CT;
+            const float gm = a.gamma_per_head ? a.gamma_per_head[h] : a.gamma;
+            const float gsv[2] = {gm * a.scale, (1.0f - gm) * a.scale};
+            const float lg[2] = {__builtin_amdgcn_logf(fabsf(gsv[0])), __builtin_amdgcn_logf(fabsf(gsv[1]))};
+            const bool neg[2] = {gsv[0] < 0.f, gsv[1] < 0.f};
+            float seg_decay = 0.f;   // lane l: log2 of the segment decay of (state l / 32, feature 32 pw + l % 32)
+
+            const TIO *q0 = static_cast<const TIO *>(a.q) + seg0, *k0 = static_cast<const TIO *>(a.k) + seg0,
+                      *v0 = static_cast<const TIO *>(a.v) + seg0;
+            const TG *g10 = static_cast<const TG *>(a.g1) + seg0, *g20 = static_cast<const TG *>(a.g2) + seg0;
+            auto src_of = [&](int n) -> StepSrc {   // step n, or the last step when n is past the end
+                const int m = n < nsteps ? n : nsteps - 1;
+                const size_t so = static_cast<size_t>(m) * sstep;
+                const int vm = valid_of(m);   // >= 1
+                StepSrc s;
+                s.q = q0 + so; s.k = k0 + so; s.v = v0 + so; s.g1 = g10 + so; s.g2 = g20 + so;
+                const uint32_t l = opaque(static_cast<uint32_t>(lane));
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int j = 0; j < 16; ++j) dst[sb + (32 * dt + 16 * (j >> 3) + (j & 7)) * D] = acc[dt][j];
+                for (int j = 0; j < RPT; ++j) {
+                    uint32_t row = (l >> 2) * RPT + j;
+                    row = row < static_cast<uint32_t>(vm) ? row : static_cast<uint32_t>(vm - 1);
+                    s.off[j] = row * rs + 32 * pw + 8 * (l & 3);
+                }
+                return s;
+            };
+            using AllLoads = std::make_integer_sequence<int, N_LOADS>;
+
+            // two register sets of raw inputs: while step m is prepared from one, step m+1 streams into the other
+            RawStep r0, r1;
+            load_all(r0, src_of(0), AllLoads{});
+            load_all(r1, src_of(1), AllLoads{});
+            produce(sm, 0, r0, valid_of(0), pw, lane, lg, neg, seg_decay, NoLoads{}, clk);
+            lds_barrier();   // operands of step 0 are ready
+            for (int n = 0; n < nsteps; n += 2) {
+                // consumers work on step n from set 0: prepare step n+1 into set 1 while step n+2 streams in
+                if (SETS == 1) lds_barrier();     // one set: wait until step n is consumed
+                clk.mark(5);
+                {
+                    const StepSrc nx = src_of(n + 2);
+                    produce(sm, SETS - 1, r1, valid_of(n + 1), pw, lane, lg, neg, seg_decay, NextLoads{r0, nx}, clk);
+                }
+                lds_barrier();
+                if (SETS == 1) lds_barrier();
+                clk.mark(5);
+                {
+                    const StepSrc nx = src_of(n + 3);
+                    produce(sm, 0, r0, valid_of(n + 2), pw, lane, lg, neg, seg_decay, NextLoads{r1, nx}, clk);
+                }
+                lds_barrier();
+            }
+#ifdef DSLA_PHASE_CLOCKS
+            clk.flush(a.dbg);
+#endif
+            if (!kFull) {
+                // log2 decay of segment p goes to decay slot p
+                a.ws_decay[(static_cast<size_t>(p) * BH + bh) * 2 * D + (lane >> 5) * D + 32 * pw + (lane & 31)] = seg_decay;
+            }
         }
     }
 };
 
-template <int D, int C, class TIO, class TG, bool kFull>
-__global__ __launch_bounds__(kFull ? 4 * D : 2 * D, kFull ? 2 : 3) void prefill_kernel(PrefillArgs a)
+template <int D, class TIO, class TG, bool kFull>
+__global__ __launch_bounds__(4 * D, 2) void prefill_kernel(PrefillArgs a)
 {
-    using K = Kern<D, C, TIO, TG, kFull>;
+    using K = Kern<D, TIO, TG, kFull>;
     __shared__ __attribute__((aligned(16))) char smem[K::LDS_BYTES];
     K::run(a, lds_addr_of(smem));
 }
@@ -1090,38 +937,47 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restri
     }
 }
 
-template <int D, int C, class TIO, class TG>
+#ifdef DSLA_PHASE_CLOCKS
+long long *clock_buffer(hipStream_t stream)
+{
+    static long long *dbg = nullptr;
+    if (!dbg) (void)hipMalloc(&dbg, 16 * 12 * sizeof(long long));
+    (void)hipMemsetAsync(dbg, 0, 16 * 12 * sizeof(long long), stream);
+    return dbg;
+}
+void clock_print(const char *what, const long long *dbg, int waves, hipStream_t stream)
+{
+    long long h[16 * 12];
+    (void)hipStreamSynchronize(stream);
+    (void)hipMemcpy(h, dbg, sizeof(h), hipMemcpyDeviceToHost);
+    for (int w = 0; w < waves; ++w) {
+        long long tot = 0;
+        for (int n = 0; n < 12; ++n) tot += h[w * 12 + n];
+        fprintf(stderr, "[%s clocks] wave %d total %lld:", what, w, tot);
+        for (int n = 0; n < 12; ++n) fprintf(stderr, " %d=%lld", n, h[w * 12 + n]);
+        fprintf(stderr, "\n");
+    }
+}
+#endif
+
+template <int D, class TIO, class TG>
 hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a, hipStream_t stream)
 {
     const int BH = d.B * d.H;
     hipError_t err;
     if (plan.segments > 1) {
 #ifdef DSLA_PHASE_CLOCKS
-        static long long *dbg1 = nullptr;
-        if (!dbg1) (void)hipMalloc(&dbg1, 16 * 12 * sizeof(long long));
-        (void)hipMemsetAsync(dbg1, 0, 16 * 12 * sizeof(long long), stream);
-        a.dbg = dbg1;
+        a.dbg = clock_buffer(stream);
 #endif
         {
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_STATE, stream);
-            hipLaunchKernelGGL((prefill_kernel<D, C, TIO, TG, false>), dim3(BH * (plan.segments - 1) * 2), dim3(2 * D),
-                               0, stream, a);
+            hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, false>), dim3(BH * (plan.segments - 1)), dim3(4 * D), 0,
+                               stream, a);
             err = hipGetLastError();
         }
         if (err != hipSuccess) return err;
 #ifdef DSLA_PHASE_CLOCKS
-        {
-            long long h[16 * 12];
-            (void)hipStreamSynchronize(stream);
-            (void)hipMemcpy(h, dbg1, sizeof(h), hipMemcpyDeviceToHost);
-            for (int w = 0; w < 4 * D / 64; w += 4) {
-                long long tot = 0;
-                for (int n = 0; n < 12; ++n) tot += h[w * 12 + n];
-                fprintf(stderr, "[segment_state clocks] wave %d total %lld:", w, tot);
-                for (int n = 0; n < 12; ++n) fprintf(stderr, " %d=%lld", n, h[w * 12 + n]);
-                fprintf(stderr, "\n");
-            }
-        }
+        clock_print("segment_state", a.dbg, D / 8, stream);
 #endif
         {
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_SCAN, stream);
@@ -1133,46 +989,30 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
         if (err != hipSuccess) return err;
     }
 #ifdef DSLA_PHASE_CLOCKS
-    static long long *dbg = nullptr;
-    if (!dbg) (void)hipMalloc(&dbg, 16 * 12 * sizeof(long long));
-    (void)hipMemsetAsync(dbg, 0, 16 * 12 * sizeof(long long), stream);
-    a.dbg = dbg;
+    a.dbg = clock_buffer(stream);
 #endif
     {
         ProfileScope ps(DSLA_KERNEL_PREFILL_CHUNK_LOOP, stream);
-        hipLaunchKernelGGL((prefill_kernel<D, C, TIO, TG, true>), dim3(BH * plan.segments), dim3(4 * D), 0, stream, a);
+        hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, true>), dim3(BH * plan.segments), dim3(4 * D), 0, stream, a);
     }
     err = hipGetLastError();
 #ifdef DSLA_PHASE_CLOCKS
-    {
-        long long h[16 * 12];
-        (void)hipStreamSynchronize(stream);
-        (void)hipMemcpy(h, dbg, sizeof(h), hipMemcpyDeviceToHost);
-        static const char *names[12] = {"prep:cumsum", "prep:B1", "prep:scan+B2", "prep:operands", "loads+B3", "scores+state",
-                                        "B4", "output", "B5", "finish", "loads+update", "B6+store"};
-        for (int w = 0; w < 4 * D / 64; ++w) {
-            long long tot = 0;
-            for (int n = 0; n < 12; ++n) tot += h[w * 12 + n];
-            fprintf(stderr, "[phase clocks] wave %d total %lld:", w, tot);
-            for (int n = 0; n < 12; ++n) fprintf(stderr, " %s=%lld", names[n], h[w * 12 + n]);
-            fprintf(stderr, "\n");
-        }
-    }
+    clock_print("chunk_loop", a.dbg, D / 8, stream);
 #endif
     return err;
 }
 
-template <int D, int C, class TIO>
+template <int D, class TIO>
 hipError_t launch_g(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a, hipStream_t stream)
 {
-    if (d.gate_dtype == DSLA_BF16) return launch_t<D, C, TIO, bf16_t>(d, plan, a, stream);
-    return launch_t<D, C, TIO, float>(d, plan, a, stream);
+    if (d.gate_dtype == DSLA_BF16) return launch_t<D, TIO, bf16_t>(d, plan, a, stream);
+    return launch_t<D, TIO, float>(d, plan, a, stream);
 }
 
+// The chunk length only sets the granularity of the segment split; the kernels step through 32 tokens at a time.
 bool combo_built(int D, int C, int io)
 {
-    if (io == DSLA_BF16) return (D == 64 || D == 128) && (C == 32 || C == 64);
-    return (D == 64 && (C == 32 || C == 64)) || (D == 128 && C == 32);
+    return (io == DSLA_BF16 || io == DSLA_F32) && (D == 64 || D == 128) && (C == 32 || C == 64);
 }
 
 }  // namespace
@@ -1233,16 +1073,13 @@ hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T
     a.P = plan.segments;
     a.gamma = d.gamma;
     a.scale = d.scale;
-    const int D = d.d_k, C = plan.chunk;
+    const int D = d.d_k;
     if (d.io_dtype == DSLA_BF16) {
-        if (D == 128 && C == 64) return launch_g<128, 64, bf16_t>(d, plan, a, stream);
-        if (D == 128 && C == 32) return launch_g<128, 32, bf16_t>(d, plan, a, stream);
-        if (D == 64 && C == 64) return launch_g<64, 64, bf16_t>(d, plan, a, stream);
-        if (D == 64 && C == 32) return launch_g<64, 32, bf16_t>(d, plan, a, stream);
+        if (D == 128) return launch_g<128, bf16_t>(d, plan, a, stream);
+        if (D == 64) return launch_g<64, bf16_t>(d, plan, a, stream);
     } else {
-        if (D == 64 && C == 64) return launch_g<64, 64, float>(d, plan, a, stream);
-        if (D == 64 && C == 32) return launch_g<64, 32, float>(d, plan, a, stream);
-        if (D == 128 && C == 32) return launch_g<128, 32, float>(d, plan, a, stream);
+        if (D == 128) return launch_g<128, float>(d, plan, a, stream);
+        if (D == 64) return launch_g<64, float>(d, plan, a, stream);
     }
     return hipErrorInvalidValue;
 }
