@@ -29,6 +29,10 @@
 
 #include "dsla_internal.h"
 
+#ifndef DSLA_EXP_MARK_SCHED
+#define DSLA_EXP_MARK_SCHED 0
+#endif
+
 namespace dsla {
 namespace {
 
@@ -74,7 +78,16 @@ struct PhaseClock {
 #else
 struct PhaseClock {
     __device__ __forceinline__ void start() {}
-    __device__ __forceinline__ void mark(int) {}
+    // A phase boundary also bounds instruction scheduling: moving work of one phase into another lengthens
+    // dependency stalls more often than it hides them (measured).
+    __device__ __forceinline__ void mark(int)
+    {
+#if DSLA_EXP_MARK_SCHED == 1
+        __builtin_amdgcn_sched_barrier(0);
+#elif DSLA_EXP_MARK_SCHED == 2
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#endif
+    }
 };
 #endif
 
@@ -144,6 +157,12 @@ struct ArithBf16 {
         return r;
     }
     static __device__ __forceinline__ void store_row(uint32_t a, const Row8 &r) { lds_st<u32x4>(a, r.u); }
+    static constexpr uint32_t kSignBits = 0x80008000u;   // sign bits of the two values of a packed word
+    static __device__ __forceinline__ Row8 flip_sign(Row8 r, uint32_t bits)   // bits: kSignBits or 0
+    {
+        r.u ^= u32x4{bits, bits, bits, bits};
+        return r;
+    }
     // element e of RPT consecutive tokens -> RPT adjacent LDS elements
     template <int RPT>
     static __device__ __forceinline__ void store_tokens(uint32_t a, const Row8 (&r)[RPT], int e)
@@ -202,6 +221,13 @@ struct ArithF32 {
     {
         lds_st<f32x4>(a, f32x4{r.x[0], r.x[1], r.x[2], r.x[3]});
         lds_st<f32x4>(a + 16, f32x4{r.x[4], r.x[5], r.x[6], r.x[7]});
+    }
+    static constexpr uint32_t kSignBits = 0x80000000u;
+    static __device__ __forceinline__ Row8 flip_sign(Row8 r, uint32_t bits)   // bits: kSignBits or 0
+    {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) r.x[e] = __uint_as_float(__float_as_uint(r.x[e]) ^ bits);
+        return r;
     }
     template <int RPT>
     static __device__ __forceinline__ void store_tokens(uint32_t a, const Row8 (&r)[RPT], int e)
@@ -391,6 +417,7 @@ struct PrefillArgs {
     int64_t seg_tokens;
     int H;
     int P;
+    int chunk_steps;         // 32-token steps per chunk
     float gamma, scale;
 #ifdef DSLA_PHASE_CLOCKS
     long long *dbg;
@@ -406,12 +433,27 @@ struct PrefillArgs {
 // preparation and the MFMA-bound contractions of neighbouring steps overlap.  A step is S = 32 tokens (a chunk
 // of 64 is two steps): two operand sets of 32 tokens fit in the 160 KB LDS, two sets of 64 do not.
 //
-// Step algebra (Section 4.1 unrolled over the S tokens of a step; b_s = log2 of the gate product from the first
-// token of the step up to and including token s, bS = b of the last token, all per state and feature):
-//     Q' = gamma_i scale q 2^{b - bS}        K^ = k 2^{bS - b}          (|K^| <= |k|, |Q'| <= |q| 2^{|bS|})
-//     state  <- diag(2^{bS}) state                                       (decay over the whole step, done first)
-//     o      =  Q' state  +  mask_{key <= query}(Q' K^^T) V              (both states in one contraction of width 2 d_k)
-//     state  <- state + K^^T V
+// Chunk algebra (Section 4.1 unrolled over the tokens of a chunk; b_s = log2 of the gate product from the first
+// token of the chunk up to and including token s, bC = b of the last token of the chunk, per state and feature;
+// T = the state in the frame of the chunk start: T = S at the chunk start):
+//     Q~ = gamma_i scale q 2^{b}             K~ = k 2^{-b}              (|Q~| <= |q|, |K~| <= |k| 2^{|bC|})
+//   per step of 32 tokens inside the chunk:
+//     o  =  Q~ T  +  mask_{key <= query}(Q~ K~^T) V                      (both states in one contraction of width 2 d_k)
+//     T <-  T + K~^T V
+//   after the last step of the chunk:
+//     S  =  diag(2^{bC}) T
+#ifndef DSLA_EXP_STORE_FIRST
+#define DSLA_EXP_STORE_FIRST 0
+#endif
+#ifndef DSLA_EXP_PRODUCER_FIRST
+#define DSLA_EXP_PRODUCER_FIRST 0
+#endif
+#ifndef DSLA_EXP_PRIO
+#define DSLA_EXP_PRIO 3
+#endif
+#ifndef DSLA_EXP_BALANCE
+#define DSLA_EXP_BALANCE 0
+#endif
 template <int D, class TIO, class TG, bool kFull>
 struct Kern {
     using A = ArithOf<TIO>;
@@ -443,7 +485,17 @@ struct Kern {
     // otherwise (fp32 at d = 128): the producers then only load ahead and prepare between two barriers.
     static constexpr int SETS = (2 * SET_BYTES + CT * 4096 <= LDS_MAX) ? 2 : 1;
     static constexpr uint32_t O_CS = SETS * SET_BYTES;                         // per producer wavefront: float [2][16][32]
-    static constexpr uint32_t LDS_BYTES = O_CS + CT * 4096;
+    // Output staging (16-bit io only): two buffers of S rows of d_v elements.  The consumers leave the output tile of
+    // a step here and write it to memory one step later as whole rows (a row is then complete: it has passed the
+    // barrier), which is what the memory system wants; 8-byte pieces straight from the accumulators cost a quarter
+    // of the kernel time.
+    static constexpr uint32_t LDS_NOSTAGE = O_CS + CT * 4096, LDS_STAGE = LDS_NOSTAGE + 2 * S * D * ESZ;
+    static constexpr bool kStage =   // only where it does not cost a resident workgroup
+        kFull && ESZ == 2 && LDS_STAGE <= LDS_MAX && LDS_MAX / LDS_STAGE == LDS_MAX / LDS_NOSTAGE;
+    static constexpr uint32_t O_ST = O_CS + CT * 4096;
+    static constexpr uint32_t ST_BYTES = S * D * ESZ;
+    static constexpr int NC = D * ESZ / 16;                                    // 16-byte pieces per output row
+    static constexpr uint32_t LDS_BYTES = O_ST + (kStage ? 2 * ST_BYTES : 0);
     static_assert(LDS_BYTES <= LDS_MAX, "LDS budget");
 
     // rho: bits 2 and 3 of an index swapped.  Features are stored in Kt rows in rho order and tokens in Kt / Vt
@@ -452,198 +504,379 @@ struct Kern {
     // MFMA input fragment read from 8 consecutive positions, so results are fed back as inputs without LDS.
     static __device__ __forceinline__ uint32_t rho(uint32_t x) { return (x & ~12u) | ((x & 4u) << 1) | ((x & 8u) >> 1); }
 
-    struct RawStep {   // inputs of one step as loaded (unconverted): this thread's 2 tokens x 8 features
+    // Inputs of one step as loaded (unconverted): this thread's 2 tokens x 8 features.
+    struct RawIO {
         Raw8<TIO> q[RPT], k[RPT], v[RPT];
+    };
+    struct RawGates {
         Raw8<TG> g1[RPT], g2[RPT];
     };
     // Where a producer lane reads a step from.  Loads are never predicated (the number of loads in flight stays
     // a compile-time fact, so waiting for the oldest never waits for the newest): a step past the end of the
-    // segment re-reads the last one and a token past the end re-reads the last token; produce() zeroes those.
+    // segment re-reads the last one and a token past the end re-reads the last token; the producer zeroes those.
     struct StepSrc {
         const TIO *q, *k, *v;   // uniform: first token of the step, this (batch, head)
         const TG *g1, *g2;
         uint32_t off[RPT];      // per lane: element offset of token 2 sg + j, features 32 pw + 8 dgl ..
     };
-    static constexpr int N_LOADS = (kFull ? 5 : 4) * RPT;
-    template <int IDX>
-    static __device__ __forceinline__ void load_one(RawStep &r, const StepSrc &s)
+    static __device__ __forceinline__ void load_gates(RawGates &g, const StepSrc &s)
     {
-        constexpr int j = IDX % RPT, ten = IDX / RPT;
-        if (ten == 0) r.g1[j].load(s.g1, s.off[j]);
-        if (ten == 1) r.g2[j].load(s.g2, s.off[j]);
-        if (ten == 2) r.k[j].load(s.k, s.off[j]);
-        if (ten == 3) r.v[j].load(s.v, s.off[j]);
-        if (ten == 4) r.q[j].load(s.q, s.off[j]);
+#pragma unroll
+        for (int j = 0; j < RPT; ++j) {
+            g.g1[j].load(s.g1, s.off[j]);
+            g.g2[j].load(s.g2, s.off[j]);
+        }
     }
-    template <int... I>
-    static __device__ __forceinline__ void load_all(RawStep &r, const StepSrc &s, std::integer_sequence<int, I...>)
+    static __device__ __forceinline__ void load_io(RawIO &r, const StepSrc &s)
     {
-        (load_one<I>(r, s), ...);
+#pragma unroll
+        for (int j = 0; j < RPT; ++j) {
+            r.k[j].load(s.k, s.off[j]);
+            if (kFull) r.q[j].load(s.q, s.off[j]);
+            r.v[j].load(s.v, s.off[j]);
+        }
     }
+    // The loads a producer issues while it prepares step m, one at a time between its stages: q, k, v of step
+    // m + 1 and the gates of step m + 3.  Slot numbers are constants after unrolling.
     struct NoLoads {
         __device__ __forceinline__ void at(int) const {}
     };
-    struct NextLoads {   // the loads of a later step, issued one at a time between the stages of produce()
-        RawStep &r;
-        const StepSrc &s;
-        template <int... I>
-        __device__ __forceinline__ void pick(int idx, std::integer_sequence<int, I...>) const
+    struct NextLoads {
+        RawIO &r;
+        const StepSrc &rs;
+        RawGates &g;
+        const StepSrc &gs;
+        __device__ __forceinline__ void at(int slot) const
         {
-            ((idx == I ? (load_one<I>(r, s), 0) : 0), ...);
+            if (slot == 0) g.g1[0].load(gs.g1, gs.off[0]);
+            if (slot == 1) g.g1[1].load(gs.g1, gs.off[1]);
+            if (slot == 2) g.g2[0].load(gs.g2, gs.off[0]);
+            if (slot == 3) g.g2[1].load(gs.g2, gs.off[1]);
+            if (slot == 4) r.k[0].load(rs.k, rs.off[0]);
+            if (slot == 5) r.k[1].load(rs.k, rs.off[1]);
+            if (slot == 6 && kFull) r.q[0].load(rs.q, rs.off[0]);
+            if (slot == 7 && kFull) r.q[1].load(rs.q, rs.off[1]);
+            if (slot == 8) r.v[0].load(rs.v, rs.off[0]);
+            if (slot == 9) r.v[1].load(rs.v, rs.off[1]);
         }
-        // idx is a constant after unrolling; slots beyond the loads of a step are empty
-        __device__ __forceinline__ void at(int idx) const { pick(idx, std::make_integer_sequence<int, N_LOADS>{}); }
+    };
+
+    // L2 prefetch of q, k, v: every producer thread reads 4 bytes of one 128-byte line (or a few) of a step that
+    // will be loaded two calls later, so that those loads find their lines in L2.  The value read is kept "in use"
+    // until the next prefetch is issued (its register must not be reused while the load is in flight).
+    static constexpr int PT = 64 * CT;                                       // producer threads
+    static constexpr int T_LPR = D * static_cast<int>(sizeof(TIO)) / 128;    // lines per token row
+    static constexpr int T_NTEN = kFull ? 3 : 2;                             // k, v, (q)
+    static constexpr int T_LINES = S * T_NTEN * T_LPR;
+    static constexpr int T_N = (T_LINES + PT - 1) / PT;
+    struct Touch {
+        const char *base[T_N];   // per lane: tensor (first token of the segment) + byte offset of the line in its row
+        uint32_t row[T_N];       // per lane: token row of the line
+        uint32_t x[T_N];         // values read by the last prefetch
+        __device__ __forceinline__ Touch(const TIO *q, const TIO *k, const TIO *v, int pu)
+        {
+#pragma unroll
+            for (int ps = 0; ps < T_N; ++ps) {
+                int L = ps * PT + pu;
+                L = L < T_LINES ? L : T_LINES - 1;
+                const int ten = L / (S * T_LPR), l = L % (S * T_LPR);
+                const TIO *t = ten == 0 ? k : (ten == 1 ? v : q);
+                base[ps] = reinterpret_cast<const char *>(t) + (l % T_LPR) * 128;
+                row[ps] = l / T_LPR;
+                x[ps] = 0;
+            }
+        }
+        // step_bytes: byte offset of the step's first token; valid >= 1: tokens of the step that exist
+        __device__ __forceinline__ void issue(size_t step_bytes, uint32_t row_bytes, int valid)
+        {
+#pragma unroll
+            for (int ps = 0; ps < T_N; ++ps) {
+                asm volatile("" ::"v"(x[ps]));   // the previous prefetch has landed before its register is reused
+                const uint32_t rw = row[ps] < static_cast<uint32_t>(valid) ? row[ps] : static_cast<uint32_t>(valid - 1);
+                x[ps] = *reinterpret_cast<const uint32_t *>(base[ps] + step_bytes + static_cast<size_t>(rw) * row_bytes);
+            }
+        }
+        __device__ __forceinline__ void finish() const
+        {
+#pragma unroll
+            for (int ps = 0; ps < T_N; ++ps) asm volatile("" ::"v"(x[ps]));
+        }
     };
 
     // wavefront-private LDS hand-over: the LDS pipeline runs the requests of one wavefront in order; only the
     // compiler has to be kept from moving accesses across
-    static __device__ __forceinline__ void wave_sync() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-
-    // ------------------------------------------------------------------------------------------------------
-    // Producer: gate scan and operand preparation of one step into operand set `set`.
-    // Lane (sg, dgl) of producer wavefront pw handles tokens 2sg, 2sg+1 and features 32 pw + 8 dgl .. + 7 of both
-    // states (and the same columns of v).  All 16 token pairs of a feature live in one wavefront, so the scan of
-    // the gates over the tokens needs no workgroup barrier.  `valid` = tokens of the step that exist (0: the whole
-    // step lies past the end: the operands written are never consumed and the segment decay is not touched).
-    // ------------------------------------------------------------------------------------------------------
-    template <class Loads>
-    static __device__ __forceinline__ void produce(uint32_t sm, uint32_t set, RawStep &r, int valid, int pw, int lane,
-                                                   const float (&lg)[2], const bool (&neg)[2], float &seg_log2_decay,
-                                                   const Loads &next, PhaseClock &clk)
+#ifndef DSLA_EXP_WAVE_SYNC
+#define DSLA_EXP_WAVE_SYNC 0
+#endif
+    static __device__ __forceinline__ void wave_sync()
     {
-        clk.mark(0);
-        const uint32_t lo = opaque(static_cast<uint32_t>(lane));   // per-step copy: derived addresses stay short-lived
-        const uint32_t sg = lo >> 2, dgl = lo & 3;
-        const uint32_t f0 = 32 * pw + 8 * dgl;
-        const uint32_t csw = sm + O_CS + pw * 4096;
-        const uint32_t setb = sm + set * SET_BYTES;
+#if DSLA_EXP_WAVE_SYNC == 2
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#elif DSLA_EXP_WAVE_SYNC == 1
+        asm volatile("" ::: "memory");
+#endif
+    }
 
-        if (valid < S) {   // ragged tail: tokens past the end act as "no decay, no key, no value"
+    // Per-lane LDS addresses of a producer (operand set 0; a set adds SET_BYTES), computed once.
+    // Lane (sg, dgl) of producer wavefront pw handles tokens 2sg, 2sg+1 and features 32 pw + 8 dgl .. + 7 of both
+    // states (and the same columns of v); for the scan over tokens lane l owns column (state l/32, feature l%32).
+    struct ProdAddr {
+        uint32_t tot;   // scan scratch [state][sg][feature]: this lane's 8 features of state 0 (state 1: + 2048)
+        uint32_t col;   // scan scratch: this lane's column, token pair 0
+        uint32_t dec;   // decay factor of this lane's column
+        uint32_t row;   // row-layout operands: token 2sg, element f0 (token + 1: + QP, state 1: + D elements)
+        uint32_t kt;    // Kt: row of feature e = 0 of state 0, column rho(2sg)
+        uint32_t vt;    // Vt: row of column f0, column rho(2sg)
+        uint32_t sg;
+        uint32_t state;   // state of the column this lane scans
+        __device__ __forceinline__ ProdAddr(uint32_t sm, int pw, uint32_t lane)
+        {
+            sg = lane >> 2;
+            state = lane >> 5;
+            const uint32_t dgl = lane & 3, f0 = 32 * pw + 8 * dgl;
+            const uint32_t csw = sm + O_CS + pw * 4096;
+            tot = csw + (sg * 32 + 8 * dgl) * 4;
+            col = csw + ((lane >> 5) * SGN * 32 + (lane & 31)) * 4;
+            dec = sm + O_DEC + ((lane >> 5) * D + 32 * pw + (lane & 31)) * 4;
+            row = sm + (sg * RPT * QP + f0) * ESZ;
+            // feature 8 dgl + e of the wavefront's 32 goes to row rho(8 dgl + e) = 16 (dgl/2) + 8 (e/4) + 4 (dgl%2) + e%4
+            kt = sm + O_KT + ((32 * pw + 16 * (dgl >> 1) + 4 * (dgl & 1)) * TP + rho(2 * sg)) * ESZ;
+            vt = sm + O_VT + (f0 * TP + rho(2 * sg)) * ESZ;
+        }
+    };
+
+    // ------------------------------------------------------------------------------------------------------
+    // Producer, gate scan of one step, in three stages with a wavefront-private LDS round trip between them.  All 16
+    // token pairs of a feature live in one wavefront, so the scan over the tokens needs no workgroup barrier.  The
+    // stages of step m + 1 are spread over the operand preparation of step m, which hides the round trips.
+    // ------------------------------------------------------------------------------------------------------
+    struct ScanOut {
+        float c[2][RPT][8];   // natural-log gate sums over this thread's tokens: c[i][j] = g[0] + .. + g[j]
+        float pre[2][8];      // natural-log gate sum from the first token of the chunk to before this thread's tokens
+    };
+    // stage A: sums over this thread's tokens; totals of the token pair -> scan scratch.
+    // `valid` = tokens of the step that exist; tokens past the end act as "no decay".
+    static __device__ __forceinline__ void scan_a(const ProdAddr &pa, RawGates &r, int valid, ScanOut &o)
+    {
+        if (valid < S) {
 #pragma unroll
             for (int j = 0; j < RPT; ++j)
-                if (static_cast<int>(sg) * RPT + j >= valid) {
+                if (static_cast<int>(pa.sg) * RPT + j >= valid) {
                     r.g1[j].zero();
                     r.g2[j].zero();
+                }
+        }
+        float g[8];
+#pragma unroll
+        for (int j = 0; j < RPT; ++j) {
+            r.g1[j].unpack(g);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o.c[0][j][e] = j ? o.c[0][j - 1][e] + g[e] : g[e];
+            r.g2[j].unpack(g);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o.c[1][j][e] = j ? o.c[1][j - 1][e] + g[e] : g[e];
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint32_t a = pa.tot + i * SGN * 32 * 4;
+            lds_st<f32x4>(a, f32x4{o.c[i][RPT - 1][0], o.c[i][RPT - 1][1], o.c[i][RPT - 1][2], o.c[i][RPT - 1][3]});
+            lds_st<f32x4>(a + 16, f32x4{o.c[i][RPT - 1][4], o.c[i][RPT - 1][5], o.c[i][RPT - 1][6], o.c[i][RPT - 1][7]});
+        }
+    }
+    // stage B: scan of this lane's column over the 16 token pairs, continuing the chunk.
+    // carry: natural-log gate sum of the column from the first token of the chunk to the end of the previous step;
+    // decf: decay factor of the chunk up to the end of this step (used when the step closes its chunk).
+    static __device__ __forceinline__ void scan_b_read(const ProdAddr &pa, float (&t)[SGN])
+    {
+        wave_sync();
+#pragma unroll
+        for (int s2 = 0; s2 < SGN; ++s2) t[s2] = lds_ld<float>(pa.col + s2 * 32 * 4);
+    }
+    static __device__ __forceinline__ void scan_b(const ProdAddr &pa, const float (&t)[SGN], int valid, uint32_t close_mask,
+                                                  float &carry, float &seg_log2_decay, float &decf)
+    {
+        const bool close = (close_mask >> pa.state) & 1u;   // does the chunk of this lane's state end with this step
+        float run = carry;
+#pragma unroll
+        for (int s2 = 0; s2 < SGN; ++s2) {
+            lds_st<float>(pa.col + s2 * 32 * 4, run);
+            run += t[s2];
+        }
+        decf = __builtin_amdgcn_exp2f(run * kLog2e);
+        if (valid > 0) {
+            seg_log2_decay += (run - carry) * kLog2e;
+            carry = close ? 0.f : run;
+        }
+    }
+    // stage C: the exclusive prefixes of this thread's token pair
+    static __device__ __forceinline__ void scan_c(const ProdAddr &pa, ScanOut &o)
+    {
+        wave_sync();
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint32_t a = pa.tot + i * SGN * 32 * 4;
+            const f32x4 p0 = lds_ld<f32x4>(a), p1 = lds_ld<f32x4>(a + 16);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                o.pre[i][e] = p0[e];
+                o.pre[i][4 + e] = p1[e];
+            }
+        }
+    }
+
+    // ------------------------------------------------------------------------------------------------------
+    // Producer, one call: operands of step m into operand set `set` from its inputs `r` and scan results `sc`, and,
+    // interleaved, the gate scan of step m + 1 (gates `gn` -> `sn`) and the loads of later steps (`next`).
+    // valid: of step m; valid_n / close_n: of step m + 1.  decf: in: decay factor computed by the scan of step m
+    // (written to the operand set); out: that of step m + 1.
+    // ------------------------------------------------------------------------------------------------------
+    template <class Loads>
+    static __device__ __forceinline__ void produce(const ProdAddr &pa, uint32_t set, RawIO &r, const ScanOut &sc, int valid,
+                                                   RawGates &gn, ScanOut &sn, int valid_n, uint32_t close_n,
+                                                   const float (&lg)[2], const uint32_t (&sgn)[2], float &carry,
+                                                   float &seg_log2_decay, float &decf, const Loads &next, PhaseClock &clk)
+    {
+        clk.mark(0);
+#ifdef DSLA_EXP_NO_PRODUCE
+        if (valid >= 0) return;
+#endif
+        const uint32_t so = set * SET_BYTES;
+        // decay from the start of the chunk to the end of this step; the consumers apply it when the chunk ends here
+        lds_st<float>(pa.dec + so, decf);
+        if (valid < S) {   // ragged tail: tokens past the end act as "no key, no value"
+#pragma unroll
+            for (int j = 0; j < RPT; ++j)
+                if (static_cast<int>(pa.sg) * RPT + j >= valid) {
                     r.k[j].zero();
                     r.v[j].zero();
                 }
         }
-
+        scan_a(pa, gn, valid_n, sn);
+        next.at(0);
+        next.at(1);
         clk.mark(7);
-        float c[2][RPT][8];   // cumulative natural-log gates over this thread's tokens
-        {
-            float g[8];
-#pragma unroll
-            for (int j = 0; j < RPT; ++j) {
-                r.g1[j].unpack(g);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) c[0][j][e] = j ? c[0][j - 1][e] + g[e] : g[e];
-                r.g2[j].unpack(g);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) c[1][j][e] = j ? c[1][j - 1][e] + g[e] : g[e];
-            }
-        }
-        // totals of this token pair -> scan scratch [i][sg][feature in wavefront]
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const uint32_t a = csw + ((i * SGN + sg) * 32 + 8 * dgl) * 4;
-            lds_st<f32x4>(a, f32x4{c[i][RPT - 1][0], c[i][RPT - 1][1], c[i][RPT - 1][2], c[i][RPT - 1][3]});
-            lds_st<f32x4>(a + 16, f32x4{c[i][RPT - 1][4], c[i][RPT - 1][5], c[i][RPT - 1][6], c[i][RPT - 1][7]});
-        }
-        wave_sync();
-        clk.mark(6);
-        const uint32_t dec_a = setb + O_DEC + ((lo >> 5) * D + 32 * pw + (lo & 31)) * 4;
-        {   // lane l scans column (state l / 32, feature l % 32) over the 16 token pairs
-            const uint32_t col = csw + ((lo >> 5) * SGN * 32 + (lo & 31)) * 4;
-            float t[SGN];
-#pragma unroll
-            for (int s2 = 0; s2 < SGN; ++s2) t[s2] = lds_ld<float>(col + s2 * 32 * 4);
-            float run = 0.f;
-#pragma unroll
-            for (int s2 = 0; s2 < SGN; ++s2) {
-                lds_st<float>(col + s2 * 32 * 4, run);
-                run += t[s2];
-            }
-            const float run2 = run * kLog2e;
-            // log2 decay of the step: parked in the slot of the decay factor until the operands are done
-            lds_st<float>(dec_a, run2);
-            seg_log2_decay += (valid > 0) ? run2 : 0.f;
-        }
-        wave_sync();
-        clk.mark(1);
 
+        Row8 kt[RPT];
+        auto block = [&](int i, int j, int slot_k, int slot_q) {
+            // log2 exponents of the factors before this thread's first token: K~ = k 2^{-b}, Q~ = gamma_i scale q 2^{b}
+            next.at(slot_k);
+            {   // row layout for the scores, token-contiguous (below) for the update
+                float kf[8], kh[8];
+                r.k[j].unpack(kf);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            float ak[8], aq[8];   // exponents (log2) of the K^ and Q' factors before this thread's first token
-            {
-                const uint32_t a = csw + ((i * SGN + sg) * 32 + 8 * dgl) * 4;
-                const f32x4 p0 = lds_ld<f32x4>(a), p1 = lds_ld<f32x4>(a + 16);
-                const uint32_t b = setb + O_DEC + (i * D + f0) * 4;
-                const f32x4 c0 = lds_ld<f32x4>(b), c1 = lds_ld<f32x4>(b + 16);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    ak[e] = fmaf(p0[e], -kLog2e, c0[e]);   // bS - (log2 decay before this thread's first token)
-                    ak[4 + e] = fmaf(p1[e], -kLog2e, c1[e]);
-                }
-#pragma unroll
-                for (int e = 0; e < 8; ++e) aq[e] = lg[i] - ak[e];
+                for (int e = 0; e < 8; ++e)
+                    kh[e] = kf[e] * __builtin_amdgcn_exp2f(-kLog2e * (sc.pre[i][e] + sc.c[i][j][e]));
+                kt[j] = A::pack_row(kh);
+                if (kFull) A::store_row(pa.row + so + O_KS + (j * QP + i * D) * ESZ, kt[j]);
             }
-            Row8 khat[RPT];
+            next.at(slot_q);
+            if (kFull) {
+                float qf[8], qt[8];
+                r.q[j].unpack(qf);
 #pragma unroll
-            for (int j = 0; j < RPT; ++j) {
-                if (i == 0) next.at(4 * j);
-                if (i == 1) next.at(4 * j + 2);
-                {   // ---- K^ = k 2^{bS - b}: row layout for the scores, token-contiguous for the update ----
-                    float kf[8], kh[8];
-                    r.k[j].unpack(kf);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) kh[e] = kf[e] * __builtin_amdgcn_exp2f(fmaf(c[i][j][e], -kLog2e, ak[e]));
-                    khat[j] = A::pack_row(kh);
-                    if (kFull) A::store_row(setb + O_KS + ((sg * RPT + j) * QP + i * D + f0) * ESZ, khat[j]);
-                }
-                if (i == 0) next.at(4 * j + 1);
-                if (i == 1) next.at(4 * j + 3);
-                if (kFull) {   // ---- Q' = gamma_i scale q 2^{b - bS} ----
-                    float qf[8], qt[8];
-                    r.q[j].unpack(qf);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) qt[e] = qf[e] * __builtin_amdgcn_exp2f(fmaf(c[i][j][e], kLog2e, aq[e]));
-                    if (neg[i]) {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) qt[e] = -qt[e];
-                    }
-                    A::store_row(setb + O_QS + ((sg * RPT + j) * QP + i * D + f0) * ESZ, A::pack_row(qt));
-                }
+                for (int e = 0; e < 8; ++e)
+                    qt[e] = qf[e] * __builtin_amdgcn_exp2f(fmaf(sc.pre[i][e] + sc.c[i][j][e], kLog2e, lg[i]));
+                A::store_row(pa.row + so + O_QS + (j * QP + i * D) * ESZ, A::flip_sign(A::pack_row(qt), sgn[i]));
             }
-            // feature 8 dgl + e of the wavefront's 32 goes to row rho(.); the token pair to column rho(2 sg)
-            const uint32_t tcolb = rho(2 * sg) * ESZ;
+        };
+        auto kt_rows = [&](int i) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const uint32_t row = i * D + 32 * pw + 16 * (dgl >> 1) + 8 * (e >> 2) + 4 * (dgl & 1) + (e & 3);
-                A::template store_tokens<RPT>(setb + O_KT + row * TP * ESZ + tcolb, khat, e);
-            }
-        }
-        next.at(8);
-        // 2^{bS} for the consumers: the lane that scanned column (i, f) replaces the log by the factor
-        lds_st<float>(dec_a, __builtin_amdgcn_exp2f(lds_ld<float>(dec_a)));
-        next.at(9);
-        // V transposed: columns 32 pw + 8 dgl .. + 7, the token pair at column rho(2 sg)
-        {
-            const uint32_t tcolb = rho(2 * sg) * ESZ;
+            for (int e = 0; e < 8; ++e)
+                A::template store_tokens<RPT>(pa.kt + so + ((i * D + 8 * (e >> 2) + (e & 3)) * TP) * ESZ, kt, e);
+        };
+
+        float t[SGN];
+        scan_b_read(pa, t);   // the answers arrive while the first block is computed
+        block(0, 0, 2, 3);
+        clk.mark(8);
+        scan_b(pa, t, valid_n, close_n, carry, seg_log2_decay, decf);
+        clk.mark(6);
+        block(0, 1, 4, 5);
+        clk.mark(9);
+        kt_rows(0);
+        scan_c(pa, sn);
+        clk.mark(1);
+        block(1, 0, 6, 7);
+        clk.mark(10);
+        block(1, 1, 8, 9);
+        clk.mark(11);
+        kt_rows(1);
+        // V transposed
 #pragma unroll
-            for (int e = 0; e < 8; ++e) store_v_tokens<RPT>(setb + O_VT + (f0 + e) * TP * ESZ + tcolb, r.v, e);
-        }
+        for (int e = 0; e < 8; ++e) store_v_tokens<RPT>(pa.vt + so + e * TP * ESZ, r.v, e);
         clk.mark(2);
     }
 
     // ------------------------------------------------------------------------------------------------------
     // Consumer: all contractions of one step from operand set `set`.  acc[i][dt]: rows 32 dt .. of state i (Kt row
     // order), columns 32 ct ...  Register j of lane (ln, g) holds feature 32 dt + 16 (j / 8) + 8 g + j % 8.
+    // Inside a chunk acc holds the state in the frame of the chunk start (see the step algebra above).
     // ------------------------------------------------------------------------------------------------------
+#ifndef DSLA_EXP_C_NOVALU
+#define DSLA_EXP_C_NOVALU 0
+#endif
+#ifndef DSLA_EXP_C_NOMFMA
+#define DSLA_EXP_C_NOMFMA 0
+#endif
+#ifndef DSLA_EXP_C_NOLDS
+#define DSLA_EXP_C_NOLDS 0
+#endif
+#ifndef DSLA_EXP_C_NOSTORE
+#define DSLA_EXP_C_NOSTORE 0
+#endif
+    struct AC : A {
+        static __device__ __forceinline__ Frag load_frag(uint32_t a)
+        {
+#if DSLA_EXP_C_NOLDS
+            Frag f;
+            __builtin_memset(&f, 0, sizeof(f));
+            asm volatile("" : "+v"(*reinterpret_cast<u32x4 *>(&f)) : "v"(a));
+            return f;
+#else
+            return A::load_frag(a);
+#endif
+        }
+    };
+    static __device__ __forceinline__ void cmma(f32x16 &acc, const Frag &a, const Frag &b)
+    {
+#if DSLA_EXP_C_NOMFMA
+        asm volatile("" ::"v"(*reinterpret_cast<const u32x4 *>(&a)), "v"(*reinterpret_cast<const u32x4 *>(&b)));
+#else
+        A::mma(acc, a, b);
+#endif
+    }
+    static __device__ __forceinline__ Frag cfrom(const f32x16 &acc, int half, const Frag &other)
+    {
+#if DSLA_EXP_C_NOVALU
+        return other;
+#else
+        return A::from_acc(acc, half);
+#endif
+    }
+    // Staged output rows of one step -> memory.  Consumer wavefront ct writes rows 32/CT * ct ..; a group of NC lanes
+    // writes one whole row.
+    static __device__ __forceinline__ void flush_rows(uint32_t sm, uint32_t parity, int ct, int lane, TIO *orow, uint32_t rs,
+                                                      int valid)
+    {
+        constexpr int RPI = 64 / NC;   // rows per instruction
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const uint32_t r = (S / CT) * ct + RPI * it + static_cast<uint32_t>(lane) / NC, c = static_cast<uint32_t>(lane) % NC;
+            const uint32_t a = sm + O_ST + parity * ST_BYTES + r * (D * ESZ) + ((c ^ (r & (NC - 1))) << 4);
+            const u32x4 x = lds_ld<u32x4>(a);
+            if (static_cast<int>(r) < valid)
+                *reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(orow) + (static_cast<size_t>(r) * rs * ESZ + c * 16)) = x;
+        }
+    }
+
     static __device__ __forceinline__ void consume(uint32_t sm, uint32_t set, f32x16 (&acc)[2][DT], int ct, int lane,
-                                                   TIO *orow, uint32_t rs, int valid, PhaseClock &clk)
+                                                   TIO *orow, uint32_t rs, int valid, uint32_t close_mask,
+                                                   uint32_t set_parity, PhaseClock &clk)
     {
         clk.mark(0);
+#ifdef DSLA_EXP_NO_CONSUME
+        if (valid >= 0) return;
+#endif
         const uint32_t lo = opaque(static_cast<uint32_t>(lane));
         const uint32_t ln = lo & 31, g = lo >> 5;
         const uint32_t setb = sm + set * SET_BYTES;
@@ -653,84 +886,59 @@ struct Kern {
 
         Frag vf[KB];   // V fragments of this wavefront's columns: input of the output and of the update
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) vf[kb] = A::load_frag(vt_r + 16 * kb * ESZ);
+        for (int kb = 0; kb < KB; ++kb) vf[kb] = AC::load_frag(vt_r + 16 * kb * ESZ);
 
-        // ---- decay the states over the step ----
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-#pragma unroll
-            for (int dt2 = 0; dt2 < DT; dt2 += 2) {
-                f32x4 dd[2][4];
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int jb = 0; jb < 4; ++jb)
-                        dd[t][jb] = lds_ld<f32x4>(dec_r + (i * D + 32 * (dt2 + t) + 16 * (jb >> 1) + 4 * (jb & 1)) * 4);
-                asm volatile("" : "+v"(dd[0][0]), "+v"(dd[0][1]), "+v"(dd[0][2]), "+v"(dd[0][3]), "+v"(dd[1][0]),
-                             "+v"(dd[1][1]), "+v"(dd[1][2]), "+v"(dd[1][3]));
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int jb = 0; jb < 4; ++jb)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[i][dt2 + t][4 * jb + e] *= dd[t][jb][e];
-            }
-        clk.mark(1);
-
+        f32x16 oacc;
         if (kFull) {
             const uint32_t qs_r = setb + O_QS + (ln * QP + 8 * g) * ESZ;
             const uint32_t ks_r = setb + O_KS + (ln * QP + 8 * g) * ESZ;
-            // One pass over the 2 d_k features, 16 at a time, with the Q' fragment shared by two products:
-            //   sc[j]   = S^T[key 8(j/4) + 4g + j%4][query ln]        (Q' K^^T, both states blended)
+            // One pass over the 2 d_k features, 16 at a time, with the Q~ fragment shared by two products:
+            //   sc[j]   = S^T[key 8(j/4) + 4g + j%4][query ln]        (Q~ K~^T, both states blended)
             //   oacc[j] = o^T[column 8(j/4) + 4g + j%4][query ln]     (carried states: the accumulators themselves
             //                                                          are the input fragments)
-            f32x16 sc, oacc;
+            f32x16 sc;
 #pragma unroll
             for (int j = 0; j < 16; ++j) sc[j] = oacc[j] = 0.f;
             {
                 Frag held;   // the Ks fragment of a block waits here for its Qs partner
-                pipelined_steps<2 * NK, 8, A>(
+                pipelined_steps<2 * NK, 8, AC>(
                     [&](int s2) -> uint32_t { return ((s2 & 1) ? qs_r : ks_r) + 16 * (s2 >> 1) * ESZ; },
                     [&](int s2, const Frag &f) {
                         if ((s2 & 1) == 0) {
                             held = f;
                         } else {
                             const int kb = s2 >> 1, i = kb / (2 * DT), dt = (kb / 2) % DT, half = kb & 1;
-                            A::mma(sc, held, f);
-                            A::mma(oacc, A::from_acc(acc[i][dt], half), f);
+                            cmma(sc, held, f);
+                            cmma(oacc, cfrom(acc[i][dt], half, held), f);
                         }
                     });
             }
             clk.mark(2);
             // keep key <= query; the two halves of the tile become the score fragments of the two token blocks
+#if !DSLA_EXP_C_NOVALU
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 const uint32_t key = 8 * (j >> 2) + 4 * g + (j & 3);
                 sc[j] = (key <= ln) ? sc[j] : 0.f;
             }
+#endif
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb) A::mma(oacc, vf[kb], A::from_acc(sc, kb));
-            // ---- store: lane (ln, g) holds query ln, columns 32 ct + 8 jb + 4 g .. + 3 ----
-            if (static_cast<int>(ln) < valid) {
-                TIO *op = orow + static_cast<size_t>(ln) * rs + 32 * ct + 4 * g;
-#pragma unroll
-                for (int jb = 0; jb < 4; ++jb)
-                    store4_global(op + 8 * jb, oacc[4 * jb], oacc[4 * jb + 1], oacc[4 * jb + 2], oacc[4 * jb + 3]);
-            }
+            for (int kb = 0; kb < KB; ++kb) cmma(oacc, vf[kb], cfrom(sc, kb, vf[kb]));
         }
         clk.mark(3);
+        __builtin_amdgcn_sched_barrier(0);   // the instruction groups requested below start here
 
-        // ---- add K^^T V ----
+        // ---- add K~^T V (the output tile finishes in the matrix pipeline meanwhile) ----
         {
             constexpr int NS = KB * 2 * DT;   // (token block, state, tile)
-            pipelined_steps<NS, 4, A>(
+            pipelined_steps<NS, 4, AC>(
                 [&](int s2) -> uint32_t {
                     const int kb = s2 / (2 * DT), i = (s2 / DT) % 2, dt = s2 % DT;
                     return kt_r + ((i * D + 32 * dt) * TP + 16 * kb) * ESZ;
                 },
                 [&](int s2, const Frag &f) {
                     const int kb = s2 / (2 * DT), i = (s2 / DT) % 2, dt = s2 % DT;
-                    A::mma(acc[i][dt], f, vf[kb]);
+                    cmma(acc[i][dt], f, vf[kb]);
                 });
             constexpr int RD = ESZ == 2 ? 1 : 2, MM = ESZ == 2 ? 1 : 8;
             __builtin_amdgcn_sched_group_barrier(0x100, 4 * RD, 0);
@@ -742,6 +950,45 @@ struct Kern {
             __builtin_amdgcn_sched_group_barrier(0x008, 4 * MM, 0);
         }
         clk.mark(4);
+
+        // ---- store: lane (ln, g) holds query ln, columns 32 ct + 8 jb + 4 g .. + 3 ----
+        if constexpr (kStage) {
+            // piece (row ln, 16-byte piece c) lives at piece position c ^ (ln mod NC) of its row
+            const uint32_t st_w = sm + O_ST + set_parity * ST_BYTES + ln * (D * ESZ) + 8 * g;
+#pragma unroll
+            for (int jb = 0; jb < 4; ++jb)
+                A::store4(st_w + (((4 * ct + jb) ^ (ln & (NC - 1))) << 4), oacc[4 * jb], oacc[4 * jb + 1], oacc[4 * jb + 2],
+                          oacc[4 * jb + 3]);
+        } else if (kFull && static_cast<int>(ln) < valid) {
+            TIO *op = orow + static_cast<size_t>(ln) * rs + 32 * ct + 4 * g;
+#pragma unroll
+            for (int jb = 0; jb < 4; ++jb)
+                store4_global(op + 8 * jb, oacc[4 * jb], oacc[4 * jb + 1], oacc[4 * jb + 2], oacc[4 * jb + 3]);
+        }
+
+        // ---- end of a chunk: the decay over the whole chunk brings a state to its own frame ----
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+            if (!DSLA_EXP_C_NOVALU && ((close_mask >> i) & 1u)) {
+#pragma unroll
+                for (int dt2 = 0; dt2 < DT; dt2 += 2) {
+                    f32x4 dd[2][4];
+#pragma unroll
+                    for (int t = 0; t < 2; ++t)
+#pragma unroll
+                        for (int jb = 0; jb < 4; ++jb)
+                            dd[t][jb] = lds_ld<f32x4>(dec_r + (i * D + 32 * (dt2 + t) + 16 * (jb >> 1) + 4 * (jb & 1)) * 4);
+                    asm volatile("" : "+v"(dd[0][0]), "+v"(dd[0][1]), "+v"(dd[0][2]), "+v"(dd[0][3]), "+v"(dd[1][0]),
+                                 "+v"(dd[1][1]), "+v"(dd[1][2]), "+v"(dd[1][3]));
+#pragma unroll
+                    for (int t = 0; t < 2; ++t)
+#pragma unroll
+                        for (int jb = 0; jb < 4; ++jb)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[i][dt2 + t][4 * jb + e] *= dd[t][jb][e];
+                }
+            }
+        clk.mark(1);
     }
 
     static __device__ void run(const PrefillArgs &a, uint32_t sm)
@@ -751,6 +998,9 @@ struct Kern {
         const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform, kept in scalar registers
         PhaseClock clk;
         clk.start();
+#ifdef DSLA_PHASE_CLOCKS
+        const long long wg_rt0 = __builtin_amdgcn_s_memrealtime(), wg_c0 = __builtin_amdgcn_s_memtime();
+#endif
 
         const int nseg = kFull ? a.P : a.P - 1;
         const int bh = blockIdx.x / nseg;
@@ -762,6 +1012,7 @@ struct Kern {
         const int64_t t1 = (t0 + a.seg_tokens < a.T) ? t0 + a.seg_tokens : a.T;
         const int ntok = static_cast<int>(t1 - t0);               // tokens of this segment (>= 1)
         const int nsteps = (ntok + S - 1) / S;
+        const int wsteps = a.chunk_steps;                          // steps per chunk (a segment starts a chunk)
         const uint32_t rs = static_cast<uint32_t>(a.H) * D;       // elements between consecutive tokens
         // uniform element offset of (b, t0, h, 0); per-lane offsets are 32-bit
         const size_t seg0 = (static_cast<size_t>(bidx) * a.T * a.H + h) * D + static_cast<size_t>(t0) * rs;
@@ -770,12 +1021,19 @@ struct Kern {
             const int left = ntok - n * S;
             return left >= S ? S : (left > 0 ? left : 0);
         };
+        // Which states end a chunk with step n (bit i = state i).  The chunks of state 1 are shifted by half a chunk
+        // against those of state 0, so that every step carries about the same decay work.
+        auto closes = [&](int n) -> uint32_t {
+            if (n + 1 >= nsteps) return 3u;
+            const uint32_t c0 = (n + 1) % wsteps == 0, c1 = (n + 1 + (DSLA_EXP_BALANCE ? wsteps / 2 : 0)) % wsteps == 0;
+            return c0 | (c1 << 1);
+        };
         // The step loop runs in pairs (set 0, set 1), so both roles pass the same number of barriers:
         // 1 + 2 * ceil(nsteps / 2) with two sets, twice as many in the loop with one.
 
-        if (wave < CT) {
+        if (DSLA_EXP_PRODUCER_FIRST ? wave >= CT : wave < CT) {
             // =============================== consumer ===============================
-            const int ct = wave;
+            const int ct = DSLA_EXP_PRODUCER_FIRST ? wave - CT : wave;
             const int ln = lane & 31, g = lane >> 5;
             f32x16 acc[2][DT];
             const uint32_t sbase = static_cast<uint32_t>(8 * g) * D + 32 * ct + ln;   // lane part of the state offset
@@ -800,19 +1058,32 @@ struct Kern {
             TIO *orow = static_cast<TIO *>(a.o) + seg0;
             lds_barrier();   // operands of step 0 are ready
             for (int n = 0; n < nsteps; n += 2) {
-                consume(sm, 0, acc, ct, lane, orow, rs, valid_of(n), clk);
+                if (kStage && n > 0) flush_rows(sm, 1, ct, lane, orow - sstep, rs, S);
+                consume(sm, 0, acc, ct, lane, orow, rs, valid_of(n), closes(n), 0, clk);
                 orow += sstep;
                 lds_barrier();                    // step n consumed (two sets: and step n+1 ready)
                 if (SETS == 1) lds_barrier();     // one set: step n+1 ready
                 if (n + 1 < nsteps) {
-                    consume(sm, SETS - 1, acc, ct, lane, orow, rs, valid_of(n + 1), clk);
+                    if (kStage) flush_rows(sm, 0, ct, lane, orow - sstep, rs, S);
+                    consume(sm, SETS - 1, acc, ct, lane, orow, rs, valid_of(n + 1), closes(n + 1), 1, clk);
                     orow += sstep;
                 }
                 lds_barrier();
                 if (SETS == 1) lds_barrier();
             }
+            // the last step (every staged row has passed a barrier)
+            if (kStage) flush_rows(sm, (nsteps - 1) & 1, ct, lane, orow - sstep, rs, valid_of(nsteps - 1));
 #ifdef DSLA_PHASE_CLOCKS
             clk.flush(a.dbg);
+            if (tid == 0 && kFull && a.dbg) {
+                long long *w = a.dbg + 16 * 12 + 4 * blockIdx.x;
+                w[0] = wg_rt0;
+                w[1] = __builtin_amdgcn_s_memrealtime();
+                w[2] = __builtin_amdgcn_s_memtime() - wg_c0;
+                uint32_t xcc;
+                asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+                w[3] = xcc & 0xf;
+            }
 #endif
             // ---- write the states out ----
 #pragma unroll
@@ -834,56 +1105,90 @@ struct Kern {
             }
         } else {
             // =============================== producer ===============================
-            const int pw = wave - CT;
+            // The producers are the critical path of a step; the consumers have slack.  Where both want the same
+            // issue slot the producer goes first.
+            __builtin_amdgcn_s_setprio(DSLA_EXP_PRIO);
+            const int pw = DSLA_EXP_PRODUCER_FIRST ? wave : wave - CT;
             const float gm = a.gamma_per_head ? a.gamma_per_head[h] : a.gamma;
             const float gsv[2] = {gm * a.scale, (1.0f - gm) * a.scale};
             const float lg[2] = {__builtin_amdgcn_logf(fabsf(gsv[0])), __builtin_amdgcn_logf(fabsf(gsv[1]))};
-            const bool neg[2] = {gsv[0] < 0.f, gsv[1] < 0.f};
+            const uint32_t sgn[2] = {gsv[0] < 0.f ? A::kSignBits : 0u, gsv[1] < 0.f ? A::kSignBits : 0u};
             float seg_decay = 0.f;   // lane l: log2 of the segment decay of (state l / 32, feature 32 pw + l % 32)
+            float carry = 0.f;       // lane l: natural-log gate sum of that column since the start of the chunk
+            const ProdAddr pa(sm, pw, static_cast<uint32_t>(lane));
 
             const TIO *q0 = static_cast<const TIO *>(a.q) + seg0, *k0 = static_cast<const TIO *>(a.k) + seg0,
                       *v0 = static_cast<const TIO *>(a.v) + seg0;
             const TG *g10 = static_cast<const TG *>(a.g1) + seg0, *g20 = static_cast<const TG *>(a.g2) + seg0;
+            const uint32_t lane_col = 32 * pw + 8 * (lane & 3);
             auto src_of = [&](int n) -> StepSrc {   // step n, or the last step when n is past the end
                 const int m = n < nsteps ? n : nsteps - 1;
                 const size_t so = static_cast<size_t>(m) * sstep;
                 const int vm = valid_of(m);   // >= 1
                 StepSrc s;
                 s.q = q0 + so; s.k = k0 + so; s.v = v0 + so; s.g1 = g10 + so; s.g2 = g20 + so;
-                const uint32_t l = opaque(static_cast<uint32_t>(lane));
 #pragma unroll
                 for (int j = 0; j < RPT; ++j) {
-                    uint32_t row = (l >> 2) * RPT + j;
+                    uint32_t row = pa.sg * RPT + j;
                     row = row < static_cast<uint32_t>(vm) ? row : static_cast<uint32_t>(vm - 1);
-                    s.off[j] = row * rs + 32 * pw + 8 * (l & 3);
+                    s.off[j] = row * rs + lane_col;
                 }
                 return s;
             };
-            using AllLoads = std::make_integer_sequence<int, N_LOADS>;
 
-            // two register sets of raw inputs: while step m is prepared from one, step m+1 streams into the other
-            RawStep r0, r1;
-            load_all(r0, src_of(0), AllLoads{});
-            load_all(r1, src_of(1), AllLoads{});
-            produce(sm, 0, r0, valid_of(0), pw, lane, lg, neg, seg_decay, NoLoads{}, clk);
+            // Software pipeline over the steps, two of everything (even / odd step): while the operands of step m are
+            // prepared, q, k, v of step m + 1 stream in, the gates of step m + 1 are scanned and those of step m + 3
+            // stream in.
+            RawIO r0, r1;
+            RawGates g0, g1;
+            ScanOut s0, s1;
+            float decf = 1.f;
+            Touch touch(q0, k0, v0, 64 * pw + lane);
+            auto prefetch = [&](int n) {   // step n, or the last step when n is past the end
+                const int m = n < nsteps ? n : nsteps - 1;
+                touch.issue(static_cast<size_t>(m) * sstep * sizeof(TIO), rs * static_cast<uint32_t>(sizeof(TIO)), valid_of(m));
+            };
+            prefetch(2);
+            load_gates(g0, src_of(0));
+            load_gates(g1, src_of(1));
+            load_io(r0, src_of(0));
+            scan_a(pa, g0, valid_of(0), s0);
+            {
+                float t[SGN];
+                scan_b_read(pa, t);
+                scan_b(pa, t, valid_of(0), closes(0), carry, seg_decay, decf);
+            }
+            scan_c(pa, s0);
+            load_gates(g0, src_of(2));
+            {
+                const StepSrc io = src_of(1), gs = src_of(3);
+                produce(pa, 0, r0, s0, valid_of(0), g1, s1, valid_of(1), closes(1), lg, sgn, carry, seg_decay,
+                        decf, NextLoads{r1, io, g1, gs}, clk);
+                prefetch(3);
+            }
             lds_barrier();   // operands of step 0 are ready
             for (int n = 0; n < nsteps; n += 2) {
-                // consumers work on step n from set 0: prepare step n+1 into set 1 while step n+2 streams in
+                // consumers work on step n from set 0: prepare step n+1 into set 1
                 if (SETS == 1) lds_barrier();     // one set: wait until step n is consumed
                 clk.mark(5);
                 {
-                    const StepSrc nx = src_of(n + 2);
-                    produce(sm, SETS - 1, r1, valid_of(n + 1), pw, lane, lg, neg, seg_decay, NextLoads{r0, nx}, clk);
+                    const StepSrc io = src_of(n + 2), gs = src_of(n + 4);
+                    produce(pa, SETS - 1, r1, s1, valid_of(n + 1), g0, s0, valid_of(n + 2), closes(n + 2), lg,
+                            sgn, carry, seg_decay, decf, NextLoads{r0, io, g0, gs}, clk);
+                    prefetch(n + 4);
                 }
                 lds_barrier();
                 if (SETS == 1) lds_barrier();
                 clk.mark(5);
                 {
-                    const StepSrc nx = src_of(n + 3);
-                    produce(sm, 0, r0, valid_of(n + 2), pw, lane, lg, neg, seg_decay, NextLoads{r1, nx}, clk);
+                    const StepSrc io = src_of(n + 3), gs = src_of(n + 5);
+                    produce(pa, 0, r0, s0, valid_of(n + 2), g1, s1, valid_of(n + 3), closes(n + 3), lg, sgn,
+                            carry, seg_decay, decf, NextLoads{r1, io, g1, gs}, clk);
+                    prefetch(n + 5);
                 }
                 lds_barrier();
             }
+            touch.finish();
 #ifdef DSLA_PHASE_CLOCKS
             clk.flush(a.dbg);
 #endif
@@ -941,15 +1246,23 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restri
 long long *clock_buffer(hipStream_t stream)
 {
     static long long *dbg = nullptr;
-    if (!dbg) (void)hipMalloc(&dbg, 16 * 12 * sizeof(long long));
-    (void)hipMemsetAsync(dbg, 0, 16 * 12 * sizeof(long long), stream);
+    if (!dbg) (void)hipMalloc(&dbg, (16 * 12 + 4 * 2048) * sizeof(long long));
+    (void)hipMemsetAsync(dbg, 0, (16 * 12 + 4 * 2048) * sizeof(long long), stream);
     return dbg;
 }
-void clock_print(const char *what, const long long *dbg, int waves, hipStream_t stream)
+void clock_print(const char *what, const long long *dbg, int waves, hipStream_t stream, int nwg = 0)
 {
-    long long h[16 * 12];
+    static long long h[16 * 12 + 4 * 2048];
     (void)hipStreamSynchronize(stream);
     (void)hipMemcpy(h, dbg, sizeof(h), hipMemcpyDeviceToHost);
+    if (nwg > 0 && nwg <= 2048) {
+        long long t0 = h[16 * 12];
+        for (int w = 0; w < nwg; ++w) t0 = h[16 * 12 + 4 * w] < t0 ? h[16 * 12 + 4 * w] : t0;
+        fprintf(stderr, "[%s workgroups] start/end in 10ns units after the first start, duration in shader clocks\n", what);
+        for (int w = 0; w < nwg; ++w)
+            fprintf(stderr, "  wg %4d xcc %lld: %6lld .. %6lld  clocks %lld\n", w, h[16 * 12 + 4 * w + 3], h[16 * 12 + 4 * w] - t0,
+                    h[16 * 12 + 4 * w + 1] - t0, h[16 * 12 + 4 * w + 2]);
+    }
     for (int w = 0; w < waves; ++w) {
         long long tot = 0;
         for (int n = 0; n < 12; ++n) tot += h[w * 12 + n];
@@ -997,7 +1310,7 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
     }
     err = hipGetLastError();
 #ifdef DSLA_PHASE_CLOCKS
-    clock_print("chunk_loop", a.dbg, D / 8, stream);
+    clock_print("chunk_loop", a.dbg, D / 8, stream, BH * plan.segments);
 #endif
     return err;
 }
@@ -1071,6 +1384,7 @@ hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T
     a.seg_tokens = plan.segment_tokens;
     a.H = d.H;
     a.P = plan.segments;
+    a.chunk_steps = plan.chunk / 32;
     a.gamma = d.gamma;
     a.scale = d.scale;
     const int D = d.d_k;
