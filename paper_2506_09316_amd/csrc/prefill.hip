@@ -29,10 +29,6 @@
 
 #include "dsla_internal.h"
 
-#ifndef DSLA_EXP_MARK_SCHED
-#define DSLA_EXP_MARK_SCHED 0
-#endif
-
 namespace dsla {
 namespace {
 
@@ -78,16 +74,7 @@ struct PhaseClock {
 #else
 struct PhaseClock {
     __device__ __forceinline__ void start() {}
-    // A phase boundary also bounds instruction scheduling: moving work of one phase into another lengthens
-    // dependency stalls more often than it hides them (measured).
-    __device__ __forceinline__ void mark(int)
-    {
-#if DSLA_EXP_MARK_SCHED == 1
-        __builtin_amdgcn_sched_barrier(0);
-#elif DSLA_EXP_MARK_SCHED == 2
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#endif
-    }
+    __device__ __forceinline__ void mark(int) {}
 };
 #endif
 
@@ -442,18 +429,6 @@ struct PrefillArgs {
 //     T <-  T + K~^T V
 //   after the last step of the chunk:
 //     S  =  diag(2^{bC}) T
-#ifndef DSLA_EXP_STORE_FIRST
-#define DSLA_EXP_STORE_FIRST 0
-#endif
-#ifndef DSLA_EXP_PRODUCER_FIRST
-#define DSLA_EXP_PRODUCER_FIRST 0
-#endif
-#ifndef DSLA_EXP_PRIO
-#define DSLA_EXP_PRIO 3
-#endif
-#ifndef DSLA_EXP_BALANCE
-#define DSLA_EXP_BALANCE 0
-#endif
 template <int D, class TIO, class TG, bool kFull>
 struct Kern {
     using A = ArithOf<TIO>;
@@ -561,61 +536,9 @@ struct Kern {
         }
     };
 
-    // L2 prefetch of q, k, v: every producer thread reads 4 bytes of one 128-byte line (or a few) of a step that
-    // will be loaded two calls later, so that those loads find their lines in L2.  The value read is kept "in use"
-    // until the next prefetch is issued (its register must not be reused while the load is in flight).
-    static constexpr int PT = 64 * CT;                                       // producer threads
-    static constexpr int T_LPR = D * static_cast<int>(sizeof(TIO)) / 128;    // lines per token row
-    static constexpr int T_NTEN = kFull ? 3 : 2;                             // k, v, (q)
-    static constexpr int T_LINES = S * T_NTEN * T_LPR;
-    static constexpr int T_N = (T_LINES + PT - 1) / PT;
-    struct Touch {
-        const char *base[T_N];   // per lane: tensor (first token of the segment) + byte offset of the line in its row
-        uint32_t row[T_N];       // per lane: token row of the line
-        uint32_t x[T_N];         // values read by the last prefetch
-        __device__ __forceinline__ Touch(const TIO *q, const TIO *k, const TIO *v, int pu)
-        {
-#pragma unroll
-            for (int ps = 0; ps < T_N; ++ps) {
-                int L = ps * PT + pu;
-                L = L < T_LINES ? L : T_LINES - 1;
-                const int ten = L / (S * T_LPR), l = L % (S * T_LPR);
-                const TIO *t = ten == 0 ? k : (ten == 1 ? v : q);
-                base[ps] = reinterpret_cast<const char *>(t) + (l % T_LPR) * 128;
-                row[ps] = l / T_LPR;
-                x[ps] = 0;
-            }
-        }
-        // step_bytes: byte offset of the step's first token; valid >= 1: tokens of the step that exist
-        __device__ __forceinline__ void issue(size_t step_bytes, uint32_t row_bytes, int valid)
-        {
-#pragma unroll
-            for (int ps = 0; ps < T_N; ++ps) {
-                asm volatile("" ::"v"(x[ps]));   // the previous prefetch has landed before its register is reused
-                const uint32_t rw = row[ps] < static_cast<uint32_t>(valid) ? row[ps] : static_cast<uint32_t>(valid - 1);
-                x[ps] = *reinterpret_cast<const uint32_t *>(base[ps] + step_bytes + static_cast<size_t>(rw) * row_bytes);
-            }
-        }
-        __device__ __forceinline__ void finish() const
-        {
-#pragma unroll
-            for (int ps = 0; ps < T_N; ++ps) asm volatile("" ::"v"(x[ps]));
-        }
-    };
-
     // wavefront-private LDS hand-over: the LDS pipeline runs the requests of one wavefront in order; only the
     // compiler has to be kept from moving accesses across
-#ifndef DSLA_EXP_WAVE_SYNC
-#define DSLA_EXP_WAVE_SYNC 0
-#endif
-    static __device__ __forceinline__ void wave_sync()
-    {
-#if DSLA_EXP_WAVE_SYNC == 2
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#elif DSLA_EXP_WAVE_SYNC == 1
-        asm volatile("" ::: "memory");
-#endif
-    }
+    static __device__ __forceinline__ void wave_sync() { asm volatile("" ::: "memory"); }
 
     // Per-lane LDS addresses of a producer (operand set 0; a set adds SET_BYTES), computed once.
     // Lane (sg, dgl) of producer wavefront pw handles tokens 2sg, 2sg+1 and features 32 pw + 8 dgl .. + 7 of both
@@ -737,9 +660,6 @@ struct Kern {
                                                    float &seg_log2_decay, float &decf, const Loads &next, PhaseClock &clk)
     {
         clk.mark(0);
-#ifdef DSLA_EXP_NO_PRODUCE
-        if (valid >= 0) return;
-#endif
         const uint32_t so = set * SET_BYTES;
         // decay from the start of the chunk to the end of this step; the consumers apply it when the chunk ends here
         lds_st<float>(pa.dec + so, decf);
@@ -812,47 +732,6 @@ struct Kern {
     // order), columns 32 ct ...  Register j of lane (ln, g) holds feature 32 dt + 16 (j / 8) + 8 g + j % 8.
     // Inside a chunk acc holds the state in the frame of the chunk start (see the step algebra above).
     // ------------------------------------------------------------------------------------------------------
-#ifndef DSLA_EXP_C_NOVALU
-#define DSLA_EXP_C_NOVALU 0
-#endif
-#ifndef DSLA_EXP_C_NOMFMA
-#define DSLA_EXP_C_NOMFMA 0
-#endif
-#ifndef DSLA_EXP_C_NOLDS
-#define DSLA_EXP_C_NOLDS 0
-#endif
-#ifndef DSLA_EXP_C_NOSTORE
-#define DSLA_EXP_C_NOSTORE 0
-#endif
-    struct AC : A {
-        static __device__ __forceinline__ Frag load_frag(uint32_t a)
-        {
-#if DSLA_EXP_C_NOLDS
-            Frag f;
-            __builtin_memset(&f, 0, sizeof(f));
-            asm volatile("" : "+v"(*reinterpret_cast<u32x4 *>(&f)) : "v"(a));
-            return f;
-#else
-            return A::load_frag(a);
-#endif
-        }
-    };
-    static __device__ __forceinline__ void cmma(f32x16 &acc, const Frag &a, const Frag &b)
-    {
-#if DSLA_EXP_C_NOMFMA
-        asm volatile("" ::"v"(*reinterpret_cast<const u32x4 *>(&a)), "v"(*reinterpret_cast<const u32x4 *>(&b)));
-#else
-        A::mma(acc, a, b);
-#endif
-    }
-    static __device__ __forceinline__ Frag cfrom(const f32x16 &acc, int half, const Frag &other)
-    {
-#if DSLA_EXP_C_NOVALU
-        return other;
-#else
-        return A::from_acc(acc, half);
-#endif
-    }
     // Staged output rows of one step -> memory.  Consumer wavefront ct writes rows 32/CT * ct ..; a group of NC lanes
     // writes one whole row.
     static __device__ __forceinline__ void flush_rows(uint32_t sm, uint32_t parity, int ct, int lane, TIO *orow, uint32_t rs,
@@ -874,9 +753,6 @@ struct Kern {
                                                    uint32_t set_parity, PhaseClock &clk)
     {
         clk.mark(0);
-#ifdef DSLA_EXP_NO_CONSUME
-        if (valid >= 0) return;
-#endif
         const uint32_t lo = opaque(static_cast<uint32_t>(lane));
         const uint32_t ln = lo & 31, g = lo >> 5;
         const uint32_t setb = sm + set * SET_BYTES;
@@ -886,7 +762,7 @@ struct Kern {
 
         Frag vf[KB];   // V fragments of this wavefront's columns: input of the output and of the update
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) vf[kb] = AC::load_frag(vt_r + 16 * kb * ESZ);
+        for (int kb = 0; kb < KB; ++kb) vf[kb] = A::load_frag(vt_r + 16 * kb * ESZ);
 
         f32x16 oacc;
         if (kFull) {
@@ -901,29 +777,27 @@ struct Kern {
             for (int j = 0; j < 16; ++j) sc[j] = oacc[j] = 0.f;
             {
                 Frag held;   // the Ks fragment of a block waits here for its Qs partner
-                pipelined_steps<2 * NK, 8, AC>(
+                pipelined_steps<2 * NK, 8, A>(
                     [&](int s2) -> uint32_t { return ((s2 & 1) ? qs_r : ks_r) + 16 * (s2 >> 1) * ESZ; },
                     [&](int s2, const Frag &f) {
                         if ((s2 & 1) == 0) {
                             held = f;
                         } else {
                             const int kb = s2 >> 1, i = kb / (2 * DT), dt = (kb / 2) % DT, half = kb & 1;
-                            cmma(sc, held, f);
-                            cmma(oacc, cfrom(acc[i][dt], half, held), f);
+                            A::mma(sc, held, f);
+                            A::mma(oacc, A::from_acc(acc[i][dt], half), f);
                         }
                     });
             }
             clk.mark(2);
             // keep key <= query; the two halves of the tile become the score fragments of the two token blocks
-#if !DSLA_EXP_C_NOVALU
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 const uint32_t key = 8 * (j >> 2) + 4 * g + (j & 3);
                 sc[j] = (key <= ln) ? sc[j] : 0.f;
             }
-#endif
 #pragma unroll
-            for (int kb = 0; kb < KB; ++kb) cmma(oacc, vf[kb], cfrom(sc, kb, vf[kb]));
+            for (int kb = 0; kb < KB; ++kb) A::mma(oacc, vf[kb], A::from_acc(sc, kb));
         }
         clk.mark(3);
         __builtin_amdgcn_sched_barrier(0);   // the instruction groups requested below start here
@@ -931,14 +805,14 @@ struct Kern {
         // ---- add K~^T V (the output tile finishes in the matrix pipeline meanwhile) ----
         {
             constexpr int NS = KB * 2 * DT;   // (token block, state, tile)
-            pipelined_steps<NS, 4, AC>(
+            pipelined_steps<NS, 4, A>(
                 [&](int s2) -> uint32_t {
                     const int kb = s2 / (2 * DT), i = (s2 / DT) % 2, dt = s2 % DT;
                     return kt_r + ((i * D + 32 * dt) * TP + 16 * kb) * ESZ;
                 },
                 [&](int s2, const Frag &f) {
                     const int kb = s2 / (2 * DT), i = (s2 / DT) % 2, dt = s2 % DT;
-                    cmma(acc[i][dt], f, vf[kb]);
+                    A::mma(acc[i][dt], f, vf[kb]);
                 });
             constexpr int RD = ESZ == 2 ? 1 : 2, MM = ESZ == 2 ? 1 : 8;
             __builtin_amdgcn_sched_group_barrier(0x100, 4 * RD, 0);
@@ -969,7 +843,7 @@ struct Kern {
         // ---- end of a chunk: the decay over the whole chunk brings a state to its own frame ----
 #pragma unroll
         for (int i = 0; i < 2; ++i)
-            if (!DSLA_EXP_C_NOVALU && ((close_mask >> i) & 1u)) {
+            if ((close_mask >> i) & 1u) {
 #pragma unroll
                 for (int dt2 = 0; dt2 < DT; dt2 += 2) {
                     f32x4 dd[2][4];
@@ -1021,19 +895,14 @@ struct Kern {
             const int left = ntok - n * S;
             return left >= S ? S : (left > 0 ? left : 0);
         };
-        // Which states end a chunk with step n (bit i = state i).  The chunks of state 1 are shifted by half a chunk
-        // against those of state 0, so that every step carries about the same decay work.
-        auto closes = [&](int n) -> uint32_t {
-            if (n + 1 >= nsteps) return 3u;
-            const uint32_t c0 = (n + 1) % wsteps == 0, c1 = (n + 1 + (DSLA_EXP_BALANCE ? wsteps / 2 : 0)) % wsteps == 0;
-            return c0 | (c1 << 1);
-        };
+        // Which states end a chunk with step n (bit i = state i); wsteps is 1 or 2.
+        auto closes = [&](int n) -> uint32_t { return (n + 1 >= nsteps || ((n + 1) & (wsteps - 1)) == 0) ? 3u : 0u; };
         // The step loop runs in pairs (set 0, set 1), so both roles pass the same number of barriers:
         // 1 + 2 * ceil(nsteps / 2) with two sets, twice as many in the loop with one.
 
-        if (DSLA_EXP_PRODUCER_FIRST ? wave >= CT : wave < CT) {
+        if (wave < CT) {
             // =============================== consumer ===============================
-            const int ct = DSLA_EXP_PRODUCER_FIRST ? wave - CT : wave;
+            const int ct = wave;
             const int ln = lane & 31, g = lane >> 5;
             f32x16 acc[2][DT];
             const uint32_t sbase = static_cast<uint32_t>(8 * g) * D + 32 * ct + ln;   // lane part of the state offset
@@ -1105,10 +974,7 @@ struct Kern {
             }
         } else {
             // =============================== producer ===============================
-            // The producers are the critical path of a step; the consumers have slack.  Where both want the same
-            // issue slot the producer goes first.
-            __builtin_amdgcn_s_setprio(DSLA_EXP_PRIO);
-            const int pw = DSLA_EXP_PRODUCER_FIRST ? wave : wave - CT;
+            const int pw = wave - CT;
             const float gm = a.gamma_per_head ? a.gamma_per_head[h] : a.gamma;
             const float gsv[2] = {gm * a.scale, (1.0f - gm) * a.scale};
             const float lg[2] = {__builtin_amdgcn_logf(fabsf(gsv[0])), __builtin_amdgcn_logf(fabsf(gsv[1]))};
@@ -1143,12 +1009,6 @@ struct Kern {
             RawGates g0, g1;
             ScanOut s0, s1;
             float decf = 1.f;
-            Touch touch(q0, k0, v0, 64 * pw + lane);
-            auto prefetch = [&](int n) {   // step n, or the last step when n is past the end
-                const int m = n < nsteps ? n : nsteps - 1;
-                touch.issue(static_cast<size_t>(m) * sstep * sizeof(TIO), rs * static_cast<uint32_t>(sizeof(TIO)), valid_of(m));
-            };
-            prefetch(2);
             load_gates(g0, src_of(0));
             load_gates(g1, src_of(1));
             load_io(r0, src_of(0));
@@ -1164,7 +1024,6 @@ struct Kern {
                 const StepSrc io = src_of(1), gs = src_of(3);
                 produce(pa, 0, r0, s0, valid_of(0), g1, s1, valid_of(1), closes(1), lg, sgn, carry, seg_decay,
                         decf, NextLoads{r1, io, g1, gs}, clk);
-                prefetch(3);
             }
             lds_barrier();   // operands of step 0 are ready
             for (int n = 0; n < nsteps; n += 2) {
@@ -1175,7 +1034,6 @@ struct Kern {
                     const StepSrc io = src_of(n + 2), gs = src_of(n + 4);
                     produce(pa, SETS - 1, r1, s1, valid_of(n + 1), g0, s0, valid_of(n + 2), closes(n + 2), lg,
                             sgn, carry, seg_decay, decf, NextLoads{r0, io, g0, gs}, clk);
-                    prefetch(n + 4);
                 }
                 lds_barrier();
                 if (SETS == 1) lds_barrier();
@@ -1184,11 +1042,9 @@ struct Kern {
                     const StepSrc io = src_of(n + 3), gs = src_of(n + 5);
                     produce(pa, 0, r0, s0, valid_of(n + 2), g1, s1, valid_of(n + 3), closes(n + 3), lg, sgn,
                             carry, seg_decay, decf, NextLoads{r1, io, g1, gs}, clk);
-                    prefetch(n + 5);
                 }
                 lds_barrier();
             }
-            touch.finish();
 #ifdef DSLA_PHASE_CLOCKS
             clk.flush(a.dbg);
 #endif
