@@ -43,12 +43,13 @@ def read_traffic(kernel: str):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50,
+                    help="untimed steps first; the clocks and caches of the device need a few dozen to settle")
     ap.add_argument("--T", type=int, default=16384, help="prefill length (default: the headline 16384)")
     ap.add_argument("--segments", type=int, default=0)
     ap.add_argument("--chunk", type=int, default=64)
-    ap.add_argument("--decode-steps", type=int, default=256)
+    ap.add_argument("--decode-steps", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--no-calibration-copy", action="store_true",
@@ -190,7 +191,7 @@ def main():
                 s = i % NSETS
                 dsla.dsla_decode(ddesc, dq[s], dk[s], dv[s], dg1[s], dg2[s], sets[s][0], sets[s][1], do)
 
-        decode_steps(16)
+        decode_steps(64)
         torch.cuda.synchronize()
         nd = args.decode_steps
         dsla.profile_enable(True, nd + 8)

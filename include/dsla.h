@@ -30,8 +30,8 @@
  *    returns an error other than DSLA_ERR_HIP has done nothing.  DSLA_ERR_HIP reports a
  *    failed launch (hipGetLastError text available through dsla_last_hip_error()).
  *  - Same inputs give bit-identical outputs (no atomics, fixed reduction order).
- *  - Supported shapes: d_k = d_v in {64, 128}; chunk in {0 (library default), 32, 64} subject
- *    to the table in dsla_prefill(); B, H, T >= 1 (T == 0 is accepted and does nothing).
+ *  - Supported shapes: d_k = d_v in {64, 128}; chunk in {0 (library default), 32, 64};
+ *    B, H, T >= 1 (T == 0 is accepted and does nothing).
  *  - Supported gate domain for dsla_prefill: within any one chunk of `chunk` consecutive
  *    tokens the sum of |g| over the tokens must stay below 80 for every feature (the
  *    chunk-local factorisation forms exp(+|sum g|)).  dsla_decode has no such limit.
@@ -103,9 +103,11 @@ DSLA_API size_t dsla_prefill_workspace_bytes(const dsla_desc *desc, int64_t T);
  *                     calling again with the next T' tokens continues the sequence
  *   workspace       : at least dsla_prefill_workspace_bytes(desc, T) bytes, 256-byte
  *                     aligned; contents are scratch (undefined before and after)
- * Built combinations: io bf16: (d=128, C in {32, 64}), (d=64, C in {32, 64});
- *                     io f32 : (d=64, C in {32, 64}), (d=128, C=32).
- *                     chunk = 0 selects 64 when built for the shape, else 32.
+ * Built combinations: d in {64, 128}, chunk in {32, 64}, io and gate dtype bf16 or f32;
+ *                     chunk = 0 selects 64.  The chunk length is how often the states are
+ *                     brought back to their own frame (it bounds the exponents, see the
+ *                     gate domain above) and the granularity of the internal split of
+ *                     long sequences; the result does not depend on it beyond rounding.
  * io f32 uses fp32 arithmetic throughout; io bf16 rounds contraction operands to bf16
  * and accumulates in fp32; states are fp32 in both.
  */
