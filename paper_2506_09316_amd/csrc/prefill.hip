@@ -1,28 +1,24 @@
 // Chunked DSLA prefill for gfx950 (paper Section 4.1: state-update equation and blended
-// read-out, evaluated C tokens at a time).
+// read-out, evaluated 32 tokens at a time).
 //
-// Chunk algebra (local positions r, s = 1..C inside a chunk, b^i_r = sum_{tau<=r} log2 alpha^i_tau,
-// S^i = state entering the chunk, gamma_1 = gamma, gamma_2 = 1 - gamma):
-//   o_r   = sum_i gamma_i scale (q_r * 2^{b^i_r}) S^i                       (read-out of carried state)
-//         + sum_{s<=r} [ sum_i gamma_i scale (q_r * 2^{b^i_r}) . (k_s * 2^{-b^i_s}) ] v_s   (inside the chunk)
-//   S^i  <- diag(2^{b^i_C}) S^i + sum_s (k_s * 2^{b^i_C - b^i_s})^T v_s
-// which is the token recurrence regrouped; every bracket is a dense contraction and runs on MFMA.
-// With Qc = [gamma_1 q~^1 | gamma_2 q~^2] and Kc = [k~^1 | k~^2] (width 2 d_k) the blend of the two
-// states is part of the contraction: scores = Qc Kc^T, carried read-out = Qc [S^1; S^2].
+// The token recurrence is regrouped so that every bracket is a dense contraction and runs on MFMA; the
+// algebra is written out above the kernel body ("Chunk algebra").  With Qc = [Q~^1 | Q~^2] and
+// Kc = [K~^1 | K~^2] (width 2 d_k) the blend of the two states is part of the contractions:
+// scores = Qc Kc^T, carried read-out = Qc [T^1; T^2].
 //
 // Parallel decomposition.  A sequence is cut into P segments so that B*H*P workgroups fill the
 // chip.  (1) segment_state: every segment but the last computes, from a zero state, its state
 // contribution U and its total log-decay.  (2) segment_scan: an elementwise scan over segments
 // turns these into the true state entering each segment.  (3) chunk_loop: every segment runs the
-// fused chunk loop from its true initial state and writes o; the last segment writes the final
-// states.  P = 1 runs (3) alone.
+// fused step loop from its true initial state and writes o; the last segment writes the final
+// states.  P = 1 runs (3) alone.  (1) and (3) are one kernel template.
 //
-// Workgroup = D/32 wavefronts (D = d_k = d_v).  Wavefront w owns state columns [32w, 32w+32) of
-// both states for all d_k rows, as fp32 MFMA accumulators (tiles with m = state row, n = column).
-// Because an MFMA accumulator tile and an MFMA input fragment both index lanes by the tile column,
-// those accumulators are fed back as the input fragment of the carried read-out without passing
-// through LDS; the partner operand is stored in LDS with the matching order of the contraction
-// index (bits 2 and 3 of the feature index swapped).
+// Workgroup = D/8 wavefronts (D = d_k = d_v): D/32 consumers and D/32 producers, see "Workgroup layout".
+// Consumer w owns state columns [32w, 32w+32) of both states for all d_k rows, as fp32 MFMA accumulators
+// (tiles with m = state row, n = column).  Because an MFMA accumulator tile and an MFMA input fragment both
+// index lanes by the tile column, those accumulators are fed back as the input fragment of the carried
+// read-out without passing through LDS; the partner operand is stored in LDS with the matching order of
+// the contraction index (bits 2 and 3 of the feature index swapped).
 #include <cstdio>
 #include <type_traits>
 #include <utility>
