@@ -23,10 +23,16 @@ def check(name, got, ref, tol):
 
 
 def run_prefill_case(B, T, H, d, io, gd, *, chunk=0, segments=0, gamma=0.5, scale=1.0, tau=16.0, seed=1,
-                     qk_scale=1.0, init=False, gph=None):
+                     qk_scale=1.0, init=False, gph=None, gate_mean=2.0):
     print(f"  prefill B={B} T={T} H={H} d={d} io={io} gates={gd} chunk={chunk} segments={segments} "
           f"gamma={gamma} scale={scale} tau={tau} init={init}", flush=True)
-    x = wl.layer_inputs(seed, B, T, H, d, d, io_dtype=io, gate_dtype=gd, tau=tau, qk_scale=qk_scale)
+    x = wl.layer_inputs(seed, B, T, H, d, d, io_dtype=io, gate_dtype=gd, tau=tau, qk_scale=qk_scale,
+                        gate_mean=gate_mean)
+    if gate_mean != 2.0:
+        per_chunk = -x["g1"].reshape(B, -1, chunk, H, d).sum(2) if T % chunk == 0 else None
+        if per_chunk is not None:
+            print(f"    sum |log alpha| per chunk: mean {per_chunk.mean():.1f} max {per_chunk.max():.1f}", flush=True)
+            assert per_chunk.max() < 80.0, "workload outside the documented gate domain"
     layer = GpuLayer(B, H, d, io, gd, gamma=gamma, scale=scale, chunk=chunk, segments=segments, gamma_per_head=gph)
     S10 = S20 = None
     if init:
@@ -82,6 +88,20 @@ def test_prefill_fp32_shapes(chunk, segments, T):
 def test_prefill_fp32_d128_chunk32_per_head_gamma():
     run_prefill_case(1, 150, 2, 128, "f32", "bf16", chunk=32, segments=2, seed=9, init=True, gph=np.array([0.2, 0.9]),
                      qk_scale=128 ** -0.5)
+
+
+def test_prefill_fp32_d128_chunk64():
+    run_prefill_case(1, 200, 2, 128, "f32", "f32", chunk=64, segments=2, gamma=0.6, seed=13, init=True,
+                     qk_scale=128 ** -0.5)
+
+
+def test_prefill_fp32_gates_near_the_domain_limit():
+    """tau = 1 gates with pre-activations around 0: |log alpha| averages 0.8 per token, about 50 (at most about 70)
+    per chunk of 64, close to the documented limit of 80; the chunk-local factors then span 30 orders of magnitude."""
+    run_prefill_case(1, 256, 2, 64, "f32", "f32", chunk=64, segments=2, gamma=0.5, tau=1.0, seed=17, init=True,
+                     gate_mean=0.0)
+    run_prefill_case(1, 256, 2, 128, "bf16", "f32", chunk=32, segments=1, gamma=0.5, tau=1.0, seed=19, init=True,
+                     gate_mean=-0.5, qk_scale=128 ** -0.5)
 
 
 def test_prefill_fp32_gamma_extremes():
@@ -160,6 +180,10 @@ def test_cfg2_full_size_sampled_heads():
 
 def test_cfg3_16k_full_size_sampled_heads():
     _sampled_heads_check("cfg3_16k", heads=(5, 30))
+
+
+def test_cfg3_64k_full_size_sampled_heads():
+    _sampled_heads_check("cfg3_64k", heads=(11,))
 
 
 # ---------------------------------------------------------------- boundary behaviour
