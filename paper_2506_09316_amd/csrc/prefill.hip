@@ -439,7 +439,11 @@ struct Kern {
     static constexpr int SGN = 16;          // token pairs per step
     static constexpr int RPT = 2;           // tokens per producer thread
     static constexpr int QP = 2 * D + 8;    // pitch of row-layout operands (elements)
-    static constexpr int TP = S + 8;        // pitch of token-contiguous operands (elements)
+    // Token-contiguous operands (Kt, Vt): a row holds the S tokens of one feature (column) as 4 pieces of 8 tokens,
+    // without padding; piece c of row R sits at piece position c ^ ((R / 2) % 4), so that the 8 rows a group of 8
+    // lanes reads with one 16-byte access each fall into 8 different bank groups.
+    static constexpr int TP = S;            // pitch of token-contiguous operands (elements)
+    static __device__ __forceinline__ uint32_t tpiece(uint32_t piece, uint32_t row) { return piece ^ ((row >> 1) & 3u); }
     static constexpr int DT = D / 32;       // 32-row tiles of a state
     static constexpr int KB = S / 16;       // contraction blocks over tokens
     static constexpr int NK = 2 * D / 16;   // contraction blocks over the 2 d_k features
@@ -544,8 +548,8 @@ struct Kern {
         uint32_t col;   // scan scratch: this lane's column, token pair 0
         uint32_t dec;   // decay factor of this lane's column
         uint32_t row;   // row-layout operands: token 2sg, element f0 (token + 1: + QP, state 1: + D elements)
-        uint32_t kt;    // Kt: row of feature e = 0 of state 0, column rho(2sg)
-        uint32_t vt;    // Vt: row of column f0, column rho(2sg)
+        uint32_t kt[2];   // Kt: row of feature e = 0 of state 0, position of tokens 2sg, 2sg+1; [x]: for features e with (e/2)%2 = x
+        uint32_t vt[4];   // Vt: row of column f0, position of tokens 2sg, 2sg+1; [x]: for columns e with (e/2)%4 = x
         uint32_t sg;
         uint32_t state;   // state of the column this lane scans
         __device__ __forceinline__ ProdAddr(uint32_t sm, int pw, uint32_t lane)
@@ -559,8 +563,14 @@ struct Kern {
             dec = sm + O_DEC + ((lane >> 5) * D + 32 * pw + (lane & 31)) * 4;
             row = sm + (sg * RPT * QP + f0) * ESZ;
             // feature 8 dgl + e of the wavefront's 32 goes to row rho(8 dgl + e) = 16 (dgl/2) + 8 (e/4) + 4 (dgl%2) + e%4
-            kt = sm + O_KT + ((32 * pw + 16 * (dgl >> 1) + 4 * (dgl & 1)) * TP + rho(2 * sg)) * ESZ;
-            vt = sm + O_VT + (f0 * TP + rho(2 * sg)) * ESZ;
+            // the row of feature e is R = (multiple of 8) + 4 (dgl%2) + e%4 (+ 8 (e/4)): (R/2)%4 = 2 (dgl%2) + (e/2)%2
+            const uint32_t tok = rho(2 * sg), piece = tok >> 3, within = tok & 7;
+#pragma unroll
+            for (uint32_t x = 0; x < 2; ++x)
+                kt[x] = sm + O_KT + ((32 * pw + 16 * (dgl >> 1) + 4 * (dgl & 1)) * TP + 8 * (piece ^ (2 * (dgl & 1)) ^ x) + within) * ESZ;
+            // the row of column e is R = 32 pw + 8 dgl + e: (R/2)%4 = (e/2)%4
+#pragma unroll
+            for (uint32_t x = 0; x < 4; ++x) vt[x] = sm + O_VT + (f0 * TP + 8 * (piece ^ x) + within) * ESZ;
         }
     };
 
@@ -698,7 +708,7 @@ struct Kern {
         auto kt_rows = [&](int i) {
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-                A::template store_tokens<RPT>(pa.kt + so + ((i * D + 8 * (e >> 2) + (e & 3)) * TP) * ESZ, kt, e);
+                A::template store_tokens<RPT>(pa.kt[(e >> 1) & 1] + so + ((i * D + 8 * (e >> 2) + (e & 3)) * TP) * ESZ, kt, e);
         };
 
         float t[SGN];
@@ -719,7 +729,7 @@ struct Kern {
         kt_rows(1);
         // V transposed
 #pragma unroll
-        for (int e = 0; e < 8; ++e) store_v_tokens<RPT>(pa.vt + so + e * TP * ESZ, r.v, e);
+        for (int e = 0; e < 8; ++e) store_v_tokens<RPT>(pa.vt[(e >> 1) & 3] + so + e * TP * ESZ, r.v, e);
         clk.mark(2);
     }
 
@@ -752,13 +762,16 @@ struct Kern {
         const uint32_t lo = opaque(static_cast<uint32_t>(lane));
         const uint32_t ln = lo & 31, g = lo >> 5;
         const uint32_t setb = sm + set * SET_BYTES;
-        const uint32_t vt_r = setb + O_VT + ((32 * ct + ln) * TP + 8 * g) * ESZ;
-        const uint32_t kt_r = setb + O_KT + (ln * TP + 8 * g) * ESZ;
+        // token block kb of a row: piece g + 2 kb, stored at piece position (g + 2 kb) ^ ((row / 2) % 4); all row
+        // numbers used below are ln plus a multiple of 8
+        const uint32_t p0 = 8 * tpiece(g, ln), p1 = 8 * tpiece(g + 2, ln);
+        const uint32_t vt_r[KB] = {setb + O_VT + ((32 * ct + ln) * TP + p0) * ESZ, setb + O_VT + ((32 * ct + ln) * TP + p1) * ESZ};
+        const uint32_t kt_r[KB] = {setb + O_KT + (ln * TP + p0) * ESZ, setb + O_KT + (ln * TP + p1) * ESZ};
         const uint32_t dec_r = setb + O_DEC + (8 * g) * 4;
 
         Frag vf[KB];   // V fragments of this wavefront's columns: input of the output and of the update
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) vf[kb] = A::load_frag(vt_r + 16 * kb * ESZ);
+        for (int kb = 0; kb < KB; ++kb) vf[kb] = A::load_frag(vt_r[kb]);
 
         f32x16 oacc;
         if (kFull) {
@@ -804,7 +817,7 @@ struct Kern {
             pipelined_steps<NS, 4, A>(
                 [&](int s2) -> uint32_t {
                     const int kb = s2 / (2 * DT), i = (s2 / DT) % 2, dt = s2 % DT;
-                    return kt_r + ((i * D + 32 * dt) * TP + 16 * kb) * ESZ;
+                    return kt_r[kb] + ((i * D + 32 * dt) * TP) * ESZ;
                 },
                 [&](int s2, const Frag &f) {
                     const int kb = s2 / (2 * DT), i = (s2 / DT) % 2, dt = s2 % DT;
