@@ -30,7 +30,7 @@
  *    returns an error other than DSLA_ERR_HIP has done nothing.  DSLA_ERR_HIP reports a
  *    failed launch (hipGetLastError text available through dsla_last_hip_error()).
  *  - Same inputs give bit-identical outputs (no atomics, fixed reduction order).
- *  - Supported shapes: d_k = d_v in {64, 128}; chunk in {0 (library default), 32, 64};
+ *  - Supported shapes: d_k = d_v in {64, 128}; chunk in {0 (library default), 32, 64, 128};
  *    B, H, T >= 1 (T == 0 is accepted and does nothing).
  *  - Supported gate domain for dsla_prefill: within any one chunk of `chunk` consecutive
  *    tokens the sum of |g| over the tokens must stay below 80 for every feature (the
@@ -103,7 +103,7 @@ DSLA_API size_t dsla_prefill_workspace_bytes(const dsla_desc *desc, int64_t T);
  *                     calling again with the next T' tokens continues the sequence
  *   workspace       : at least dsla_prefill_workspace_bytes(desc, T) bytes, 256-byte
  *                     aligned; contents are scratch (undefined before and after)
- * Built combinations: d in {64, 128}, chunk in {32, 64}, io and gate dtype bf16 or f32;
+ * Built combinations: d in {64, 128}, chunk in {32, 64, 128}, io and gate dtype bf16 or f32;
  *                     chunk = 0 selects 64.  The chunk length is how often the states are
  *                     brought back to their own frame (it bounds the exponents, see the
  *                     gate domain above) and the granularity of the internal split of

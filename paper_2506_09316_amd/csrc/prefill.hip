@@ -904,7 +904,7 @@ struct Kern {
             const int left = ntok - n * S;
             return left >= S ? S : (left > 0 ? left : 0);
         };
-        // Which states end a chunk with step n (bit i = state i); wsteps is 1 or 2.
+        // Which states end a chunk with step n (bit i = state i); wsteps is 1, 2 or 4.
         auto closes = [&](int n) -> uint32_t { return (n + 1 >= nsteps || ((n + 1) & (wsteps - 1)) == 0) ? 3u : 0u; };
         // The step loop runs in pairs (set 0, set 1), so both roles pass the same number of barriers:
         // 1 + 2 * ceil(nsteps / 2) with two sets, twice as many in the loop with one.
@@ -1190,7 +1190,7 @@ hipError_t launch_g(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
 // The chunk length only sets the granularity of the segment split; the kernels step through 32 tokens at a time.
 bool combo_built(int D, int C, int io)
 {
-    return (io == DSLA_BF16 || io == DSLA_F32) && (D == 64 || D == 128) && (C == 32 || C == 64);
+    return (io == DSLA_BF16 || io == DSLA_F32) && (D == 64 || D == 128) && (C == 32 || C == 64 || C == 128);
 }
 
 }  // namespace

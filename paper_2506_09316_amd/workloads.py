@@ -81,4 +81,8 @@ CONFIGS = {
                      gate_dtype="bf16", qk_scale=128 ** -0.5, seed=BASE_SEED + 3500),
     "cfg4": dict(B=64, T=2048, H=32, dk=128, dv=128, chunk=64, io_dtype="bf16", gate_dtype="bf16",
                  qk_scale=128 ** -0.5, decode_steps=256, seed=BASE_SEED + 4000),
+    # the DSLA layers of a hybrid 32-layer stack: 16 layer instances, each with its own blend coefficient
+    # (drawn by the caller from U(0.2, 0.8) with the layer's seed) and its own inputs; seed of layer l = seed + 10 l
+    "cfg5": dict(B=8, T=8192, H=32, dk=128, dv=128, chunk=64, io_dtype="bf16", gate_dtype="bf16",
+                 qk_scale=128 ** -0.5, decode_steps=128, layers=16, seed=BASE_SEED + 5000),
 }

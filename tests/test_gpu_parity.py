@@ -118,6 +118,12 @@ def test_prefill_bf16_shapes(d, chunk, segments, T, gd):
                      qk_scale=d ** -0.5)
 
 
+@pytest.mark.parametrize("io,d,segments,T", [("bf16", 128, 2, 700), ("bf16", 128, 0, 4096), ("f32", 64, 3, 450)])
+def test_prefill_chunk128(io, d, segments, T):
+    run_prefill_case(1, T, 2, d, io, "f32" if io == "f32" else "bf16", chunk=128, segments=segments, gamma=0.45, seed=23,
+                     init=True, qk_scale=d ** -0.5)
+
+
 def test_prefill_bf16_strong_decay_tau1():
     run_prefill_case(1, 512, 4, 128, "bf16", "f32", chunk=64, segments=2, gamma=0.5, tau=1.0, seed=31,
                      qk_scale=128 ** -0.5)
@@ -145,7 +151,7 @@ def test_chunk_and_segment_invariance_and_determinism():
     B, T, H, d = 1, 512, 2, 128
     x = wl.layer_inputs(41, B, T, H, d, d, io_dtype="bf16", gate_dtype="bf16", qk_scale=d ** -0.5)
     outs = []
-    for chunk, seg in ((64, 1), (64, 1), (64, 4), (32, 2)):
+    for chunk, seg in ((64, 1), (64, 1), (64, 4), (32, 2), (128, 2)):
         layer = GpuLayer(B, H, d, "bf16", "bf16", chunk=chunk, segments=seg)
         outs.append((layer.prefill(x),) + layer.states())
     for a, b in zip(outs[0], outs[1]):
@@ -184,6 +190,33 @@ def test_cfg3_16k_full_size_sampled_heads():
 
 def test_cfg3_64k_full_size_sampled_heads():
     _sampled_heads_check("cfg3_64k", heads=(11,))
+
+
+def test_cfg5_layer_instances_slice():
+    """The DSLA part of the hybrid serving step: several layer instances, each with its own blend coefficient and
+    inputs, prefill T=8192 then 128 decode steps.  A slice is checked: 3 of the 16 layers, 2 of the 8 sequences,
+    2 heads each, element by element against the oracle over prefill + decode tokens."""
+    c = wl.CONFIGS["cfg5"]
+    T, H, d, steps, B = c["T"], c["H"], c["dk"], c["decode_steps"], 2
+    for layer_no in (0, 7, 15):
+        seed = c["seed"] + 10 * layer_no
+        gamma = float(np.random.default_rng(seed + 9).uniform(0.2, 0.8))
+        print(f"  layer {layer_no}: gamma={gamma:.4f}", flush=True)
+        x = wl.layer_inputs(seed, B, T + steps, H, d, d, io_dtype="bf16", gate_dtype="bf16", qk_scale=c["qk_scale"])
+        layer = GpuLayer(B, H, d, "bf16", "bf16", gamma=gamma, chunk=c["chunk"])
+        outs = [layer.prefill(slice_t(x, 0, T))]
+        for t in range(T, T + steps):
+            outs.append(layer.decode(slice_t(x, t, t + 1)))
+        o = np.concatenate(outs, 1)
+        S1, S2 = layer.states()
+        assert np.all(np.isfinite(o))
+        for b, h in ((0, 3 + layer_no), (1, 20)):
+            xs = {n: x[n][b:b + 1, :, h:h + 1] for n in x}
+            ro, rS1, rS2 = orc.recurrent(xs["q"], xs["k"], xs["v"], xs["g1"], xs["g2"], gamma)
+            check(f"o prefill[b={b},h={h}]", o[b:b + 1, :T, h:h + 1], ro[:, :T], 2e-2)
+            check(f"o decode[b={b},h={h}]", o[b:b + 1, T:, h:h + 1], ro[:, T:], 2e-2)
+            check(f"S1[b={b},h={h}]", S1[b:b + 1, h:h + 1], rS1, 2e-2)
+            check(f"S2[b={b},h={h}]", S2[b:b + 1, h:h + 1], rS2, 2e-2)
 
 
 # ---------------------------------------------------------------- boundary behaviour

@@ -51,7 +51,7 @@ def test_argument_checks_need_no_gpu(lib):
     # misaligned pointer
     odd = ctypes.c_void_p(4100)
     assert lib.dsla_decode(ctypes.byref(d), odd, *([fake] * 8)) == 2
-    # chunk lengths other than 32 and 64 are not built
+    # chunk lengths other than 32, 64 and 128 are not built
     big = dsla.make_desc(1, 2, 128, 128, io_dtype=0, gate_dtype=0, chunk=48)
     assert lib.dsla_prefill(ctypes.byref(big), 128, *([fake] * 8), None, 0, None) == 3
     # missing workspace when the plan needs one
