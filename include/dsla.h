@@ -33,8 +33,8 @@
  *  - Supported shapes: d_k = d_v in {64, 128}; chunk in {0 (library default), 32, 64, 128};
  *    B, H, T >= 1 (T == 0 is accepted and does nothing).
  *  - Supported gate domain for dsla_prefill: within any one chunk of `chunk` consecutive
- *    tokens the sum of |g| over the tokens must stay below 80 for every feature (the
- *    chunk-local factorisation forms exp(+|sum g|)).  dsla_decode has no such limit.
+ *    tokens the sum of |log alpha| over the tokens must stay below 80 for every feature (the
+ *    chunk-local factorisation forms exp(+|sum log alpha|)).  dsla_decode has no such limit.
  */
 #ifndef DSLA_H
 #define DSLA_H
@@ -60,6 +60,17 @@ typedef enum {
 
 typedef enum { DSLA_F32 = 0, DSLA_BF16 = 1 } dsla_dtype;
 
+/*
+ * What the gate tensors g1, g2 hold.  The paper names the gates "data-driven" and produced by single linear
+ * layers (Section 4.1, Section 5.3) without giving the map into (0,1]; this library takes the parametrisation
+ * of the gated linear attention work the method extends: alpha = sigmoid(z)^(1/tau).
+ *   DSLA_GATE_LOG    : g = log alpha <= 0, computed by the caller (any map into (0,1] can be used this way)
+ *   DSLA_GATE_PREACT : g = z, the output of the gate projection; the kernels form
+ *                      log alpha = -softplus(-z) / tau = (min(z,0) - log(1 + exp(-|z|))) / tau in fp32
+ *                      themselves, which saves the caller one pass over both gate tensors
+ */
+typedef enum { DSLA_GATE_LOG = 0, DSLA_GATE_PREACT = 1 } dsla_gate_mode;
+
 /* Layer descriptor (HOST memory, read during the call only). */
 typedef struct {
     int32_t B;          /* sequences in the batch                                       */
@@ -72,6 +83,9 @@ typedef struct {
                            the result does not depend on it beyond rounding             */
     int32_t io_dtype;   /* dsla_dtype of q, k, v, o                                     */
     int32_t gate_dtype; /* dsla_dtype of g1, g2                                         */
+    int32_t gate_mode;  /* dsla_gate_mode: what g1, g2 hold                             */
+    float tau;          /* DSLA_GATE_PREACT: temperature, finite and > 0 (16 in the gated linear attention
+                           work; 1 = plain sigmoid); ignored for DSLA_GATE_LOG          */
     float gamma;        /* blend coefficient of the layer (read-out equation); any real */
     float scale;        /* multiplies q (e.g. d_k^-1/2); 1.0 = the paper's plain form   */
     const float *gamma_per_head; /* optional DEVICE array [H] overriding gamma; or NULL */

@@ -55,6 +55,19 @@ def _gamma_vec(gamma, H):
     return np.ascontiguousarray(g)
 
 
+def log_gates_from_preactivations(z, tau):
+    """log alpha for alpha = sigmoid(z) ** (1 / tau), fp64.
+
+    The paper does not print the map from the gate projections to (0,1] (Section 4.1 calls the gates
+    data-driven, Section 5.3 says they come from single linear layers); this is the reading taken: the
+    temperature-sigmoid of the gated linear attention work the method extends.  Written from the definition,
+    log alpha = -log(1 + e^-z) / tau, with the library's overflow-free log-sum-exp for the logarithm.
+    """
+    z = np.asarray(z, dtype=np.float64)
+    assert float(tau) > 0.0
+    return -np.logaddexp(0.0, -z) / float(tau)
+
+
 def recurrent(q, k, v, g1, g2, gamma, scale=1.0, S1=None, S2=None):
     """Token-by-token DSLA recurrence (Section 4.1, state-update and read-out equations).
 

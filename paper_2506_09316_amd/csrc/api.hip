@@ -27,6 +27,8 @@ dsla_status check_desc(const dsla_desc *d)
     if ((d->io_dtype != DSLA_F32 && d->io_dtype != DSLA_BF16) ||
         (d->gate_dtype != DSLA_F32 && d->gate_dtype != DSLA_BF16))
         return DSLA_ERR_UNSUPPORTED;
+    if (d->gate_mode != DSLA_GATE_LOG && d->gate_mode != DSLA_GATE_PREACT) return DSLA_ERR_UNSUPPORTED;
+    if (d->gate_mode == DSLA_GATE_PREACT && !(d->tau > 0.f && d->tau < 3.0e38f)) return DSLA_ERR_SHAPE;
     if (static_cast<int64_t>(d->B) * d->H > 0x7fffffffLL / 8) return DSLA_ERR_SHAPE;
     if (!decode_supported(*d)) return DSLA_ERR_UNSUPPORTED;  // d_k = d_v in {64, 128}
     return DSLA_OK;

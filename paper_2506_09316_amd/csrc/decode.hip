@@ -38,7 +38,7 @@ template <int DK, int DV, int SPLIT, bool NT, class TIO, class TG>
 __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
     const TIO *__restrict__ q, const TIO *__restrict__ k, const TIO *__restrict__ v, const TG *__restrict__ g1,
     const TG *__restrict__ g2, float *__restrict__ S1, float *__restrict__ S2, TIO *__restrict__ o, int H,
-    float gamma, const float *__restrict__ gamma_per_head, float scale)
+    float gamma, const float *__restrict__ gamma_per_head, float scale, float gate_inv_tau)
 {
     constexpr int COLG = DV / 4 / SPLIT;          // threads across this workgroup's part of a state row (float4 each)
     constexpr int ROWG = kDecodeThreads / COLG;   // row groups
@@ -74,8 +74,13 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
     for (int d = tid; d < DK; d += kDecodeThreads) {
         s_q[d] = scale * to_f32(q[kb + d]);
         s_k[d] = to_f32(k[kb + d]);
-        s_a1[d] = __expf(to_f32(g1[kb + d]));
-        s_a2[d] = __expf(to_f32(g2[kb + d]));
+        float x1 = to_f32(g1[kb + d]), x2 = to_f32(g2[kb + d]);
+        if (gate_inv_tau != 0.f) {   // pre-activations: log(sigmoid(z)^(1/tau)) = (min(z, 0) - log(1 + e^-|z|)) / tau
+            x1 = (fminf(x1, 0.f) - log1pf(expf(-fabsf(x1)))) * gate_inv_tau;
+            x2 = (fminf(x2, 0.f) - log1pf(expf(-fabsf(x2)))) * gate_inv_tau;
+        }
+        s_a1[d] = __expf(x1);
+        s_a2[d] = __expf(x2);
     }
     const TIO *vp = v + static_cast<size_t>(bh) * DV + (part * COLG + cg) * 4;
     const float v0 = to_f32(vp[0]), v1 = to_f32(vp[1]), v2 = to_f32(vp[2]), v3 = to_f32(vp[3]);
@@ -167,7 +172,7 @@ hipError_t launch_decode_v(const dsla_desc &d, const void *q, const void *k, con
     hipLaunchKernelGGL((decode_kernel<D, D, SPLIT, NT, TIO, TG>), dim3(grid), dim3(kDecodeThreads), 0, stream,
                        static_cast<const TIO *>(q), static_cast<const TIO *>(k), static_cast<const TIO *>(v),
                        static_cast<const TG *>(g1), static_cast<const TG *>(g2), S1, S2, static_cast<TIO *>(o), d.H,
-                       d.gamma, d.gamma_per_head, d.scale);
+                       d.gamma, d.gamma_per_head, d.scale, d.gate_mode == DSLA_GATE_PREACT ? 1.0f / d.tau : 0.f);
     return hipGetLastError();
 }
 

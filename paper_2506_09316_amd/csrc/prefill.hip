@@ -253,6 +253,7 @@ struct Raw8<bf16_t> {
         u = *reinterpret_cast<const u32x4 *>(reinterpret_cast<const char *>(base) + elem_off * 2u);
     }
     __device__ __forceinline__ void zero() { u = u32x4{0, 0, 0, 0}; }
+    __device__ __forceinline__ void fill_huge() { u = u32x4{0x7e007e00u, 0x7e007e00u, 0x7e007e00u, 0x7e007e00u}; }   // 2^125
     // orders every later use of the loaded value after `dep` has been computed (no instruction is emitted)
     __device__ __forceinline__ void pin_after(float dep) { asm volatile("" : "+v"(u) : "v"(dep)); }
     __device__ __forceinline__ void unpack(float (&f)[8]) const
@@ -274,6 +275,7 @@ struct Raw8<float> {
         b = *reinterpret_cast<const f32x4 *>(p + 16);
     }
     __device__ __forceinline__ void zero() { a = b = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    __device__ __forceinline__ void fill_huge() { a = b = f32x4{0x1p125f, 0x1p125f, 0x1p125f, 0x1p125f}; }
     __device__ __forceinline__ void pin_after(float dep) { asm volatile("" : "+v"(a), "+v"(b) : "v"(dep)); }
     __device__ __forceinline__ void unpack(float (&f)[8]) const
     {
@@ -402,6 +404,7 @@ struct PrefillArgs {
     int P;
     int chunk_steps;         // 32-token steps per chunk
     float gamma, scale;
+    float gate_inv_tau;      // 0: g1, g2 are log-gates; else they are pre-activations and this is 1 / tau
 #ifdef DSLA_PHASE_CLOCKS
     long long *dbg;
 #endif
@@ -552,6 +555,8 @@ struct Kern {
         uint32_t vt[4];   // Vt: row of column f0, position of tokens 2sg, 2sg+1; [x]: for columns e with (e/2)%4 = x
         uint32_t sg;
         uint32_t state;   // state of the column this lane scans
+        bool preact;      // the gate tensors hold pre-activations, not log-gates (uniform)
+        float unit;       // gate sums times this = log2 of the decay: log2 e for log-gates, 1 / tau for pre-activations
         __device__ __forceinline__ ProdAddr(uint32_t sm, int pw, uint32_t lane)
         {
             sg = lane >> 2;
@@ -580,28 +585,47 @@ struct Kern {
     // stages of step m + 1 are spread over the operand preparation of step m, which hides the round trips.
     // ------------------------------------------------------------------------------------------------------
     struct ScanOut {
-        float c[2][RPT][8];   // natural-log gate sums over this thread's tokens: c[i][j] = g[0] + .. + g[j]
-        float pre[2][8];      // natural-log gate sum from the first token of the chunk to before this thread's tokens
+        float c[2][RPT][8];   // gate sums over this thread's tokens: c[i][j] = g[0] + .. + g[j]  (times ProdAddr::unit = log2 of a decay)
+        float pre[2][8];      // gate sum from the first token of the chunk to before this thread's tokens
     };
+    // Gate pre-activations z -> tau log2(alpha) for alpha = sigmoid(z)^(1/tau):
+    //   tau log2 alpha = min(y, 0) - log2(1 + 2^-|y|),  y = z log2 e
+    // (the 1 / tau is applied where the sums are exponentiated: ProdAddr::unit).
+    static __device__ __forceinline__ void activate(float (&g)[8])
+    {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float y = g[e] * kLog2e;
+            const float l = __builtin_amdgcn_logf(1.0f + __builtin_amdgcn_exp2f(-__builtin_fabsf(y)));
+            g[e] = fminf(y, 0.f) - l;
+        }
+    }
     // stage A: sums over this thread's tokens; totals of the token pair -> scan scratch.
     // `valid` = tokens of the step that exist; tokens past the end act as "no decay".
     static __device__ __forceinline__ void scan_a(const ProdAddr &pa, RawGates &r, int valid, ScanOut &o)
     {
-        if (valid < S) {
+        if (valid < S) {   // a token past the end: log-gate 0, or a pre-activation whose log-gate is exactly 0
 #pragma unroll
             for (int j = 0; j < RPT; ++j)
                 if (static_cast<int>(pa.sg) * RPT + j >= valid) {
-                    r.g1[j].zero();
-                    r.g2[j].zero();
+                    if (pa.preact) {
+                        r.g1[j].fill_huge();
+                        r.g2[j].fill_huge();
+                    } else {
+                        r.g1[j].zero();
+                        r.g2[j].zero();
+                    }
                 }
         }
         float g[8];
 #pragma unroll
         for (int j = 0; j < RPT; ++j) {
             r.g1[j].unpack(g);
+            if (pa.preact) activate(g);
 #pragma unroll
             for (int e = 0; e < 8; ++e) o.c[0][j][e] = j ? o.c[0][j - 1][e] + g[e] : g[e];
             r.g2[j].unpack(g);
+            if (pa.preact) activate(g);
 #pragma unroll
             for (int e = 0; e < 8; ++e) o.c[1][j][e] = j ? o.c[1][j - 1][e] + g[e] : g[e];
         }
@@ -613,7 +637,7 @@ struct Kern {
         }
     }
     // stage B: scan of this lane's column over the 16 token pairs, continuing the chunk.
-    // carry: natural-log gate sum of the column from the first token of the chunk to the end of the previous step;
+    // carry: gate sum of the column from the first token of the chunk to the end of the previous step;
     // decf: decay factor of the chunk up to the end of this step (used when the step closes its chunk).
     static __device__ __forceinline__ void scan_b_read(const ProdAddr &pa, float (&t)[SGN])
     {
@@ -631,9 +655,9 @@ struct Kern {
             lds_st<float>(pa.col + s2 * 32 * 4, run);
             run += t[s2];
         }
-        decf = __builtin_amdgcn_exp2f(run * kLog2e);
+        decf = __builtin_amdgcn_exp2f(run * pa.unit);
         if (valid > 0) {
-            seg_log2_decay += (run - carry) * kLog2e;
+            seg_log2_decay += (run - carry) * pa.unit;
             carry = close ? 0.f : run;
         }
     }
@@ -691,7 +715,7 @@ struct Kern {
                 r.k[j].unpack(kf);
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    kh[e] = kf[e] * __builtin_amdgcn_exp2f(-kLog2e * (sc.pre[i][e] + sc.c[i][j][e]));
+                    kh[e] = kf[e] * __builtin_amdgcn_exp2f(-pa.unit * (sc.pre[i][e] + sc.c[i][j][e]));
                 kt[j] = A::pack_row(kh);
                 if (kFull) A::store_row(pa.row + so + O_KS + (j * QP + i * D) * ESZ, kt[j]);
             }
@@ -701,7 +725,7 @@ struct Kern {
                 r.q[j].unpack(qf);
 #pragma unroll
                 for (int e = 0; e < 8; ++e)
-                    qt[e] = qf[e] * __builtin_amdgcn_exp2f(fmaf(sc.pre[i][e] + sc.c[i][j][e], kLog2e, lg[i]));
+                    qt[e] = qf[e] * __builtin_amdgcn_exp2f(fmaf(sc.pre[i][e] + sc.c[i][j][e], pa.unit, lg[i]));
                 A::store_row(pa.row + so + O_QS + (j * QP + i * D) * ESZ, A::flip_sign(A::pack_row(qt), sgn[i]));
             }
         };
@@ -989,8 +1013,10 @@ struct Kern {
             const float lg[2] = {__builtin_amdgcn_logf(fabsf(gsv[0])), __builtin_amdgcn_logf(fabsf(gsv[1]))};
             const uint32_t sgn[2] = {gsv[0] < 0.f ? A::kSignBits : 0u, gsv[1] < 0.f ? A::kSignBits : 0u};
             float seg_decay = 0.f;   // lane l: log2 of the segment decay of (state l / 32, feature 32 pw + l % 32)
-            float carry = 0.f;       // lane l: natural-log gate sum of that column since the start of the chunk
-            const ProdAddr pa(sm, pw, static_cast<uint32_t>(lane));
+            float carry = 0.f;       // lane l: gate sum of that column since the start of the chunk
+            ProdAddr pa(sm, pw, static_cast<uint32_t>(lane));
+            pa.preact = a.gate_inv_tau != 0.f;
+            pa.unit = pa.preact ? a.gate_inv_tau : kLog2e;
 
             const TIO *q0 = static_cast<const TIO *>(a.q) + seg0, *k0 = static_cast<const TIO *>(a.k) + seg0,
                       *v0 = static_cast<const TIO *>(a.v) + seg0;
@@ -1252,6 +1278,7 @@ hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T
     a.chunk_steps = plan.chunk / 32;
     a.gamma = d.gamma;
     a.scale = d.scale;
+    a.gate_inv_tau = d.gate_mode == DSLA_GATE_PREACT ? 1.0f / d.tau : 0.f;
     const int D = d.d_k;
     if (d.io_dtype == DSLA_BF16) {
         if (D == 128) return launch_g<128, bf16_t>(d, plan, a, stream);

@@ -45,8 +45,10 @@ def log_gate_from_preact(z: np.ndarray, tau: float) -> np.ndarray:
 
 def layer_inputs(seed: int, B: int, T: int, H: int, dk: int, dv: int, *, io_dtype: str = "bf16",
                  gate_dtype: str = "f32", tau: float = 16.0, qk_scale: float = 1.0,
-                 gate_mean: float = 2.0) -> dict:
-    """One batch of layer inputs: dict with q, k, g1, g2 [B,T,H,dk] and v [B,T,H,dv]."""
+                 gate_mean: float = 2.0, gates: str = "log") -> dict:
+    """One batch of layer inputs: dict with q, k, g1, g2 [B,T,H,dk] and v [B,T,H,dv].
+    gates = "log": g1, g2 are log-gates; "preact": they are the pre-activations z themselves (same draws)."""
+    assert gates in ("log", "preact")
     out = {}
     for j, (name, d) in enumerate((("q", dk), ("k", dk), ("v", dv))):
         rng = np.random.default_rng(seed + j)
@@ -55,7 +57,7 @@ def layer_inputs(seed: int, B: int, T: int, H: int, dk: int, dv: int, *, io_dtyp
     for j, name in enumerate(("g1", "g2")):
         rng = np.random.default_rng(seed + 3 + j)
         z = rng.standard_normal((B, T, H, dk), dtype=np.float32) + np.float32(gate_mean)
-        out[name] = _store(log_gate_from_preact(z, tau), gate_dtype)
+        out[name] = _store(z if gates == "preact" else log_gate_from_preact(z, tau), gate_dtype)
     return out
 
 

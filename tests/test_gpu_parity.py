@@ -192,6 +192,37 @@ def test_cfg3_64k_full_size_sampled_heads():
     _sampled_heads_check("cfg3_64k", heads=(11,))
 
 
+@pytest.mark.parametrize("io,gate,d,T,tau,tol", [("bf16", "bf16", 128, 1500, 16.0, 2e-2), ("bf16", "f32", 64, 700, 16.0, 2e-2),
+                                                 ("f32", "f32", 64, 520, 16.0, 1e-4), ("f32", "f32", 128, 300, 1.0, 1e-4),
+                                                 ("f32", "bf16", 128, 200, 4.0, 1e-4)])
+def test_gate_preactivation_mode(io, gate, d, T, tau, tol):
+    """The gate tensors hold pre-activations z and the kernels form log alpha themselves; the oracle gets
+    log alpha from its own map of the same (storage-rounded) z.  Prefill, a continuation call, and decode
+    steps; the z of a few tokens are pushed far out (|z| up to 30) to cover both asymptotes of the map."""
+    B, H, steps = 2, 3, 5
+    x = wl.layer_inputs(77, B, T + steps, H, d, d, io_dtype=io, gate_dtype=gate, gates="preact", qk_scale=d ** -0.5,
+                        gate_mean=2.0 if tau > 1 else 4.0)
+    for n, sign in (("g1", 1.0), ("g2", -1.0)):
+        x[n][:, 5::97] = np.float32(30.0 * sign) if tau > 1 else np.float32(30.0)
+        x[n][:, 11::131, :, ::7] = np.float32(-6.0) if tau > 1 else np.float32(-2.0)
+    lg = {n: orc.log_gates_from_preactivations(x[n], tau) for n in ("g1", "g2")}
+    C = 64
+    worst = max(float(np.max(-np.add.reduceat(lg[n][:, :T].astype(np.float64), np.arange(0, T, C), axis=1))) for n in lg)
+    assert worst < 80.0, worst
+    layer = GpuLayer(B, H, d, io, gate, gamma=0.35, chunk=C, gate_mode=1, tau=tau)
+    T1 = 2 * T // 3 + 5
+    outs = [layer.prefill(slice_t(x, 0, T1)), layer.prefill(slice_t(x, T1, T))]
+    for t in range(T, T + steps):
+        outs.append(layer.decode(slice_t(x, t, t + 1)))
+    o = np.concatenate(outs, 1)
+    S1, S2 = layer.states()
+    ro, rS1, rS2 = orc.recurrent(x["q"], x["k"], x["v"], lg["g1"], lg["g2"], 0.35)
+    check("o prefill", o[:, :T], ro[:, :T], tol)
+    check("o decode", o[:, T:], ro[:, T:], tol)
+    check("S1", S1, rS1, tol)
+    check("S2", S2, rS2, tol)
+
+
 def test_cfg5_layer_instances_slice():
     """The DSLA part of the hybrid serving step: several layer instances, each with its own blend coefficient and
     inputs, prefill T=8192 then 128 decode steps.  A slice is checked: 3 of the 16 layers, 2 of the 8 sequences,

@@ -60,6 +60,15 @@ def test_argument_checks_need_no_gpu(lib):
     assert need > 0
     assert lib.dsla_prefill(ctypes.byref(seg), 1024, *([fake] * 8), None, 0, None) == 4
     assert lib.dsla_prefill(ctypes.byref(seg), 1024, *([fake] * 8), fake, need - 1, None) == 4
+    # gate mode: unknown mode; pre-activation mode needs a finite positive temperature
+    bad = dsla.make_desc(1, 2, 64, 64, io_dtype=0, gate_dtype=0, gate_mode=2)
+    assert lib.dsla_decode(ctypes.byref(bad), *([fake] * 9)) == 3
+    for tau in (0.0, -1.0, float("inf"), float("nan")):
+        bad = dsla.make_desc(1, 2, 64, 64, io_dtype=0, gate_dtype=0, gate_mode=1, tau=tau)
+        assert lib.dsla_decode(ctypes.byref(bad), *([fake] * 9)) == 2
+        assert lib.dsla_prefill_workspace_bytes(ctypes.byref(bad), 1024) == 0
+    ignored = dsla.make_desc(1, 2, 64, 64, io_dtype=0, gate_dtype=0, gate_mode=0, tau=0.0)   # tau unused for log gates
+    assert lib.dsla_prefill(ctypes.byref(ignored), 0, None, None, None, None, None, fake, fake, None, None, 0, None) == 0
     # T = 0 does nothing and needs no tensors
     assert lib.dsla_prefill(ctypes.byref(d), 0, None, None, None, None, None, fake, fake, None, None, 0, None) == 0
     assert lib.dsla_prefill(ctypes.byref(d), -1, *([fake] * 8), None, 0, None) == 2

@@ -285,5 +285,31 @@ def test_planted_mistakes_are_caught():
         assert np.max(np.abs(emulate(**kw) - o[0, :, 0])) > 1e-3
 
 
+def test_gate_map_against_sigmoid_power_and_asymptotes():
+    """The pre-activation -> log-gate map: alpha = sigmoid(z)^(1/tau), pinned by the direct sigmoid power on a
+    moderate range, by its values at 0, by both asymptotes, by sigmoid's reflection identity at tau = 1 and by
+    its derivative sigmoid(-z) / tau (a sign error, a missing 1/tau or softplus(+z) fails several of these)."""
+    import math
+    z = np.linspace(-12.0, 12.0, 97)
+    for tau in (1.0, 4.0, 16.0):
+        g = orc.log_gates_from_preactivations(z, tau)
+        assert g.dtype == np.float64 and np.all(g < 0)
+        direct = (1.0 / (1.0 + np.exp(-z))) ** (1.0 / tau)
+        np.testing.assert_allclose(np.exp(g), direct, rtol=1e-13)
+        assert abs(float(orc.log_gates_from_preactivations(0.0, tau)) + math.log(2.0) / tau) < 1e-16
+        assert np.all(np.diff(g) > 0)                       # more positive z = less forgetting
+        # z -> -inf: alpha -> e^(z/tau);  z -> +inf: log alpha -> -e^-z / tau (no overflow, no flush to zero)
+        assert abs(float(orc.log_gates_from_preactivations(-60.0, tau)) + 60.0 / tau) < 1e-20
+        assert float(orc.log_gates_from_preactivations(-800.0, tau)) == -800.0 / tau
+        hi = float(orc.log_gates_from_preactivations(40.0, tau))
+        assert hi < 0 and abs(hi * tau / -math.exp(-40.0) - 1.0) < 1e-12
+        # derivative by central differences
+        h = 1e-5
+        num = (orc.log_gates_from_preactivations(z + h, tau) - orc.log_gates_from_preactivations(z - h, tau)) / (2 * h)
+        np.testing.assert_allclose(num, (1.0 / (1.0 + np.exp(z))) / tau, rtol=1e-8, atol=1e-12)
+    g = orc.log_gates_from_preactivations(z, 1.0)
+    np.testing.assert_allclose(np.exp(g) + np.exp(g[::-1]), 1.0, rtol=1e-14)   # sigmoid(z) + sigmoid(-z) = 1
+
+
 def test_oracle_threads_reported():
     assert orc.threads() >= 1
