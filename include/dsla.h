@@ -132,6 +132,38 @@ DSLA_API dsla_status dsla_prefill(const dsla_desc *desc, int64_t T,
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * dsla_prefill_varlen - dsla_prefill for a batch of sequences of different lengths packed back to back along
+ * the token axis, with each sequence's states at a caller-chosen place in a pool of states: the prefill half
+ * of the mixed prefill/decode batches of the paper's serving system (Section 4.3 and the batching appendix),
+ * where requests of different prompt lengths are processed together and each keeps its own pair of states.
+ * Every sequence is an independent instance of the recurrence of Section 4.1.
+ *
+ *   desc->B        : number of sequences in the batch
+ *   total_T        : tokens in the batch = cu_seqlens[B]; at most 2^31 - 1
+ *   max_T          : an upper bound of the sequence lengths, max_T <= total_T.  It is used for planning only;
+ *                    a sequence longer than max_T is NOT processed correctly (the library cannot see the
+ *                    lengths without synchronising)
+ *   cu_seqlens     : DEVICE int32 [B + 1], non-decreasing, cu_seqlens[0] >= 0: sequence b is the tokens
+ *                    cu_seqlens[b] .. cu_seqlens[b+1] - 1.  A sequence of length 0 is legal: its states stay
+ *                    as they are and it has no output rows
+ *   state_slot     : DEVICE int32 [B] or NULL.  The states of sequence b are entry state_slot[b] of S1, S2
+ *                    ([n_slots][H][d_k][d_v], n_slots known to the caller only); NULL = entry b.  Values must
+ *                    be valid and distinct (two sequences on one entry race); other entries are not touched
+ *   q, k, g1, g2   : [total_T][H][d_k]      v, o : [total_T][H][d_v]
+ *   workspace      : at least dsla_prefill_varlen_workspace_bytes(desc, total_T, max_T) bytes, 256-byte aligned
+ * Everything else (chunking, gate domain, dtypes, in-place continuation of the states) is as for dsla_prefill.
+ * desc->segments > 0 cuts a sequence of max_T tokens into that many segments; shorter sequences use the first
+ * few of them.
+ */
+DSLA_API size_t dsla_prefill_varlen_workspace_bytes(const dsla_desc *desc, int64_t total_T, int64_t max_T);
+DSLA_API dsla_status dsla_prefill_varlen(const dsla_desc *desc, int64_t total_T, int64_t max_T,
+                                const int32_t *cu_seqlens, const int32_t *state_slot,
+                                const void *q, const void *k, const void *v,
+                                const void *g1, const void *g2,
+                                float *S1, float *S2, void *o,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * dsla_decode - one token per sequence: the state update and read-out of Section 4.1
  * applied once, fused so that each state is read from and written to memory exactly once.
  *   q, k, g1, g2 : [B][H][d_k]     v : [B][H][d_v]     o : [B][H][d_v] (written)
@@ -141,6 +173,17 @@ DSLA_API dsla_status dsla_decode(const dsla_desc *desc,
                         const void *q, const void *k, const void *v,
                         const void *g1, const void *g2,
                         float *S1, float *S2, void *o, void *stream);
+
+/*
+ * dsla_decode_slots - dsla_decode with the states of sequence b at entry state_slot[b] (DEVICE int32 [B], valid
+ * and distinct) of S1, S2 = [n_slots][H][d_k][d_v]: the decode half of a mixed batch, where the requests that
+ * are decoding in this step are a changing subset of the requests whose states are resident (Section 4.3).
+ * Entries not named are not touched.
+ */
+DSLA_API dsla_status dsla_decode_slots(const dsla_desc *desc,
+                              const void *q, const void *k, const void *v,
+                              const void *g1, const void *g2, const int32_t *state_slot,
+                              float *S1, float *S2, void *o, void *stream);
 
 /* Text for a status code (static storage). */
 DSLA_API const char *dsla_status_string(dsla_status s);

@@ -15,6 +15,7 @@ _lib = None
 DSLA_F32, DSLA_BF16 = 0, 1
 KERNEL_NAMES = ("state_init", "prefill_segment_state", "prefill_segment_scan", "prefill_chunk_loop", "decode")
 EXPORTS = ("dsla_state_init", "dsla_prefill_workspace_bytes", "dsla_prefill", "dsla_decode",
+           "dsla_prefill_varlen_workspace_bytes", "dsla_prefill_varlen", "dsla_decode_slots",
            "dsla_status_string", "dsla_last_hip_error", "dsla_profile_enable", "dsla_profile_collect")
 
 
@@ -55,6 +56,12 @@ def load_library():
     lib.dsla_prefill.restype = ctypes.c_int
     lib.dsla_decode.argtypes = [dp] + [vp] * 9
     lib.dsla_decode.restype = ctypes.c_int
+    lib.dsla_prefill_varlen_workspace_bytes.argtypes = [dp, ctypes.c_int64, ctypes.c_int64]
+    lib.dsla_prefill_varlen_workspace_bytes.restype = ctypes.c_size_t
+    lib.dsla_prefill_varlen.argtypes = [dp, ctypes.c_int64, ctypes.c_int64] + [vp] * 11 + [ctypes.c_size_t, vp]
+    lib.dsla_prefill_varlen.restype = ctypes.c_int
+    lib.dsla_decode_slots.argtypes = [dp] + [vp] * 10
+    lib.dsla_decode_slots.restype = ctypes.c_int
     lib.dsla_status_string.argtypes = [ctypes.c_int]
     lib.dsla_status_string.restype = ctypes.c_char_p
     lib.dsla_last_hip_error.argtypes = []
@@ -125,6 +132,26 @@ def dsla_decode(desc: DslaDesc, q, k, v, g1, g2, S1, S2, o):
     """One fused decode step (include/dsla.h: dsla_decode)."""
     _check(load_library().dsla_decode(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g1), _ptr(g2),
                                       _ptr(S1), _ptr(S2), _ptr(o), _stream()))
+
+
+def dsla_prefill_varlen_workspace_bytes(desc: DslaDesc, total_T: int, max_T: int) -> int:
+    return int(load_library().dsla_prefill_varlen_workspace_bytes(ctypes.byref(desc), int(total_T), int(max_T)))
+
+
+def dsla_prefill_varlen(desc: DslaDesc, total_T, max_T, cu_seqlens, state_slot, q, k, v, g1, g2, S1, S2, o,
+                        workspace=None):
+    """Prefill of packed sequences (include/dsla.h: dsla_prefill_varlen).  cu_seqlens: int32 GPU tensor [B+1];
+    state_slot: int32 GPU tensor [B] or None."""
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().dsla_prefill_varlen(ctypes.byref(desc), int(total_T), int(max_T), _ptr(cu_seqlens),
+                                              _ptr(state_slot), _ptr(q), _ptr(k), _ptr(v), _ptr(g1), _ptr(g2),
+                                              _ptr(S1), _ptr(S2), _ptr(o), _ptr(workspace), wbytes, _stream()))
+
+
+def dsla_decode_slots(desc: DslaDesc, q, k, v, g1, g2, state_slot, S1, S2, o):
+    """One decode step on states picked from a pool (include/dsla.h: dsla_decode_slots)."""
+    _check(load_library().dsla_decode_slots(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g1), _ptr(g2),
+                                            _ptr(state_slot), _ptr(S1), _ptr(S2), _ptr(o), _stream()))
 
 
 def profile_enable(enable: bool, max_records: int = 4096):

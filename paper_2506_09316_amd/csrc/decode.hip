@@ -37,8 +37,8 @@ __device__ __forceinline__ void store_f4(float4 *p, const float4 &v, bool nt)
 template <int DK, int DV, int SPLIT, bool NT, class TIO, class TG>
 __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
     const TIO *__restrict__ q, const TIO *__restrict__ k, const TIO *__restrict__ v, const TG *__restrict__ g1,
-    const TG *__restrict__ g2, float *__restrict__ S1, float *__restrict__ S2, TIO *__restrict__ o, int H,
-    float gamma, const float *__restrict__ gamma_per_head, float scale, float gate_inv_tau)
+    const TG *__restrict__ g2, const int32_t *__restrict__ slot, float *__restrict__ S1, float *__restrict__ S2,
+    TIO *__restrict__ o, int H, float gamma, const float *__restrict__ gamma_per_head, float scale, float gate_inv_tau)
 {
     constexpr int COLG = DV / 4 / SPLIT;          // threads across this workgroup's part of a state row (float4 each)
     constexpr int ROWG = kDecodeThreads / COLG;   // row groups
@@ -55,7 +55,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
     const int cg = tid % COLG;
     const int rg = tid / COLG;
     constexpr int ROWF4 = DV / 4;                 // float4 per state row
-    const size_t sbase = static_cast<size_t>(bh) * DK * DV;
+    // the states of sequence b live in entry slot[b] of the state arrays (entry b without a slot list)
+    const size_t sbase = (slot ? static_cast<size_t>(slot[bh / H]) * H + bh % H : static_cast<size_t>(bh)) * DK * DV;
     float4 *p1 = reinterpret_cast<float4 *>(S1 + sbase) + part * COLG + cg;
     float4 *p2 = reinterpret_cast<float4 *>(S2 + sbase) + part * COLG + cg;
 
@@ -165,25 +166,25 @@ inline DecodeVariant decode_variant()
 
 template <int D, int SPLIT, bool NT, class TIO, class TG>
 hipError_t launch_decode_v(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
-                           const void *g2, float *S1, float *S2, void *o, hipStream_t stream)
+                           const void *g2, const int32_t *slot, float *S1, float *S2, void *o, hipStream_t stream)
 {
     const unsigned grid = static_cast<unsigned>(d.B) * static_cast<unsigned>(d.H) * SPLIT;
     ProfileScope ps(DSLA_KERNEL_DECODE, stream);
     hipLaunchKernelGGL((decode_kernel<D, D, SPLIT, NT, TIO, TG>), dim3(grid), dim3(kDecodeThreads), 0, stream,
                        static_cast<const TIO *>(q), static_cast<const TIO *>(k), static_cast<const TIO *>(v),
-                       static_cast<const TG *>(g1), static_cast<const TG *>(g2), S1, S2, static_cast<TIO *>(o), d.H,
+                       static_cast<const TG *>(g1), static_cast<const TG *>(g2), slot, S1, S2, static_cast<TIO *>(o), d.H,
                        d.gamma, d.gamma_per_head, d.scale, d.gate_mode == DSLA_GATE_PREACT ? 1.0f / d.tau : 0.f);
     return hipGetLastError();
 }
 
 template <int D, class TIO, class TG>
 hipError_t launch_decode_t(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
-                           const void *g2, float *S1, float *S2, void *o, hipStream_t stream)
+                           const void *g2, const int32_t *slot, float *S1, float *S2, void *o, hipStream_t stream)
 {
     const DecodeVariant var = decode_variant();
 #define DSLA_DECODE_CASE(SP, N)                                                                          \
     if (var.split == SP && var.nt == N)                                                                  \
-        return launch_decode_v<D, SP, N, TIO, TG>(d, q, k, v, g1, g2, S1, S2, o, stream)
+        return launch_decode_v<D, SP, N, TIO, TG>(d, q, k, v, g1, g2, slot, S1, S2, o, stream)
     DSLA_DECODE_CASE(1, false);
     DSLA_DECODE_CASE(1, true);
     DSLA_DECODE_CASE(2, false);
@@ -196,13 +197,13 @@ hipError_t launch_decode_t(const dsla_desc &d, const void *q, const void *k, con
 
 template <int D>
 hipError_t launch_decode_d(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
-                           const void *g2, float *S1, float *S2, void *o, hipStream_t stream)
+                           const void *g2, const int32_t *slot, float *S1, float *S2, void *o, hipStream_t stream)
 {
     const bool io16 = d.io_dtype == DSLA_BF16, g16 = d.gate_dtype == DSLA_BF16;
-    if (io16 && g16) return launch_decode_t<D, bf16_t, bf16_t>(d, q, k, v, g1, g2, S1, S2, o, stream);
-    if (io16 && !g16) return launch_decode_t<D, bf16_t, float>(d, q, k, v, g1, g2, S1, S2, o, stream);
-    if (!io16 && g16) return launch_decode_t<D, float, bf16_t>(d, q, k, v, g1, g2, S1, S2, o, stream);
-    return launch_decode_t<D, float, float>(d, q, k, v, g1, g2, S1, S2, o, stream);
+    if (io16 && g16) return launch_decode_t<D, bf16_t, bf16_t>(d, q, k, v, g1, g2, slot, S1, S2, o, stream);
+    if (io16 && !g16) return launch_decode_t<D, bf16_t, float>(d, q, k, v, g1, g2, slot, S1, S2, o, stream);
+    if (!io16 && g16) return launch_decode_t<D, float, bf16_t>(d, q, k, v, g1, g2, slot, S1, S2, o, stream);
+    return launch_decode_t<D, float, float>(d, q, k, v, g1, g2, slot, S1, S2, o, stream);
 }
 
 }  // namespace
@@ -210,10 +211,10 @@ hipError_t launch_decode_d(const dsla_desc &d, const void *q, const void *k, con
 bool decode_supported(const dsla_desc &d) { return d.d_k == d.d_v && (d.d_k == 64 || d.d_k == 128); }
 
 hipError_t launch_decode(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
-                         const void *g2, float *S1, float *S2, void *o, hipStream_t stream)
+                         const void *g2, const int32_t *slot, float *S1, float *S2, void *o, hipStream_t stream)
 {
-    if (d.d_k == 128) return launch_decode_d<128>(d, q, k, v, g1, g2, S1, S2, o, stream);
-    return launch_decode_d<64>(d, q, k, v, g1, g2, S1, S2, o, stream);
+    if (d.d_k == 128) return launch_decode_d<128>(d, q, k, v, g1, g2, slot, S1, S2, o, stream);
+    return launch_decode_d<64>(d, q, k, v, g1, g2, slot, S1, S2, o, stream);
 }
 
 hipError_t launch_state_init(float *S1, float *S2, size_t elems_per_state, hipStream_t stream)

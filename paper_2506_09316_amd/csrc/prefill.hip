@@ -398,7 +398,9 @@ struct PrefillArgs {
     float *ws_state;         // [P][BH][2][D][D] fp32 (P > 1)
     float *ws_decay;         // [P-1][BH][2][D] fp32, log2 of the segment decay (P > 1)
     const float *gamma_per_head;
-    int64_t T;
+    const int32_t *cu;       // packed sequences: [B + 1] token offsets (sequence b = tokens cu[b] .. cu[b+1]-1); or null
+    const int32_t *slot;     // [B] index of each sequence's states in S1, S2; or null (sequence b uses entry b)
+    int64_t T;               // tokens per sequence (cu == null); with cu: upper bound of the sequence lengths
     int64_t seg_tokens;
     int H;
     int P;
@@ -915,14 +917,21 @@ struct Kern {
         const int bidx = bh / a.H, h = bh % a.H;
         const int BH = gridDim.x / nseg;
 
+        // this sequence: first token in the token-major tensors, length, where its states live
+        const int64_t seq0 = a.cu ? static_cast<int64_t>(a.cu[bidx]) : static_cast<int64_t>(bidx) * a.T;
+        const int64_t Tb = a.cu ? static_cast<int64_t>(a.cu[bidx + 1]) - seq0 : a.T;
+        const size_t sbh = static_cast<size_t>(a.slot ? a.slot[bidx] : bidx) * a.H + h;
         const int64_t t0 = static_cast<int64_t>(p) * a.seg_tokens;
-        const int64_t t1 = (t0 + a.seg_tokens < a.T) ? t0 + a.seg_tokens : a.T;
+        // A shorter sequence has fewer segments: the chunk loop has nothing to do past its end, and the state
+        // of a segment is only needed if another segment follows.  (Uniform exit, before any barrier.)
+        if (kFull ? t0 >= Tb : t0 + a.seg_tokens >= Tb) return;
+        const int64_t t1 = (t0 + a.seg_tokens < Tb) ? t0 + a.seg_tokens : Tb;
         const int ntok = static_cast<int>(t1 - t0);               // tokens of this segment (>= 1)
         const int nsteps = (ntok + S - 1) / S;
         const int wsteps = a.chunk_steps;                          // steps per chunk (a segment starts a chunk)
         const uint32_t rs = static_cast<uint32_t>(a.H) * D;       // elements between consecutive tokens
         // uniform element offset of (b, t0, h, 0); per-lane offsets are 32-bit
-        const size_t seg0 = (static_cast<size_t>(bidx) * a.T * a.H + h) * D + static_cast<size_t>(t0) * rs;
+        const size_t seg0 = (static_cast<size_t>(seq0 + t0) * a.H + h) * D;
         const size_t sstep = static_cast<size_t>(S) * rs;
         auto valid_of = [&](int n) -> int {   // tokens of step n that exist
             const int left = ntok - n * S;
@@ -943,7 +952,7 @@ struct Kern {
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
                     const float *src = (a.P > 1) ? a.ws_state + ((static_cast<size_t>(p) * BH + bh) * 2 + i) * D * D
-                                                 : (i ? a.S2 : a.S1) + static_cast<size_t>(bh) * D * D;
+                                                 : (i ? a.S2 : a.S1) + sbh * D * D;
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -992,7 +1001,7 @@ struct Kern {
             for (int i = 0; i < 2; ++i) {
                 float *dst = nullptr;
                 if (kFull) {
-                    if (p == a.P - 1) dst = (i ? a.S2 : a.S1) + static_cast<size_t>(bh) * D * D;
+                    if (t1 == Tb) dst = (i ? a.S2 : a.S1) + sbh * D * D;   // the segment with the last token
                 } else {
                     // contribution of segment p goes to state slot p+1
                     dst = a.ws_state + ((static_cast<size_t>(p + 1) * BH + bh) * 2 + i) * D * D;
@@ -1104,7 +1113,10 @@ __global__ __launch_bounds__(4 * D, 2) void prefill_kernel(PrefillArgs a)
 template <int D>
 __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restrict__ S1, const float *__restrict__ S2,
                                                            float *__restrict__ ws_state,
-                                                           const float *__restrict__ ws_decay, int BH, int P)
+                                                           const float *__restrict__ ws_decay, int BH, int P,
+                                                           const int32_t *__restrict__ cu,
+                                                           const int32_t *__restrict__ slot, int H,
+                                                           int64_t seg_tokens)
 {
     // one thread per 4 adjacent columns of one (bh, state, row)
     const size_t n4 = static_cast<size_t>(BH) * 2 * D * (D / 4);
@@ -1116,14 +1128,21 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restri
     const size_t bi = r / D;         // bh*2 + i
     const int i = static_cast<int>(bi & 1);
     const size_t bh = bi >> 1;
-    const float *src = (i ? S2 : S1) + (bh * D + row) * D + c4 * 4;
+    const size_t b = bh / H;
+    if (cu) {   // a shorter sequence has fewer segments
+        const int64_t Tb = static_cast<int64_t>(cu[b + 1]) - cu[b];
+        const int64_t Pb = Tb > 0 ? (Tb + seg_tokens - 1) / seg_tokens : 1;
+        if (Pb < P) P = static_cast<int>(Pb);
+    }
+    const size_t sbh = static_cast<size_t>(slot ? slot[b] : b) * H + bh % H;
+    const float *src = (i ? S2 : S1) + (sbh * D + row) * D + c4 * 4;
     float4 s = *reinterpret_cast<const float4 *>(src);
-    const size_t slot = static_cast<size_t>(BH) * 2 * D * D;
+    const size_t seg_stride = static_cast<size_t>(BH) * 2 * D * D;   // elements between the state slots of two segments
     float *w = ws_state + r * D + c4 * 4;
     *reinterpret_cast<float4 *>(w) = s;
     for (int p = 0; p + 1 < P; ++p) {
         const float dec = __builtin_amdgcn_exp2f(ws_decay[(static_cast<size_t>(p) * BH + bh) * 2 * D + i * D + row]);
-        float4 *u = reinterpret_cast<float4 *>(w + static_cast<size_t>(p + 1) * slot);
+        float4 *u = reinterpret_cast<float4 *>(w + static_cast<size_t>(p + 1) * seg_stride);
         const float4 x = *u;
         s.x = fmaf(dec, s.x, x.x);
         s.y = fmaf(dec, s.y, x.y);
@@ -1187,7 +1206,8 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_SCAN, stream);
             const size_t n4 = static_cast<size_t>(BH) * 2 * D * (D / 4);
             hipLaunchKernelGGL((segment_scan_kernel<D>), dim3(static_cast<unsigned>((n4 + 255) / 256)), dim3(256), 0,
-                               stream, a.S1, a.S2, a.ws_state, a.ws_decay, BH, plan.segments);
+                               stream, a.S1, a.S2, a.ws_state, a.ws_decay, BH, plan.segments, a.cu, a.slot, a.H,
+                               a.seg_tokens);
             err = hipGetLastError();
         }
         if (err != hipSuccess) return err;
@@ -1221,25 +1241,12 @@ bool combo_built(int D, int C, int io)
 
 }  // namespace
 
-bool prefill_plan(const dsla_desc &d, int64_t T, PrefillPlan *plan)
+namespace {
+// Fills the plan from the chunk length, the number of segments P the longest sequence is cut into, and its length.
+void finish_plan(const dsla_desc &d, int C, int64_t P, int64_t nchunks, PrefillPlan *plan)
 {
-    if (d.d_k != d.d_v) return false;
     const int D = d.d_k;
-    int C = d.chunk;
-    if (C == 0) C = combo_built(D, 64, d.io_dtype) ? 64 : 32;
-    if (!combo_built(D, C, d.io_dtype)) return false;
-    const int64_t nchunks = (T + C - 1) / C;
     const int64_t BH = static_cast<int64_t>(d.B) * d.H;
-    int64_t P;
-    if (d.segments > 0) {
-        P = d.segments;
-    } else {
-        // enough workgroups to cover the 256 compute units (two per unit for the small head size),
-        // but at least 4 chunks per segment so that the extra segment_state pass stays cheap
-        const int64_t target = (D == 64) ? 512 : 256;
-        P = target / BH;
-        if (P > nchunks / 4) P = nchunks / 4;
-    }
     if (P < 1) P = 1;
     if (P > nchunks) P = nchunks;
     const int64_t cps = (nchunks + P - 1) / P;
@@ -1256,12 +1263,61 @@ bool prefill_plan(const dsla_desc &d, int64_t T, PrefillPlan *plan)
         plan->ws_decay_bytes = 0;
     }
     plan->ws_total_bytes = plan->ws_state_bytes + plan->ws_decay_bytes;
+}
+int plan_chunk(const dsla_desc &d)
+{
+    if (d.d_k != d.d_v) return 0;
+    int C = d.chunk;
+    if (C == 0) C = combo_built(d.d_k, 64, d.io_dtype) ? 64 : 32;
+    return combo_built(d.d_k, C, d.io_dtype) ? C : 0;
+}
+}  // namespace
+
+bool prefill_plan(const dsla_desc &d, int64_t T, PrefillPlan *plan)
+{
+    const int C = plan_chunk(d);
+    if (!C) return false;
+    const int64_t nchunks = (T + C - 1) / C;
+    const int64_t BH = static_cast<int64_t>(d.B) * d.H;
+    int64_t P;
+    if (d.segments > 0) {
+        P = d.segments;
+    } else {
+        // enough workgroups to cover the 256 compute units (two per unit for the small head size),
+        // but at least 4 chunks per segment so that the extra segment_state pass stays cheap
+        const int64_t target = (d.d_k == 64) ? 512 : 256;
+        P = target / BH;
+        if (P > nchunks / 4) P = nchunks / 4;
+    }
+    finish_plan(d, C, P, nchunks, plan);
     return true;
 }
 
-hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T, const void *q, const void *k,
-                          const void *v, const void *g1, const void *g2, float *S1, float *S2, void *o,
-                          void *workspace, hipStream_t stream)
+// Packed sequences of different lengths share one segment length; a sequence of length T_b uses the first
+// ceil(T_b / segment_tokens) of the P segment slots.  The segment length is chosen so that all sequences together
+// make about one workgroup per compute unit (the same rule as above, on the total instead of a common length).
+bool prefill_plan_varlen(const dsla_desc &d, int64_t total_T, int64_t max_T, PrefillPlan *plan)
+{
+    const int C = plan_chunk(d);
+    if (!C) return false;
+    const int64_t nchunks = (max_T + C - 1) / C;
+    int64_t P;
+    if (d.segments > 0) {
+        P = d.segments;
+    } else {
+        const int64_t target = (d.d_k == 64) ? 512 : 256;
+        int64_t cps = (total_T * d.H / target + C - 1) / C;   // chunks per segment
+        if (cps < 4) cps = 4;
+        P = (nchunks + cps - 1) / cps;
+        if (P > 64) P = 64;   // bounds the workspace: P slots of both states for every sequence
+    }
+    finish_plan(d, C, P, nchunks, plan);
+    return true;
+}
+
+hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T, const int32_t *cu_seqlens,
+                          const int32_t *state_slot, const void *q, const void *k, const void *v, const void *g1,
+                          const void *g2, float *S1, float *S2, void *o, void *workspace, hipStream_t stream)
 {
     PrefillArgs a;
     a.q = q; a.k = k; a.v = v; a.g1 = g1; a.g2 = g2; a.o = o;
@@ -1271,6 +1327,8 @@ hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T
                      ? reinterpret_cast<float *>(static_cast<char *>(workspace) + plan.ws_state_bytes)
                      : nullptr;
     a.gamma_per_head = d.gamma_per_head;
+    a.cu = cu_seqlens;
+    a.slot = state_slot;
     a.T = T;
     a.seg_tokens = plan.segment_tokens;
     a.H = d.H;

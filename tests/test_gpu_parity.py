@@ -8,7 +8,8 @@ import pytest
 
 from oracle import dsla_oracle as orc
 from paper_2506_09316_amd import workloads as wl
-from tests.util import GpuLayer, max_rel_err, slice_t
+import paper_2506_09316_amd as dsla
+from tests.util import GpuLayer, code, max_rel_err, slice_t, to_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -221,6 +222,95 @@ def test_gate_preactivation_mode(io, gate, d, T, tau, tol):
     check("o decode", o[:, T:], ro[:, T:], tol)
     check("S1", S1, rS1, tol)
     check("S2", S2, rS2, tol)
+
+
+def _run_varlen(lengths, H, d, io, gate, tol, *, slots=None, n_slots=None, segments=0, chunk=64, seed=91, decode_steps=0,
+                max_T=None):
+    """Packed prefill of sequences with the given lengths (and optionally decode steps on the same state pool),
+    each sequence checked against the oracle run on it alone; pool entries no sequence names must stay bit-equal."""
+    import torch
+    B = len(lengths)
+    total = int(sum(lengths))
+    n_slots = n_slots or B
+    slots = list(range(B)) if slots is None else list(slots)
+    x = wl.layer_inputs(seed, 1, total + decode_steps * B, H, d, d, io_dtype=io, gate_dtype=gate, qk_scale=d ** -0.5)
+    S1_0, S2_0 = wl.initial_states(seed, n_slots, H, d, d, amplitude=0.3)
+    desc = dsla.make_desc(B, H, d, d, io_dtype=code(io), gate_dtype=code(gate), gamma=0.6, chunk=chunk, segments=segments)
+    S1, S2 = (torch.from_numpy(a.copy()).cuda() for a in (S1_0, S2_0))
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    cu_t = torch.from_numpy(cu).cuda()
+    slot_t = torch.tensor(slots, dtype=torch.int32, device="cuda")
+    q, k, v = (to_gpu(x[n][0, :total], io) for n in ("q", "k", "v"))
+    g1, g2 = (to_gpu(x[n][0, :total], gate) for n in ("g1", "g2"))
+    o = torch.full_like(v, float("nan"))
+    mT = max(lengths) if max_T is None else max_T
+    nbytes = dsla.dsla_prefill_varlen_workspace_bytes(desc, total, mT)
+    ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device="cuda") if nbytes else None
+    dsla.dsla_prefill_varlen(desc, total, mT, cu_t, slot_t, q, k, v, g1, g2, S1, S2, o, ws)
+    outs_dec = []
+    for s in range(decode_steps):
+        a, b = total + s * B, total + (s + 1) * B
+        dq, dk_, dv_ = (to_gpu(x[n][0, a:b], io) for n in ("q", "k", "v"))
+        dg1, dg2 = (to_gpu(x[n][0, a:b], gate) for n in ("g1", "g2"))
+        do = torch.full_like(dv_, float("nan"))
+        dsla.dsla_decode_slots(desc, dq, dk_, dv_, dg1, dg2, slot_t, S1, S2, do)
+        outs_dec.append(do.float().cpu().numpy())
+    torch.cuda.synchronize()
+    o = o.float().cpu().numpy()
+    S1, S2 = S1.cpu().numpy(), S2.cpu().numpy()
+    for b, L in enumerate(lengths):
+        sl = slots[b]
+        rows = list(range(cu[b], cu[b + 1])) + [total + s * B + b for s in range(decode_steps)]
+        xs = {n: x[n][:, rows] for n in x}
+        ro, rS1, rS2 = orc.recurrent(xs["q"], xs["k"], xs["v"], xs["g1"], xs["g2"], 0.6,
+                                     S1=S1_0[sl:sl + 1], S2=S2_0[sl:sl + 1])
+        if L:
+            check(f"o[seq {b}, {L} tokens]", o[cu[b]:cu[b + 1]][None], ro[:, :L], tol)
+        for s in range(decode_steps):
+            check(f"o decode[seq {b}, step {s}]", outs_dec[s][b][None, None], ro[:, L + s:L + s + 1], tol)
+        check(f"S1[seq {b}]", S1[sl:sl + 1], rS1, tol)
+        check(f"S2[seq {b}]", S2[sl:sl + 1], rS2, tol)
+    for sl in set(range(n_slots)) - set(slots):
+        assert np.array_equal(S1[sl], S1_0[sl]) and np.array_equal(S2[sl], S2_0[sl]), f"pool entry {sl} was touched"
+    assert np.all(np.isfinite(o))
+
+
+def test_varlen_fp32_ragged_lengths_one_segment():
+    _run_varlen([1, 31, 32, 33, 0, 200, 64, 97], 2, 64, "f32", "f32", 1e-4)
+
+
+def test_varlen_fp32_segments_differ_per_sequence():
+    # longest sequence cut into 5 segments of 128 tokens; the others use 0, 1, 2, 5 and 3 of them, one ends on a boundary
+    _run_varlen([600, 0, 100, 256, 513, 300], 2, 64, "f32", "f32", 1e-4, segments=5)
+    _run_varlen([130, 640, 7], 1, 128, "f32", "f32", 1e-4, segments=5, chunk=32, max_T=640)
+
+
+def test_varlen_bf16_state_pool_and_decode():
+    # serving shape in miniature: 5 requests in a pool of 9 state entries, prompts of mixed length, then 3 decode steps
+    _run_varlen([700, 45, 1300, 1, 256], 3, 128, "bf16", "bf16", 2e-2, slots=[7, 2, 0, 8, 4], n_slots=9, decode_steps=3)
+    _run_varlen([513, 2100], 2, 64, "bf16", "f32", 2e-2, slots=[1, 0], n_slots=3, segments=0, decode_steps=1, max_T=2500)
+
+
+def test_varlen_equals_dense_bitwise():
+    """Equal lengths, identity slots: the packed entry point runs the same kernels on the same plan."""
+    import torch
+    B, T, H, d = 3, 384, 2, 128
+    x = wl.layer_inputs(17, B, T, H, d, d, io_dtype="bf16", gate_dtype="bf16", qk_scale=d ** -0.5)
+    layer = GpuLayer(B, H, d, "bf16", "bf16", gamma=0.6, chunk=64, segments=3)
+    o_dense = layer.prefill(x)
+    S1d, S2d = layer.states()
+    desc = dsla.make_desc(B, H, d, d, io_dtype=code("bf16"), gate_dtype=code("bf16"), gamma=0.6, chunk=64, segments=3)
+    S1 = torch.zeros(B, H, d, d, device="cuda"); S2 = torch.zeros_like(S1)
+    cu = torch.arange(0, (B + 1) * T, T, dtype=torch.int32, device="cuda")
+    t = {n: to_gpu(x[n].reshape(B * T, H, d), "bf16") for n in x}
+    o = torch.full_like(t["v"], float("nan"))
+    nbytes = dsla.dsla_prefill_varlen_workspace_bytes(desc, B * T, T)
+    assert nbytes == dsla.dsla_prefill_workspace_bytes(desc, T)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    dsla.dsla_prefill_varlen(desc, B * T, T, cu, None, t["q"], t["k"], t["v"], t["g1"], t["g2"], S1, S2, o, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(o.float().cpu().numpy().reshape(B, T, H, d), o_dense)
+    assert np.array_equal(S1.cpu().numpy(), S1d) and np.array_equal(S2.cpu().numpy(), S2d)
 
 
 def test_cfg5_layer_instances_slice():

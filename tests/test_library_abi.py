@@ -69,9 +69,34 @@ def test_argument_checks_need_no_gpu(lib):
         assert lib.dsla_prefill_workspace_bytes(ctypes.byref(bad), 1024) == 0
     ignored = dsla.make_desc(1, 2, 64, 64, io_dtype=0, gate_dtype=0, gate_mode=0, tau=0.0)   # tau unused for log gates
     assert lib.dsla_prefill(ctypes.byref(ignored), 0, None, None, None, None, None, fake, fake, None, None, 0, None) == 0
+    # packed sequences: the bound of the lengths cannot exceed the total; the offsets are required
+    assert lib.dsla_prefill_varlen(ctypes.byref(d), 100, 101, fake, None, *([fake] * 8), None, 0, None) == 2
+    assert lib.dsla_prefill_varlen(ctypes.byref(d), 100, 50, None, None, *([fake] * 8), None, 0, None) == 1
+    assert lib.dsla_prefill_varlen(ctypes.byref(d), 2 ** 31, 50, fake, None, *([fake] * 8), None, 0, None) == 2
+    assert lib.dsla_prefill_varlen(ctypes.byref(d), 0, 0, fake, None, None, None, None, None, None, fake, fake, None,
+                                   None, 0, None) == 0
+    assert lib.dsla_prefill_varlen(ctypes.byref(seg), 4096, 1024, fake, None, *([fake] * 8), None, 0, None) == 4
+    assert lib.dsla_decode_slots(ctypes.byref(d), *([fake] * 5), None, *([fake] * 3), None) == 1
+    assert lib.dsla_decode_slots(ctypes.byref(d), *([fake] * 5), ctypes.c_void_p(4098), *([fake] * 3), None) == 2
     # T = 0 does nothing and needs no tensors
     assert lib.dsla_prefill(ctypes.byref(d), 0, None, None, None, None, None, fake, fake, None, None, 0, None) == 0
     assert lib.dsla_prefill(ctypes.byref(d), -1, *([fake] * 8), None, 0, None) == 2
+
+
+def test_varlen_workspace_plan(lib):
+    # 8 sequences, 32 heads: 256 (sequence, head) pairs; total 32768 tokens, longest 16384.  The segment length
+    # follows the total (about one workgroup per compute unit overall): 32768 * 32 / 256 = 4096 tokens, so the
+    # longest sequence has 4 segments and the workspace holds 4 slots of both states for all 256 pairs.
+    d = dsla.make_desc(8, 32, 128, 128, io_dtype=1, gate_dtype=1, chunk=64)
+    state = 256 * 128 * 128 * 4 * 2
+    decay = 3 * 256 * 2 * 128 * 4
+    assert lib.dsla_prefill_varlen_workspace_bytes(ctypes.byref(d), 32768, 16384) == 4 * state + decay
+    # short sequences only: one segment, no workspace
+    assert lib.dsla_prefill_varlen_workspace_bytes(ctypes.byref(d), 2048, 256) == 0
+    # the number of segments is capped at 64
+    d1 = dsla.make_desc(1, 1, 64, 64, io_dtype=1, gate_dtype=1, chunk=32)
+    n = lib.dsla_prefill_varlen_workspace_bytes(ctypes.byref(d1), 1 << 20, 1 << 20)
+    assert n == 64 * 64 * 64 * 4 * 2 + 63 * 2 * 64 * 4 + (-(63 * 2 * 64 * 4) % 256)
 
 
 def test_workspace_plan(lib):
