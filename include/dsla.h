@@ -196,14 +196,15 @@ DSLA_API const char *dsla_last_hip_error(void);
  * bracketed by two HIP events recorded on the launch stream (events come from a pool
  * created by dsla_profile_enable, so the launch path still allocates nothing).
  * Kernel ids: 0 state_init, 1 prefill_segment_state, 2 prefill_segment_scan,
- * 3 prefill_chunk_loop, 4 decode.
+ * 3 prefill_chunk_loop, 4 decode, 5 prefill_segment_list (packed sequences only).
  */
 #define DSLA_KERNEL_STATE_INIT 0
 #define DSLA_KERNEL_PREFILL_SEGMENT_STATE 1
 #define DSLA_KERNEL_PREFILL_SEGMENT_SCAN 2
 #define DSLA_KERNEL_PREFILL_CHUNK_LOOP 3
 #define DSLA_KERNEL_DECODE 4
-#define DSLA_KERNEL_COUNT 5
+#define DSLA_KERNEL_PREFILL_SEGMENT_LIST 5
+#define DSLA_KERNEL_COUNT 6
 
 /* enable != 0: create the event pool (max_records launches can be recorded between two
  * collects) and start recording; enable == 0: stop and destroy the pool. */

@@ -55,8 +55,11 @@ struct PrefillPlan {
     int segments;            // P >= 1
     int64_t segment_tokens;  // tokens per segment (multiple of C), last segment may be shorter
     size_t state_elems;      // B*H*d_k*d_v
-    size_t ws_state_bytes;   // P slots of both states (fp32) when P > 1
-    size_t ws_decay_bytes;   // P-1 slots of both segment decays (fp32 log2) when P > 1
+    size_t ws_state_bytes;   // one slot of both states (fp32) per (segment, sequence, head) when P > 1
+    size_t ws_decay_bytes;   // one slot of both segment decays (fp32 log2) per (segment, sequence, head) when P > 1
+    int64_t max_items;       // packed sequences with P > 1: capacity of the list of all segments (else 0)
+    int64_t max_pre_items;   //   and of the list of segments that have a successor
+    size_t ws_lists_bytes;   //   and the bytes of the lists
     size_t ws_total_bytes;
 };
 bool prefill_plan(const dsla_desc &d, int64_t T, PrefillPlan *plan);  // false: unsupported combination

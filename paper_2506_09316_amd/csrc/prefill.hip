@@ -395,11 +395,19 @@ struct PrefillArgs {
     const void *q, *k, *v, *g1, *g2;
     void *o;
     float *S1, *S2;          // caller's states
-    float *ws_state;         // [P][BH][2][D][D] fp32 (P > 1)
-    float *ws_decay;         // [P-1][BH][2][D] fp32, log2 of the segment decay (P > 1)
+    // One workspace slot per (segment, sequence, head): slot = (p B + b) H + h, or with work lists
+    // (seg_first[b] + p) H + h.  The last segment of a sequence has no decay entry that anyone reads.
+    float *ws_state;         // [slot][2][D][D] fp32 (P > 1): state at the start of the segment
+    float *ws_decay;         // [slot][2][D] fp32 (P > 1): log2 of the decay over the segment
     const float *gamma_per_head;
     const int32_t *cu;       // packed sequences: [B + 1] token offsets (sequence b = tokens cu[b] .. cu[b+1]-1); or null
     const int32_t *slot;     // [B] index of each sequence's states in S1, S2; or null (sequence b uses entry b)
+    // Packed sequences cut into segments: the work lists written by segment_list_kernel.  A workgroup is
+    // (list entry, head); entries past the count exit.  Null when every sequence is one segment or cu is null.
+    const int32_t *seg_first;   // [B + 1] index of the first segment of each sequence among all segments
+    const int32_t *seg_count;   // [2] entries in list_full, list_pre
+    const int2 *list_full;      // (sequence, segment) of every segment
+    const int2 *list_pre;       // (sequence, segment) of every segment that is followed by another one
     int64_t T;               // tokens per sequence (cu == null); with cu: upper bound of the sequence lengths
     int64_t seg_tokens;
     int H;
@@ -911,11 +919,27 @@ struct Kern {
         const long long wg_rt0 = __builtin_amdgcn_s_memrealtime(), wg_c0 = __builtin_amdgcn_s_memtime();
 #endif
 
-        const int nseg = kFull ? a.P : a.P - 1;
-        const int bh = blockIdx.x / nseg;
-        const int p = blockIdx.x % nseg;
-        const int bidx = bh / a.H, h = bh % a.H;
-        const int BH = gridDim.x / nseg;
+        int bidx, h, p;
+        size_t slot0;   // workspace slot of (segment 0, this sequence, this head); segment p' is p' * slot_step further
+        size_t slot_step;
+        if (a.list_full) {
+            const int it = blockIdx.x / a.H;
+            if (it >= a.seg_count[kFull ? 0 : 1]) return;   // the lists are sized for the worst case
+            const int2 e = (kFull ? a.list_full : a.list_pre)[it];
+            bidx = e.x;
+            p = e.y;
+            h = blockIdx.x % a.H;
+            slot0 = static_cast<size_t>(a.seg_first[bidx]) * a.H + h;
+            slot_step = a.H;
+        } else {
+            const int nseg = kFull ? a.P : a.P - 1;
+            const int bh = blockIdx.x / nseg;
+            p = blockIdx.x % nseg;
+            bidx = bh / a.H;
+            h = bh % a.H;
+            slot0 = bh;
+            slot_step = gridDim.x / nseg;   // B H
+        }
 
         // this sequence: first token in the token-major tensors, length, where its states live
         const int64_t seq0 = a.cu ? static_cast<int64_t>(a.cu[bidx]) : static_cast<int64_t>(bidx) * a.T;
@@ -951,7 +975,8 @@ struct Kern {
             if (kFull) {
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
-                    const float *src = (a.P > 1) ? a.ws_state + ((static_cast<size_t>(p) * BH + bh) * 2 + i) * D * D
+                    // the first segment starts from the caller's states, a later one from what the segment scan left
+                    const float *src = (p > 0) ? a.ws_state + ((slot0 + p * slot_step) * 2 + i) * D * D
                                                  : (i ? a.S2 : a.S1) + sbh * D * D;
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt)
@@ -1004,7 +1029,7 @@ struct Kern {
                     if (t1 == Tb) dst = (i ? a.S2 : a.S1) + sbh * D * D;   // the segment with the last token
                 } else {
                     // contribution of segment p goes to state slot p+1
-                    dst = a.ws_state + ((static_cast<size_t>(p + 1) * BH + bh) * 2 + i) * D * D;
+                    dst = a.ws_state + ((slot0 + (p + 1) * slot_step) * 2 + i) * D * D;
                 }
                 if (dst) {
                     const uint32_t sb = opaque(static_cast<uint32_t>(8 * g) * D + 32 * ct + ln);
@@ -1094,7 +1119,7 @@ struct Kern {
 #endif
             if (!kFull) {
                 // log2 decay of segment p goes to decay slot p
-                a.ws_decay[(static_cast<size_t>(p) * BH + bh) * 2 * D + (lane >> 5) * D + 32 * pw + (lane & 31)] = seg_decay;
+                a.ws_decay[(slot0 + p * slot_step) * 2 * D + (lane >> 5) * D + 32 * pw + (lane & 31)] = seg_decay;
             }
         }
     }
@@ -1108,14 +1133,68 @@ __global__ __launch_bounds__(4 * D, 2) void prefill_kernel(PrefillArgs a)
     K::run(a, lds_addr_of(smem));
 }
 
-// Elementwise scan over segments: slot 0 <- caller's state; slot p+1 <- 2^{decay_p} * slot p + U_p,
-// where U_p was left in slot p+1 by the segment_state kernel.
+// Work lists for packed sequences (one workgroup): sequence b has ceil(T_b / seg_tokens) segments;
+// seg_first = exclusive prefix sum of that over the sequences, list_full = every (sequence, segment),
+// list_pre = those with a successor.  Thread t takes a contiguous run of sequences.
+__global__ __launch_bounds__(256) void segment_list_kernel(const int32_t *__restrict__ cu, int B, int64_t seg_tokens,
+                                                           int32_t *__restrict__ seg_first,
+                                                           int32_t *__restrict__ seg_count, int2 *__restrict__ list_full,
+                                                           int2 *__restrict__ list_pre, int cap_full, int cap_pre)
+{
+    __shared__ int s_sum[256];
+    const int t = threadIdx.x;
+    const int per = (B + 255) / 256;
+    const int b0 = t * per, b1 = (b0 + per < B) ? b0 + per : B;
+    auto segments_of = [&](int b) -> int {
+        const int64_t Tb = static_cast<int64_t>(cu[b + 1]) - cu[b];
+        return Tb > 0 ? static_cast<int>((Tb + seg_tokens - 1) / seg_tokens) : 0;
+    };
+    int mine = 0, mine_seq = 0;   // segments, and sequences with at least one, in this thread's run
+    for (int b = b0; b < b1; ++b) {
+        const int n = segments_of(b);
+        mine += n;
+        mine_seq += n > 0;
+    }
+    // exclusive scans over the 256 threads of (segments) and (segments - non-empty sequences) = entries of list_pre
+    s_sum[t] = mine;
+    __syncthreads();
+    int before = 0, before_seq = 0;
+    for (int u = 0; u < t; ++u) before += s_sum[u];
+    __syncthreads();
+    s_sum[t] = mine_seq;
+    __syncthreads();
+    for (int u = 0; u < t; ++u) before_seq += s_sum[u];
+    int at = before, at_pre = before - before_seq;
+    for (int b = b0; b < b1; ++b) {
+        const int n = segments_of(b);
+        seg_first[b] = at;
+        // the capacities hold whenever the offsets add up to the total the caller gave; offsets that do not
+        // must not write past the lists (the segments that do not fit are dropped)
+        for (int p = 0; p < n; ++p) {
+            if (at + p < cap_full) list_full[at + p] = make_int2(b, p);
+            if (p + 1 < n) {
+                if (at_pre < cap_pre) list_pre[at_pre] = make_int2(b, p);
+                ++at_pre;
+            }
+        }
+        at += n;
+    }
+    if (t == 255) {
+        seg_first[B] = at;
+        seg_count[0] = at < cap_full ? at : cap_full;
+        seg_count[1] = at_pre < cap_pre ? at_pre : cap_pre;
+    }
+}
+
+// Elementwise scan over the segments of every (sequence, head): s_0 = caller's state; s_{p+1} = 2^{decay_p} s_p + U_p
+// goes to the slot of segment p+1, where the segment_state kernel had left U_p.  (The slot of segment 0 is not used.)
 template <int D>
 __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restrict__ S1, const float *__restrict__ S2,
                                                            float *__restrict__ ws_state,
                                                            const float *__restrict__ ws_decay, int BH, int P,
                                                            const int32_t *__restrict__ cu,
-                                                           const int32_t *__restrict__ slot, int H,
+                                                           const int32_t *__restrict__ slot,
+                                                           const int32_t *__restrict__ seg_first, int H,
                                                            int64_t seg_tokens)
 {
     // one thread per 4 adjacent columns of one (bh, state, row)
@@ -1128,21 +1207,23 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restri
     const size_t bi = r / D;         // bh*2 + i
     const int i = static_cast<int>(bi & 1);
     const size_t bh = bi >> 1;
-    const size_t b = bh / H;
-    if (cu) {   // a shorter sequence has fewer segments
+    const size_t b = bh / H, h = bh % H;
+    size_t slot0 = bh, slot_step = BH;
+    if (cu) {   // a shorter sequence has fewer segments, an empty one none
         const int64_t Tb = static_cast<int64_t>(cu[b + 1]) - cu[b];
-        const int64_t Pb = Tb > 0 ? (Tb + seg_tokens - 1) / seg_tokens : 1;
+        const int64_t Pb = Tb > 0 ? (Tb + seg_tokens - 1) / seg_tokens : 0;
         if (Pb < P) P = static_cast<int>(Pb);
+        if (P <= 1) return;
+        slot0 = static_cast<size_t>(seg_first[b]) * H + h;
+        slot_step = H;
     }
-    const size_t sbh = static_cast<size_t>(slot ? slot[b] : b) * H + bh % H;
+    const size_t sbh = static_cast<size_t>(slot ? slot[b] : b) * H + h;
     const float *src = (i ? S2 : S1) + (sbh * D + row) * D + c4 * 4;
     float4 s = *reinterpret_cast<const float4 *>(src);
-    const size_t seg_stride = static_cast<size_t>(BH) * 2 * D * D;   // elements between the state slots of two segments
-    float *w = ws_state + r * D + c4 * 4;
-    *reinterpret_cast<float4 *>(w) = s;
+    const size_t in_slot = (static_cast<size_t>(i) * D + row) * D + c4 * 4;   // this thread's place inside a slot
     for (int p = 0; p + 1 < P; ++p) {
-        const float dec = __builtin_amdgcn_exp2f(ws_decay[(static_cast<size_t>(p) * BH + bh) * 2 * D + i * D + row]);
-        float4 *u = reinterpret_cast<float4 *>(w + static_cast<size_t>(p + 1) * seg_stride);
+        const float dec = __builtin_amdgcn_exp2f(ws_decay[(slot0 + p * slot_step) * 2 * D + i * D + row]);
+        float4 *u = reinterpret_cast<float4 *>(ws_state + (slot0 + (p + 1) * slot_step) * 2 * D * D + in_slot);
         const float4 x = *u;
         s.x = fmaf(dec, s.x, x.x);
         s.y = fmaf(dec, s.y, x.y);
@@ -1187,15 +1268,28 @@ template <int D, class TIO, class TG>
 hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a, hipStream_t stream)
 {
     const int BH = d.B * d.H;
-    hipError_t err;
+    // workgroups of the two big kernels: one per (segment, sequence, head); with work lists one per (list entry, head)
+    const unsigned grid_pre = a.list_full ? static_cast<unsigned>(plan.max_pre_items * d.H)
+                                          : static_cast<unsigned>(BH * (plan.segments - 1));
+    const unsigned grid_full = a.list_full ? static_cast<unsigned>(plan.max_items * d.H)
+                                           : static_cast<unsigned>(BH * plan.segments);
+    hipError_t err = hipSuccess;
     if (plan.segments > 1) {
 #ifdef DSLA_PHASE_CLOCKS
         a.dbg = clock_buffer(stream);
 #endif
-        {
+        if (a.list_full) {
+            ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_LIST, stream);
+            hipLaunchKernelGGL(segment_list_kernel, dim3(1), dim3(256), 0, stream, a.cu, d.B, a.seg_tokens,
+                               const_cast<int32_t *>(a.seg_first), const_cast<int32_t *>(a.seg_count),
+                               const_cast<int2 *>(a.list_full), const_cast<int2 *>(a.list_pre),
+                               static_cast<int>(plan.max_items), static_cast<int>(plan.max_pre_items));
+            err = hipGetLastError();
+            if (err != hipSuccess) return err;
+        }
+        if (grid_pre > 0) {
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_STATE, stream);
-            hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, false>), dim3(BH * (plan.segments - 1)), dim3(4 * D), 0,
-                               stream, a);
+            hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, false>), dim3(grid_pre), dim3(4 * D), 0, stream, a);
             err = hipGetLastError();
         }
         if (err != hipSuccess) return err;
@@ -1206,8 +1300,8 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_SCAN, stream);
             const size_t n4 = static_cast<size_t>(BH) * 2 * D * (D / 4);
             hipLaunchKernelGGL((segment_scan_kernel<D>), dim3(static_cast<unsigned>((n4 + 255) / 256)), dim3(256), 0,
-                               stream, a.S1, a.S2, a.ws_state, a.ws_decay, BH, plan.segments, a.cu, a.slot, a.H,
-                               a.seg_tokens);
+                               stream, a.S1, a.S2, a.ws_state, a.ws_decay, BH, plan.segments, a.cu, a.slot,
+                               a.seg_first, a.H, a.seg_tokens);
             err = hipGetLastError();
         }
         if (err != hipSuccess) return err;
@@ -1217,11 +1311,11 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
 #endif
     {
         ProfileScope ps(DSLA_KERNEL_PREFILL_CHUNK_LOOP, stream);
-        hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, true>), dim3(BH * plan.segments), dim3(4 * D), 0, stream, a);
+        hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, true>), dim3(grid_full), dim3(4 * D), 0, stream, a);
     }
     err = hipGetLastError();
 #ifdef DSLA_PHASE_CLOCKS
-    clock_print("chunk_loop", a.dbg, D / 8, stream, BH * plan.segments);
+    clock_print("chunk_loop", a.dbg, D / 8, stream, static_cast<int>(grid_full));
 #endif
     return err;
 }
@@ -1255,6 +1349,8 @@ void finish_plan(const dsla_desc &d, int C, int64_t P, int64_t nchunks, PrefillP
     plan->segments = static_cast<int>(P);
     plan->segment_tokens = cps * C;
     plan->state_elems = static_cast<size_t>(BH) * D * D;
+    plan->max_items = plan->max_pre_items = 0;
+    plan->ws_lists_bytes = 0;
     if (P > 1) {
         plan->ws_state_bytes = static_cast<size_t>(P) * plan->state_elems * 2 * sizeof(float);
         plan->ws_decay_bytes = ((static_cast<size_t>(P - 1) * BH * 2 * D * sizeof(float)) + 255) / 256 * 256;
@@ -1293,9 +1389,13 @@ bool prefill_plan(const dsla_desc &d, int64_t T, PrefillPlan *plan)
     return true;
 }
 
-// Packed sequences of different lengths share one segment length; a sequence of length T_b uses the first
-// ceil(T_b / segment_tokens) of the P segment slots.  The segment length is chosen so that all sequences together
-// make about one workgroup per compute unit (the same rule as above, on the total instead of a common length).
+// Packed sequences of different lengths share one segment length; a sequence of length T_b has
+// ceil(T_b / segment_tokens) segments.  The segment length is chosen so that all sequences together make about
+// one workgroup per compute unit, the same rule as above on the total instead of a common length (measured on
+// mixed batches: twice as many segments gain on some mixes and lose on others, within 10 %).
+// The kernels find their work in lists built on the device (the lengths are not known here); list and workspace
+// sizes are worst cases: sum_b ceil(T_b / L) <= total_T / L + B segments, of which at most total_T / L have a
+// successor.
 bool prefill_plan_varlen(const dsla_desc &d, int64_t total_T, int64_t max_T, PrefillPlan *plan)
 {
     const int C = plan_chunk(d);
@@ -1309,9 +1409,20 @@ bool prefill_plan_varlen(const dsla_desc &d, int64_t total_T, int64_t max_T, Pre
         int64_t cps = (total_T * d.H / target + C - 1) / C;   // chunks per segment
         if (cps < 4) cps = 4;
         P = (nchunks + cps - 1) / cps;
-        if (P > 64) P = 64;   // bounds the workspace: P slots of both states for every sequence
     }
     finish_plan(d, C, P, nchunks, plan);
+    if (plan->segments > 1) {
+        const int D = d.d_k;
+        auto up = [](size_t n) { return (n + 255) / 256 * 256; };
+        plan->max_pre_items = total_T / plan->segment_tokens;
+        plan->max_items = plan->max_pre_items + d.B;
+        const size_t slots = static_cast<size_t>(plan->max_items) * d.H;
+        plan->ws_state_bytes = slots * 2 * D * D * sizeof(float);
+        plan->ws_decay_bytes = up(slots * 2 * D * sizeof(float));
+        plan->ws_lists_bytes = up((static_cast<size_t>(d.B) + 1) * 4) + 256 + up(plan->max_items * 8) +
+                               up(plan->max_pre_items * 8);
+        plan->ws_total_bytes = plan->ws_state_bytes + plan->ws_decay_bytes + plan->ws_lists_bytes;
+    }
     return true;
 }
 
@@ -1329,6 +1440,19 @@ hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T
     a.gamma_per_head = d.gamma_per_head;
     a.cu = cu_seqlens;
     a.slot = state_slot;
+    a.seg_first = a.seg_count = nullptr;
+    a.list_full = a.list_pre = nullptr;
+    if (plan.max_items > 0) {   // packed sequences, more than one segment: carve the work lists
+        auto up = [](size_t n) { return (n + 255) / 256 * 256; };
+        char *w = static_cast<char *>(workspace) + plan.ws_state_bytes + plan.ws_decay_bytes;
+        a.seg_first = reinterpret_cast<int32_t *>(w);
+        w += up((static_cast<size_t>(d.B) + 1) * 4);
+        a.seg_count = reinterpret_cast<int32_t *>(w);
+        w += 256;
+        a.list_full = reinterpret_cast<int2 *>(w);
+        w += up(plan.max_items * 8);
+        a.list_pre = reinterpret_cast<int2 *>(w);
+    }
     a.T = T;
     a.seg_tokens = plan.segment_tokens;
     a.H = d.H;

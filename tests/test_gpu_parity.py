@@ -292,7 +292,8 @@ def test_varlen_bf16_state_pool_and_decode():
 
 
 def test_varlen_equals_dense_bitwise():
-    """Equal lengths, identity slots: the packed entry point runs the same kernels on the same plan."""
+    """Equal lengths, identity slots: the packed entry point runs the same kernels with the same segment length
+    (its workgroups find their segments through the device-built lists instead of their index)."""
     import torch
     B, T, H, d = 3, 384, 2, 128
     x = wl.layer_inputs(17, B, T, H, d, d, io_dtype="bf16", gate_dtype="bf16", qk_scale=d ** -0.5)
@@ -305,7 +306,6 @@ def test_varlen_equals_dense_bitwise():
     t = {n: to_gpu(x[n].reshape(B * T, H, d), "bf16") for n in x}
     o = torch.full_like(t["v"], float("nan"))
     nbytes = dsla.dsla_prefill_varlen_workspace_bytes(desc, B * T, T)
-    assert nbytes == dsla.dsla_prefill_workspace_bytes(desc, T)
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     dsla.dsla_prefill_varlen(desc, B * T, T, cu, None, t["q"], t["k"], t["v"], t["g1"], t["g2"], S1, S2, o, ws)
     torch.cuda.synchronize()

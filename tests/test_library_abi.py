@@ -84,19 +84,22 @@ def test_argument_checks_need_no_gpu(lib):
 
 
 def test_varlen_workspace_plan(lib):
-    # 8 sequences, 32 heads: 256 (sequence, head) pairs; total 32768 tokens, longest 16384.  The segment length
-    # follows the total (about one workgroup per compute unit overall): 32768 * 32 / 256 = 4096 tokens, so the
-    # longest sequence has 4 segments and the workspace holds 4 slots of both states for all 256 pairs.
+    up = lambda n: (n + 255) // 256 * 256
+    # 8 sequences, 32 heads; total 32768 tokens, longest 16384.  The segment length follows the total (about one
+    # workgroup per compute unit overall): 32768 * 32 / 256 = 4096 tokens, so the longest sequence has 4 segments.
+    # Worst case 32768 / 4096 + 8 = 16 segments in all, 8 of them with a successor.
     d = dsla.make_desc(8, 32, 128, 128, io_dtype=1, gate_dtype=1, chunk=64)
-    state = 256 * 128 * 128 * 4 * 2
-    decay = 3 * 256 * 2 * 128 * 4
-    assert lib.dsla_prefill_varlen_workspace_bytes(ctypes.byref(d), 32768, 16384) == 4 * state + decay
-    # short sequences only: one segment, no workspace
+    slots = 16 * 32
+    want = slots * 2 * 128 * 128 * 4 + up(slots * 2 * 128 * 4) + up(9 * 4) + 256 + up(16 * 8) + up(8 * 8)
+    assert lib.dsla_prefill_varlen_workspace_bytes(ctypes.byref(d), 32768, 16384) == want
+    # short sequences only: one segment each, no workspace
     assert lib.dsla_prefill_varlen_workspace_bytes(ctypes.byref(d), 2048, 256) == 0
-    # the number of segments is capped at 64
-    d1 = dsla.make_desc(1, 1, 64, 64, io_dtype=1, gate_dtype=1, chunk=32)
-    n = lib.dsla_prefill_varlen_workspace_bytes(ctypes.byref(d1), 1 << 20, 1 << 20)
-    assert n == 64 * 64 * 64 * 4 * 2 + 63 * 2 * 64 * 4 + (-(63 * 2 * 64 * 4) % 256)
+    # equal lengths and a given segment count: the workspace differs from the dense call's only by the lists
+    d3 = dsla.make_desc(3, 2, 128, 128, io_dtype=1, gate_dtype=1, chunk=64, segments=3)
+    dense = lib.dsla_prefill_workspace_bytes(ctypes.byref(d3), 384)
+    packed = lib.dsla_prefill_varlen_workspace_bytes(ctypes.byref(d3), 3 * 384, 384)
+    assert dense == 3 * 6 * 2 * 128 * 128 * 4 + up(2 * 6 * 2 * 128 * 4)
+    assert packed == 12 * 2 * 2 * 128 * 128 * 4 + up(12 * 2 * 2 * 128 * 4) + up(4 * 4) + 256 + up(12 * 8) + up(9 * 8)
 
 
 def test_workspace_plan(lib):
