@@ -1,0 +1,112 @@
+"""The DSLA share of a hybrid serving step, as a usage example and a measurement:
+
+    python -m paper_2506_09316_amd.serving_step [--layers 16 --B 8 --T 8192 --decode 128]
+
+L layer instances (each with its own blend coefficient and its own pair of states per sequence) prefill a
+prompt of T tokens for B sequences and then decode token by token.  The decode step of all layers is captured
+into one HIP graph and replayed per token (the library enqueues only kernels and allocates nothing, so it can be
+captured); the eager loop is timed beside it.  Inputs are synthetic and shared by the layers: the projections that
+would produce them, the softmax-attention layers and the MLPs of the stack are not part of this library.
+Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--layers", type=int, default=16)
+    ap.add_argument("--B", type=int, default=8)
+    ap.add_argument("--T", type=int, default=8192)
+    ap.add_argument("--H", type=int, default=32)
+    ap.add_argument("--d", type=int, default=128)
+    ap.add_argument("--decode", type=int, default=128)
+    ap.add_argument("--repeat", type=int, default=5, help="timed repetitions of the prefill of all layers")
+    a = ap.parse_args()
+
+    import torch
+    import paper_2506_09316_amd as dsla
+    from paper_2506_09316_amd.binding import DSLA_BF16
+
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20250609)
+    L, B, T, H, d = a.layers, a.B, a.T, a.H, a.d
+
+    def rnd(*shape):
+        return (torch.randn(*shape, device=dev, generator=gen) * d ** -0.5).to(torch.bfloat16)
+
+    def gates(*shape):   # log alpha = -softplus(-z) / 16, z ~ N(2, 1)
+        z = torch.randn(*shape, device=dev, generator=gen) + 2.0
+        return (-torch.nn.functional.softplus(-z) / 16.0).to(torch.bfloat16)
+
+    q, k, v, g1, g2 = rnd(B, T, H, d), rnd(B, T, H, d), rnd(B, T, H, d), gates(B, T, H, d), gates(B, T, H, d)
+    o = torch.empty_like(v)
+    gammas = torch.rand(L, generator=torch.Generator().manual_seed(7)) * 0.6 + 0.2
+    descs = [dsla.make_desc(B, H, d, d, io_dtype=DSLA_BF16, gate_dtype=DSLA_BF16, gamma=float(gammas[l]), chunk=64)
+             for l in range(L)]
+    S = [(torch.empty(B, H, d, d, device=dev), torch.empty(B, H, d, d, device=dev)) for _ in range(L)]
+    nws = dsla.dsla_prefill_workspace_bytes(descs[0], T)
+    ws = torch.empty(max(nws, 256), dtype=torch.uint8, device=dev)
+
+    def prefill_all():
+        for l in range(L):
+            dsla.dsla_state_init(descs[l], *S[l])
+            dsla.dsla_prefill(descs[l], T, q, k, v, g1, g2, S[l][0], S[l][1], o, ws)
+
+    def timed(fn, n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    for _ in range(2):
+        prefill_all()
+    ms_prefill = timed(prefill_all, a.repeat)
+
+    # decode: one token per sequence and layer; the inputs of a step live in fixed buffers (a real stack would
+    # write its projections there), so one captured step serves every token
+    dq, dk, dv, dg1, dg2 = rnd(L, B, H, d), rnd(L, B, H, d), rnd(L, B, H, d), gates(L, B, H, d), gates(L, B, H, d)
+    do = torch.empty_like(dv)
+
+    def decode_step():
+        for l in range(L):
+            dsla.dsla_decode(descs[l], dq[l], dk[l], dv[l], dg1[l], dg2[l], S[l][0], S[l][1], do[l])
+
+    for _ in range(3):
+        decode_step()
+    ms_eager = timed(decode_step, a.decode)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        decode_step()
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        decode_step()
+    graph.replay()
+    ms_graph = timed(graph.replay, a.decode)
+    assert bool(torch.isfinite(do.float()).all()) and bool(torch.isfinite(o.float()).all())
+
+    state_bytes = L * B * H * (2 * d * d * 4 * 2 + 6 * d * 2)
+    print(json.dumps({
+        "workload": f"DSLA share of a serving step: {L} layer instances, B={B} H={H} d={d}, prompt T={T}, "
+                    f"{a.decode} decode steps, bf16 io, fp32 states, synthetic inputs",
+        "prefill_ms_all_layers": round(ms_prefill, 3),
+        "prefill_layer_tokens_per_s": round(L * B * T / (ms_prefill * 1e-3), 1),
+        "decode_step_ms_all_layers_eager": round(ms_eager, 4),
+        "decode_step_ms_all_layers_graph": round(ms_graph, 4),
+        "decode_layer_tokens_per_s_graph": round(L * B / (ms_graph * 1e-3), 1),
+        "decode_GBps_graph": round(state_bytes / (ms_graph * 1e-3) / 1e9, 1),
+        "request_ms_prompt_plus_decode": round(ms_prefill + a.decode * ms_graph, 2),
+    }))
+
+
+if __name__ == "__main__":
+    main()
