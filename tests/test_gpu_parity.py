@@ -291,6 +291,41 @@ def test_varlen_bf16_state_pool_and_decode():
     _run_varlen([513, 2100], 2, 64, "bf16", "f32", 2e-2, slots=[1, 0], n_slots=3, segments=0, decode_steps=1, max_T=2500)
 
 
+def test_varlen_many_sequences():
+    """More sequences than the list-building workgroup has threads (each thread then takes a run of sequences),
+    most of them a few tokens long, a few long enough to be cut into segments."""
+    rng = np.random.default_rng(5)
+    lengths = [int(x) for x in rng.integers(0, 40, size=300)]
+    for at, L in ((3, 900), (150, 1300), (299, 517)):
+        lengths[at] = L
+    _run_varlen(lengths, 1, 64, "bf16", "bf16", 2e-2, segments=6, chunk=32, seed=93)
+
+
+def test_varlen_gate_preactivations():
+    import torch
+    lengths, H, d, tau = [300, 77, 1, 640], 2, 128, 16.0
+    B, total = len(lengths), sum(lengths)
+    x = wl.layer_inputs(95, 1, total, H, d, d, io_dtype="bf16", gate_dtype="bf16", gates="preact", qk_scale=d ** -0.5)
+    lg = {n: orc.log_gates_from_preactivations(x[n], tau) for n in ("g1", "g2")}
+    desc = dsla.make_desc(B, H, d, d, io_dtype=code("bf16"), gate_dtype=code("bf16"), gamma=0.3, chunk=64, segments=3,
+                          gate_mode=1, tau=tau)
+    S1 = torch.zeros(B, H, d, d, device="cuda"); S2 = torch.zeros_like(S1)
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    t = {n: to_gpu(x[n][0], "bf16") for n in x}
+    o = torch.full_like(t["v"], float("nan"))
+    ws = torch.empty(max(dsla.dsla_prefill_varlen_workspace_bytes(desc, total, max(lengths)), 1), dtype=torch.uint8, device="cuda")
+    dsla.dsla_prefill_varlen(desc, total, max(lengths), torch.from_numpy(cu).cuda(), None, t["q"], t["k"], t["v"], t["g1"],
+                             t["g2"], S1, S2, o, ws)
+    torch.cuda.synchronize()
+    o = o.float().cpu().numpy()
+    for b in range(B):
+        sl = slice(cu[b], cu[b + 1])
+        ro, rS1, rS2 = orc.recurrent(x["q"][:, sl], x["k"][:, sl], x["v"][:, sl], lg["g1"][:, sl], lg["g2"][:, sl], 0.3)
+        check(f"o[seq {b}]", o[sl][None], ro, 2e-2)
+        check(f"S1[seq {b}]", S1[b:b + 1].cpu().numpy(), rS1, 2e-2)
+        check(f"S2[seq {b}]", S2[b:b + 1].cpu().numpy(), rS2, 2e-2)
+
+
 def test_varlen_equals_dense_bitwise():
     """Equal lengths, identity slots: the packed entry point runs the same kernels with the same segment length
     (its workgroups find their segments through the device-built lists instead of their index)."""
