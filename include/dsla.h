@@ -134,18 +134,24 @@ DSLA_API dsla_status dsla_prefill(const dsla_desc *desc, int64_t T,
 /*
  * dsla_prefill_varlen - dsla_prefill for a batch of sequences of different lengths packed back to back along
  * the token axis, with each sequence's states at a caller-chosen place in a pool of states: the prefill half
- * of the mixed prefill/decode batches of the paper's serving system (Section 4.3 and the batching appendix),
+ * of the mixed prefill/decode batches of the paper's serving system (Section 4.5 and the appendix "Serving of Mixed Batch"),
  * where requests of different prompt lengths are processed together and each keeps its own pair of states.
  * Every sequence is an independent instance of the recurrence of Section 4.1.
  *
- *   desc->B        : number of sequences in the batch
- *   total_T        : tokens in the batch = cu_seqlens[B]; at most 2^31 - 1
+ *   desc->B        : number of sequences this call processes
+ *   total_T        : tokens in the packed batch (cu_seqlens' last entry); at most 2^31 - 1
  *   max_T          : an upper bound of the sequence lengths, max_T <= total_T.  It is used for planning only;
  *                    a sequence longer than max_T is NOT processed correctly (the library cannot see the
  *                    lengths without synchronising)
  *   cu_seqlens     : DEVICE int32 [B + 1], non-decreasing, cu_seqlens[0] >= 0: sequence b is the tokens
  *                    cu_seqlens[b] .. cu_seqlens[b+1] - 1.  A sequence of length 0 is legal: its states stay
  *                    as they are and it has no output rows
+ *   seq_index      : DEVICE int32 [B] or NULL.  Which of the packed sequences take part: entry b of this call is
+ *                    sequence seq_index[b] of cu_seqlens (which then has more than B + 1 entries); NULL = the
+ *                    first B, in order.  This is how the requests of a mixed batch that use the DSLA form of
+ *                    a layer are processed where they lie, without a split into a sub-batch and a merge
+ *                    afterwards (Section 4.5): the rows of the other sequences are neither read nor written.
+ *                    total_T stays the size of the whole packed batch, max_T bounds the participating lengths
  *   state_slot     : DEVICE int32 [B] or NULL.  The states of sequence b are entry state_slot[b] of S1, S2
  *                    ([n_slots][H][d_k][d_v], n_slots known to the caller only); NULL = entry b.  Values must
  *                    be valid and distinct (two sequences on one entry race); other entries are not touched
@@ -157,7 +163,7 @@ DSLA_API dsla_status dsla_prefill(const dsla_desc *desc, int64_t T,
  */
 DSLA_API size_t dsla_prefill_varlen_workspace_bytes(const dsla_desc *desc, int64_t total_T, int64_t max_T);
 DSLA_API dsla_status dsla_prefill_varlen(const dsla_desc *desc, int64_t total_T, int64_t max_T,
-                                const int32_t *cu_seqlens, const int32_t *state_slot,
+                                const int32_t *cu_seqlens, const int32_t *seq_index, const int32_t *state_slot,
                                 const void *q, const void *k, const void *v,
                                 const void *g1, const void *g2,
                                 float *S1, float *S2, void *o,
@@ -177,12 +183,16 @@ DSLA_API dsla_status dsla_decode(const dsla_desc *desc,
 /*
  * dsla_decode_slots - dsla_decode with the states of sequence b at entry state_slot[b] (DEVICE int32 [B], valid
  * and distinct) of S1, S2 = [n_slots][H][d_k][d_v]: the decode half of a mixed batch, where the requests that
- * are decoding in this step are a changing subset of the requests whose states are resident (Section 4.3).
- * Entries not named are not touched.
+ * are decoding in this step are a changing subset of the requests whose states are resident (Section 4.5).
+ * Entries not named are not touched.  row_index (DEVICE int32 [B], distinct, or NULL = row b): the token of
+ * sequence b is row row_index[b] of q, k, v, g1, g2 ([rows][H][d]) and its output goes to the same row of o, so
+ * the DSLA requests of a larger batch are served in place (no split and merge, Section 4.5); other rows of o
+ * are not written.
  */
 DSLA_API dsla_status dsla_decode_slots(const dsla_desc *desc,
                               const void *q, const void *k, const void *v,
-                              const void *g1, const void *g2, const int32_t *state_slot,
+                              const void *g1, const void *g2,
+                              const int32_t *row_index, const int32_t *state_slot,
                               float *S1, float *S2, void *o, void *stream);
 
 /* Text for a status code (static storage). */

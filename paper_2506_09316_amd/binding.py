@@ -59,9 +59,9 @@ def load_library():
     lib.dsla_decode.restype = ctypes.c_int
     lib.dsla_prefill_varlen_workspace_bytes.argtypes = [dp, ctypes.c_int64, ctypes.c_int64]
     lib.dsla_prefill_varlen_workspace_bytes.restype = ctypes.c_size_t
-    lib.dsla_prefill_varlen.argtypes = [dp, ctypes.c_int64, ctypes.c_int64] + [vp] * 11 + [ctypes.c_size_t, vp]
+    lib.dsla_prefill_varlen.argtypes = [dp, ctypes.c_int64, ctypes.c_int64] + [vp] * 12 + [ctypes.c_size_t, vp]
     lib.dsla_prefill_varlen.restype = ctypes.c_int
-    lib.dsla_decode_slots.argtypes = [dp] + [vp] * 10
+    lib.dsla_decode_slots.argtypes = [dp] + [vp] * 11
     lib.dsla_decode_slots.restype = ctypes.c_int
     lib.dsla_status_string.argtypes = [ctypes.c_int]
     lib.dsla_status_string.restype = ctypes.c_char_p
@@ -140,19 +140,19 @@ def dsla_prefill_varlen_workspace_bytes(desc: DslaDesc, total_T: int, max_T: int
 
 
 def dsla_prefill_varlen(desc: DslaDesc, total_T, max_T, cu_seqlens, state_slot, q, k, v, g1, g2, S1, S2, o,
-                        workspace=None):
-    """Prefill of packed sequences (include/dsla.h: dsla_prefill_varlen).  cu_seqlens: int32 GPU tensor [B+1];
-    state_slot: int32 GPU tensor [B] or None."""
+                        workspace=None, seq_index=None):
+    """Prefill of packed sequences (include/dsla.h: dsla_prefill_varlen).  cu_seqlens: int32 GPU tensor;
+    state_slot, seq_index: int32 GPU tensors [B] or None."""
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load_library().dsla_prefill_varlen(ctypes.byref(desc), int(total_T), int(max_T), _ptr(cu_seqlens),
-                                              _ptr(state_slot), _ptr(q), _ptr(k), _ptr(v), _ptr(g1), _ptr(g2),
+                                              _ptr(seq_index), _ptr(state_slot), _ptr(q), _ptr(k), _ptr(v), _ptr(g1), _ptr(g2),
                                               _ptr(S1), _ptr(S2), _ptr(o), _ptr(workspace), wbytes, _stream()))
 
 
-def dsla_decode_slots(desc: DslaDesc, q, k, v, g1, g2, state_slot, S1, S2, o):
+def dsla_decode_slots(desc: DslaDesc, q, k, v, g1, g2, state_slot, S1, S2, o, row_index=None):
     """One decode step on states picked from a pool (include/dsla.h: dsla_decode_slots)."""
     _check(load_library().dsla_decode_slots(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g1), _ptr(g2),
-                                            _ptr(state_slot), _ptr(S1), _ptr(S2), _ptr(o), _stream()))
+                                            _ptr(row_index), _ptr(state_slot), _ptr(S1), _ptr(S2), _ptr(o), _stream()))
 
 
 def profile_enable(enable: bool, max_records: int = 4096):

@@ -126,7 +126,7 @@ dsla_status dsla_prefill(const dsla_desc *desc, int64_t T, const void *q, const 
         if (!workspace || workspace_bytes < plan.ws_total_bytes) return DSLA_ERR_WORKSPACE;
         if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return DSLA_ERR_SHAPE;
     }
-    return hip_status(launch_prefill(*desc, plan, T, nullptr, nullptr, q, k, v, g1, g2, S1, S2, o, workspace,
+    return hip_status(launch_prefill(*desc, plan, T, nullptr, nullptr, nullptr, q, k, v, g1, g2, S1, S2, o, workspace,
                                      static_cast<hipStream_t>(stream)));
 }
 
@@ -149,7 +149,7 @@ size_t dsla_prefill_varlen_workspace_bytes(const dsla_desc *desc, int64_t total_
 }
 
 dsla_status dsla_prefill_varlen(const dsla_desc *desc, int64_t total_T, int64_t max_T, const int32_t *cu_seqlens,
-                                const int32_t *state_slot, const void *q, const void *k, const void *v,
+                                const int32_t *seq_index, const int32_t *state_slot, const void *q, const void *k, const void *v,
                                 const void *g1, const void *g2, float *S1, float *S2, void *o, void *workspace,
                                 size_t workspace_bytes, void *stream)
 {
@@ -160,7 +160,7 @@ dsla_status dsla_prefill_varlen(const dsla_desc *desc, int64_t total_T, int64_t 
     if (!q || !k || !v || !g1 || !g2 || !o) return DSLA_ERR_NULL;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g1) || !aligned16(g2) || !aligned16(o) ||
         !aligned16(S1) || !aligned16(S2) || (reinterpret_cast<uintptr_t>(cu_seqlens) & 3u) ||
-        (reinterpret_cast<uintptr_t>(state_slot) & 3u))
+        (reinterpret_cast<uintptr_t>(seq_index) & 3u) || (reinterpret_cast<uintptr_t>(state_slot) & 3u))
         return DSLA_ERR_SHAPE;
     PrefillPlan plan;
     if (!prefill_plan_varlen(*desc, total_T, max_T, &plan)) return DSLA_ERR_UNSUPPORTED;
@@ -168,7 +168,7 @@ dsla_status dsla_prefill_varlen(const dsla_desc *desc, int64_t total_T, int64_t 
         if (!workspace || workspace_bytes < plan.ws_total_bytes) return DSLA_ERR_WORKSPACE;
         if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return DSLA_ERR_SHAPE;
     }
-    return hip_status(launch_prefill(*desc, plan, max_T, cu_seqlens, state_slot, q, k, v, g1, g2, S1, S2, o,
+    return hip_status(launch_prefill(*desc, plan, max_T, cu_seqlens, seq_index, state_slot, q, k, v, g1, g2, S1, S2, o,
                                      workspace, static_cast<hipStream_t>(stream)));
 }
 
@@ -181,19 +181,22 @@ dsla_status dsla_decode(const dsla_desc *desc, const void *q, const void *k, con
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g1) || !aligned16(g2) || !aligned16(o) ||
         !aligned16(S1) || !aligned16(S2))
         return DSLA_ERR_SHAPE;
-    return hip_status(launch_decode(*desc, q, k, v, g1, g2, nullptr, S1, S2, o, static_cast<hipStream_t>(stream)));
+    return hip_status(launch_decode(*desc, q, k, v, g1, g2, nullptr, nullptr, S1, S2, o, static_cast<hipStream_t>(stream)));
 }
 
 dsla_status dsla_decode_slots(const dsla_desc *desc, const void *q, const void *k, const void *v, const void *g1,
-                              const void *g2, const int32_t *state_slot, float *S1, float *S2, void *o, void *stream)
+                              const void *g2, const int32_t *row_index, const int32_t *state_slot, float *S1,
+                              float *S2, void *o, void *stream)
 {
     dsla_status st = check_desc(desc);
     if (st != DSLA_OK) return st;
     if (!q || !k || !v || !g1 || !g2 || !state_slot || !S1 || !S2 || !o) return DSLA_ERR_NULL;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(g1) || !aligned16(g2) || !aligned16(o) ||
-        !aligned16(S1) || !aligned16(S2) || (reinterpret_cast<uintptr_t>(state_slot) & 3u))
+        !aligned16(S1) || !aligned16(S2) || (reinterpret_cast<uintptr_t>(state_slot) & 3u) ||
+        (reinterpret_cast<uintptr_t>(row_index) & 3u))
         return DSLA_ERR_SHAPE;
-    return hip_status(launch_decode(*desc, q, k, v, g1, g2, state_slot, S1, S2, o, static_cast<hipStream_t>(stream)));
+    return hip_status(launch_decode(*desc, q, k, v, g1, g2, row_index, state_slot, S1, S2, o,
+                                    static_cast<hipStream_t>(stream)));
 }
 
 dsla_status dsla_profile_enable(int enable, int max_records)

@@ -37,8 +37,8 @@ __device__ __forceinline__ void store_f4(float4 *p, const float4 &v, bool nt)
 template <int DK, int DV, int SPLIT, bool NT, class TIO, class TG>
 __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
     const TIO *__restrict__ q, const TIO *__restrict__ k, const TIO *__restrict__ v, const TG *__restrict__ g1,
-    const TG *__restrict__ g2, const int32_t *__restrict__ slot, float *__restrict__ S1, float *__restrict__ S2,
-    TIO *__restrict__ o, int H, float gamma, const float *__restrict__ gamma_per_head, float scale, float gate_inv_tau)
+    const TG *__restrict__ g2, const int32_t *__restrict__ row, const int32_t *__restrict__ slot,
+    float *__restrict__ S1, float *__restrict__ S2, TIO *__restrict__ o, int H, float gamma, const float *__restrict__ gamma_per_head, float scale, float gate_inv_tau)
 {
     constexpr int COLG = DV / 4 / SPLIT;          // threads across this workgroup's part of a state row (float4 each)
     constexpr int ROWG = kDecodeThreads / COLG;   // row groups
@@ -71,7 +71,9 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
 
     // 2. per-token vectors -> LDS (gates exponentiated once per row)
     const float gm = gamma_per_head ? gamma_per_head[bh % H] : gamma;
-    const size_t kb = static_cast<size_t>(bh) * DK;
+    // the token of sequence b sits in row row[b] of q, k, v, g1, g2 and o (row b without a row list)
+    const size_t tbh = row ? static_cast<size_t>(row[bh / H]) * H + bh % H : static_cast<size_t>(bh);
+    const size_t kb = tbh * DK;
     for (int d = tid; d < DK; d += kDecodeThreads) {
         s_q[d] = scale * to_f32(q[kb + d]);
         s_k[d] = to_f32(k[kb + d]);
@@ -83,7 +85,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
         s_a1[d] = __expf(x1);
         s_a2[d] = __expf(x2);
     }
-    const TIO *vp = v + static_cast<size_t>(bh) * DV + (part * COLG + cg) * 4;
+    const TIO *vp = v + tbh * DV + (part * COLG + cg) * 4;
     const float v0 = to_f32(vp[0]), v1 = to_f32(vp[1]), v2 = to_f32(vp[2]), v3 = to_f32(vp[3]);
     __syncthreads();
 
@@ -126,7 +128,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
             const float4 t = s_red[w][tid];
             r.x += t.x; r.y += t.y; r.z += t.z; r.w += t.w;
         }
-        TIO *op = o + static_cast<size_t>(bh) * DV + (part * COLG + tid) * 4;
+        TIO *op = o + tbh * DV + (part * COLG + tid) * 4;
         op[0] = from_f32<TIO>(r.x);
         op[1] = from_f32<TIO>(r.y);
         op[2] = from_f32<TIO>(r.z);
@@ -166,25 +168,27 @@ inline DecodeVariant decode_variant()
 
 template <int D, int SPLIT, bool NT, class TIO, class TG>
 hipError_t launch_decode_v(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
-                           const void *g2, const int32_t *slot, float *S1, float *S2, void *o, hipStream_t stream)
+                           const void *g2, const int32_t *row, const int32_t *slot, float *S1, float *S2, void *o,
+                           hipStream_t stream)
 {
     const unsigned grid = static_cast<unsigned>(d.B) * static_cast<unsigned>(d.H) * SPLIT;
     ProfileScope ps(DSLA_KERNEL_DECODE, stream);
     hipLaunchKernelGGL((decode_kernel<D, D, SPLIT, NT, TIO, TG>), dim3(grid), dim3(kDecodeThreads), 0, stream,
                        static_cast<const TIO *>(q), static_cast<const TIO *>(k), static_cast<const TIO *>(v),
-                       static_cast<const TG *>(g1), static_cast<const TG *>(g2), slot, S1, S2, static_cast<TIO *>(o), d.H,
+                       static_cast<const TG *>(g1), static_cast<const TG *>(g2), row, slot, S1, S2, static_cast<TIO *>(o), d.H,
                        d.gamma, d.gamma_per_head, d.scale, d.gate_mode == DSLA_GATE_PREACT ? 1.0f / d.tau : 0.f);
     return hipGetLastError();
 }
 
 template <int D, class TIO, class TG>
 hipError_t launch_decode_t(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
-                           const void *g2, const int32_t *slot, float *S1, float *S2, void *o, hipStream_t stream)
+                           const void *g2, const int32_t *row, const int32_t *slot, float *S1, float *S2, void *o,
+                           hipStream_t stream)
 {
     const DecodeVariant var = decode_variant();
 #define DSLA_DECODE_CASE(SP, N)                                                                          \
     if (var.split == SP && var.nt == N)                                                                  \
-        return launch_decode_v<D, SP, N, TIO, TG>(d, q, k, v, g1, g2, slot, S1, S2, o, stream)
+        return launch_decode_v<D, SP, N, TIO, TG>(d, q, k, v, g1, g2, row, slot, S1, S2, o, stream)
     DSLA_DECODE_CASE(1, false);
     DSLA_DECODE_CASE(1, true);
     DSLA_DECODE_CASE(2, false);
@@ -197,13 +201,14 @@ hipError_t launch_decode_t(const dsla_desc &d, const void *q, const void *k, con
 
 template <int D>
 hipError_t launch_decode_d(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
-                           const void *g2, const int32_t *slot, float *S1, float *S2, void *o, hipStream_t stream)
+                           const void *g2, const int32_t *row, const int32_t *slot, float *S1, float *S2, void *o,
+                           hipStream_t stream)
 {
     const bool io16 = d.io_dtype == DSLA_BF16, g16 = d.gate_dtype == DSLA_BF16;
-    if (io16 && g16) return launch_decode_t<D, bf16_t, bf16_t>(d, q, k, v, g1, g2, slot, S1, S2, o, stream);
-    if (io16 && !g16) return launch_decode_t<D, bf16_t, float>(d, q, k, v, g1, g2, slot, S1, S2, o, stream);
-    if (!io16 && g16) return launch_decode_t<D, float, bf16_t>(d, q, k, v, g1, g2, slot, S1, S2, o, stream);
-    return launch_decode_t<D, float, float>(d, q, k, v, g1, g2, slot, S1, S2, o, stream);
+    if (io16 && g16) return launch_decode_t<D, bf16_t, bf16_t>(d, q, k, v, g1, g2, row, slot, S1, S2, o, stream);
+    if (io16 && !g16) return launch_decode_t<D, bf16_t, float>(d, q, k, v, g1, g2, row, slot, S1, S2, o, stream);
+    if (!io16 && g16) return launch_decode_t<D, float, bf16_t>(d, q, k, v, g1, g2, row, slot, S1, S2, o, stream);
+    return launch_decode_t<D, float, float>(d, q, k, v, g1, g2, row, slot, S1, S2, o, stream);
 }
 
 }  // namespace
@@ -211,10 +216,11 @@ hipError_t launch_decode_d(const dsla_desc &d, const void *q, const void *k, con
 bool decode_supported(const dsla_desc &d) { return d.d_k == d.d_v && (d.d_k == 64 || d.d_k == 128); }
 
 hipError_t launch_decode(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
-                         const void *g2, const int32_t *slot, float *S1, float *S2, void *o, hipStream_t stream)
+                         const void *g2, const int32_t *row, const int32_t *slot, float *S1, float *S2, void *o,
+                           hipStream_t stream)
 {
-    if (d.d_k == 128) return launch_decode_d<128>(d, q, k, v, g1, g2, slot, S1, S2, o, stream);
-    return launch_decode_d<64>(d, q, k, v, g1, g2, slot, S1, S2, o, stream);
+    if (d.d_k == 128) return launch_decode_d<128>(d, q, k, v, g1, g2, row, slot, S1, S2, o, stream);
+    return launch_decode_d<64>(d, q, k, v, g1, g2, row, slot, S1, S2, o, stream);
 }
 
 hipError_t launch_state_init(float *S1, float *S2, size_t elems_per_state, hipStream_t stream)

@@ -44,9 +44,10 @@ struct ProfileScope {
 // ---- launchers (one per kernel family; each returns the launch error) ------------------------
 hipError_t launch_state_init(float *S1, float *S2, size_t elems_per_state, hipStream_t stream);
 
+// row_index: which row of the token tensors belongs to sequence b (nullptr: row b); state_slot as for the prefill.
 hipError_t launch_decode(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
-                         const void *g2, const int32_t *state_slot, float *S1, float *S2, void *o,
-                         hipStream_t stream);
+                         const void *g2, const int32_t *row_index, const int32_t *state_slot, float *S1, float *S2,
+                         void *o, hipStream_t stream);
 bool decode_supported(const dsla_desc &d);
 
 // Prefill plan: how a sequence is cut into segments and chunks.
@@ -65,9 +66,10 @@ struct PrefillPlan {
 bool prefill_plan(const dsla_desc &d, int64_t T, PrefillPlan *plan);  // false: unsupported combination
 bool prefill_plan_varlen(const dsla_desc &d, int64_t total_T, int64_t max_T, PrefillPlan *plan);
 // cu_seqlens == nullptr: B sequences of T tokens each; else packed sequences and T = upper bound of their lengths.
+// seq_index (with cu_seqlens only): which packed sequences take part; nullptr: all, in order.
 // state_slot == nullptr: sequence b owns entry b of S1, S2.
 hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T, const int32_t *cu_seqlens,
-                          const int32_t *state_slot, const void *q, const void *k, const void *v, const void *g1,
+                          const int32_t *seq_index, const int32_t *state_slot, const void *q, const void *k, const void *v, const void *g1,
                           const void *g2, float *S1, float *S2, void *o, void *workspace, hipStream_t stream);
 
 }  // namespace dsla

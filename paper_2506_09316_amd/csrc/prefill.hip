@@ -401,6 +401,7 @@ struct PrefillArgs {
     float *ws_decay;         // [slot][2][D] fp32 (P > 1): log2 of the decay over the segment
     const float *gamma_per_head;
     const int32_t *cu;       // packed sequences: [B + 1] token offsets (sequence b = tokens cu[b] .. cu[b+1]-1); or null
+    const int32_t *seq;      // with cu: [B] which of the packed sequences take part (entry b names sequence seq[b]); or null (all, in order)
     const int32_t *slot;     // [B] index of each sequence's states in S1, S2; or null (sequence b uses entry b)
     // Packed sequences cut into segments: the work lists written by segment_list_kernel.  A workgroup is
     // (list entry, head); entries past the count exit.  Null when every sequence is one segment or cu is null.
@@ -942,8 +943,9 @@ struct Kern {
         }
 
         // this sequence: first token in the token-major tensors, length, where its states live
-        const int64_t seq0 = a.cu ? static_cast<int64_t>(a.cu[bidx]) : static_cast<int64_t>(bidx) * a.T;
-        const int64_t Tb = a.cu ? static_cast<int64_t>(a.cu[bidx + 1]) - seq0 : a.T;
+        const int sq = (a.cu && a.seq) ? a.seq[bidx] : bidx;
+        const int64_t seq0 = a.cu ? static_cast<int64_t>(a.cu[sq]) : static_cast<int64_t>(bidx) * a.T;
+        const int64_t Tb = a.cu ? static_cast<int64_t>(a.cu[sq + 1]) - seq0 : a.T;
         const size_t sbh = static_cast<size_t>(a.slot ? a.slot[bidx] : bidx) * a.H + h;
         const int64_t t0 = static_cast<int64_t>(p) * a.seg_tokens;
         // A shorter sequence has fewer segments: the chunk loop has nothing to do past its end, and the state
@@ -1136,7 +1138,8 @@ __global__ __launch_bounds__(4 * D, 2) void prefill_kernel(PrefillArgs a)
 // Work lists for packed sequences (one workgroup): sequence b has ceil(T_b / seg_tokens) segments;
 // seg_first = exclusive prefix sum of that over the sequences, list_full = every (sequence, segment),
 // list_pre = those with a successor.  Thread t takes a contiguous run of sequences.
-__global__ __launch_bounds__(256) void segment_list_kernel(const int32_t *__restrict__ cu, int B, int64_t seg_tokens,
+__global__ __launch_bounds__(256) void segment_list_kernel(const int32_t *__restrict__ cu, const int32_t *__restrict__ seq,
+                                                           int B, int64_t seg_tokens,
                                                            int32_t *__restrict__ seg_first,
                                                            int32_t *__restrict__ seg_count, int2 *__restrict__ list_full,
                                                            int2 *__restrict__ list_pre, int cap_full, int cap_pre)
@@ -1146,7 +1149,8 @@ __global__ __launch_bounds__(256) void segment_list_kernel(const int32_t *__rest
     const int per = (B + 255) / 256;
     const int b0 = t * per, b1 = (b0 + per < B) ? b0 + per : B;
     auto segments_of = [&](int b) -> int {
-        const int64_t Tb = static_cast<int64_t>(cu[b + 1]) - cu[b];
+        const int sq = seq ? seq[b] : b;
+        const int64_t Tb = static_cast<int64_t>(cu[sq + 1]) - cu[sq];
         return Tb > 0 ? static_cast<int>((Tb + seg_tokens - 1) / seg_tokens) : 0;
     };
     int mine = 0, mine_seq = 0;   // segments, and sequences with at least one, in this thread's run
@@ -1193,6 +1197,7 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restri
                                                            float *__restrict__ ws_state,
                                                            const float *__restrict__ ws_decay, int BH, int P,
                                                            const int32_t *__restrict__ cu,
+                                                           const int32_t *__restrict__ seq,
                                                            const int32_t *__restrict__ slot,
                                                            const int32_t *__restrict__ seg_first, int H,
                                                            int64_t seg_tokens)
@@ -1210,7 +1215,8 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restri
     const size_t b = bh / H, h = bh % H;
     size_t slot0 = bh, slot_step = BH;
     if (cu) {   // a shorter sequence has fewer segments, an empty one none
-        const int64_t Tb = static_cast<int64_t>(cu[b + 1]) - cu[b];
+        const size_t sq = seq ? static_cast<size_t>(seq[b]) : b;
+        const int64_t Tb = static_cast<int64_t>(cu[sq + 1]) - cu[sq];
         const int64_t Pb = Tb > 0 ? (Tb + seg_tokens - 1) / seg_tokens : 0;
         if (Pb < P) P = static_cast<int>(Pb);
         if (P <= 1) return;
@@ -1280,7 +1286,7 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
 #endif
         if (a.list_full) {
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_LIST, stream);
-            hipLaunchKernelGGL(segment_list_kernel, dim3(1), dim3(256), 0, stream, a.cu, d.B, a.seg_tokens,
+            hipLaunchKernelGGL(segment_list_kernel, dim3(1), dim3(256), 0, stream, a.cu, a.seq, d.B, a.seg_tokens,
                                const_cast<int32_t *>(a.seg_first), const_cast<int32_t *>(a.seg_count),
                                const_cast<int2 *>(a.list_full), const_cast<int2 *>(a.list_pre),
                                static_cast<int>(plan.max_items), static_cast<int>(plan.max_pre_items));
@@ -1300,7 +1306,7 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_SCAN, stream);
             const size_t n4 = static_cast<size_t>(BH) * 2 * D * (D / 4);
             hipLaunchKernelGGL((segment_scan_kernel<D>), dim3(static_cast<unsigned>((n4 + 255) / 256)), dim3(256), 0,
-                               stream, a.S1, a.S2, a.ws_state, a.ws_decay, BH, plan.segments, a.cu, a.slot,
+                               stream, a.S1, a.S2, a.ws_state, a.ws_decay, BH, plan.segments, a.cu, a.seq, a.slot,
                                a.seg_first, a.H, a.seg_tokens);
             err = hipGetLastError();
         }
@@ -1427,7 +1433,7 @@ bool prefill_plan_varlen(const dsla_desc &d, int64_t total_T, int64_t max_T, Pre
 }
 
 hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T, const int32_t *cu_seqlens,
-                          const int32_t *state_slot, const void *q, const void *k, const void *v, const void *g1,
+                          const int32_t *seq_index, const int32_t *state_slot, const void *q, const void *k, const void *v, const void *g1,
                           const void *g2, float *S1, float *S2, void *o, void *workspace, hipStream_t stream)
 {
     PrefillArgs a;
@@ -1439,6 +1445,7 @@ hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T
                      : nullptr;
     a.gamma_per_head = d.gamma_per_head;
     a.cu = cu_seqlens;
+    a.seq = seq_index;
     a.slot = state_slot;
     a.seg_first = a.seg_count = nullptr;
     a.list_full = a.list_pre = nullptr;

@@ -326,6 +326,52 @@ def test_varlen_gate_preactivations():
         check(f"S2[seq {b}]", S2[b:b + 1].cpu().numpy(), rS2, 2e-2)
 
 
+def test_sub_batch_served_in_place():
+    """A mixed batch of 7 requests of which 4 use the DSLA form of this layer: the prefill names them through
+    seq_index, the decode step through row_index, their states live in a pool.  Each is checked against the oracle
+    run on it alone; the output rows of the other requests must keep the bytes they had."""
+    import torch
+    lengths, H, d = [120, 700, 33, 0, 1500, 64, 257], 2, 128
+    dsla_seqs = [4, 1, 6, 2]          # participating requests, in the order this call lists them
+    slots, n_slots = [5, 0, 3, 2], 6
+    B_all, total = len(lengths), sum(lengths)
+    x = wl.layer_inputs(97, 1, total + B_all, H, d, d, io_dtype="bf16", gate_dtype="bf16", qk_scale=d ** -0.5)
+    S1_0, S2_0 = wl.initial_states(97, n_slots, H, d, d, amplitude=0.3)
+    S1, S2 = (torch.from_numpy(a.copy()).cuda() for a in (S1_0, S2_0))
+    cu = np.concatenate([[0], np.cumsum(lengths)]).astype(np.int32)
+    desc = dsla.make_desc(len(dsla_seqs), H, d, d, io_dtype=code("bf16"), gate_dtype=code("bf16"), gamma=0.45, chunk=64,
+                          segments=4)
+    t = {n: to_gpu(x[n][0, :total], "bf16") for n in x}
+    marker = 1.5
+    o = torch.full_like(t["v"], marker)
+    max_T = max(lengths[i] for i in dsla_seqs)
+    ws = torch.empty(dsla.dsla_prefill_varlen_workspace_bytes(desc, total, max_T), dtype=torch.uint8, device="cuda")
+    seq_t = torch.tensor(dsla_seqs, dtype=torch.int32, device="cuda")
+    slot_t = torch.tensor(slots, dtype=torch.int32, device="cuda")
+    dsla.dsla_prefill_varlen(desc, total, max_T, torch.from_numpy(cu).cuda(), slot_t, t["q"], t["k"], t["v"], t["g1"],
+                             t["g2"], S1, S2, o, ws, seq_index=seq_t)
+    # one decode token for every request of the batch lies in rows total .. total + B_all - 1; only the DSLA ones are served
+    dt = {n: to_gpu(x[n][0, total:], "bf16") for n in x}
+    do = torch.full_like(dt["v"], marker)
+    dsla.dsla_decode_slots(desc, dt["q"], dt["k"], dt["v"], dt["g1"], dt["g2"], slot_t, S1, S2, do, row_index=seq_t)
+    torch.cuda.synchronize()
+    o, do = o.float().cpu().numpy(), do.float().cpu().numpy()
+    S1, S2 = S1.cpu().numpy(), S2.cpu().numpy()
+    for b, (sq, sl) in enumerate(zip(dsla_seqs, slots)):
+        rows = list(range(cu[sq], cu[sq + 1])) + [total + sq]
+        xs = {n: x[n][:, rows] for n in x}
+        ro, rS1, rS2 = orc.recurrent(xs["q"], xs["k"], xs["v"], xs["g1"], xs["g2"], 0.45, S1=S1_0[sl:sl + 1], S2=S2_0[sl:sl + 1])
+        L = lengths[sq]
+        check(f"o[request {sq}]", o[cu[sq]:cu[sq + 1]][None], ro[:, :L], 2e-2)
+        check(f"o decode[request {sq}]", do[sq][None, None], ro[:, L:], 2e-2)
+        check(f"S1[request {sq}]", S1[sl:sl + 1], rS1, 2e-2)
+        check(f"S2[request {sq}]", S2[sl:sl + 1], rS2, 2e-2)
+    for sq in set(range(B_all)) - set(dsla_seqs):
+        assert np.all(o[cu[sq]:cu[sq + 1]] == marker) and np.all(do[sq] == marker), f"rows of request {sq} were written"
+    for sl in set(range(n_slots)) - set(slots):
+        assert np.array_equal(S1[sl], S1_0[sl]) and np.array_equal(S2[sl], S2_0[sl])
+
+
 def test_varlen_equals_dense_bitwise():
     """Equal lengths, identity slots: the packed entry point runs the same kernels with the same segment length
     (its workgroups find their segments through the device-built lists instead of their index)."""

@@ -70,14 +70,17 @@ def test_argument_checks_need_no_gpu(lib):
     ignored = dsla.make_desc(1, 2, 64, 64, io_dtype=0, gate_dtype=0, gate_mode=0, tau=0.0)   # tau unused for log gates
     assert lib.dsla_prefill(ctypes.byref(ignored), 0, None, None, None, None, None, fake, fake, None, None, 0, None) == 0
     # packed sequences: the bound of the lengths cannot exceed the total; the offsets are required
-    assert lib.dsla_prefill_varlen(ctypes.byref(d), 100, 101, fake, None, *([fake] * 8), None, 0, None) == 2
-    assert lib.dsla_prefill_varlen(ctypes.byref(d), 100, 50, None, None, *([fake] * 8), None, 0, None) == 1
-    assert lib.dsla_prefill_varlen(ctypes.byref(d), 2 ** 31, 50, fake, None, *([fake] * 8), None, 0, None) == 2
-    assert lib.dsla_prefill_varlen(ctypes.byref(d), 0, 0, fake, None, None, None, None, None, None, fake, fake, None,
-                                   None, 0, None) == 0
-    assert lib.dsla_prefill_varlen(ctypes.byref(seg), 4096, 1024, fake, None, *([fake] * 8), None, 0, None) == 4
-    assert lib.dsla_decode_slots(ctypes.byref(d), *([fake] * 5), None, *([fake] * 3), None) == 1
-    assert lib.dsla_decode_slots(ctypes.byref(d), *([fake] * 5), ctypes.c_void_p(4098), *([fake] * 3), None) == 2
+    assert lib.dsla_prefill_varlen(ctypes.byref(d), 100, 101, fake, None, None, *([fake] * 8), None, 0, None) == 2
+    assert lib.dsla_prefill_varlen(ctypes.byref(d), 100, 50, None, None, None, *([fake] * 8), None, 0, None) == 1
+    assert lib.dsla_prefill_varlen(ctypes.byref(d), 2 ** 31, 50, fake, None, None, *([fake] * 8), None, 0, None) == 2
+    assert lib.dsla_prefill_varlen(ctypes.byref(d), 0, 0, fake, None, None, None, None, None, None, None, fake, fake,
+                                   None, None, 0, None) == 0
+    assert lib.dsla_prefill_varlen(ctypes.byref(seg), 4096, 1024, fake, None, None, *([fake] * 8), None, 0, None) == 4
+    assert lib.dsla_prefill_varlen(ctypes.byref(d), 100, 50, fake, ctypes.c_void_p(4098), None, *([fake] * 8), None, 0,
+                                   None) == 2
+    assert lib.dsla_decode_slots(ctypes.byref(d), *([fake] * 5), None, None, *([fake] * 3), None) == 1
+    assert lib.dsla_decode_slots(ctypes.byref(d), *([fake] * 5), None, ctypes.c_void_p(4098), *([fake] * 3), None) == 2
+    assert lib.dsla_decode_slots(ctypes.byref(d), *([fake] * 5), ctypes.c_void_p(4098), fake, *([fake] * 3), None) == 2
     # T = 0 does nothing and needs no tensors
     assert lib.dsla_prefill(ctypes.byref(d), 0, None, None, None, None, None, fake, fake, None, None, 0, None) == 0
     assert lib.dsla_prefill(ctypes.byref(d), -1, *([fake] * 8), None, 0, None) == 2
