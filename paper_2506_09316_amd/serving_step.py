@@ -1,6 +1,7 @@
 """The DSLA share of a hybrid serving step, as a usage example and a measurement:
 
     python -m paper_2506_09316_amd.serving_step [--layers 16 --B 8 --T 8192 --decode 128]
+    python -m paper_2506_09316_amd.serving_step --packed {equal,pow2,serving,one_long}
 
 L layer instances (each with its own blend coefficient and its own pair of states per sequence) prefill a
 prompt of T tokens for B sequences and then decode token by token.  The decode step of all layers is captured
@@ -15,8 +16,60 @@ import argparse
 import json
 
 
+# Mixed-length prompt batches for --packed (tokens per request; Llama-2-7B head shape).
+MIXES = {
+    "equal": [16384] * 4,
+    "pow2": [16384] + [8192] * 2 + [4096] * 4 + [2048] * 8,
+    "serving": [8192, 6000, 5000, 4100, 3000, 2500, 2048, 1500, 1200, 1000, 800, 600, 512, 300, 200, 100, 64, 33, 7, 1] * 2,
+    "one_long": [32768] + [512] * 64,
+}
+
+
+def packed(mix: str, H: int, d: int):
+    """Prefill of one packed batch of requests of different lengths (dsla_prefill_varlen); prints one JSON line."""
+    import torch
+    import paper_2506_09316_amd as dsla
+    from paper_2506_09316_amd import binding
+    from paper_2506_09316_amd.binding import DSLA_BF16
+
+    lengths = MIXES[mix]
+    B, total, mx = len(lengths), sum(lengths), max(lengths)
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20250609)
+    rnd = lambda: (torch.randn(total, H, d, device=dev, generator=gen) * d ** -0.5).to(torch.bfloat16)
+    gat = lambda: (-torch.nn.functional.softplus(-(torch.randn(total, H, d, device=dev, generator=gen) + 2.0)) / 16.0
+                   ).to(torch.bfloat16)
+    q, k, v, g1, g2 = rnd(), rnd(), rnd(), gat(), gat()
+    o = torch.empty_like(v)
+    cu = torch.tensor([0] + list(torch.tensor(lengths).cumsum(0)), dtype=torch.int32, device=dev)
+    S1 = torch.zeros(B, H, d, d, device=dev)
+    S2 = torch.zeros_like(S1)
+    desc = dsla.make_desc(B, H, d, d, io_dtype=DSLA_BF16, gate_dtype=DSLA_BF16, chunk=64)
+    nws = dsla.dsla_prefill_varlen_workspace_bytes(desc, total, mx)
+    ws = torch.empty(max(nws, 256), dtype=torch.uint8, device=dev)
+
+    def step():
+        dsla.dsla_prefill_varlen(desc, total, mx, cu, None, q, k, v, g1, g2, S1, S2, o, ws)
+
+    for _ in range(30):
+        step()
+    torch.cuda.synchronize()
+    binding.profile_enable(True, 4096)
+    for _ in range(100):
+        step()
+    res = binding.profile_collect()
+    binding.profile_enable(False, 0)
+    kernels = {n: round(1e3 * m / c, 1) for n, (m, c) in res.items() if c}
+    us = sum(kernels.values())
+    print(json.dumps({"workload": f"packed prefill, mix '{mix}': {B} requests, {total} tokens, longest {mx}, H={H} d={d} bf16",
+                      "kernel_us": kernels, "prefill_us": round(us, 1), "tokens_per_s": round(total / us * 1e6, 1),
+                      "workspace_MB": round(nws / 1e6, 1)}))
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--packed", choices=sorted(MIXES), help="time one packed mixed-length prefill batch instead")
     ap.add_argument("--layers", type=int, default=16)
     ap.add_argument("--B", type=int, default=8)
     ap.add_argument("--T", type=int, default=8192)
@@ -25,6 +78,8 @@ def main():
     ap.add_argument("--decode", type=int, default=128)
     ap.add_argument("--repeat", type=int, default=5, help="timed repetitions of the prefill of all layers")
     a = ap.parse_args()
+    if a.packed:
+        return packed(a.packed, a.H, a.d)
 
     import torch
     import paper_2506_09316_amd as dsla
