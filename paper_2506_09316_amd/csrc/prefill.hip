@@ -12,6 +12,11 @@
 // turns these into the true state entering each segment.  (3) chunk_loop: every segment runs the
 // fused step loop from its true initial state and writes o; the last segment writes the final
 // states.  P = 1 runs (3) alone.  (1) and (3) are one kernel template.
+// Packed sequences of different lengths share one segment length; a one-workgroup kernel (segment_list) turns
+// their offsets into the lists of (sequence, segment) pairs that (1) and (3) take their work from, so that no
+// workgroup is launched for a segment that does not exist.  Sequences may be a subset of the packed batch and
+// their states entries of a pool (both through index arrays).  Gates arrive as log-gates or as the
+// pre-activations of a temperature-sigmoid, which the producers then apply themselves.
 //
 // Workgroup = D/8 wavefronts (D = d_k = d_v): D/32 consumers and D/32 producers, see "Workgroup layout".
 // Consumer w owns state columns [32w, 32w+32) of both states for all d_k rows, as fp32 MFMA accumulators
