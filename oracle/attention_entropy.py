@@ -1,0 +1,28 @@
+"""CPU oracle of the attention-entropy sensitivity signal.  TEST INFRASTRUCTURE: only tests/, the smoke check and
+the benchmark's CPU baseline may import this; the product path never does.
+
+What it computes (Section 4.3, "Layer Ranking via Sensitivity"): for the final query q_T of a softmax-attention
+head, the attention distribution over the keys, A_i = softmax_i(scale * q_T . k_i), i = 0..T-1, and its Shannon
+entropy.  The paper's display prints sum_i A_i log A_i without a minus sign while the text around it treats
+"lower entropy" as "focused on fewer tokens"; the reading taken is the entropy proper, H = -sum_i A_i log A_i >= 0
+(natural logarithm), which is the negative of the printed sum.  Plain numpy, fp64, one (batch, head) at a time
+through library primitives (matrix-vector product, exp, log, sum); no blocking or streaming.
+"""
+import numpy as np
+
+
+def attention_entropy(q_last, k, scale):
+    """q_last: [B, H, d]; k: [B, T, H, d]; returns H: [B, H] fp64.  A term with A_i == 0 contributes 0."""
+    q_last = np.asarray(q_last, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    B, T, H, d = k.shape
+    assert q_last.shape == (B, H, d) and T >= 1
+    out = np.zeros((B, H), dtype=np.float64)
+    for b in range(B):
+        for h in range(H):
+            s = float(scale) * (k[b, :, h, :] @ q_last[b, h])      # scores of the final query against every key
+            e = np.exp(s - s.max())
+            a = e / e.sum()                                         # the attention row
+            nz = a > 0
+            out[b, h] = -np.sum(a[nz] * np.log(a[nz]))
+    return out

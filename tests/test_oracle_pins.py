@@ -311,5 +311,50 @@ def test_gate_map_against_sigmoid_power_and_asymptotes():
     np.testing.assert_allclose(np.exp(g) + np.exp(g[::-1]), 1.0, rtol=1e-14)   # sigmoid(z) + sigmoid(-z) = 1
 
 
+def test_attention_entropy_pins():
+    """Entropy of the final query's attention row: uniform scores give log T, one dominant key gives the two-level
+    closed form, a shift of all scores changes nothing, keys scaled by c behave like scale scaled by c, and a
+    brute-force loop over a tiny case agrees (a missing minus sign, log of the scores instead of the weights, or a
+    softmax over the wrong axis fails at least one)."""
+    import math
+    from oracle import attention_entropy as ent
+    rng = np.random.default_rng(3)
+    B, T, H, d = 2, 37, 3, 8
+    k = rng.standard_normal((B, T, H, d))
+    q = rng.standard_normal((B, H, d))
+    # uniform: q = 0 -> every score 0 -> H = log T
+    np.testing.assert_allclose(ent.attention_entropy(np.zeros_like(q), k, 1.0), math.log(T), rtol=1e-14)
+    # keys all equal -> uniform as well, whatever q is
+    np.testing.assert_allclose(ent.attention_entropy(q, np.broadcast_to(k[:, :1], k.shape), 0.7), math.log(T), rtol=1e-12)
+    # two-level scores: key 5 scores c, all others 0:  p = e^c / (e^c + T - 1) on it, (1 - p) / (T - 1) on each other
+    kk = np.zeros((1, T, 1, d)); kk[0, 5, 0, 0] = 1.0
+    qq = np.zeros((1, 1, d)); qq[0, 0, 0] = 3.0
+    c = 3.0 * 0.5
+    p = math.exp(c) / (math.exp(c) + T - 1)
+    want = -(p * math.log(p) + (1 - p) * math.log((1 - p) / (T - 1)))
+    np.testing.assert_allclose(ent.attention_entropy(qq, kk, 0.5), want, rtol=1e-13)
+    # a dominant key: entropy -> 0 from above; no NaN from 0 log 0
+    qq[0, 0, 0] = 2000.0
+    h0 = ent.attention_entropy(qq, kk, 1.0)
+    assert h0.shape == (1, 1) and 0.0 <= h0[0, 0] < 1e-300
+    # shift invariance: adding the same vector u to every key adds q.u to every score
+    base = ent.attention_entropy(q, k, 0.3)
+    u = rng.standard_normal((B, 1, H, d))
+    np.testing.assert_allclose(ent.attention_entropy(q, k + u, 0.3), base, rtol=1e-10)
+    np.testing.assert_allclose(ent.attention_entropy(q, 2.0 * k, 0.15), base, rtol=1e-12)
+    assert np.all(base > 0) and np.all(base < math.log(T))
+    # brute force
+    for b in range(B):
+        for h in range(H):
+            s = [0.3 * sum(q[b, h, j] * k[b, t, h, j] for j in range(d)) for t in range(T)]
+            z = sum(math.exp(x) for x in s)
+            hb = -sum(math.exp(x) / z * math.log(math.exp(x) / z) for x in s)
+            assert abs(hb - base[b, h]) < 1e-12
+    # permutation of the keys changes nothing; heads and batches are independent
+    perm = rng.permutation(T)
+    np.testing.assert_allclose(ent.attention_entropy(q, k[:, perm], 0.3), base, rtol=1e-12)
+    np.testing.assert_allclose(ent.attention_entropy(q[1:], k[1:], 0.3), base[1:], rtol=1e-14)
+
+
 def test_oracle_threads_reported():
     assert orc.threads() >= 1
