@@ -195,6 +195,26 @@ DSLA_API dsla_status dsla_decode_slots(const dsla_desc *desc,
                               const int32_t *row_index, const int32_t *state_slot,
                               float *S1, float *S2, void *o, void *stream);
 
+/*
+ * dsla_attention_entropy - the sensitivity signal of Section 4.3 ("Layer Ranking via Sensitivity") for a
+ * softmax-attention layer: for every (batch, head), the attention row of the final query over the T keys,
+ * A_i = softmax_i(scale * q_T . k_i), and its entropy.  The paper's display shows sum_i A_i log A_i; this returns
+ * the entropy proper, H = -sum_i A_i log A_i >= 0 (natural logarithm), the negative of that sum: low values mean
+ * attention focused on few tokens, which the paper takes as "less sensitive to conversion".  Averaging over
+ * heads and ranking the layers is left to the caller.
+ *   B, H, d     : batch, heads, head size (d in {64, 128});  T >= 1 keys per sequence
+ *   io_dtype    : dsla_dtype of q_last and k
+ *   q_last      : [B][H][d], the query of the last position      k : [B][T][H][d]
+ *   entropy     : [B][H] fp32, written
+ *   workspace   : at least dsla_attention_entropy_workspace_bytes(B, H, d, T) bytes, 16-byte aligned (0 bytes when
+ *                 there are enough (batch, head) pairs to fill the device; then it may be NULL)
+ * Arithmetic is fp32; one pass over the keys.  Errors and stream semantics as for the other entry points.
+ */
+DSLA_API size_t dsla_attention_entropy_workspace_bytes(int32_t B, int32_t H, int32_t d, int64_t T);
+DSLA_API dsla_status dsla_attention_entropy(int32_t B, int32_t H, int32_t d, int64_t T, int32_t io_dtype, float scale,
+                                   const void *q_last, const void *k, float *entropy,
+                                   void *workspace, size_t workspace_bytes, void *stream);
+
 /* Text for a status code (static storage). */
 DSLA_API const char *dsla_status_string(dsla_status s);
 
@@ -206,7 +226,8 @@ DSLA_API const char *dsla_last_hip_error(void);
  * bracketed by two HIP events recorded on the launch stream (events come from a pool
  * created by dsla_profile_enable, so the launch path still allocates nothing).
  * Kernel ids: 0 state_init, 1 prefill_segment_state, 2 prefill_segment_scan,
- * 3 prefill_chunk_loop, 4 decode, 5 prefill_segment_list (packed sequences only).
+ * 3 prefill_chunk_loop, 4 decode, 5 prefill_segment_list (packed sequences only), 6 attention_entropy
+ * (both of its kernels).
  */
 #define DSLA_KERNEL_STATE_INIT 0
 #define DSLA_KERNEL_PREFILL_SEGMENT_STATE 1
@@ -214,7 +235,8 @@ DSLA_API const char *dsla_last_hip_error(void);
 #define DSLA_KERNEL_PREFILL_CHUNK_LOOP 3
 #define DSLA_KERNEL_DECODE 4
 #define DSLA_KERNEL_PREFILL_SEGMENT_LIST 5
-#define DSLA_KERNEL_COUNT 6
+#define DSLA_KERNEL_ATTENTION_ENTROPY 6
+#define DSLA_KERNEL_COUNT 7
 
 /* enable != 0: create the event pool (max_records launches can be recorded between two
  * collects) and start recording; enable == 0: stop and destroy the pool. */

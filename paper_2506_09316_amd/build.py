@@ -1,6 +1,6 @@
 """Builds libdsla.so (the C-ABI library) from csrc/ with hipcc for gfx950, in-tree.
 
-The three translation units are compiled in parallel and linked into
+The translation units are compiled in parallel and linked into
 paper_2506_09316_amd/libdsla.so.  hipcc cross-compiles without a GPU.
 """
 import os
@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdsla.so")
-SOURCES = ["api.hip", "decode.hip", "prefill.hip"]
+SOURCES = ["api.hip", "decode.hip", "entropy.hip", "prefill.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -72,4 +72,14 @@ hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T
                           const int32_t *seq_index, const int32_t *state_slot, const void *q, const void *k, const void *v, const void *g1,
                           const void *g2, float *S1, float *S2, void *o, void *workspace, hipStream_t stream);
 
+// Attention entropy of the final query: the keys of one (batch, head) are split into `parts` ranges.
+struct EntropyPlan {
+    int parts;
+    int64_t rows_per_part;
+    size_t ws_bytes;   // parts > 1: three floats per (batch, head, part)
+};
+bool entropy_plan(int B, int H, int d, int64_t T, EntropyPlan *plan);  // false: head size not built
+hipError_t launch_entropy(int B, int H, int d, int64_t T, int io_dtype, const EntropyPlan &plan, float scale,
+                          const void *q_last, const void *k, float *entropy, void *workspace, hipStream_t stream);
+
 }  // namespace dsla

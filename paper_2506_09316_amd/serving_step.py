@@ -2,6 +2,7 @@
 
     python -m paper_2506_09316_amd.serving_step [--layers 16 --B 8 --T 8192 --decode 128]
     python -m paper_2506_09316_amd.serving_step --packed {equal,pow2,serving,one_long}
+    python -m paper_2506_09316_amd.serving_step --entropy [--B 8 --T 8192]
 
 L layer instances (each with its own blend coefficient and its own pair of states per sequence) prefill a
 prompt of T tokens for B sequences and then decode token by token.  The decode step of all layers is captured
@@ -67,8 +68,41 @@ def packed(mix: str, H: int, d: int):
                       "workspace_MB": round(nws / 1e6, 1)}))
 
 
+def entropy(B: int, T: int, H: int, d: int):
+    """Attention entropy of the final query for one softmax layer's keys (dsla_attention_entropy); one JSON line."""
+    import torch
+    import paper_2506_09316_amd as dsla
+    from paper_2506_09316_amd import binding
+
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20250609)
+    NSETS = 4   # rotate over several key tensors so that the last-level cache cannot serve them
+    ks = [torch.randn(B, T, H, d, device=dev, generator=gen).to(torch.bfloat16) for _ in range(NSETS)]
+    q_last = (torch.randn(B, H, d, device=dev, generator=gen) * 1.5).to(torch.bfloat16)
+    out = torch.empty(B, H, device=dev)
+    nws = dsla.dsla_attention_entropy_workspace_bytes(B, H, d, T)
+    ws = torch.empty(max(nws, 16), dtype=torch.uint8, device=dev)
+    for i in range(16):
+        dsla.dsla_attention_entropy(q_last, ks[i % NSETS], out, d ** -0.5, ws)
+    torch.cuda.synchronize()
+    binding.profile_enable(True, 4096)
+    for i in range(200):
+        dsla.dsla_attention_entropy(q_last, ks[i % NSETS], out, d ** -0.5, ws)
+    res = binding.profile_collect()
+    binding.profile_enable(False, 0)
+    ms, n = res["attention_entropy"]
+    us = 1e3 * ms / n
+    nbytes = B * T * H * d * 2
+    print(json.dumps({"workload": f"attention entropy of the final query: B={B} H={H} d={d} T={T} bf16 keys",
+                      "us_per_call": round(us, 2), "key_bytes": nbytes, "GBps": round(nbytes / us / 1e3, 1),
+                      "frac_of_8TBps": round(nbytes / us / 1e3 / 8000, 4),
+                      "mean_entropy": round(float(out.mean()), 4)}))
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--entropy", action="store_true", help="time the attention-entropy kernel on one layer's keys instead")
     ap.add_argument("--packed", choices=sorted(MIXES), help="time one packed mixed-length prefill batch instead")
     ap.add_argument("--layers", type=int, default=16)
     ap.add_argument("--B", type=int, default=8)
@@ -80,6 +114,8 @@ def main():
     a = ap.parse_args()
     if a.packed:
         return packed(a.packed, a.H, a.d)
+    if a.entropy:
+        return entropy(a.B, a.T, a.H, a.d)
 
     import torch
     import paper_2506_09316_amd as dsla

@@ -1,0 +1,79 @@
+"""GPU parity of dsla_attention_entropy (the sensitivity signal of Section 4.3) against the fp64 oracle,
+element by element.  The arithmetic is fp32 on exact inputs (bf16 or fp32 values), so one tolerance holds for both
+storage types: 1e-4 of the largest entropy in the tensor, plus special cases with known values."""
+import math
+
+import numpy as np
+import pytest
+
+import paper_2506_09316_amd as dsla
+from oracle import attention_entropy as ent
+from paper_2506_09316_amd import workloads as wl
+from tests.util import max_rel_err, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def run(q_last, k, scale, io):
+    import torch
+    B, T, H, d = k.shape
+    qg, kg = to_gpu(q_last, io), to_gpu(k, io)
+    out = torch.full((B, H), float("nan"), device="cuda", dtype=torch.float32)
+    n = dsla.dsla_attention_entropy_workspace_bytes(B, H, d, T)
+    ws = torch.empty(n, dtype=torch.uint8, device="cuda") if n else None
+    dsla.dsla_attention_entropy(qg, kg, out, scale, ws)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), n
+
+
+def inputs(seed, B, T, H, d, io, spread=1.0):
+    x = wl.layer_inputs(seed, B, T + 1, H, d, d, io_dtype=io, gate_dtype="f32", qk_scale=1.0)
+    k = x["k"][:, :T]
+    q_last = x["q"][:, T] * np.float32(spread)
+    if io == "bf16":
+        q_last = wl.round_to_bf16(q_last)
+    return q_last, k
+
+
+@pytest.mark.parametrize("io,B,T,H,d", [("bf16", 2, 1000, 3, 128), ("bf16", 1, 4097, 2, 64), ("f32", 2, 700, 2, 128),
+                                        ("f32", 1, 333, 4, 64), ("bf16", 3, 1, 2, 128), ("bf16", 1, 17, 1, 128),
+                                        ("bf16", 70, 300, 8, 128)])
+def test_entropy_against_oracle(io, B, T, H, d):
+    q_last, k = inputs(7 + T, B, T, H, d, io)
+    got, nws = run(q_last, k, d ** -0.5, io)
+    ref = ent.attention_entropy(q_last, k, d ** -0.5)
+    print(f"  B={B} T={T} H={H} d={d} {io}: workspace {nws} B, entropy range {ref.min():.4f} .. {ref.max():.4f}, "
+          f"max err {np.max(np.abs(got - ref)):.2e}", flush=True)
+    assert np.all(np.isfinite(got))
+    if T == 1:
+        assert np.all(np.abs(got) < 1e-6)
+    else:
+        assert max_rel_err(got, ref) < 1e-4
+
+
+def test_entropy_peaked_and_flat_rows():
+    """Sharp attention (large |q|: entropy far below log T, a few keys carry the row) and flat attention (q = 0:
+    exactly log T), with the keys split over several workgroups."""
+    B, T, H, d = 1, 6000, 2, 128
+    q_last, k = inputs(11, B, T, H, d, "bf16", spread=6.0)
+    got, nws = run(q_last, k, d ** -0.5, "bf16")
+    assert nws > 0
+    ref = ent.attention_entropy(q_last, k, d ** -0.5)
+    assert ref.max() < 0.7 * math.log(T)
+    assert np.max(np.abs(got - ref)) < 1e-4 * math.log(T)
+    got, _ = run(np.zeros_like(q_last), k, 1.0, "bf16")
+    assert np.max(np.abs(got - math.log(T))) < 1e-5 * math.log(T)
+
+
+def test_entropy_full_size_sampled_heads():
+    """The shape of the hybrid serving configuration (B = 8, H = 32, d = 128, T = 8192), all 256 rows computed,
+    16 of them checked against the oracle."""
+    B, T, H, d = 8, 8192, 32, 128
+    rng = np.random.default_rng(13)
+    k = wl.round_to_bf16(rng.standard_normal((B, T, H, d), dtype=np.float32))
+    q_last = wl.round_to_bf16(rng.standard_normal((B, H, d), dtype=np.float32) * np.float32(1.5))
+    got, nws = run(q_last, k, d ** -0.5, "bf16")
+    assert np.all(np.isfinite(got))
+    for b, h in [(b, (5 * b + j) % H) for b in range(B) for j in (0, 17)]:
+        ref = ent.attention_entropy(q_last[b:b + 1, h:h + 1], k[b:b + 1, :, h:h + 1], d ** -0.5)[0, 0]
+        assert abs(got[b, h] - ref) < 1e-4 * math.log(T), (b, h, got[b, h], ref)

@@ -86,6 +86,26 @@ def test_argument_checks_need_no_gpu(lib):
     assert lib.dsla_prefill(ctypes.byref(d), -1, *([fake] * 8), None, 0, None) == 2
 
 
+def test_attention_entropy_argument_checks_and_plan(lib):
+    fake = ctypes.c_void_p(4096)
+    call = lambda B, H, d, T, io, q=fake, k=fake, o=fake, ws=None, n=0: lib.dsla_attention_entropy(
+        B, H, d, T, io, 1.0, q, k, o, ws, n, None)
+    assert call(0, 4, 128, 100, 1) == 2
+    assert call(2, 4, 128, 0, 1) == 2
+    assert call(2, 4, 96, 100, 1) == 3
+    assert call(2, 4, 128, 100, 7) == 3
+    assert call(2, 4, 128, 100, 1, q=None) == 1
+    assert call(2, 4, 128, 100, 1, k=ctypes.c_void_p(4100)) == 2
+    # 8 x 32 (batch, head) pairs: two workgroups each -> parts of 4096 keys, 3 floats per part
+    assert lib.dsla_attention_entropy_workspace_bytes(8, 32, 128, 8192) == 256 * 2 * 3 * 4
+    # 1024 pairs fill the device on their own: no split, no workspace
+    assert lib.dsla_attention_entropy_workspace_bytes(32, 32, 128, 8192) == 0
+    # a short sequence is not split below 256 keys per workgroup
+    assert lib.dsla_attention_entropy_workspace_bytes(1, 2, 64, 600) == 2 * 3 * 3 * 4
+    assert call(1, 2, 64, 600, 1) == 4          # workspace needed and missing
+    assert lib.dsla_attention_entropy_workspace_bytes(1, 2, 48, 600) == 0
+
+
 def test_varlen_workspace_plan(lib):
     up = lambda n: (n + 255) // 256 * 256
     # 8 sequences, 32 heads; total 32768 tokens, longest 16384.  The segment length follows the total (about one
