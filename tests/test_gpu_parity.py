@@ -105,6 +105,17 @@ def test_prefill_fp32_gates_near_the_domain_limit():
                      gate_mean=-0.5, qk_scale=128 ** -0.5)
 
 
+def test_prefill_bf16_negative_blend_factors():
+    """gamma > 1 makes the recency factor negative, a negative scale flips both: the sign travels in the packed
+    bf16 Q~ operand (its magnitude in the exponent)."""
+    run_prefill_case(1, 300, 2, 128, "bf16", "bf16", chunk=64, segments=2, gamma=1.3, scale=1.0, seed=41, init=True,
+                     qk_scale=128 ** -0.5)
+    run_prefill_case(1, 200, 2, 64, "bf16", "f32", chunk=32, segments=1, gamma=0.4, scale=-0.5, seed=43, init=True,
+                     qk_scale=64 ** -0.5)
+    run_prefill_case(1, 100, 2, 128, "bf16", "bf16", chunk=64, segments=1, gamma=0.0, scale=1.0, seed=45, init=True,
+                     qk_scale=128 ** -0.5)
+
+
 def test_prefill_fp32_gamma_extremes():
     for gamma in (0.0, 1.0, 1.5):
         run_prefill_case(1, 130, 2, 64, "f32", "f32", chunk=64, segments=2, gamma=gamma, seed=11, init=True)
