@@ -405,6 +405,49 @@ def test_varlen_equals_dense_bitwise():
     assert np.array_equal(S1.cpu().numpy(), S1d) and np.array_equal(S2.cpu().numpy(), S2d)
 
 
+def test_random_configurations():
+    """Forty seeded random small configurations of the dense entry points: head size, storage types, chunk, segment
+    count, sequence length (ragged against both), batch, heads, blend factor (also outside [0, 1]), scale, gate mode,
+    carried-in states, a continuation call and decode steps, each against the oracle."""
+    rng = np.random.default_rng(20250609)
+    for case in range(40):
+        d = int(rng.choice([64, 128]))
+        io = str(rng.choice(["bf16", "f32"]))
+        gate = str(rng.choice(["bf16", "f32"]))
+        chunk = int(rng.choice([0, 32, 64, 128]))
+        T = int(rng.integers(1, 330))
+        segments = int(rng.integers(0, 6))
+        B, H = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        gamma = float(rng.choice([0.0, 0.25, 0.5, 0.8, 1.0, 1.4, -0.3]))
+        scale = float(rng.choice([1.0, 0.5, -0.7]))
+        mode = int(rng.integers(0, 2))
+        steps = int(rng.integers(0, 3))
+        tol = 1e-4 if io == "f32" else 2e-2
+        print(f"  case {case}: d={d} io={io} gate={gate} chunk={chunk} T={T} segments={segments} B={B} H={H} "
+              f"gamma={gamma} scale={scale} gate_mode={mode} decode={steps}", flush=True)
+        x = wl.layer_inputs(1000 + case, B, T + steps, H, d, d, io_dtype=io, gate_dtype=gate, qk_scale=d ** -0.5,
+                            gates="preact" if mode else "log")
+        g1, g2 = ((orc.log_gates_from_preactivations(x[n], 16.0) for n in ("g1", "g2")) if mode else (x["g1"], x["g2"]))
+        S1_0, S2_0 = wl.initial_states(2000 + case, B, H, d, d, amplitude=0.3)
+        layer = GpuLayer(B, H, d, io, gate, gamma=gamma, scale=scale, chunk=chunk, segments=segments, gate_mode=mode)
+        layer.set_states(S1_0, S2_0)
+        cut = int(rng.integers(0, T + 1))
+        outs = []
+        if cut:
+            outs.append(layer.prefill(slice_t(x, 0, cut)))
+        if cut < T:
+            outs.append(layer.prefill(slice_t(x, cut, T)))
+        for t in range(T, T + steps):
+            outs.append(layer.decode(slice_t(x, t, t + 1)))
+        o = np.concatenate(outs, 1)
+        S1, S2 = layer.states()
+        ro, rS1, rS2 = orc.recurrent(x["q"], x["k"], x["v"], g1, g2, gamma, scale, S1=S1_0, S2=S2_0)
+        assert np.all(np.isfinite(o))
+        for name, got, ref in (("o", o, ro), ("S1", S1, rS1), ("S2", S2, rS2)):
+            err = max_rel_err(got, ref)
+            assert err <= tol, f"case {case} {name}: {err:.3e} > {tol}"
+
+
 def test_cfg5_layer_instances_slice():
     """The DSLA part of the hybrid serving step: several layer instances, each with its own blend coefficient and
     inputs, prefill T=8192 then 128 decode steps.  A slice is checked: 3 of the 16 layers, 2 of the 8 sequences,
