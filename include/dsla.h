@@ -200,8 +200,8 @@ DSLA_API dsla_status dsla_decode_slots(const dsla_desc *desc,
  * softmax-attention layer: for every (batch, head), the attention row of the final query over the T keys,
  * A_i = softmax_i(scale * q_T . k_i), and its entropy.  The paper's display shows sum_i A_i log A_i; this returns
  * the entropy proper, H = -sum_i A_i log A_i >= 0 (natural logarithm), the negative of that sum: low values mean
- * attention focused on few tokens, which the paper takes as "less sensitive to conversion".  Averaging over
- * heads and ranking the layers is left to the caller.
+ * attention concentrated on few tokens, which the paper reads as a layer that loses little when converted.
+ * Averaging over heads and ranking the layers is left to the caller.
  *   B, H, d     : batch, heads, head size (d in {64, 128});  T >= 1 keys per sequence
  *   io_dtype    : dsla_dtype of q_last and k
  *   q_last      : [B][H][d], the query of the last position      k : [B][T][H][d]

@@ -3,8 +3,8 @@ the benchmark's CPU baseline may import this; the product path never does.
 
 What it computes (Section 4.3, "Layer Ranking via Sensitivity"): for the final query q_T of a softmax-attention
 head, the attention distribution over the keys, A_i = softmax_i(scale * q_T . k_i), i = 0..T-1, and its Shannon
-entropy.  The paper's display prints sum_i A_i log A_i without a minus sign while the text around it treats
-"lower entropy" as "focused on fewer tokens"; the reading taken is the entropy proper, H = -sum_i A_i log A_i >= 0
+entropy.  The paper's display prints sum_i A_i log A_i without a minus sign while the text around it takes a low
+value to mean attention concentrated on few tokens; the reading taken is the entropy proper, H = -sum_i A_i log A_i >= 0
 (natural logarithm), which is the negative of the printed sum.  Plain numpy, fp64, one (batch, head) at a time
 through library primitives (matrix-vector product, exp, log, sum); no blocking or streaming.
 """
