@@ -61,7 +61,7 @@ typedef enum {
 typedef enum { DSLA_F32 = 0, DSLA_BF16 = 1 } dsla_dtype;
 
 /*
- * What the gate tensors g1, g2 hold.  The paper names the gates "data-driven" and produced by single linear
+ * What the gate tensors g1, g2 hold.  The paper describes the gates as driven by the data and produced by single linear
  * layers (Section 4.1, Section 5.3) without giving the map into (0,1]; this library takes the parametrisation
  * of the gated linear attention work the method extends: alpha = sigmoid(z)^(1/tau).
  *   DSLA_GATE_LOG    : g = log alpha <= 0, computed by the caller (any map into (0,1] can be used this way)
