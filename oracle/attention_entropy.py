@@ -1,4 +1,5 @@
-"""CPU oracle of the attention-entropy sensitivity signal.  TEST INFRASTRUCTURE: only tests/, the smoke check and
+"""CPU oracle of the two softmax-attention pieces beside the DSLA layer: the attention-entropy sensitivity signal and
+the single-query (decode) attention of an unconverted layer.  TEST INFRASTRUCTURE: only tests/, the smoke check and
 the benchmark's CPU baseline may import this; the product path never does.
 
 What it computes (Section 4.3, "Layer Ranking via Sensitivity"): for the final query q_T of a softmax-attention
@@ -25,4 +26,24 @@ def attention_entropy(q_last, k, scale):
             a = e / e.sum()                                         # the attention row
             nz = a > 0
             out[b, h] = -np.sum(a[nz] * np.log(a[nz]))
+    return out
+
+
+def attention_decode(q_last, k, v, scale):
+    """Softmax attention of one query per (batch, head) over T cached keys and values: the decode step of a layer
+    that has NOT been converted, which the paper's serving system runs beside the DSLA layers (Section 4.3; its
+    cost grows with the context, Section 5.3).  o = sum_i softmax_i(scale * q . k_i) v_i, fp64, from the definition.
+    q_last: [B, H, d]; k, v: [B, T, H, d]; returns o: [B, H, d]."""
+    q_last = np.asarray(q_last, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    B, T, H, d = k.shape
+    assert q_last.shape == (B, H, d) and v.shape[:3] == (B, T, H) and T >= 1
+    out = np.zeros((B, H, v.shape[3]), dtype=np.float64)
+    for b in range(B):
+        for h in range(H):
+            s = float(scale) * (k[b, :, h, :] @ q_last[b, h])
+            e = np.exp(s - s.max())
+            a = e / e.sum()
+            out[b, h] = a @ v[b, :, h, :]
     return out

@@ -356,5 +356,49 @@ def test_attention_entropy_pins():
     np.testing.assert_allclose(ent.attention_entropy(q[1:], k[1:], 0.3), base[1:], rtol=1e-14)
 
 
+def test_attention_decode_pins():
+    """Single-query softmax attention: q = 0 gives the mean of the values, a dominant key returns its value, the
+    output is linear in v and a convex combination of the values, a two-key case has a closed form, and a brute-force
+    loop agrees (a missing normaliser, a softmax over features, or k and v swapped fails at least one)."""
+    import math
+    from oracle import attention_entropy as ent
+    rng = np.random.default_rng(4)
+    B, T, H, d = 2, 29, 3, 8
+    k = rng.standard_normal((B, T, H, d))
+    v = rng.standard_normal((B, T, H, d))
+    q = rng.standard_normal((B, H, d))
+    np.testing.assert_allclose(ent.attention_decode(np.zeros_like(q), k, v, 1.0), v.mean(axis=1), rtol=1e-13, atol=1e-15)
+    # dominant key 7
+    kk = np.zeros_like(k); kk[:, 7] = 50.0 * q / np.sum(q * q, axis=-1, keepdims=True)
+    np.testing.assert_allclose(ent.attention_decode(q, kk, v, 1.0), v[:, 7], rtol=1e-12, atol=1e-12)
+    base = ent.attention_decode(q, k, v, 0.4)
+    # linear in v; convex combination: within the range of the values, per feature
+    v2 = rng.standard_normal(v.shape)
+    np.testing.assert_allclose(ent.attention_decode(q, k, 2.0 * v - 3.0 * v2, 0.4),
+                               2.0 * base - 3.0 * ent.attention_decode(q, k, v2, 0.4), rtol=1e-11, atol=1e-12)
+    assert np.all(base <= v.max(axis=1) + 1e-12) and np.all(base >= v.min(axis=1) - 1e-12)
+    # two keys: weights sigmoid(+-(s0 - s1))
+    q2 = np.array([[[1.0, 2.0]]]); k2 = np.array([[[[0.5, -1.0]], [[2.0, 0.25]]]]); v2k = np.array([[[[1.0, 0.0]], [[0.0, 1.0]]]])
+    s0, s1 = 0.3 * (0.5 - 2.0), 0.3 * (2.0 + 0.5)
+    w0 = 1.0 / (1.0 + math.exp(s1 - s0))
+    np.testing.assert_allclose(ent.attention_decode(q2, k2, v2k, 0.3)[0, 0], [w0, 1.0 - w0], rtol=1e-14)
+    # brute force
+    for b in range(B):
+        for h in range(H):
+            s = [0.4 * sum(q[b, h, j] * k[b, t, h, j] for j in range(d)) for t in range(T)]
+            z = sum(math.exp(x) for x in s)
+            for j in range(d):
+                o = sum(math.exp(s[t]) / z * v[b, t, h, j] for t in range(T))
+                assert abs(o - base[b, h, j]) < 1e-12
+    # the weights behind it are the ones whose entropy the other function returns: with one-hot values
+    # v_i = e_i the output IS the attention row
+    Tn = 6
+    eye = np.zeros((1, Tn, 1, Tn)); eye[0, :, 0, :] = np.eye(Tn)
+    kq = rng.standard_normal((1, Tn, 1, 4)); qq = rng.standard_normal((1, 1, 4))
+    a = ent.attention_decode(qq, kq, eye, 0.7)[0, 0]
+    assert abs(a.sum() - 1.0) < 1e-14
+    assert abs(-np.sum(a * np.log(a)) - ent.attention_entropy(qq, kq, 0.7)[0, 0]) < 1e-13
+
+
 def test_oracle_threads_reported():
     assert orc.threads() >= 1
