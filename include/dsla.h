@@ -215,6 +215,25 @@ DSLA_API dsla_status dsla_attention_entropy(int32_t B, int32_t H, int32_t d, int
                                    const void *q_last, const void *k, float *entropy,
                                    void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * dsla_attention_decode - one decode step of a softmax-attention layer that has NOT been converted: one query per
+ * (batch, head) against the T cached keys and values of its sequence (the current token included),
+ *     o = sum_i softmax_i(scale * q . k_i) v_i .
+ * This is what the paper's serving system runs beside the DSLA layers of a partly converted model (Section 4.3) and
+ * what the constant-cost DSLA decode step is measured against (Section 5.3): its traffic is the whole cache, 4 d T
+ * bytes per head in bf16, against two fixed states.
+ *   B, H, d     : batch, heads, head size (d in {64, 128});  T >= 1 cached positions, the same for every sequence
+ *   io_dtype    : dsla_dtype of q, k, v, o
+ *   q           : [B][H][d]      k, v : [B][T][H][d]      o : [B][H][d], written
+ *   workspace   : at least dsla_attention_decode_workspace_bytes(B, H, d, T) bytes, 16-byte aligned (0 bytes when
+ *                 there are enough (batch, head) pairs to fill the device; then it may be NULL)
+ * fp32 arithmetic, one pass over keys and values.  Errors and stream semantics as for the other entry points.
+ */
+DSLA_API size_t dsla_attention_decode_workspace_bytes(int32_t B, int32_t H, int32_t d, int64_t T);
+DSLA_API dsla_status dsla_attention_decode(int32_t B, int32_t H, int32_t d, int64_t T, int32_t io_dtype, float scale,
+                                  const void *q, const void *k, const void *v, void *o,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
 /* Text for a status code (static storage). */
 DSLA_API const char *dsla_status_string(dsla_status s);
 
@@ -226,8 +245,8 @@ DSLA_API const char *dsla_last_hip_error(void);
  * bracketed by two HIP events recorded on the launch stream (events come from a pool
  * created by dsla_profile_enable, so the launch path still allocates nothing).
  * Kernel ids: 0 state_init, 1 prefill_segment_state, 2 prefill_segment_scan,
- * 3 prefill_chunk_loop, 4 decode, 5 prefill_segment_list (packed sequences only), 6 attention_entropy
- * (both of its kernels).
+ * 3 prefill_chunk_loop, 4 decode, 5 prefill_segment_list (packed sequences only), 6 attention_entropy,
+ * 7 attention_decode (each with its merge kernel).
  */
 #define DSLA_KERNEL_STATE_INIT 0
 #define DSLA_KERNEL_PREFILL_SEGMENT_STATE 1
@@ -236,7 +255,8 @@ DSLA_API const char *dsla_last_hip_error(void);
 #define DSLA_KERNEL_DECODE 4
 #define DSLA_KERNEL_PREFILL_SEGMENT_LIST 5
 #define DSLA_KERNEL_ATTENTION_ENTROPY 6
-#define DSLA_KERNEL_COUNT 7
+#define DSLA_KERNEL_ATTENTION_DECODE 7
+#define DSLA_KERNEL_COUNT 8
 
 /* enable != 0: create the event pool (max_records launches can be recorded between two
  * collects) and start recording; enable == 0: stop and destroy the pool. */

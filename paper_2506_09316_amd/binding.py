@@ -14,10 +14,11 @@ _lib = None
 
 DSLA_F32, DSLA_BF16 = 0, 1
 KERNEL_NAMES = ("state_init", "prefill_segment_state", "prefill_segment_scan", "prefill_chunk_loop", "decode",
-                "prefill_segment_list", "attention_entropy")
+                "prefill_segment_list", "attention_entropy", "attention_decode")
 EXPORTS = ("dsla_state_init", "dsla_prefill_workspace_bytes", "dsla_prefill", "dsla_decode",
            "dsla_prefill_varlen_workspace_bytes", "dsla_prefill_varlen", "dsla_decode_slots",
            "dsla_attention_entropy_workspace_bytes", "dsla_attention_entropy",
+           "dsla_attention_decode_workspace_bytes", "dsla_attention_decode",
            "dsla_status_string", "dsla_last_hip_error", "dsla_profile_enable", "dsla_profile_collect")
 
 
@@ -69,6 +70,11 @@ def load_library():
     lib.dsla_attention_entropy.argtypes = ([ctypes.c_int32] * 3 + [ctypes.c_int64, ctypes.c_int32, ctypes.c_float]
                                            + [vp] * 4 + [ctypes.c_size_t, vp])
     lib.dsla_attention_entropy.restype = ctypes.c_int
+    lib.dsla_attention_decode_workspace_bytes.argtypes = [ctypes.c_int32] * 3 + [ctypes.c_int64]
+    lib.dsla_attention_decode_workspace_bytes.restype = ctypes.c_size_t
+    lib.dsla_attention_decode.argtypes = ([ctypes.c_int32] * 3 + [ctypes.c_int64, ctypes.c_int32, ctypes.c_float]
+                                          + [vp] * 5 + [ctypes.c_size_t, vp])
+    lib.dsla_attention_decode.restype = ctypes.c_int
     lib.dsla_status_string.argtypes = [ctypes.c_int]
     lib.dsla_status_string.restype = ctypes.c_char_p
     lib.dsla_last_hip_error.argtypes = []
@@ -173,6 +179,20 @@ def dsla_attention_entropy(q_last, k, entropy, scale: float, workspace=None):
     _check(load_library().dsla_attention_entropy(int(B), int(H), int(d), int(T), _dtype_code(k), float(scale),
                                                  _ptr(q_last), _ptr(k), _ptr(entropy), _ptr(workspace), wbytes,
                                                  _stream()))
+
+
+def dsla_attention_decode_workspace_bytes(B: int, H: int, d: int, T: int) -> int:
+    return int(load_library().dsla_attention_decode_workspace_bytes(int(B), int(H), int(d), int(T)))
+
+
+def dsla_attention_decode(q, k, v, o, scale: float, workspace=None):
+    """Single-query softmax attention over cached keys and values (include/dsla.h: dsla_attention_decode).
+    q, o [B,H,d]; k, v [B,T,H,d] (all bf16 or all fp32 GPU tensors)."""
+    B, T, H, d = k.shape
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().dsla_attention_decode(int(B), int(H), int(d), int(T), _dtype_code(k), float(scale),
+                                                _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(workspace), wbytes,
+                                                _stream()))
 
 
 def profile_enable(enable: bool, max_records: int = 4096):

@@ -225,6 +225,32 @@ dsla_status dsla_attention_entropy(int32_t B, int32_t H, int32_t d, int64_t T, i
                                      static_cast<hipStream_t>(stream)));
 }
 
+size_t dsla_attention_decode_workspace_bytes(int32_t B, int32_t H, int32_t d, int64_t T)
+{
+    EntropyPlan plan;
+    if (B <= 0 || H <= 0 || T <= 0 || !entropy_plan(B, H, d, T, &plan, 2 + d)) return 0;
+    return plan.ws_bytes;
+}
+
+dsla_status dsla_attention_decode(int32_t B, int32_t H, int32_t d, int64_t T, int32_t io_dtype, float scale,
+                                  const void *q, const void *k, const void *v, void *o, void *workspace,
+                                  size_t workspace_bytes, void *stream)
+{
+    if (B <= 0 || H <= 0 || d <= 0 || T <= 0 || T > 0x7fffffffLL) return DSLA_ERR_SHAPE;
+    if (static_cast<int64_t>(B) * H > 0x7fffffffLL / 1024) return DSLA_ERR_SHAPE;
+    if (io_dtype != DSLA_F32 && io_dtype != DSLA_BF16) return DSLA_ERR_UNSUPPORTED;
+    EntropyPlan plan;
+    if (!entropy_plan(B, H, d, T, &plan, 2 + d)) return DSLA_ERR_UNSUPPORTED;
+    if (!q || !k || !v || !o) return DSLA_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return DSLA_ERR_SHAPE;
+    if (plan.ws_bytes > 0) {
+        if (!workspace || workspace_bytes < plan.ws_bytes) return DSLA_ERR_WORKSPACE;
+        if (!aligned16(workspace)) return DSLA_ERR_SHAPE;
+    }
+    return hip_status(launch_attn_decode(B, H, d, T, io_dtype, plan, scale, q, k, v, o, workspace,
+                                         static_cast<hipStream_t>(stream)));
+}
+
 dsla_status dsla_profile_enable(int enable, int max_records)
 {
     std::lock_guard<std::mutex> lk(g_prof.mu);

@@ -72,13 +72,17 @@ hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T
                           const int32_t *seq_index, const int32_t *state_slot, const void *q, const void *k, const void *v, const void *g1,
                           const void *g2, float *S1, float *S2, void *o, void *workspace, hipStream_t stream);
 
-// Attention entropy of the final query: the keys of one (batch, head) are split into `parts` ranges.
+// Single-query attention kernels (entropy of the final query, decode attention over a cache): the keys of one
+// (batch, head) are split into `parts` ranges, each leaving a record of floats_per_part floats to merge.
 struct EntropyPlan {
     int parts;
     int64_t rows_per_part;
-    size_t ws_bytes;   // parts > 1: three floats per (batch, head, part)
+    size_t ws_bytes;   // parts > 1: one record per (batch, head, part)
 };
-bool entropy_plan(int B, int H, int d, int64_t T, EntropyPlan *plan);  // false: head size not built
+bool entropy_plan(int B, int H, int d, int64_t T, EntropyPlan *plan, int floats_per_part = 3);  // false: head size not built
+hipError_t launch_attn_decode(int B, int H, int d, int64_t T, int io_dtype, const EntropyPlan &plan, float scale,
+                              const void *q_last, const void *k, const void *v, void *o, void *workspace,
+                              hipStream_t stream);
 hipError_t launch_entropy(int B, int H, int d, int64_t T, int io_dtype, const EntropyPlan &plan, float scale,
                           const void *q_last, const void *k, float *entropy, void *workspace, hipStream_t stream);
 

@@ -3,6 +3,7 @@
     python -m paper_2506_09316_amd.serving_step [--layers 16 --B 8 --T 8192 --decode 128]
     python -m paper_2506_09316_amd.serving_step --packed {equal,pow2,serving,one_long}
     python -m paper_2506_09316_amd.serving_step --entropy [--B 8 --T 8192]
+    python -m paper_2506_09316_amd.serving_step --attention-decode [--B 8 --T 8192]
 
 L layer instances (each with its own blend coefficient and its own pair of states per sequence) prefill a
 prompt of T tokens for B sequences and then decode token by token.  The decode step of all layers is captured
@@ -100,8 +101,59 @@ def entropy(B: int, T: int, H: int, d: int):
                       "mean_entropy": round(float(out.mean()), 4)}))
 
 
+def attention_decode(B: int, T: int, H: int, d: int):
+    """One decode step of an unconverted softmax layer over a cache of T positions (dsla_attention_decode), with the
+    DSLA decode step of the same batch beside it; one JSON line."""
+    import torch
+    import paper_2506_09316_amd as dsla
+    from paper_2506_09316_amd import binding
+    from paper_2506_09316_amd.binding import DSLA_BF16
+
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20250609)
+    rnd = lambda *shape: torch.randn(*shape, device=dev, generator=gen).to(torch.bfloat16)
+    NSETS = 3   # rotate over several caches so that the last-level cache cannot serve them
+    caches = [(rnd(B, T, H, d), rnd(B, T, H, d)) for _ in range(NSETS)]
+    q = rnd(B, H, d)
+    o = torch.empty_like(q)
+    nws = dsla.dsla_attention_decode_workspace_bytes(B, H, d, T)
+    ws = torch.empty(max(nws, 16), dtype=torch.uint8, device=dev)
+    # the DSLA step of the same batch
+    desc = dsla.make_desc(B, H, d, d, io_dtype=DSLA_BF16, gate_dtype=DSLA_BF16)
+    states = [(torch.randn(B, H, d, d, device=dev, generator=gen) * 0.1, torch.randn(B, H, d, d, device=dev, generator=gen) * 0.1)
+              for _ in range(8)]
+    g = (-torch.nn.functional.softplus(-(torch.randn(B, H, d, device=dev, generator=gen) + 2.0)) / 16.0).to(torch.bfloat16)
+    kd, vd = rnd(B, H, d), rnd(B, H, d)
+
+    def run(n):
+        for i in range(n):
+            kc, vc = caches[i % NSETS]
+            dsla.dsla_attention_decode(q, kc, vc, o, d ** -0.5, ws)
+            s1, s2 = states[i % 8]
+            dsla.dsla_decode(desc, q, kd, vd, g, g, s1, s2, o)
+
+    run(12)
+    torch.cuda.synchronize()
+    binding.profile_enable(True, 4096)
+    run(120)
+    res = binding.profile_collect()
+    binding.profile_enable(False, 0)
+    us_attn = 1e3 * res["attention_decode"][0] / res["attention_decode"][1]
+    us_dsla = 1e3 * res["decode"][0] / res["decode"][1]
+    cache_bytes = 2 * B * T * H * d * 2
+    print(json.dumps({"workload": f"decode step of one layer, B={B} H={H} d={d}, context T={T}, bf16",
+                      "softmax_attention_us": round(us_attn, 2), "kv_cache_bytes": cache_bytes,
+                      "softmax_attention_GBps": round(cache_bytes / us_attn / 1e3, 1),
+                      "softmax_attention_frac_of_8TBps": round(cache_bytes / us_attn / 1e3 / 8000, 4),
+                      "dsla_decode_us": round(us_dsla, 2), "dsla_state_bytes": B * H * 2 * d * d * 4,
+                      "ratio": round(us_attn / us_dsla, 2)}))
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--attention-decode", action="store_true",
+                    help="time the decode step of an unconverted softmax layer against the DSLA decode step instead")
     ap.add_argument("--entropy", action="store_true", help="time the attention-entropy kernel on one layer's keys instead")
     ap.add_argument("--packed", choices=sorted(MIXES), help="time one packed mixed-length prefill batch instead")
     ap.add_argument("--layers", type=int, default=16)
@@ -116,6 +168,8 @@ def main():
         return packed(a.packed, a.H, a.d)
     if a.entropy:
         return entropy(a.B, a.T, a.H, a.d)
+    if a.attention_decode:
+        return attention_decode(a.B, a.T, a.H, a.d)
 
     import torch
     import paper_2506_09316_amd as dsla

@@ -1,5 +1,5 @@
-"""GPU parity of dsla_attention_entropy (the sensitivity signal of Section 4.3) against the fp64 oracle,
-element by element.  The arithmetic is fp32 on exact inputs (bf16 or fp32 values), so one tolerance holds for both
+"""GPU parity of dsla_attention_entropy (the sensitivity signal of Section 4.3) and dsla_attention_decode (the
+decode step of an unconverted softmax layer) against the fp64 oracle, element by element.  The arithmetic is fp32 on exact inputs (bf16 or fp32 values), so one tolerance holds for both
 storage types: 1e-4 of the largest entropy in the tensor, plus special cases with known values."""
 import math
 
@@ -77,3 +77,50 @@ def test_entropy_full_size_sampled_heads():
     for b, h in [(b, (5 * b + j) % H) for b in range(B) for j in (0, 17)]:
         ref = ent.attention_entropy(q_last[b:b + 1, h:h + 1], k[b:b + 1, :, h:h + 1], d ** -0.5)[0, 0]
         assert abs(got[b, h] - ref) < 1e-4 * math.log(T), (b, h, got[b, h], ref)
+
+
+# ---------------------------------------------------------------- single-query attention over a cache
+def run_decode(q, k, v, scale, io):
+    import torch
+    B, T, H, d = k.shape
+    qg, kg, vg = to_gpu(q, io), to_gpu(k, io), to_gpu(v, io)
+    o = torch.full_like(qg, float("nan"))
+    n = dsla.dsla_attention_decode_workspace_bytes(B, H, d, T)
+    ws = torch.empty(n, dtype=torch.uint8, device="cuda") if n else None
+    dsla.dsla_attention_decode(qg, kg, vg, o, scale, ws)
+    torch.cuda.synchronize()
+    return o.float().cpu().numpy(), n
+
+
+@pytest.mark.parametrize("io,B,T,H,d,spread", [("bf16", 2, 1000, 3, 128, 1.0), ("bf16", 1, 4097, 2, 64, 1.0),
+                                               ("f32", 2, 700, 2, 128, 1.0), ("f32", 1, 333, 4, 64, 3.0),
+                                               ("bf16", 3, 1, 2, 128, 1.0), ("bf16", 1, 17, 1, 128, 5.0),
+                                               ("bf16", 70, 300, 8, 128, 2.0), ("bf16", 1, 6000, 2, 128, 6.0)])
+def test_attention_decode_against_oracle(io, B, T, H, d, spread):
+    """Tolerances as for the DSLA layer (max |x - ref| / max |ref| over the tensor): fp32 1e-4; bf16 2e-2.  With
+    bf16 the arithmetic is fp32 on exact inputs and the only rounding is that of the output (half a bf16 ulp, at
+    most 2^-8 of the element), so the error is also held to 2^-8 plus a little."""
+    q, k = inputs(21 + T, B, T, H, d, io, spread=spread)
+    v = wl.layer_inputs(77 + T, B, T, H, d, d, io_dtype=io, gate_dtype="f32")["v"]
+    got, nws = run_decode(q, k, v, d ** -0.5, io)
+    ref = ent.attention_decode(q, k, v, d ** -0.5)
+    err = max_rel_err(got, ref)
+    print(f"  B={B} T={T} H={H} d={d} {io} spread={spread}: workspace {nws} B, max rel err {err:.2e}", flush=True)
+    assert np.all(np.isfinite(got))
+    assert err < (1e-4 if io == "f32" else 2e-2)
+    if io == "bf16":
+        assert np.all(np.abs(got - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * np.max(np.abs(ref)))
+
+
+def test_attention_decode_full_size_sampled_heads():
+    """B = 8, H = 32, d = 128, T = 8192 (the serving configuration's cache of one layer), 16 rows checked."""
+    B, T, H, d = 8, 8192, 32, 128
+    rng = np.random.default_rng(15)
+    k = wl.round_to_bf16(rng.standard_normal((B, T, H, d), dtype=np.float32))
+    v = wl.round_to_bf16(rng.standard_normal((B, T, H, d), dtype=np.float32))
+    q = wl.round_to_bf16(rng.standard_normal((B, H, d), dtype=np.float32) * np.float32(2.0))
+    got, _ = run_decode(q, k, v, d ** -0.5, "bf16")
+    assert np.all(np.isfinite(got))
+    for b, h in [(b, (7 * b + j) % H) for b in range(B) for j in (1, 20)]:
+        ref = ent.attention_decode(q[b:b + 1, h:h + 1], k[b:b + 1, :, h:h + 1], v[b:b + 1, :, h:h + 1], d ** -0.5)[0, 0]
+        assert np.all(np.abs(got[b, h] - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * np.max(np.abs(ref))), (b, h)

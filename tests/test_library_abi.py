@@ -106,6 +106,20 @@ def test_attention_entropy_argument_checks_and_plan(lib):
     assert lib.dsla_attention_entropy_workspace_bytes(1, 2, 48, 600) == 0
 
 
+def test_attention_decode_argument_checks_and_plan(lib):
+    fake = ctypes.c_void_p(4096)
+    call = lambda B, H, d, T, io, q=fake, k=fake, v=fake, o=fake, ws=None, n=0: lib.dsla_attention_decode(
+        B, H, d, T, io, 1.0, q, k, v, o, ws, n, None)
+    assert call(2, 0, 128, 100, 1) == 2
+    assert call(2, 4, 100, 100, 1) == 3
+    assert call(2, 4, 128, 100, 1, v=None) == 1
+    assert call(2, 4, 128, 100, 1, o=ctypes.c_void_p(4104)) == 2
+    # same split as the entropy kernel, a record of 2 + d floats per part
+    assert lib.dsla_attention_decode_workspace_bytes(8, 32, 128, 8192) == 256 * 2 * 130 * 4
+    assert lib.dsla_attention_decode_workspace_bytes(32, 32, 128, 8192) == 0
+    assert call(8, 32, 128, 8192, 1) == 4
+
+
 def test_varlen_workspace_plan(lib):
     up = lambda n: (n + 255) // 256 * 256
     # 8 sequences, 32 heads; total 32768 tokens, longest 16384.  The segment length follows the total (about one
