@@ -1,4 +1,4 @@
-"""The DSLA share of a hybrid serving step, as a usage example and a measurement:
+"""The attention layers of a hybrid serving step, as a usage example and a measurement:
 
     python -m paper_2506_09316_amd.serving_step [--layers 16 --B 8 --T 8192 --decode 128]
     python -m paper_2506_09316_amd.serving_step --packed {equal,pow2,serving,one_long}
@@ -8,8 +8,10 @@
 L layer instances (each with its own blend coefficient and its own pair of states per sequence) prefill a
 prompt of T tokens for B sequences and then decode token by token.  The decode step of all layers is captured
 into one HIP graph and replayed per token (the library enqueues only kernels and allocates nothing, so it can be
-captured); the eager loop is timed beside it.  Inputs are synthetic and shared by the layers: the projections that
-would produce them, the softmax-attention layers and the MLPs of the stack are not part of this library.
+captured); the eager loop is timed beside it.  The decode step of the other half of the stack - as many
+softmax-attention layers, each over its own key/value cache of T positions - is timed as well, alone and
+interleaved with the DSLA layers.  Inputs are synthetic and shared by the layers: the projections that would produce
+them, the prefill of the softmax layers and the MLPs of the stack are not part of this library.
 Prints one JSON line.
 """
 from __future__ import annotations
@@ -239,6 +241,28 @@ def main():
     ms_graph = timed(graph.replay, a.decode)
     assert bool(torch.isfinite(do.float()).all()) and bool(torch.isfinite(o.float()).all())
 
+    # the other half of the hybrid stack at decode time: L softmax-attention layers, each over its own key/value
+    # cache of T positions (the DSLA layers need no cache: that is the memory the conversion frees)
+    caches = [(rnd(B, T, H, d), rnd(B, T, H, d)) for _ in range(L)]
+    aq, ao = rnd(L, B, H, d), torch.empty(L, B, H, d, dtype=torch.bfloat16, device=dev)
+    aws = torch.empty(max(dsla.dsla_attention_decode_workspace_bytes(B, H, d, T), 16), dtype=torch.uint8, device=dev)
+
+    def softmax_layers():
+        for l in range(L):
+            dsla.dsla_attention_decode(aq[l], caches[l][0], caches[l][1], ao[l], d ** -0.5, aws)
+
+    def hybrid_step():
+        for l in range(L):
+            dsla.dsla_attention_decode(aq[l], caches[l][0], caches[l][1], ao[l], d ** -0.5, aws)
+            dsla.dsla_decode(descs[l], dq[l], dk[l], dv[l], dg1[l], dg2[l], S[l][0], S[l][1], do[l])
+
+    for _ in range(2):
+        hybrid_step()
+    ms_softmax = timed(softmax_layers, 10)
+    ms_hybrid = timed(hybrid_step, 10)
+    assert bool(torch.isfinite(ao.float()).all())
+    cache_bytes = L * 2 * B * T * H * d * 2
+
     state_bytes = L * B * H * (2 * d * d * 4 * 2 + 6 * d * 2)
     print(json.dumps({
         "workload": f"DSLA share of a serving step: {L} layer instances, B={B} H={H} d={d}, prompt T={T}, "
@@ -250,6 +274,10 @@ def main():
         "decode_layer_tokens_per_s_graph": round(L * B / (ms_graph * 1e-3), 1),
         "decode_GBps_graph": round(state_bytes / (ms_graph * 1e-3) / 1e9, 1),
         "request_ms_prompt_plus_decode": round(ms_prefill + a.decode * ms_graph, 2),
+        "softmax_layers_decode_step_ms": round(ms_softmax, 4),
+        "softmax_layers_kv_cache_GB": round(cache_bytes / 1e9, 2),
+        "hybrid_decode_step_ms_softmax_plus_dsla_layers": round(ms_hybrid, 4),
+        "attention_time_of_decode_unconverted_over_half_converted": round(2 * ms_softmax / ms_hybrid, 2),
     }))
 
 
