@@ -222,16 +222,18 @@ DSLA_API dsla_status dsla_attention_entropy(int32_t B, int32_t H, int32_t d, int
  * This is what the paper's serving system runs beside the DSLA layers of a partly converted model (Section 4.3) and
  * what the constant-cost DSLA decode step is measured against (Section 5.3): its traffic is the whole cache, 4 d T
  * bytes per head in bf16, against two fixed states.
- *   B, H, d     : batch, heads, head size (d in {64, 128});  T >= 1 cached positions, the same for every sequence
+ *   B, H, d     : batch, heads, head size (d in {64, 128});  T >= 1 positions the cache of a sequence can hold
  *   io_dtype    : dsla_dtype of q, k, v, o
  *   q           : [B][H][d]      k, v : [B][T][H][d]      o : [B][H][d], written
+ *   seq_lens    : DEVICE int32 [B] or NULL.  Positions sequence b has filled, 1 <= seq_lens[b] <= T (requests of a
+ *                 batch are at different context lengths); only those are read.  NULL = T for every sequence
  *   workspace   : at least dsla_attention_decode_workspace_bytes(B, H, d, T) bytes, 16-byte aligned (0 bytes when
  *                 there are enough (batch, head) pairs to fill the device; then it may be NULL)
  * fp32 arithmetic, one pass over keys and values.  Errors and stream semantics as for the other entry points.
  */
 DSLA_API size_t dsla_attention_decode_workspace_bytes(int32_t B, int32_t H, int32_t d, int64_t T);
 DSLA_API dsla_status dsla_attention_decode(int32_t B, int32_t H, int32_t d, int64_t T, int32_t io_dtype, float scale,
-                                  const void *q, const void *k, const void *v, void *o,
+                                  const void *q, const void *k, const void *v, const int32_t *seq_lens, void *o,
                                   void *workspace, size_t workspace_bytes, void *stream);
 
 /* Text for a status code (static storage). */

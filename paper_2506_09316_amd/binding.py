@@ -73,7 +73,7 @@ def load_library():
     lib.dsla_attention_decode_workspace_bytes.argtypes = [ctypes.c_int32] * 3 + [ctypes.c_int64]
     lib.dsla_attention_decode_workspace_bytes.restype = ctypes.c_size_t
     lib.dsla_attention_decode.argtypes = ([ctypes.c_int32] * 3 + [ctypes.c_int64, ctypes.c_int32, ctypes.c_float]
-                                          + [vp] * 5 + [ctypes.c_size_t, vp])
+                                          + [vp] * 6 + [ctypes.c_size_t, vp])
     lib.dsla_attention_decode.restype = ctypes.c_int
     lib.dsla_status_string.argtypes = [ctypes.c_int]
     lib.dsla_status_string.restype = ctypes.c_char_p
@@ -185,13 +185,13 @@ def dsla_attention_decode_workspace_bytes(B: int, H: int, d: int, T: int) -> int
     return int(load_library().dsla_attention_decode_workspace_bytes(int(B), int(H), int(d), int(T)))
 
 
-def dsla_attention_decode(q, k, v, o, scale: float, workspace=None):
+def dsla_attention_decode(q, k, v, o, scale: float, workspace=None, seq_lens=None):
     """Single-query softmax attention over cached keys and values (include/dsla.h: dsla_attention_decode).
-    q, o [B,H,d]; k, v [B,T,H,d] (all bf16 or all fp32 GPU tensors)."""
+    q, o [B,H,d]; k, v [B,T,H,d] (all bf16 or all fp32 GPU tensors); seq_lens: int32 GPU tensor [B] or None."""
     B, T, H, d = k.shape
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load_library().dsla_attention_decode(int(B), int(H), int(d), int(T), _dtype_code(k), float(scale),
-                                                _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(workspace), wbytes,
+                                                _ptr(q), _ptr(k), _ptr(v), _ptr(seq_lens), _ptr(o), _ptr(workspace), wbytes,
                                                 _stream()))
 
 

@@ -233,8 +233,8 @@ size_t dsla_attention_decode_workspace_bytes(int32_t B, int32_t H, int32_t d, in
 }
 
 dsla_status dsla_attention_decode(int32_t B, int32_t H, int32_t d, int64_t T, int32_t io_dtype, float scale,
-                                  const void *q, const void *k, const void *v, void *o, void *workspace,
-                                  size_t workspace_bytes, void *stream)
+                                  const void *q, const void *k, const void *v, const int32_t *seq_lens, void *o,
+                                  void *workspace, size_t workspace_bytes, void *stream)
 {
     if (B <= 0 || H <= 0 || d <= 0 || T <= 0 || T > 0x7fffffffLL) return DSLA_ERR_SHAPE;
     if (static_cast<int64_t>(B) * H > 0x7fffffffLL / 1024) return DSLA_ERR_SHAPE;
@@ -242,12 +242,13 @@ dsla_status dsla_attention_decode(int32_t B, int32_t H, int32_t d, int64_t T, in
     EntropyPlan plan;
     if (!entropy_plan(B, H, d, T, &plan, 2 + d)) return DSLA_ERR_UNSUPPORTED;
     if (!q || !k || !v || !o) return DSLA_ERR_NULL;
-    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return DSLA_ERR_SHAPE;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || (reinterpret_cast<uintptr_t>(seq_lens) & 3u))
+        return DSLA_ERR_SHAPE;
     if (plan.ws_bytes > 0) {
         if (!workspace || workspace_bytes < plan.ws_bytes) return DSLA_ERR_WORKSPACE;
         if (!aligned16(workspace)) return DSLA_ERR_SHAPE;
     }
-    return hip_status(launch_attn_decode(B, H, d, T, io_dtype, plan, scale, q, k, v, o, workspace,
+    return hip_status(launch_attn_decode(B, H, d, T, io_dtype, plan, scale, q, k, v, seq_lens, o, workspace,
                                          static_cast<hipStream_t>(stream)));
 }
 

@@ -183,8 +183,9 @@ struct RawRow<float> {
 // Same decomposition as entropy_kernel; a part's record is (m, z, acc[D]).
 template <int D, class TIO>
 __global__ __launch_bounds__(kEntThreads) void attn_decode_kernel(const TIO *__restrict__ q_last, const TIO *__restrict__ k,
-                                                                  const TIO *__restrict__ v, float scale, int H,
-                                                                  long long T, int P, long long rows_per_part,
+                                                                  const TIO *__restrict__ v,
+                                                                  const int32_t *__restrict__ seq_lens, float scale,
+                                                                  int H, long long T, int P, long long rows_per_part,
                                                                   float *__restrict__ parts, TIO *__restrict__ o)
 {
     constexpr int LPR = D / 8;
@@ -196,8 +197,10 @@ __global__ __launch_bounds__(kEntThreads) void attn_decode_kernel(const TIO *__r
     const int bh = blockIdx.x / P, part = blockIdx.x % P;
     const int b = bh / H, h = bh % H;
     const int grp = threadIdx.x / LPR, c = threadIdx.x % LPR;
+    // the cache of sequence b holds Tb <= T positions (its rows stay T apart); a part past the end leaves an empty record
+    const long long Tb = seq_lens ? static_cast<long long>(seq_lens[b]) : T;
     const long long t0 = part * rows_per_part;
-    const long long t1 = (t0 + rows_per_part < T) ? t0 + rows_per_part : T;
+    const long long t1 = (t0 + rows_per_part < Tb) ? t0 + rows_per_part : Tb;
 
     float qf[8];
     load8(q_last + (static_cast<size_t>(bh) * D + 8 * c), qf);
@@ -300,13 +303,14 @@ __global__ __launch_bounds__(D) void attn_decode_merge_kernel(const float *__res
 
 template <int D, class TIO>
 hipError_t launch_attn_decode_t(int B, int H, int64_t T, const EntropyPlan &plan, float scale, const void *q_last,
-                                const void *k, const void *v, void *o, void *workspace, hipStream_t stream)
+                                const void *k, const void *v, const int32_t *seq_lens, void *o, void *workspace,
+                                hipStream_t stream)
 {
     const int BH = B * H;
     ProfileScope ps(DSLA_KERNEL_ATTENTION_DECODE, stream);
     hipLaunchKernelGGL((attn_decode_kernel<D, TIO>), dim3(static_cast<unsigned>(BH) * plan.parts), dim3(kEntThreads), 0,
                        stream, static_cast<const TIO *>(q_last), static_cast<const TIO *>(k), static_cast<const TIO *>(v),
-                       scale, H, static_cast<long long>(T), plan.parts, static_cast<long long>(plan.rows_per_part),
+                       seq_lens, scale, H, static_cast<long long>(T), plan.parts, static_cast<long long>(plan.rows_per_part),
                        static_cast<float *>(workspace), static_cast<TIO *>(o));
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || plan.parts == 1) return err;
@@ -363,15 +367,15 @@ hipError_t launch_entropy(int B, int H, int d, int64_t T, int io_dtype, const En
 }
 
 hipError_t launch_attn_decode(int B, int H, int d, int64_t T, int io_dtype, const EntropyPlan &plan, float scale,
-                              const void *q_last, const void *k, const void *v, void *o, void *workspace,
-                              hipStream_t stream)
+                              const void *q_last, const void *k, const void *v, const int32_t *seq_lens, void *o,
+                              void *workspace, hipStream_t stream)
 {
     if (io_dtype == DSLA_BF16) {
-        if (d == 128) return launch_attn_decode_t<128, bf16_t>(B, H, T, plan, scale, q_last, k, v, o, workspace, stream);
-        if (d == 64) return launch_attn_decode_t<64, bf16_t>(B, H, T, plan, scale, q_last, k, v, o, workspace, stream);
+        if (d == 128) return launch_attn_decode_t<128, bf16_t>(B, H, T, plan, scale, q_last, k, v, seq_lens, o, workspace, stream);
+        if (d == 64) return launch_attn_decode_t<64, bf16_t>(B, H, T, plan, scale, q_last, k, v, seq_lens, o, workspace, stream);
     } else {
-        if (d == 128) return launch_attn_decode_t<128, float>(B, H, T, plan, scale, q_last, k, v, o, workspace, stream);
-        if (d == 64) return launch_attn_decode_t<64, float>(B, H, T, plan, scale, q_last, k, v, o, workspace, stream);
+        if (d == 128) return launch_attn_decode_t<128, float>(B, H, T, plan, scale, q_last, k, v, seq_lens, o, workspace, stream);
+        if (d == 64) return launch_attn_decode_t<64, float>(B, H, T, plan, scale, q_last, k, v, seq_lens, o, workspace, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -81,8 +81,8 @@ struct EntropyPlan {
 };
 bool entropy_plan(int B, int H, int d, int64_t T, EntropyPlan *plan, int floats_per_part = 3);  // false: head size not built
 hipError_t launch_attn_decode(int B, int H, int d, int64_t T, int io_dtype, const EntropyPlan &plan, float scale,
-                              const void *q_last, const void *k, const void *v, void *o, void *workspace,
-                              hipStream_t stream);
+                              const void *q_last, const void *k, const void *v, const int32_t *seq_lens, void *o,
+                              void *workspace, hipStream_t stream);
 hipError_t launch_entropy(int B, int H, int d, int64_t T, int io_dtype, const EntropyPlan &plan, float scale,
                           const void *q_last, const void *k, float *entropy, void *workspace, hipStream_t stream);
 

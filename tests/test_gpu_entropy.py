@@ -124,3 +124,29 @@ def test_attention_decode_full_size_sampled_heads():
     for b, h in [(b, (7 * b + j) % H) for b in range(B) for j in (1, 20)]:
         ref = ent.attention_decode(q[b:b + 1, h:h + 1], k[b:b + 1, :, h:h + 1], v[b:b + 1, :, h:h + 1], d ** -0.5)[0, 0]
         assert np.all(np.abs(got[b, h] - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * np.max(np.abs(ref))), (b, h)
+
+
+def test_attention_decode_mixed_context_lengths():
+    """Requests of one batch at different context lengths in a cache of T positions each: only the filled positions
+    count (the rest of the cache holds NaN here), also where a whole key range of the split lies past the end."""
+    import torch
+    B, T, H, d = 5, 3000, 2, 128
+    lens = [3000, 1, 700, 1501, 37]
+    q, k = inputs(31, B, T, H, d, "bf16", spread=2.0)
+    v = wl.layer_inputs(33, B, T, H, d, d, io_dtype="bf16", gate_dtype="f32")["v"]
+    kg, vg = to_gpu(k, "bf16"), to_gpu(v, "bf16")
+    for b, L in enumerate(lens):
+        kg[b, L:] = float("nan")
+        vg[b, L:] = float("nan")
+    qg = to_gpu(q, "bf16")
+    o = torch.full_like(qg, float("nan"))
+    n = dsla.dsla_attention_decode_workspace_bytes(B, H, d, T)
+    assert n > 0
+    ws = torch.empty(n, dtype=torch.uint8, device="cuda")
+    dsla.dsla_attention_decode(qg, kg, vg, o, d ** -0.5, ws, seq_lens=torch.tensor(lens, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    got = o.float().cpu().numpy()
+    assert np.all(np.isfinite(got))
+    for b, L in enumerate(lens):
+        ref = ent.attention_decode(q[b:b + 1], k[b:b + 1, :L], v[b:b + 1, :L], d ** -0.5)[0]
+        assert np.all(np.abs(got[b] - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * np.max(np.abs(ref))), (b, L)

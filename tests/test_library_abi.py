@@ -108,8 +108,9 @@ def test_attention_entropy_argument_checks_and_plan(lib):
 
 def test_attention_decode_argument_checks_and_plan(lib):
     fake = ctypes.c_void_p(4096)
-    call = lambda B, H, d, T, io, q=fake, k=fake, v=fake, o=fake, ws=None, n=0: lib.dsla_attention_decode(
-        B, H, d, T, io, 1.0, q, k, v, o, ws, n, None)
+    call = lambda B, H, d, T, io, q=fake, k=fake, v=fake, o=fake, ws=None, n=0, lens=None: lib.dsla_attention_decode(
+        B, H, d, T, io, 1.0, q, k, v, lens, o, ws, n, None)
+    assert call(2, 4, 128, 100, 1, lens=ctypes.c_void_p(4098)) == 2
     assert call(2, 0, 128, 100, 1) == 2
     assert call(2, 4, 100, 100, 1) == 3
     assert call(2, 4, 128, 100, 1, v=None) == 1
