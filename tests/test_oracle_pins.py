@@ -317,7 +317,7 @@ def test_attention_entropy_pins():
     brute-force loop over a tiny case agrees (a missing minus sign, log of the scores instead of the weights, or a
     softmax over the wrong axis fails at least one)."""
     import math
-    from oracle import attention_entropy as ent
+    from oracle import attention as ent
     rng = np.random.default_rng(3)
     B, T, H, d = 2, 37, 3, 8
     k = rng.standard_normal((B, T, H, d))
@@ -361,7 +361,7 @@ def test_attention_decode_pins():
     output is linear in v and a convex combination of the values, a two-key case has a closed form, and a brute-force
     loop agrees (a missing normaliser, a softmax over features, or k and v swapped fails at least one)."""
     import math
-    from oracle import attention_entropy as ent
+    from oracle import attention as ent
     rng = np.random.default_rng(4)
     B, T, H, d = 2, 29, 3, 8
     k = rng.standard_normal((B, T, H, d))
