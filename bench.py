@@ -25,6 +25,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
+EVENT_SHARE = 8                 # kernel events bracket every launch of the first 1/EVENT_SHARE of a timed region
 
 
 def read_traffic(kernel: str):
@@ -98,7 +99,12 @@ def main():
     for _ in range(args.warmup):
         prefill_step()
     torch.cuda.synchronize()
-    dsla.profile_enable(True, 8 * (args.steps + 8))
+    # Kernel durations come from HIP events the library records around its launches, on the launch stream, inside
+    # the timed region.  An event record between two dependent kernels costs a few microseconds of stream time
+    # (21 us per step when every launch is bracketed), so only the launches of the first eighth of the region are
+    # bracketed, all of them: a kernel whose predecessor is not bracketed as well reads 10 us too long.
+    ev_steps = max(1, args.steps // EVENT_SHARE)
+    dsla.profile_enable(True, 4 * ev_steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -134,7 +140,7 @@ def main():
         "config": {"workload": "value = prefill tokens/s of cfg3: B=1 H=32 d_k=d_v=128 T=%d chunk=%d bf16 io, bf16 "
                                "log-gates, fp32 states; step = state_init + prefill; the decode part of the "
                                "metric (cfg4, B=64) is under \"decode\"" % (T, C),
-                   "segments": args.segments, "workspace_bytes": nws},
+                   "segments": args.segments, "kernel_events": "all launches of the first 1/%d of each timed region" % EVENT_SHARE, "workspace_bytes": nws},
         "roofline": roofline,
         "kernel_ms": {k: v for k, v in kern_ms.items() if v is not None},
         "end_to_end_hbm_frac": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -194,7 +200,7 @@ def main():
         decode_steps(64)
         torch.cuda.synchronize()
         nd = args.decode_steps
-        dsla.profile_enable(True, nd + 8)
+        dsla.profile_enable(True, max(1, nd // EVENT_SHARE))
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         decode_steps(nd)
