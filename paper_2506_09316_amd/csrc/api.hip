@@ -164,6 +164,7 @@ dsla_status dsla_prefill_varlen(const dsla_desc *desc, int64_t total_T, int64_t 
         return DSLA_ERR_SHAPE;
     PrefillPlan plan;
     if (!prefill_plan_varlen(*desc, total_T, max_T, &plan)) return DSLA_ERR_UNSUPPORTED;
+    if (plan.max_items * desc->H > 0x7fffffffLL) return DSLA_ERR_SHAPE;   // one workgroup per (segment, head)
     if (plan.ws_total_bytes > 0) {
         if (!workspace || workspace_bytes < plan.ws_total_bytes) return DSLA_ERR_WORKSPACE;
         if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return DSLA_ERR_SHAPE;
