@@ -122,6 +122,7 @@ dsla_status dsla_prefill(const dsla_desc *desc, int64_t T, const void *q, const 
     if (T > (int64_t(1) << 40)) return DSLA_ERR_SHAPE;
     PrefillPlan plan;
     if (!prefill_plan(*desc, T, &plan)) return DSLA_ERR_UNSUPPORTED;
+    if (static_cast<int64_t>(desc->B) * desc->H * plan.segments > 0x7fffffffLL) return DSLA_ERR_SHAPE;
     if (plan.ws_total_bytes > 0) {
         if (!workspace || workspace_bytes < plan.ws_total_bytes) return DSLA_ERR_WORKSPACE;
         if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return DSLA_ERR_SHAPE;
