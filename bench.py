@@ -26,6 +26,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 EVENT_SHARE = 8                 # kernel events bracket every launch of the first 1/EVENT_SHARE of a timed region
+EVENT_MIN_STEPS = 8             # ... and of at least this many steps
+SETTLE_SECONDS = 0.5            # untimed steps before --warmup
 
 
 def read_traffic(kernel: str):
@@ -62,7 +64,7 @@ def main():
     import numpy as np
     import torch
     import paper_2506_09316_amd as dsla
-    from paper_2506_09316_amd import workloads as wl
+    import workloads as wl
     from paper_2506_09316_amd.binding import DSLA_BF16
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
@@ -96,6 +98,14 @@ def main():
         dsla.dsla_state_init(desc, S1, S2)
         dsla.dsla_prefill(desc, T, xg["q"], xg["k"], xg["v"], xg["g1"], xg["g2"], S1, S2, o, ws if nws else None)
 
+    # Settle phase, fixed and untimed, before the caller's warm-up: the first launches after start-up run slower
+    # (clocks ramp up, code objects and page tables are touched for the first time), so a short --warmup alone
+    # would time that transient instead of the steady state.
+    t_settle = time.perf_counter()
+    while time.perf_counter() - t_settle < SETTLE_SECONDS:
+        for _ in range(20):
+            prefill_step()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         prefill_step()
     torch.cuda.synchronize()
@@ -103,7 +113,7 @@ def main():
     # the timed region.  An event record between two dependent kernels costs a few microseconds of stream time
     # (21 us per step when every launch is bracketed), so only the launches of the first eighth of the region are
     # bracketed, all of them: a kernel whose predecessor is not bracketed as well reads 10 us too long.
-    ev_steps = max(1, args.steps // EVENT_SHARE)
+    ev_steps = min(args.steps, max(EVENT_MIN_STEPS, args.steps // EVENT_SHARE))
     dsla.profile_enable(True, 4 * ev_steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -126,6 +136,7 @@ def main():
         "kernel": "prefill_chunk_loop", "bound": "hbm",
         "achieved": alg_bytes / (loop_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "traffic": read_traffic("prefill_chunk_loop"),
+        "traffic_source": "profiles/hbm_traffic.txt (rocprofv3 --pmc runs of this command, recorded; not measured in this run)",
         "avg_kernel_ms": loop_ms,
         "mfma_tflops_algorithmic": alg_flops / (loop_ms * 1e-3) / 1e12,
         "mfma_frac_of_bf16_peak": alg_flops / (loop_ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
@@ -145,6 +156,17 @@ def main():
         "kernel_ms": {k: v for k, v in kern_ms.items() if v is not None},
         "end_to_end_hbm_frac": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
     }
+
+    # all kernels of a step against the HBM roofline: algorithmic bytes over the sum of their durations
+    step_kernel_ms = sum(v for v in kern_ms.values() if v is not None)
+    out["step_roofline"] = {"bound": "hbm", "kernels": sorted(k for k, v in kern_ms.items() if v is not None),
+                            "achieved": alg_bytes / (step_kernel_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                            "frac": alg_bytes / (step_kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                            "sum_kernel_ms": step_kernel_ms}
+    # results of the last timed step, kept for the comparison with the oracle below
+    got = None
+    if not args.no_cpu_baseline:
+        got = (o.float().cpu().numpy(), S1.cpu().numpy(), S2.cpu().numpy())
 
     # ------------------------------------------------------------------ batched decode
     del xg, o, ws
@@ -216,7 +238,9 @@ def main():
             "roofline": {"kernel": "decode", "bound": "hbm", "achieved": dec_bytes / (dec_ms * 1e-3) / 1e9,
                          "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": dec_bytes / (dec_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                         "traffic": read_traffic("decode"), "avg_kernel_ms": dec_ms},
+                         "traffic": read_traffic("decode"),
+                         "traffic_source": "profiles/hbm_traffic.txt (recorded, not measured in this run)",
+                         "avg_kernel_ms": dec_ms},
             "batched_prefill_B64_T2048_ms": batched_prefill_ms,
             "batched_prefill_tokens_per_s": Bd * Tp / (batched_prefill_ms * 1e-3),
         }
@@ -228,8 +252,20 @@ def main():
         Ts = min(T, 16384)
         xs = {n: a[:, :Ts] for n, a in x.items()}
         t0 = time.perf_counter()
-        orc.recurrent(xs["q"], xs["k"], xs["v"], xs["g1"], xs["g2"], 0.5)
+        ro, rS1, rS2 = orc.recurrent(xs["q"], xs["k"], xs["v"], xs["g1"], xs["g2"], 0.5)
         dt = time.perf_counter() - t0
+        # the timed steps' own results against the oracle (every head, every token it covered)
+        def rel(a, b):
+            return float(np.max(np.abs(a - b)) / np.max(np.abs(b)))
+        out["check_vs_oracle"] = {"o_max_rel_err": rel(got[0][:, :Ts], ro), "tolerance": 2e-2,
+                                  "tokens": Ts, "heads": H}
+        if Ts == T:
+            out["check_vs_oracle"].update(S1_max_rel_err=rel(got[1], rS1), S2_max_rel_err=rel(got[2], rS2))
+        bad = [k for k, v in out["check_vs_oracle"].items() if k.endswith("rel_err") and not v <= 2e-2]
+        if bad:
+            print(json.dumps(out), flush=True)
+            sys.exit("bench.py: results of the timed steps disagree with the oracle: %s" % bad)
+        del got, ro
         out["cpu_baseline"] = {"value": B * Ts / dt, "unit": "tokens/s", "cores": orc.threads(), "kind": "oracle",
                                "sample": "prefill workload, first %d tokens of the same inputs, all %d heads, "
                                          "fp64 token-by-token recurrence, %.1f s" % (Ts, H, dt)}

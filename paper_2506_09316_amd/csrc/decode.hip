@@ -8,33 +8,14 @@
 // (one 16-byte access) in every ROWG-th row, so a wavefront access covers whole rows and is
 // fully coalesced.  All state loads are issued before anything else so that the maximum
 // number of bytes is in flight; the small per-token vectors go through LDS meanwhile.
-#include <cstdlib>
-
 #include "dsla_internal.h"
 
 namespace dsla {
 namespace {
 
 constexpr int kDecodeThreads = 256;
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ float4 load_f4(const float4 *p, bool nt)
-{
-    const f32x4 *q = reinterpret_cast<const f32x4 *>(p);
-    const f32x4 x = nt ? __builtin_nontemporal_load(q) : *q;
-    return make_float4(x[0], x[1], x[2], x[3]);
-}
-__device__ __forceinline__ void store_f4(float4 *p, const float4 &v, bool nt)
-{
-    f32x4 *q = reinterpret_cast<f32x4 *>(p);
-    const f32x4 x = {v.x, v.y, v.z, v.w};
-    if (nt)
-        __builtin_nontemporal_store(x, q);
-    else
-        *q = x;
-}
-
-template <int DK, int DV, int SPLIT, bool NT, class TIO, class TG>
+template <int DK, int DV, int SPLIT, class TIO, class TG>
 __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
     const TIO *__restrict__ q, const TIO *__restrict__ k, const TIO *__restrict__ v, const TG *__restrict__ g1,
     const TG *__restrict__ g2, const int32_t *__restrict__ row, const int32_t *__restrict__ slot,
@@ -65,8 +46,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
         const int row = rg + j * ROWG;
-        a[j] = load_f4(&p1[static_cast<size_t>(row) * ROWF4], NT);
-        b[j] = load_f4(&p2[static_cast<size_t>(row) * ROWF4], NT);
+        a[j] = p1[static_cast<size_t>(row) * ROWF4];
+        b[j] = p2[static_cast<size_t>(row) * ROWF4];
     }
 
     // 2. per-token vectors -> LDS (gates exponentiated once per row)
@@ -101,8 +82,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
         x.z = fmaf(a1, x.z, kd * v2); x.w = fmaf(a1, x.w, kd * v3);
         y.x = fmaf(a2, y.x, kd * v0); y.y = fmaf(a2, y.y, kd * v1);
         y.z = fmaf(a2, y.z, kd * v2); y.w = fmaf(a2, y.w, kd * v3);
-        store_f4(&p1[static_cast<size_t>(row) * ROWF4], x, NT);
-        store_f4(&p2[static_cast<size_t>(row) * ROWF4], y, NT);
+        p1[static_cast<size_t>(row) * ROWF4] = x;
+        p2[static_cast<size_t>(row) * ROWF4] = y;
         const float qa = qd * gm, qb = qd * gm2;
         acc.x = fmaf(qa, x.x, fmaf(qb, y.x, acc.x));
         acc.y = fmaf(qa, x.y, fmaf(qb, y.y, acc.y));
@@ -146,57 +127,22 @@ __global__ __launch_bounds__(256) void state_init_kernel(float4 *__restrict__ S1
     }
 }
 
-// Development switch (environment variable DSLA_DECODE_VARIANT, read once): column split and
-// non-temporal hint of the decode kernel.  Default "2x": two workgroups per (batch, head) (measured
-// fastest on MI355X: 5.07 TB/s against 4.80 with one and 4.91 with four; the hint makes no difference).
-struct DecodeVariant {
-    int split;
-    bool nt;
-};
-inline DecodeVariant decode_variant()
-{
-    static const DecodeVariant v = [] {
-        DecodeVariant d{2, false};
-        if (const char *e = getenv("DSLA_DECODE_VARIANT")) {
-            if (e[0] == '1' || e[0] == '2' || e[0] == '4') d.split = e[0] - '0';
-            d.nt = (e[1] == 'n');
-        }
-        return d;
-    }();
-    return v;
-}
-
-template <int D, int SPLIT, bool NT, class TIO, class TG>
-hipError_t launch_decode_v(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
-                           const void *g2, const int32_t *row, const int32_t *slot, float *S1, float *S2, void *o,
-                           hipStream_t stream)
-{
-    const unsigned grid = static_cast<unsigned>(d.B) * static_cast<unsigned>(d.H) * SPLIT;
-    ProfileScope ps(DSLA_KERNEL_DECODE, stream);
-    hipLaunchKernelGGL((decode_kernel<D, D, SPLIT, NT, TIO, TG>), dim3(grid), dim3(kDecodeThreads), 0, stream,
-                       static_cast<const TIO *>(q), static_cast<const TIO *>(k), static_cast<const TIO *>(v),
-                       static_cast<const TG *>(g1), static_cast<const TG *>(g2), row, slot, S1, S2, static_cast<TIO *>(o), d.H,
-                       d.gamma, d.gamma_per_head, d.scale, d.gate_mode == DSLA_GATE_PREACT ? 1.0f / d.tau : 0.f);
-    return hipGetLastError();
-}
+// Two workgroups per (batch, head), each one half of the columns: measured fastest on MI355X (5.07 TB/s against
+// 4.80 with one workgroup and 4.91 with four; non-temporal hints make no difference).
+constexpr int kDecodeSplit = 2;
 
 template <int D, class TIO, class TG>
 hipError_t launch_decode_t(const dsla_desc &d, const void *q, const void *k, const void *v, const void *g1,
                            const void *g2, const int32_t *row, const int32_t *slot, float *S1, float *S2, void *o,
                            hipStream_t stream)
 {
-    const DecodeVariant var = decode_variant();
-#define DSLA_DECODE_CASE(SP, N)                                                                          \
-    if (var.split == SP && var.nt == N)                                                                  \
-        return launch_decode_v<D, SP, N, TIO, TG>(d, q, k, v, g1, g2, row, slot, S1, S2, o, stream)
-    DSLA_DECODE_CASE(1, false);
-    DSLA_DECODE_CASE(1, true);
-    DSLA_DECODE_CASE(2, false);
-    DSLA_DECODE_CASE(2, true);
-    DSLA_DECODE_CASE(4, false);
-    DSLA_DECODE_CASE(4, true);
-#undef DSLA_DECODE_CASE
-    return hipErrorInvalidValue;
+    const unsigned grid = static_cast<unsigned>(d.B) * static_cast<unsigned>(d.H) * kDecodeSplit;
+    ProfileScope ps(DSLA_KERNEL_DECODE, stream);
+    hipLaunchKernelGGL((decode_kernel<D, D, kDecodeSplit, TIO, TG>), dim3(grid), dim3(kDecodeThreads), 0, stream,
+                       static_cast<const TIO *>(q), static_cast<const TIO *>(k), static_cast<const TIO *>(v),
+                       static_cast<const TG *>(g1), static_cast<const TG *>(g2), row, slot, S1, S2, static_cast<TIO *>(o), d.H,
+                       d.gamma, d.gamma_per_head, d.scale, d.gate_mode == DSLA_GATE_PREACT ? 1.0f / d.tau : 0.f);
+    return hipGetLastError();
 }
 
 template <int D>

@@ -49,36 +49,6 @@ __device__ __forceinline__ void lds_barrier()
     __builtin_amdgcn_sched_barrier(0);
 }
 
-// Development aid, compiled out unless DSLA_PHASE_CLOCKS is defined: one lane of workgroup 0 adds up the
-// shader clock spent between phase marks and the launcher prints the totals.
-#ifdef DSLA_PHASE_CLOCKS
-struct PhaseClock {
-    long long acc[12];
-    long long last;
-    __device__ __forceinline__ void start()
-    {
-        for (int n = 0; n < 12; ++n) acc[n] = 0;
-        last = __builtin_amdgcn_s_memtime();
-    }
-    __device__ __forceinline__ void mark(int n)
-    {
-        const long long now = __builtin_amdgcn_s_memtime();
-        acc[n] += now - last;
-        last = now;
-    }
-    __device__ __forceinline__ void flush(long long *dbg) const
-    {
-        if (blockIdx.x == 0 && (threadIdx.x & 63) == 0 && dbg)
-            for (int n = 0; n < 12; ++n) dbg[(threadIdx.x >> 6) * 12 + n] = acc[n];
-    }
-};
-#else
-struct PhaseClock {
-    __device__ __forceinline__ void start() {}
-    __device__ __forceinline__ void mark(int) {}
-};
-#endif
-
 // ---------------------------------------------------------------------------------------------
 // LDS access by byte address.  Every LDS address below is "per-lane base register + compile-time
 // constant"; the bases are computed once and passed through opaque() so that the compiler keeps them
@@ -421,9 +391,6 @@ struct PrefillArgs {
     int chunk_steps;         // 32-token steps per chunk
     float gamma, scale;
     float gate_inv_tau;      // 0: g1, g2 are log-gates; else they are pre-activations and this is 1 / tau
-#ifdef DSLA_PHASE_CLOCKS
-    long long *dbg;
-#endif
 };
 
 // Workgroup layout: producer / consumer wavefronts.  4 D threads = D/8 wavefronts.  The first D/32
@@ -703,9 +670,8 @@ struct Kern {
     static __device__ __forceinline__ void produce(const ProdAddr &pa, uint32_t set, RawIO &r, const ScanOut &sc, int valid,
                                                    RawGates &gn, ScanOut &sn, int valid_n, uint32_t close_n,
                                                    const float (&lg)[2], const uint32_t (&sgn)[2], float &carry,
-                                                   float &seg_log2_decay, float &decf, const Loads &next, PhaseClock &clk)
+                                                   float &seg_log2_decay, float &decf, const Loads &next)
     {
-        clk.mark(0);
         const uint32_t so = set * SET_BYTES;
         // decay from the start of the chunk to the end of this step; the consumers apply it when the chunk ends here
         lds_st<float>(pa.dec + so, decf);
@@ -720,7 +686,6 @@ struct Kern {
         scan_a(pa, gn, valid_n, sn);
         next.at(0);
         next.at(1);
-        clk.mark(7);
 
         Row8 kt[RPT];
         auto block = [&](int i, int j, int slot_k, int slot_q) {
@@ -754,23 +719,16 @@ struct Kern {
         float t[SGN];
         scan_b_read(pa, t);   // the answers arrive while the first block is computed
         block(0, 0, 2, 3);
-        clk.mark(8);
         scan_b(pa, t, valid_n, close_n, carry, seg_log2_decay, decf);
-        clk.mark(6);
         block(0, 1, 4, 5);
-        clk.mark(9);
         kt_rows(0);
         scan_c(pa, sn);
-        clk.mark(1);
         block(1, 0, 6, 7);
-        clk.mark(10);
         block(1, 1, 8, 9);
-        clk.mark(11);
         kt_rows(1);
         // V transposed
 #pragma unroll
         for (int e = 0; e < 8; ++e) store_v_tokens<RPT>(pa.vt[(e >> 1) & 3] + so + e * TP * ESZ, r.v, e);
-        clk.mark(2);
     }
 
     // ------------------------------------------------------------------------------------------------------
@@ -796,9 +754,8 @@ struct Kern {
 
     static __device__ __forceinline__ void consume(uint32_t sm, uint32_t set, f32x16 (&acc)[2][DT], int ct, int lane,
                                                    TIO *orow, uint32_t rs, int valid, uint32_t close_mask,
-                                                   uint32_t set_parity, PhaseClock &clk)
+                                                   uint32_t set_parity)
     {
-        clk.mark(0);
         const uint32_t lo = opaque(static_cast<uint32_t>(lane));
         const uint32_t ln = lo & 31, g = lo >> 5;
         const uint32_t setb = sm + set * SET_BYTES;
@@ -838,7 +795,6 @@ struct Kern {
                         }
                     });
             }
-            clk.mark(2);
             // keep key <= query; the two halves of the tile become the score fragments of the two token blocks
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
@@ -848,7 +804,6 @@ struct Kern {
 #pragma unroll
             for (int kb = 0; kb < KB; ++kb) A::mma(oacc, vf[kb], A::from_acc(sc, kb));
         }
-        clk.mark(3);
         __builtin_amdgcn_sched_barrier(0);   // the instruction groups requested below start here
 
         // ---- add K~^T V (the output tile finishes in the matrix pipeline meanwhile) ----
@@ -872,7 +827,6 @@ struct Kern {
             }
             __builtin_amdgcn_sched_group_barrier(0x008, 4 * MM, 0);
         }
-        clk.mark(4);
 
         // ---- store: lane (ln, g) holds query ln, columns 32 ct + 8 jb + 4 g .. + 3 ----
         if constexpr (kStage) {
@@ -911,7 +865,6 @@ struct Kern {
                             for (int e = 0; e < 4; ++e) acc[i][dt2 + t][4 * jb + e] *= dd[t][jb][e];
                 }
             }
-        clk.mark(1);
     }
 
     static __device__ void run(const PrefillArgs &a, uint32_t sm)
@@ -919,11 +872,6 @@ struct Kern {
         const int tid = threadIdx.x;
         const int lane = tid & 63;
         const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wavefront-uniform, kept in scalar registers
-        PhaseClock clk;
-        clk.start();
-#ifdef DSLA_PHASE_CLOCKS
-        const long long wg_rt0 = __builtin_amdgcn_s_memrealtime(), wg_c0 = __builtin_amdgcn_s_memtime();
-#endif
 
         int bidx, h, p;
         size_t slot0;   // workspace slot of (segment 0, this sequence, this head); segment p' is p' * slot_step further
@@ -982,9 +930,12 @@ struct Kern {
             if (kFull) {
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
-                    // the first segment starts from the caller's states, a later one from what the segment scan left
-                    const float *src = (p > 0) ? a.ws_state + ((slot0 + p * slot_step) * 2 + i) * D * D
-                                                 : (i ? a.S2 : a.S1) + sbh * D * D;
+                    // A sequence that is cut into segments starts every segment, the first one included, from the
+                    // slot the segment scan filled: the workgroup of the last segment overwrites the caller's states
+                    // in this same launch, so no workgroup of such a sequence may read them here.  A sequence of one
+                    // segment reads the caller's states itself (it is also the only one that writes them).
+                    const float *src = (Tb > a.seg_tokens) ? a.ws_state + ((slot0 + p * slot_step) * 2 + i) * D * D
+                                                           : (i ? a.S2 : a.S1) + sbh * D * D;
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -1002,13 +953,13 @@ struct Kern {
             lds_barrier();   // operands of step 0 are ready
             for (int n = 0; n < nsteps; n += 2) {
                 if (kStage && n > 0) flush_rows(sm, 1, ct, lane, orow - sstep, rs, S);
-                consume(sm, 0, acc, ct, lane, orow, rs, valid_of(n), closes(n), 0, clk);
+                consume(sm, 0, acc, ct, lane, orow, rs, valid_of(n), closes(n), 0);
                 orow += sstep;
                 lds_barrier();                    // step n consumed (two sets: and step n+1 ready)
                 if (SETS == 1) lds_barrier();     // one set: step n+1 ready
                 if (n + 1 < nsteps) {
                     if (kStage) flush_rows(sm, 0, ct, lane, orow - sstep, rs, S);
-                    consume(sm, SETS - 1, acc, ct, lane, orow, rs, valid_of(n + 1), closes(n + 1), 1, clk);
+                    consume(sm, SETS - 1, acc, ct, lane, orow, rs, valid_of(n + 1), closes(n + 1), 1);
                     orow += sstep;
                 }
                 lds_barrier();
@@ -1016,18 +967,6 @@ struct Kern {
             }
             // the last step (every staged row has passed a barrier)
             if (kStage) flush_rows(sm, (nsteps - 1) & 1, ct, lane, orow - sstep, rs, valid_of(nsteps - 1));
-#ifdef DSLA_PHASE_CLOCKS
-            clk.flush(a.dbg);
-            if (tid == 0 && kFull && a.dbg) {
-                long long *w = a.dbg + 16 * 12 + 4 * blockIdx.x;
-                w[0] = wg_rt0;
-                w[1] = __builtin_amdgcn_s_memrealtime();
-                w[2] = __builtin_amdgcn_s_memtime() - wg_c0;
-                uint32_t xcc;
-                asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-                w[3] = xcc & 0xf;
-            }
-#endif
             // ---- write the states out ----
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
@@ -1099,31 +1038,26 @@ struct Kern {
             {
                 const StepSrc io = src_of(1), gs = src_of(3);
                 produce(pa, 0, r0, s0, valid_of(0), g1, s1, valid_of(1), closes(1), lg, sgn, carry, seg_decay,
-                        decf, NextLoads{r1, io, g1, gs}, clk);
+                        decf, NextLoads{r1, io, g1, gs});
             }
             lds_barrier();   // operands of step 0 are ready
             for (int n = 0; n < nsteps; n += 2) {
                 // consumers work on step n from set 0: prepare step n+1 into set 1
                 if (SETS == 1) lds_barrier();     // one set: wait until step n is consumed
-                clk.mark(5);
                 {
                     const StepSrc io = src_of(n + 2), gs = src_of(n + 4);
                     produce(pa, SETS - 1, r1, s1, valid_of(n + 1), g0, s0, valid_of(n + 2), closes(n + 2), lg,
-                            sgn, carry, seg_decay, decf, NextLoads{r0, io, g0, gs}, clk);
+                            sgn, carry, seg_decay, decf, NextLoads{r0, io, g0, gs});
                 }
                 lds_barrier();
                 if (SETS == 1) lds_barrier();
-                clk.mark(5);
                 {
                     const StepSrc io = src_of(n + 3), gs = src_of(n + 5);
                     produce(pa, 0, r0, s0, valid_of(n + 2), g1, s1, valid_of(n + 3), closes(n + 3), lg, sgn,
-                            carry, seg_decay, decf, NextLoads{r1, io, g1, gs}, clk);
+                            carry, seg_decay, decf, NextLoads{r1, io, g1, gs});
                 }
                 lds_barrier();
             }
-#ifdef DSLA_PHASE_CLOCKS
-            clk.flush(a.dbg);
-#endif
             if (!kFull) {
                 // log2 decay of segment p goes to decay slot p
                 a.ws_decay[(slot0 + p * slot_step) * 2 * D + (lane >> 5) * D + 32 * pw + (lane & 31)] = seg_decay;
@@ -1195,8 +1129,9 @@ __global__ __launch_bounds__(256) void segment_list_kernel(const int32_t *__rest
     }
 }
 
-// Elementwise scan over the segments of every (sequence, head): s_0 = caller's state; s_{p+1} = 2^{decay_p} s_p + U_p
-// goes to the slot of segment p+1, where the segment_state kernel had left U_p.  (The slot of segment 0 is not used.)
+// Elementwise scan over the segments of every (sequence, head) that has more than one: s_0 = caller's state goes to
+// the slot of segment 0; s_{p+1} = 2^{decay_p} s_p + U_p goes to the slot of segment p+1, where the segment_state
+// kernel had left U_p.  The chunk loop then takes every initial state of such a sequence from the slots.
 template <int D>
 __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restrict__ S1, const float *__restrict__ S2,
                                                            float *__restrict__ ws_state,
@@ -1232,6 +1167,8 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restri
     const float *src = (i ? S2 : S1) + (sbh * D + row) * D + c4 * 4;
     float4 s = *reinterpret_cast<const float4 *>(src);
     const size_t in_slot = (static_cast<size_t>(i) * D + row) * D + c4 * 4;   // this thread's place inside a slot
+    if (P <= 1) return;
+    *reinterpret_cast<float4 *>(ws_state + slot0 * 2 * D * D + in_slot) = s;
     for (int p = 0; p + 1 < P; ++p) {
         const float dec = __builtin_amdgcn_exp2f(ws_decay[(slot0 + p * slot_step) * 2 * D + i * D + row]);
         float4 *u = reinterpret_cast<float4 *>(ws_state + (slot0 + (p + 1) * slot_step) * 2 * D * D + in_slot);
@@ -1244,36 +1181,6 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restri
     }
 }
 
-#ifdef DSLA_PHASE_CLOCKS
-long long *clock_buffer(hipStream_t stream)
-{
-    static long long *dbg = nullptr;
-    if (!dbg) (void)hipMalloc(&dbg, (16 * 12 + 4 * 2048) * sizeof(long long));
-    (void)hipMemsetAsync(dbg, 0, (16 * 12 + 4 * 2048) * sizeof(long long), stream);
-    return dbg;
-}
-void clock_print(const char *what, const long long *dbg, int waves, hipStream_t stream, int nwg = 0)
-{
-    static long long h[16 * 12 + 4 * 2048];
-    (void)hipStreamSynchronize(stream);
-    (void)hipMemcpy(h, dbg, sizeof(h), hipMemcpyDeviceToHost);
-    if (nwg > 0 && nwg <= 2048) {
-        long long t0 = h[16 * 12];
-        for (int w = 0; w < nwg; ++w) t0 = h[16 * 12 + 4 * w] < t0 ? h[16 * 12 + 4 * w] : t0;
-        fprintf(stderr, "[%s workgroups] start/end in 10ns units after the first start, duration in shader clocks\n", what);
-        for (int w = 0; w < nwg; ++w)
-            fprintf(stderr, "  wg %4d xcc %lld: %6lld .. %6lld  clocks %lld\n", w, h[16 * 12 + 4 * w + 3], h[16 * 12 + 4 * w] - t0,
-                    h[16 * 12 + 4 * w + 1] - t0, h[16 * 12 + 4 * w + 2]);
-    }
-    for (int w = 0; w < waves; ++w) {
-        long long tot = 0;
-        for (int n = 0; n < 12; ++n) tot += h[w * 12 + n];
-        fprintf(stderr, "[%s clocks] wave %d total %lld:", what, w, tot);
-        for (int n = 0; n < 12; ++n) fprintf(stderr, " %d=%lld", n, h[w * 12 + n]);
-        fprintf(stderr, "\n");
-    }
-}
-#endif
 
 template <int D, class TIO, class TG>
 hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a, hipStream_t stream)
@@ -1286,9 +1193,6 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
                                            : static_cast<unsigned>(BH * plan.segments);
     hipError_t err = hipSuccess;
     if (plan.segments > 1) {
-#ifdef DSLA_PHASE_CLOCKS
-        a.dbg = clock_buffer(stream);
-#endif
         if (a.list_full) {
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_LIST, stream);
             hipLaunchKernelGGL(segment_list_kernel, dim3(1), dim3(256), 0, stream, a.cu, a.seq, d.B, a.seg_tokens,
@@ -1304,9 +1208,6 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
             err = hipGetLastError();
         }
         if (err != hipSuccess) return err;
-#ifdef DSLA_PHASE_CLOCKS
-        clock_print("segment_state", a.dbg, D / 8, stream);
-#endif
         {
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_SCAN, stream);
             const size_t n4 = static_cast<size_t>(BH) * 2 * D * (D / 4);
@@ -1317,17 +1218,11 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
         }
         if (err != hipSuccess) return err;
     }
-#ifdef DSLA_PHASE_CLOCKS
-    a.dbg = clock_buffer(stream);
-#endif
     {
         ProfileScope ps(DSLA_KERNEL_PREFILL_CHUNK_LOOP, stream);
         hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, true>), dim3(grid_full), dim3(4 * D), 0, stream, a);
     }
     err = hipGetLastError();
-#ifdef DSLA_PHASE_CLOCKS
-    clock_print("chunk_loop", a.dbg, D / 8, stream, static_cast<int>(grid_full));
-#endif
     return err;
 }
 

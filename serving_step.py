@@ -1,9 +1,9 @@
 """The attention layers of a hybrid serving step, as a usage example and a measurement:
 
-    python -m paper_2506_09316_amd.serving_step [--layers 16 --B 8 --T 8192 --decode 128]
-    python -m paper_2506_09316_amd.serving_step --packed {equal,pow2,serving,one_long}
-    python -m paper_2506_09316_amd.serving_step --entropy [--B 8 --T 8192]
-    python -m paper_2506_09316_amd.serving_step --attention-decode [--B 8 --T 8192]
+    python serving_step.py [--layers 16 --B 8 --T 8192 --decode 128]
+    python serving_step.py --packed {equal,pow2,serving,one_long}
+    python serving_step.py --entropy [--B 8 --T 8192]
+    python serving_step.py --attention-decode [--B 8 --T 8192]
 
 L layer instances (each with its own blend coefficient and its own pair of states per sequence) prefill a
 prompt of T tokens for B sequences and then decode token by token.  The decode step of all layers is captured
@@ -18,6 +18,10 @@ from __future__ import annotations
 
 import argparse
 import json
+import os
+import sys
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 
 # Mixed-length prompt batches for --packed (tokens per request; Llama-2-7B head shape).

@@ -8,7 +8,7 @@ import pytest
 
 import paper_2506_09316_amd as dsla
 from oracle import attention as ent
-from paper_2506_09316_amd import workloads as wl
+import workloads as wl
 from tests.util import max_rel_err, to_gpu
 
 pytestmark = pytest.mark.gpu

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 import paper_2506_09316_amd as dsla
-from paper_2506_09316_amd import workloads as wl
+import workloads as wl
 from tests.util import code, to_gpu
 
 pytestmark = pytest.mark.gpu

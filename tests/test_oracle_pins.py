@@ -143,6 +143,51 @@ def test_recurrence_equals_unrolled_form():
         np.testing.assert_allclose(o, ou, rtol=1e-11, atol=1e-12)
 
 
+def chunked_form(q, k, v, g1, g2, gamma, scale, C, S1, S2):
+    """The recurrence of Section 4.1 regrouped C tokens at a time (test-side, numpy fp64, one (batch, head) pair):
+    with b^i_r the sum of the log-gates of state i from the first token of the chunk up to token r,
+        o_r  = scale * [ sum_i gamma_i (q_r * e^{b^i_r}) S^i  +  sum_{s <= r} w_{r,s} v_s ],
+        w_rs = sum_d q_r[d] k_s[d] (gamma e^{b^1_r[d] - b^1_s[d]} + (1 - gamma) e^{b^2_r[d] - b^2_s[d]}),
+        S^i <- diag(e^{b^i_C}) S^i + sum_s (k_s * e^{b^i_C - b^i_s})^T v_s,
+    gamma_1 = gamma, gamma_2 = 1 - gamma.  q, k, g: [T, dk]; v: [T, dv]; S: [dk, dv]."""
+    T = q.shape[0]
+    S = [np.array(S1, dtype=np.float64), np.array(S2, dtype=np.float64)]
+    gam = (gamma, 1.0 - gamma)
+    o = np.zeros((T, v.shape[1]))
+    for c0 in range(0, T, C):
+        c1 = min(c0 + C, T)
+        qc, kc, vc = q[c0:c1], k[c0:c1], v[c0:c1]
+        w = np.zeros((c1 - c0, c1 - c0))
+        carried = np.zeros((c1 - c0, v.shape[1]))
+        for i, g in enumerate((g1, g2)):
+            b = np.cumsum(g[c0:c1], axis=0)                                   # [r, d]
+            carried += gam[i] * (qc * np.exp(b)) @ S[i]
+            pair = np.exp(np.clip(b[:, None, :] - b[None, :, :], None, 0.0))  # [r, s, d]; only s <= r is used
+            w += gam[i] * np.einsum("rd,sd,rsd->rs", qc, kc, pair)
+            S[i] = np.exp(b[-1])[:, None] * S[i] + (kc * np.exp(b[-1][None, :] - b)).T @ vc
+        o[c0:c1] = scale * (carried + np.tril(w) @ vc)
+    return o, S[0], S[1]
+
+
+@pytest.mark.parametrize("strong", [False, True])
+def test_chunked_form_equals_recurrence(strong):
+    """The chunked evaluation a prefill uses reaches the token-by-token recurrence for every chunk length,
+    also when the length does not divide the sequence, with carried-in states."""
+    B, T, H, dk, dv = 1, 150, 2, 6, 5
+    q, k, v, g1, g2 = rand_case(900 + strong, B, T, H, dk, dv, strong=strong)
+    S1 = rnd(911, B, H, dk, dv)
+    S2 = rnd(912, B, H, dk, dv)
+    for gamma, scale in ((0.3, 1.0), (1.4, -0.7)):
+        ro, rS1, rS2 = orc.recurrent(q, k, v, g1, g2, gamma, scale, S1=S1, S2=S2)
+        for C in (1, 2, 16, 64, 128, T, 7, 37):
+            for h in range(H):
+                o, s1, s2 = chunked_form(q[0, :, h], k[0, :, h], v[0, :, h], g1[0, :, h], g2[0, :, h], gamma, scale, C,
+                                         S1[0, h], S2[0, h])
+                np.testing.assert_allclose(o, ro[0, :, h], rtol=1e-11, atol=1e-11, err_msg=f"C={C}")
+                np.testing.assert_allclose(s1, rS1[0, h], rtol=1e-11, atol=1e-11, err_msg=f"C={C}")
+                np.testing.assert_allclose(s2, rS2[0, h], rtol=1e-11, atol=1e-11, err_msg=f"C={C}")
+
+
 def test_brute_force_python_loops_tiny():
     """Quadruple loop over (t, s, d, j) with explicit gate products, tiny sizes."""
     q, k, v, g1, g2 = rand_case(300, B=1, T=6, H=1, dk=3, dv=2, strong=True)

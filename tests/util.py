@@ -14,6 +14,28 @@ def max_rel_err(x, ref):
     return float(np.max(np.abs(x - ref)) / (den if den > 0 else 1.0))
 
 
+def row_rel_err(x, ref, floor=1e-3):
+    """The error at the scale of each output row: max over rows (vectors along the last axis) of
+    max|x - ref| over the row / max(max|ref| over the row, floor * max|ref| over the tensor).  A quiet row (early
+    tokens, a strongly decayed state row) is held to its own magnitude, not to the loudest row of the tensor."""
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    top = np.max(np.abs(ref))
+    den = np.maximum(np.max(np.abs(ref), axis=-1), floor * (top if top > 0 else 1.0))
+    return float(np.max(np.max(np.abs(x - ref), axis=-1) / den))
+
+
+def elem_rel_err(x, ref, floor=1e-3):
+    """Element-wise relative error with a floor: max_i |x_i - ref_i| / max(|ref_i|, floor * max|ref|).
+    An element that is small because large terms cancel carries the rounding error of those terms, so in bf16
+    this number is not bounded by the operand precision; it is reported, and asserted only in fp32."""
+    x = np.asarray(x, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    top = np.max(np.abs(ref))
+    den = np.maximum(np.abs(ref), floor * (top if top > 0 else 1.0))
+    return float(np.max(np.abs(x - ref) / den))
+
+
 def to_gpu(a, dtype):
     import torch
     t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
