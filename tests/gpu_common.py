@@ -2,8 +2,8 @@
 
 Tolerances (written here once).  Norm of the stated tolerances: max |x - ref| / max |ref| per output tensor;
   fp32 I/O : 1e-4          bf16 I/O : 2e-2 against the fp64 oracle fed the same bf16-rounded inputs.
-Beside it every comparison holds each output row (the vector along the last axis) to the same tolerance at the
-row's own scale (row_rel_err), and reports the element-wise relative error with a floor of 1e-3 of the tensor
+Beside it every comparison holds each output row (the vector along the last axis) to ROW_TOL at the row's own
+scale (row_rel_err), and reports the element-wise relative error with a floor of 1e-3 of the tensor
 maximum; that last number is asserted in fp32 only (ELEM_TOL): in bf16 an element that is small because large terms
 cancel carries the rounding error of those terms and no operand precision bounds it.
 """
@@ -14,6 +14,11 @@ import workloads as wl
 from tests.util import GpuLayer, elem_rel_err, max_rel_err, row_rel_err
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
+# Per-row tolerance: the stated one in fp32.  In bf16 the rounding error of an element is set by the terms it sums
+# (operands rounded to 2^-9), not by the element, so the quietest of ~10^5 rows, whose largest element is a few times
+# smaller than a typical row's, shows a few times the global figure (measured: 2.8e-2 at T = 4096 against 3.8e-3 in
+# the global norm); 5e-2 still fails any systematic error confined to a few rows, which the global norm would hide.
+ROW_TOL = {1e-4: 1e-4, 2e-2: 5e-2}
 # fp32: products and sums of at most a few hundred terms of mixed sign, each rounded to 2^-24; an element kept at
 # 1e-3 of the tensor maximum by cancellation may show 1e3 times the relative error of a typical one (measured <= 4e-4)
 ELEM_TOL_F32 = 2e-3
@@ -27,7 +32,8 @@ def check(name, got, ref, tol):
           flush=True)
     assert np.all(np.isfinite(got)), f"{name} has non-finite values"
     assert err <= tol, f"{name}: {err} > {tol}"
-    assert rerr <= tol, f"{name}: per-row error {rerr} > {tol}"
+    rtol = ROW_TOL.get(tol, tol)
+    assert rerr <= rtol, f"{name}: per-row error {rerr} > {rtol}"
     if tol <= 1e-4:
         assert eerr <= ELEM_TOL_F32, f"{name}: element-wise error {eerr} > {ELEM_TOL_F32}"
 
