@@ -132,6 +132,27 @@ DSLA_API dsla_status dsla_prefill(const dsla_desc *desc, int64_t T,
                          void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * dsla_prefill_static_ws - dsla_prefill with the scratch buffer built into the library, for callers that cannot
+ * allocate device memory or size a workspace at the point of the call: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation.  Same arguments as dsla_prefill without the workspace; same
+ * kernels, same results.  The scratch is a fixed array of DSLA_STATIC_WORKSPACE_BYTES bytes in the library's
+ * device code, one copy per GPU, held from the moment the library is loaded on that GPU until the process ends.
+ *   - The call allocates and frees nothing.  The first call on a device looks up the array's address there.
+ *   - The device current at the time of the call must be the one `stream` and the buffers belong to.
+ *   - A plan that needs more than DSLA_STATIC_WORKSPACE_BYTES (see dsla_prefill_workspace_bytes) is rejected with
+ *     DSLA_ERR_WORKSPACE before anything is enqueued; the headline shape (B = 1, H = 32, d = 128, T = 16384) needs
+ *     32.2 MiB.
+ *   - All calls on one GPU share the array: calls that may overlap there (different streams, different threads)
+ *     race and must be ordered by the caller.  Nothing in the array has to start at zero and nothing in it outlives
+ *     a call: every slot is written by the call before it is read.
+ */
+#define DSLA_STATIC_WORKSPACE_BYTES ((size_t)48 << 20)
+DSLA_API dsla_status dsla_prefill_static_ws(const dsla_desc *desc, int64_t T,
+                                   const void *q, const void *k, const void *v,
+                                   const void *g1, const void *g2,
+                                   float *S1, float *S2, void *o, void *stream);
+
+/*
  * dsla_prefill_varlen - dsla_prefill for a batch of sequences of different lengths packed back to back along
  * the token axis, with each sequence's states at a caller-chosen place in a pool of states: the prefill half
  * of the mixed prefill/decode batches of the paper's serving system (Section 4.5 and the appendix "Serving of Mixed Batch"),

@@ -7,6 +7,6 @@ library has not been built.
 """
 from .binding import (DslaDesc, DslaError, dsla_attention_decode, dsla_attention_decode_workspace_bytes,  # noqa: F401
                       dsla_attention_entropy, dsla_attention_entropy_workspace_bytes,  # noqa: F401
-                      dsla_decode, dsla_decode_slots, dsla_prefill,  # noqa: F401
+                      dsla_decode, dsla_decode_slots, dsla_prefill, dsla_prefill_static_ws,  # noqa: F401
                       dsla_prefill_varlen, dsla_prefill_varlen_workspace_bytes, dsla_prefill_workspace_bytes,
                       dsla_state_init, library_path, load_library, make_desc, profile_collect, profile_enable)

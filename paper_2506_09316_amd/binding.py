@@ -15,7 +15,7 @@ _lib = None
 DSLA_F32, DSLA_BF16 = 0, 1
 KERNEL_NAMES = ("state_init", "prefill_segment_state", "prefill_segment_scan", "prefill_chunk_loop", "decode",
                 "prefill_segment_list", "attention_entropy", "attention_decode")
-EXPORTS = ("dsla_state_init", "dsla_prefill_workspace_bytes", "dsla_prefill", "dsla_decode",
+EXPORTS = ("dsla_state_init", "dsla_prefill_workspace_bytes", "dsla_prefill", "dsla_prefill_static_ws", "dsla_decode",
            "dsla_prefill_varlen_workspace_bytes", "dsla_prefill_varlen", "dsla_decode_slots",
            "dsla_attention_entropy_workspace_bytes", "dsla_attention_entropy",
            "dsla_attention_decode_workspace_bytes", "dsla_attention_decode",
@@ -57,6 +57,8 @@ def load_library():
     lib.dsla_prefill_workspace_bytes.restype = ctypes.c_size_t
     lib.dsla_prefill.argtypes = [dp, ctypes.c_int64] + [vp] * 9 + [ctypes.c_size_t, vp]
     lib.dsla_prefill.restype = ctypes.c_int
+    lib.dsla_prefill_static_ws.argtypes = [dp, ctypes.c_int64] + [vp] * 9
+    lib.dsla_prefill_static_ws.restype = ctypes.c_int
     lib.dsla_decode.argtypes = [dp] + [vp] * 9
     lib.dsla_decode.restype = ctypes.c_int
     lib.dsla_prefill_varlen_workspace_bytes.argtypes = [dp, ctypes.c_int64, ctypes.c_int64]
@@ -139,6 +141,12 @@ def dsla_prefill(desc: DslaDesc, T, q, k, v, g1, g2, S1, S2, o, workspace=None):
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(load_library().dsla_prefill(ctypes.byref(desc), int(T), _ptr(q), _ptr(k), _ptr(v), _ptr(g1), _ptr(g2),
                                        _ptr(S1), _ptr(S2), _ptr(o), _ptr(workspace), wbytes, _stream()))
+
+
+def dsla_prefill_static_ws(desc: DslaDesc, T, q, k, v, g1, g2, S1, S2, o):
+    """dsla_prefill on the library's built-in scratch buffer (include/dsla.h: dsla_prefill_static_ws)."""
+    _check(load_library().dsla_prefill_static_ws(ctypes.byref(desc), int(T), _ptr(q), _ptr(k), _ptr(v), _ptr(g1),
+                                                 _ptr(g2), _ptr(S1), _ptr(S2), _ptr(o), _stream()))
 
 
 def dsla_decode(desc: DslaDesc, q, k, v, g1, g2, S1, S2, o):

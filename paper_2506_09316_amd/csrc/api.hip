@@ -132,6 +132,34 @@ dsla_status dsla_prefill(const dsla_desc *desc, int64_t T, const void *q, const 
 }
 
 namespace {
+// Built-in prefill workspace for callers that cannot allocate.  One copy per device, part of the loaded code
+// object; its device address is looked up once per device (the name below is only a host-side handle).
+constexpr size_t kStaticWorkspaceBytes = DSLA_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices];   // device address of `scratch` on device i, or null before the first call there
+
+hipError_t static_workspace(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+}  // namespace
+
+namespace {
 dsla_status check_varlen(const dsla_desc *desc, int64_t total_T, int64_t max_T)
 {
     dsla_status st = check_desc(desc);
@@ -140,6 +168,23 @@ dsla_status check_varlen(const dsla_desc *desc, int64_t total_T, int64_t max_T)
     return DSLA_OK;
 }
 }  // namespace
+
+dsla_status dsla_prefill_static_ws(const dsla_desc *desc, int64_t T, const void *q, const void *k, const void *v,
+                                   const void *g1, const void *g2, float *S1, float *S2, void *o, void *stream)
+{
+    // the size check comes first: a plan that does not fit is an argument error and touches nothing
+    dsla_status st = check_desc(desc);
+    if (st != DSLA_OK) return st;
+    if (T < 0) return DSLA_ERR_SHAPE;
+    const size_t need = T > 0 ? dsla_prefill_workspace_bytes(desc, T) : 0;
+    if (need > kStaticWorkspaceBytes) return DSLA_ERR_WORKSPACE;
+    void *ws = nullptr;
+    if (need > 0) {
+        const hipError_t e = static_workspace(&ws);
+        if (e != hipSuccess) return hip_status(e);
+    }
+    return dsla_prefill(desc, T, q, k, v, g1, g2, S1, S2, o, ws, need, stream);
+}
 
 size_t dsla_prefill_varlen_workspace_bytes(const dsla_desc *desc, int64_t total_T, int64_t max_T)
 {

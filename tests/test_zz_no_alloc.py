@@ -1,0 +1,63 @@
+"""dsla_prefill_static_ws (the prefill on the library's built-in scratch buffer, for callers that cannot allocate)
+against dsla_prefill on a caller-provided workspace: same kernels, so the outputs and states must be bit-equal, and
+both are also held to the oracle.  Two calls in a row share the built-in buffer, the second with a smaller input."""
+import ctypes
+
+import numpy as np
+import pytest
+
+from oracle import dsla_oracle as orc
+import workloads as wl
+import paper_2506_09316_amd as dsla
+from tests.gpu_common import check
+from tests.util import code, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def _both_ways(B, T, H, d, io, gd, seed, segments, tol):
+    import torch
+    print(f"  static-ws prefill B={B} T={T} H={H} d={d} io={io} segments={segments}", flush=True)
+    x = wl.layer_inputs(seed, B, T, H, d, d, io_dtype=io, gate_dtype=gd, qk_scale=d ** -0.5)
+    S1_0, S2_0 = wl.initial_states(seed + 1, B, H, d, d, amplitude=0.5)
+    desc = dsla.make_desc(B, H, d, d, io_dtype=code(io), gate_dtype=code(gd), gamma=0.4, chunk=64, segments=segments)
+    t = {n: to_gpu(x[n], io if n in ("q", "k", "v") else gd) for n in x}
+    nbytes = dsla.dsla_prefill_workspace_bytes(desc, T)
+    assert 0 < nbytes <= 48 << 20, "the case must use the scratch buffer and fit the built-in one"
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    res = []
+    for static in (False, True):
+        S1, S2 = (torch.from_numpy(a.copy()).cuda() for a in (S1_0, S2_0))
+        o = torch.full_like(t["v"], float("nan"))
+        if static:
+            dsla.dsla_prefill_static_ws(desc, T, t["q"], t["k"], t["v"], t["g1"], t["g2"], S1, S2, o)
+        else:
+            dsla.dsla_prefill(desc, T, t["q"], t["k"], t["v"], t["g1"], t["g2"], S1, S2, o, ws)
+        torch.cuda.synchronize()
+        res.append((o.float().cpu().numpy(), S1.cpu().numpy(), S2.cpu().numpy()))
+    for name, a, b in zip(("o", "S1", "S2"), res[0], res[1]):
+        assert np.array_equal(a, b), f"{name}: built-in scratch and caller workspace disagree"
+    ro, rS1, rS2 = orc.recurrent(x["q"], x["k"], x["v"], x["g1"], x["g2"], 0.4, S1=S1_0, S2=S2_0)
+    for name, got, ref in zip(("o", "S1", "S2"), res[1], (ro, rS1, rS2)):
+        check(name, got, ref, tol)
+
+
+def test_static_ws_prefill_two_calls_second_smaller():
+    _both_ways(2, 1500, 4, 128, "bf16", "bf16", seed=301, segments=5, tol=2e-2)
+    _both_ways(1, 333, 2, 64, "f32", "f32", seed=303, segments=3, tol=1e-4)
+
+
+def test_static_ws_prefill_rejects_oversize_plan():
+    """A plan beyond the built-in buffer is an argument error: nothing is enqueued, the states stay as they are."""
+    import torch
+    B, H, d, T = 4, 32, 128, 8192
+    desc = dsla.make_desc(B, H, d, d, io_dtype=code("bf16"), gate_dtype=code("bf16"), segments=8)
+    assert dsla.dsla_prefill_workspace_bytes(desc, T) > 48 << 20
+    S1 = torch.ones(B, H, d, d, device="cuda")
+    S2 = torch.ones_like(S1)
+    q = torch.zeros(B, T, H, d, device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(dsla.DslaError) as e:
+        dsla.dsla_prefill_static_ws(desc, T, q, q, q, q, q, S1, S2, torch.empty_like(q))
+    assert e.value.status == 4
+    torch.cuda.synchronize()
+    assert bool((S1 == 1).all()) and bool((S2 == 1).all())
