@@ -32,9 +32,14 @@
  *  - Same inputs give bit-identical outputs (no atomics, fixed reduction order).
  *  - Supported shapes: d_k = d_v in {64, 128}; chunk in {0 (library default), 32, 64, 128};
  *    B, H, T >= 1 (T == 0 is accepted and does nothing).
- *  - Supported gate domain for dsla_prefill: within any one chunk of `chunk` consecutive
- *    tokens the sum of |log alpha| over the tokens must stay below 80 for every feature (the
- *    chunk-local factorisation forms exp(+|sum log alpha|)).  dsla_decode has no such limit.
+ *  - Gate domain of dsla_prefill.  The prefill works through a sequence 32 tokens at a time and splits the decay
+ *    between a query and a key of the same 32 tokens into a factor on each, both referred to the middle of those
+ *    tokens' total decay; the factors are 2^(+-R/2) with R = the sum of |log2 alpha| over the 32 tokens, per
+ *    feature.  They are exact while R <= 230, i.e. while the sum of |log alpha| over one aligned group of 32
+ *    tokens stays below 159 for every feature (an average gate of 0.007 sustained over 32 tokens); gates of any
+ *    strength are fine when they are not sustained, and nothing accumulates from one group of 32 to the next.
+ *    Beyond that the result of the affected feature is undefined (inf or NaN may appear), and the kernels report
+ *    it: if desc->status is not NULL they store DSLA_STATUS_GATE_DOMAIN there.  dsla_decode has no limit.
  */
 #ifndef DSLA_H
 #define DSLA_H
@@ -84,12 +89,19 @@ typedef struct {
     int32_t io_dtype;   /* dsla_dtype of q, k, v, o                                     */
     int32_t gate_dtype; /* dsla_dtype of g1, g2                                         */
     int32_t gate_mode;  /* dsla_gate_mode: what g1, g2 hold                             */
+    int32_t zero_init;  /* prefill: nonzero = the states are zero before the first token (dsla_state_init folded
+                           into the call): S1, S2 are not read, only written.  decode ignores it   */
     float tau;          /* DSLA_GATE_PREACT: temperature, finite and > 0 (16 in the gated linear attention
                            work; 1 = plain sigmoid); ignored for DSLA_GATE_LOG          */
     float gamma;        /* blend coefficient of the layer (read-out equation); any real */
     float scale;        /* multiplies q (e.g. d_k^-1/2); 1.0 = the paper's plain form   */
     const float *gamma_per_head; /* optional DEVICE array [H] overriding gamma; or NULL */
+    int32_t *status;    /* optional DEVICE word or NULL.  The prefill kernels store DSLA_STATUS_GATE_DOMAIN in it
+                           when a group of 32 tokens leaves the gate domain described above; they never clear it
+                           (the caller zeroes it and reads it back when it wants to know)                     */
 } dsla_desc;
+
+#define DSLA_STATUS_GATE_DOMAIN 1
 
 /*
  * dsla_state_init - set both states to zero, the initial condition implied by the
@@ -118,10 +130,10 @@ DSLA_API size_t dsla_prefill_workspace_bytes(const dsla_desc *desc, int64_t T);
  *   workspace       : at least dsla_prefill_workspace_bytes(desc, T) bytes, 256-byte
  *                     aligned; contents are scratch (undefined before and after)
  * Built combinations: d in {64, 128}, chunk in {32, 64, 128}, io and gate dtype bf16 or f32;
- *                     chunk = 0 selects 64.  The chunk length is how often the states are
- *                     brought back to their own frame (it bounds the exponents, see the
- *                     gate domain above) and the granularity of the internal split of
- *                     long sequences; the result does not depend on it beyond rounding.
+ *                     chunk = 0 selects 64.  The chunk length is the granularity of the internal
+ *                     split of long sequences into segments (a segment is a whole number of
+ *                     chunks); the contractions themselves always cover 32 tokens.  The result
+ *                     does not depend on it beyond rounding.
  * io f32 uses fp32 arithmetic throughout; io bf16 rounds contraction operands to bf16
  * and accumulates in fp32; states are fp32 in both.
  */

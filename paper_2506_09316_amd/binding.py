@@ -26,9 +26,9 @@ class DslaDesc(ctypes.Structure):
     """Mirror of `dsla_desc` in include/dsla.h."""
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d_k", ctypes.c_int32), ("d_v", ctypes.c_int32),
                 ("chunk", ctypes.c_int32), ("segments", ctypes.c_int32), ("io_dtype", ctypes.c_int32),
-                ("gate_dtype", ctypes.c_int32), ("gate_mode", ctypes.c_int32), ("tau", ctypes.c_float),
-                ("gamma", ctypes.c_float), ("scale", ctypes.c_float),
-                ("gamma_per_head", ctypes.c_void_p)]
+                ("gate_dtype", ctypes.c_int32), ("gate_mode", ctypes.c_int32), ("zero_init", ctypes.c_int32),
+                ("tau", ctypes.c_float), ("gamma", ctypes.c_float), ("scale", ctypes.c_float),
+                ("gamma_per_head", ctypes.c_void_p), ("status", ctypes.c_void_p)]
 
 
 class DslaError(RuntimeError):
@@ -120,10 +120,12 @@ def _stream():
 
 
 def make_desc(B, H, d_k, d_v, *, io_dtype, gate_dtype, gamma=0.5, scale=1.0, chunk=0, segments=0,
-              gamma_per_head=None, gate_mode=0, tau=16.0) -> DslaDesc:
+              gamma_per_head=None, gate_mode=0, tau=16.0, zero_init=False, status=None) -> DslaDesc:
+    """status: optional int32 GPU tensor of one element (the caller keeps it alive)."""
     gp = ctypes.c_void_p(gamma_per_head.data_ptr()) if gamma_per_head is not None else None
+    sp = ctypes.c_void_p(status.data_ptr()) if status is not None else None
     return DslaDesc(int(B), int(H), int(d_k), int(d_v), int(chunk), int(segments), int(io_dtype), int(gate_dtype),
-                    int(gate_mode), float(tau), float(gamma), float(scale), gp)
+                    int(gate_mode), int(bool(zero_init)), float(tau), float(gamma), float(scale), gp, sp)
 
 
 def dsla_state_init(desc: DslaDesc, S1, S2):

@@ -388,7 +388,8 @@ struct PrefillArgs {
     int64_t seg_tokens;
     int H;
     int P;
-    int chunk_steps;         // 32-token steps per chunk
+    int zero_init;           // nonzero: the states are zero on entry (the caller's S1, S2 are only written)
+    int32_t *status;         // optional device word: set to DSLA_STATUS_GATE_DOMAIN by a step whose gates leave the domain
     float gamma, scale;
     float gate_inv_tau;      // 0: g1, g2 are log-gates; else they are pre-activations and this is 1 / tau
 };
@@ -402,15 +403,17 @@ struct PrefillArgs {
 // preparation and the MFMA-bound contractions of neighbouring steps overlap.  A step is S = 32 tokens (a chunk
 // of 64 is two steps): two operand sets of 32 tokens fit in the 160 KB LDS, two sets of 64 do not.
 //
-// Chunk algebra (Section 4.1 unrolled over the tokens of a chunk; b_s = log2 of the gate product from the first
-// token of the chunk up to and including token s, bC = b of the last token of the chunk, per state and feature;
-// T = the state in the frame of the chunk start: T = S at the chunk start):
-//     Q~ = gamma_i scale q 2^{b}             K~ = k 2^{-b}              (|Q~| <= |q|, |K~| <= |k| 2^{|bC|})
-//   per step of 32 tokens inside the chunk:
-//     o  =  Q~ T  +  mask_{key <= query}(Q~ K~^T) V                      (both states in one contraction of width 2 d_k)
+// Step algebra (Section 4.1 unrolled over the S = 32 tokens of a step).  Per state and feature: b_s = log2 of the gate
+// product from the first token of the step up to and including token s (b_s <= 0), R = -b_31 the log2 decay of the whole
+// step, and c_s = b_s + R/2 the same exponent centred on the step, so that |c_s| <= R/2.  T = the state in the frame of
+// the middle of the step, T = 2^{-R/2} S at the start of the step:
+//     Q~ = gamma_i scale q 2^{c}             K~ = k 2^{-c}                 (factors between 2^{-R/2} and 2^{+R/2})
+//     o  =  Q~ T  +  mask_{key <= query}(Q~ K~^T) V                        (both states in one contraction of width 2 d_k)
 //     T <-  T + K~^T V
-//   after the last step of the chunk:
-//     S  =  diag(2^{bC}) T
+//   between two steps the state moves from one middle frame to the next, at the end of a segment to its own frame:
+//     T <-  diag(2^{-(R + R_next)/2}) T          (R_next = 0 after the last step)
+// Centring halves the largest exponent a step can produce: the factors stay finite while R < 2 * 115, and nothing
+// links the exponents of different steps.
 template <int D, class TIO, class TG, bool kFull>
 struct Kern {
     using A = ArithOf<TIO>;
@@ -439,7 +442,7 @@ struct Kern {
     static constexpr uint32_t O_KS = O_QS + (kFull ? S * QP * ESZ : 0);        // [token][i*D + d]            K^
     static constexpr uint32_t O_KT = O_KS + (kFull ? S * QP * ESZ : 0);        // [i*D + rho(d)][rho(token)]  K^
     static constexpr uint32_t O_VT = O_KT + 2 * D * TP * ESZ;                  // [column][rho(token)]        v
-    static constexpr uint32_t O_DEC = O_VT + D * TP * ESZ;                     // float [2D]  2^{bS}
+    static constexpr uint32_t O_DEC = O_VT + D * TP * ESZ;                     // float [2D]  frame change after the step
     static constexpr uint32_t SET_BYTES = O_DEC + 2 * D * 4;
     static constexpr uint32_t LDS_MAX = 160 * 1024;                            // LDS of a gfx950 compute unit
     // Two operand sets where they fit (the producers then run a whole step ahead of the consumers); one set
@@ -450,10 +453,11 @@ struct Kern {
     // a step here and write it to memory one step later as whole rows (a row is then complete: it has passed the
     // barrier), which is what the memory system wants; 8-byte pieces straight from the accumulators cost a quarter
     // of the kernel time.
-    static constexpr uint32_t LDS_NOSTAGE = O_CS + CT * 4096, LDS_STAGE = LDS_NOSTAGE + 2 * S * D * ESZ;
+    static constexpr uint32_t O_ENT = O_CS + CT * 4096;                        // float [2D]  frame change into the first step
+    static constexpr uint32_t LDS_NOSTAGE = O_ENT + 2 * D * 4, LDS_STAGE = LDS_NOSTAGE + 2 * S * D * ESZ;
     static constexpr bool kStage =   // only where it does not cost a resident workgroup
         kFull && ESZ == 2 && LDS_STAGE <= LDS_MAX && LDS_MAX / LDS_STAGE == LDS_MAX / LDS_NOSTAGE;
-    static constexpr uint32_t O_ST = O_CS + CT * 4096;
+    static constexpr uint32_t O_ST = LDS_NOSTAGE;
     static constexpr uint32_t ST_BYTES = S * D * ESZ;
     static constexpr int NC = D * ESZ / 16;                                    // 16-byte pieces per output row
     static constexpr uint32_t LDS_BYTES = O_ST + (kStage ? 2 * ST_BYTES : 0);
@@ -619,30 +623,35 @@ struct Kern {
             lds_st<f32x4>(a + 16, f32x4{o.c[i][RPT - 1][4], o.c[i][RPT - 1][5], o.c[i][RPT - 1][6], o.c[i][RPT - 1][7]});
         }
     }
-    // stage B: scan of this lane's column over the 16 token pairs, continuing the chunk.
-    // carry: gate sum of the column from the first token of the chunk to the end of the previous step;
-    // decf: decay factor of the chunk up to the end of this step (used when the step closes its chunk).
+    // stage B: scan of this lane's column over the 16 token pairs of the step, centred on the step: the exclusive
+    // prefixes start at minus half of the step's gate sum, so that the exponents built from them span [-R/2, +R/2].
+    // total: the gate sum of the column over the step (<= 0; times ProdAddr::unit = -R).
     static __device__ __forceinline__ void scan_b_read(const ProdAddr &pa, float (&t)[SGN])
     {
         wave_sync();
 #pragma unroll
         for (int s2 = 0; s2 < SGN; ++s2) t[s2] = lds_ld<float>(pa.col + s2 * 32 * 4);
     }
-    static __device__ __forceinline__ void scan_b(const ProdAddr &pa, const float (&t)[SGN], int valid, uint32_t close_mask,
-                                                  float &carry, float &seg_log2_decay, float &decf)
+    static __device__ __forceinline__ void scan_b(const ProdAddr &pa, const float (&t)[SGN], float &total)
     {
-        const bool close = (close_mask >> pa.state) & 1u;   // does the chunk of this lane's state end with this step
-        float run = carry;
+        float tot = (((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]))) +
+                    (((t[8] + t[9]) + (t[10] + t[11])) + ((t[12] + t[13]) + (t[14] + t[15])));
+        float run = -0.5f * tot;
 #pragma unroll
         for (int s2 = 0; s2 < SGN; ++s2) {
             lds_st<float>(pa.col + s2 * 32 * 4, run);
             run += t[s2];
         }
-        decf = __builtin_amdgcn_exp2f(run * pa.unit);
-        if (valid > 0) {
-            seg_log2_decay += (run - carry) * pa.unit;
-            carry = close ? 0.f : run;
-        }
+        total = tot;
+    }
+    // The largest exponent a step may produce: Q~ and K~ carry 2^{+-R/2}, and bf16 / fp32 hold 2^{+-126}.
+    static constexpr float kMaxStepLog2Decay = 230.f;
+    // bookkeeping after stage B of a step: the segment's log2 decay, and the domain check
+    static __device__ __forceinline__ void note_step(const ProdAddr &pa, float total, float &seg_log2_decay, int32_t *status)
+    {
+        const float r = total * pa.unit;   // -R
+        seg_log2_decay += r;
+        if (status && !(r >= -kMaxStepLog2Decay)) *status = DSLA_STATUS_GATE_DOMAIN;
     }
     // stage C: the exclusive prefixes of this thread's token pair
     static __device__ __forceinline__ void scan_c(const ProdAddr &pa, ScanOut &o)
@@ -663,18 +672,17 @@ struct Kern {
     // ------------------------------------------------------------------------------------------------------
     // Producer, one call: operands of step m into operand set `set` from its inputs `r` and scan results `sc`, and,
     // interleaved, the gate scan of step m + 1 (gates `gn` -> `sn`) and the loads of later steps (`next`).
-    // valid: of step m; valid_n / close_n: of step m + 1.  decf: in: decay factor computed by the scan of step m
-    // (written to the operand set); out: that of step m + 1.
+    // valid: of step m; valid_n: of step m + 1.  tot: in: gate sum of this lane's column over step m; out: over step
+    // m + 1 (zero past the end of the segment).  The factor that takes the state from the middle frame of step m to
+    // that of step m + 1 (to its own frame after the last step) goes into the operand set of step m.
     // ------------------------------------------------------------------------------------------------------
     template <class Loads>
     static __device__ __forceinline__ void produce(const ProdAddr &pa, uint32_t set, RawIO &r, const ScanOut &sc, int valid,
-                                                   RawGates &gn, ScanOut &sn, int valid_n, uint32_t close_n,
-                                                   const float (&lg)[2], const uint32_t (&sgn)[2], float &carry,
-                                                   float &seg_log2_decay, float &decf, const Loads &next)
+                                                   RawGates &gn, ScanOut &sn, int valid_n,
+                                                   const float (&lg)[2], const uint32_t (&sgn)[2], float &tot,
+                                                   float &seg_log2_decay, int32_t *status, const Loads &next)
     {
         const uint32_t so = set * SET_BYTES;
-        // decay from the start of the chunk to the end of this step; the consumers apply it when the chunk ends here
-        lds_st<float>(pa.dec + so, decf);
         if (valid < S) {   // ragged tail: tokens past the end act as "no key, no value"
 #pragma unroll
             for (int j = 0; j < RPT; ++j)
@@ -689,7 +697,7 @@ struct Kern {
 
         Row8 kt[RPT];
         auto block = [&](int i, int j, int slot_k, int slot_q) {
-            // log2 exponents of the factors before this thread's first token: K~ = k 2^{-b}, Q~ = gamma_i scale q 2^{b}
+            // K~ = k 2^{-c}, Q~ = gamma_i scale q 2^{c}: c = centred prefix before this thread's tokens + sum over its own
             next.at(slot_k);
             {   // row layout for the scores, token-contiguous (below) for the update
                 float kf[8], kh[8];
@@ -719,7 +727,13 @@ struct Kern {
         float t[SGN];
         scan_b_read(pa, t);   // the answers arrive while the first block is computed
         block(0, 0, 2, 3);
-        scan_b(pa, t, valid_n, close_n, carry, seg_log2_decay, decf);
+        {
+            float tot_n;
+            scan_b(pa, t, tot_n);
+            lds_st<float>(pa.dec + so, __builtin_amdgcn_exp2f(0.5f * pa.unit * (tot + tot_n)));
+            note_step(pa, tot_n, seg_log2_decay, status);
+            tot = tot_n;
+        }
         block(0, 1, 4, 5);
         kt_rows(0);
         scan_c(pa, sn);
@@ -753,8 +767,7 @@ struct Kern {
     }
 
     static __device__ __forceinline__ void consume(uint32_t sm, uint32_t set, f32x16 (&acc)[2][DT], int ct, int lane,
-                                                   TIO *orow, uint32_t rs, int valid, uint32_t close_mask,
-                                                   uint32_t set_parity)
+                                                   TIO *orow, uint32_t rs, int valid, uint32_t set_parity)
     {
         const uint32_t lo = opaque(static_cast<uint32_t>(lane));
         const uint32_t ln = lo & 31, g = lo >> 5;
@@ -843,28 +856,28 @@ struct Kern {
                 store4_global(op + 8 * jb, oacc[4 * jb], oacc[4 * jb + 1], oacc[4 * jb + 2], oacc[4 * jb + 3]);
         }
 
-        // ---- end of a chunk: the decay over the whole chunk brings a state to its own frame ----
+        // ---- the states move to the middle frame of the next step (after the last step: to their own frame) ----
+        // (a block of its own for the register allocator: merged into the code above it costs four spilled registers)
+        if (opaque(1u)) rescale(acc, dec_r);
+    }
+
+    // acc[i][dt][j] *= f[i D + feature of register j], f = 2 D floats at LDS address `fac` (+ 8 g floats for this lane)
+    static __device__ __forceinline__ void rescale(f32x16 (&acc)[2][DT], uint32_t fac)
+    {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
-            if ((close_mask >> i) & 1u) {
+        for (int i = 0; i < 2; ++i) {
 #pragma unroll
-                for (int dt2 = 0; dt2 < DT; dt2 += 2) {
-                    f32x4 dd[2][4];
+            for (int dt = 0; dt < DT; ++dt) {
+                f32x4 dd[4];
 #pragma unroll
-                    for (int t = 0; t < 2; ++t)
+                for (int jb = 0; jb < 4; ++jb)
+                    dd[jb] = lds_ld<f32x4>(fac + (i * D + 32 * dt + 16 * (jb >> 1) + 4 * (jb & 1)) * 4);
 #pragma unroll
-                        for (int jb = 0; jb < 4; ++jb)
-                            dd[t][jb] = lds_ld<f32x4>(dec_r + (i * D + 32 * (dt2 + t) + 16 * (jb >> 1) + 4 * (jb & 1)) * 4);
-                    asm volatile("" : "+v"(dd[0][0]), "+v"(dd[0][1]), "+v"(dd[0][2]), "+v"(dd[0][3]), "+v"(dd[1][0]),
-                                 "+v"(dd[1][1]), "+v"(dd[1][2]), "+v"(dd[1][3]));
+                for (int jb = 0; jb < 4; ++jb)
 #pragma unroll
-                    for (int t = 0; t < 2; ++t)
-#pragma unroll
-                        for (int jb = 0; jb < 4; ++jb)
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) acc[i][dt2 + t][4 * jb + e] *= dd[t][jb][e];
-                }
+                    for (int e = 0; e < 4; ++e) acc[i][dt][4 * jb + e] *= dd[jb][e];
             }
+        }
     }
 
     static __device__ void run(const PrefillArgs &a, uint32_t sm)
@@ -907,7 +920,6 @@ struct Kern {
         const int64_t t1 = (t0 + a.seg_tokens < Tb) ? t0 + a.seg_tokens : Tb;
         const int ntok = static_cast<int>(t1 - t0);               // tokens of this segment (>= 1)
         const int nsteps = (ntok + S - 1) / S;
-        const int wsteps = a.chunk_steps;                          // steps per chunk (a segment starts a chunk)
         const uint32_t rs = static_cast<uint32_t>(a.H) * D;       // elements between consecutive tokens
         // uniform element offset of (b, t0, h, 0); per-lane offsets are 32-bit
         const size_t seg0 = (static_cast<size_t>(seq0 + t0) * a.H + h) * D;
@@ -916,8 +928,6 @@ struct Kern {
             const int left = ntok - n * S;
             return left >= S ? S : (left > 0 ? left : 0);
         };
-        // Which states end a chunk with step n (bit i = state i); wsteps is 1, 2 or 4.
-        auto closes = [&](int n) -> uint32_t { return (n + 1 >= nsteps || ((n + 1) & (wsteps - 1)) == 0) ? 3u : 0u; };
         // The step loop runs in pairs (set 0, set 1), so both roles pass the same number of barriers:
         // 1 + 2 * ceil(nsteps / 2) with two sets, twice as many in the loop with one.
 
@@ -927,15 +937,16 @@ struct Kern {
             const int ln = lane & 31, g = lane >> 5;
             f32x16 acc[2][DT];
             const uint32_t sbase = static_cast<uint32_t>(8 * g) * D + 32 * ct + ln;   // lane part of the state offset
-            if (kFull) {
+            // A sequence that is cut into segments starts every segment, the first one included, from the slot the
+            // segment scan filled: the workgroup of the last segment overwrites the caller's states in this same
+            // launch, so no workgroup of such a sequence may read them here.  A sequence of one segment reads the
+            // caller's states itself (it is also the only one that writes them), unless they are zero by contract.
+            const bool cut = Tb > a.seg_tokens;
+            if (kFull && (cut || !a.zero_init)) {
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
-                    // A sequence that is cut into segments starts every segment, the first one included, from the
-                    // slot the segment scan filled: the workgroup of the last segment overwrites the caller's states
-                    // in this same launch, so no workgroup of such a sequence may read them here.  A sequence of one
-                    // segment reads the caller's states itself (it is also the only one that writes them).
-                    const float *src = (Tb > a.seg_tokens) ? a.ws_state + ((slot0 + p * slot_step) * 2 + i) * D * D
-                                                           : (i ? a.S2 : a.S1) + sbh * D * D;
+                    const float *src = cut ? a.ws_state + ((slot0 + p * slot_step) * 2 + i) * D * D
+                                           : (i ? a.S2 : a.S1) + sbh * D * D;
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -951,15 +962,16 @@ struct Kern {
             }
             TIO *orow = static_cast<TIO *>(a.o) + seg0;
             lds_barrier();   // operands of step 0 are ready
+            if (kFull) rescale(acc, sm + O_ENT + static_cast<uint32_t>(8 * g) * 4);   // into the middle frame of step 0
             for (int n = 0; n < nsteps; n += 2) {
                 if (kStage && n > 0) flush_rows(sm, 1, ct, lane, orow - sstep, rs, S);
-                consume(sm, 0, acc, ct, lane, orow, rs, valid_of(n), closes(n), 0);
+                consume(sm, 0, acc, ct, lane, orow, rs, valid_of(n), 0);
                 orow += sstep;
                 lds_barrier();                    // step n consumed (two sets: and step n+1 ready)
                 if (SETS == 1) lds_barrier();     // one set: step n+1 ready
                 if (n + 1 < nsteps) {
                     if (kStage) flush_rows(sm, 0, ct, lane, orow - sstep, rs, S);
-                    consume(sm, SETS - 1, acc, ct, lane, orow, rs, valid_of(n + 1), closes(n + 1), 1);
+                    consume(sm, SETS - 1, acc, ct, lane, orow, rs, valid_of(n + 1), 1);
                     orow += sstep;
                 }
                 lds_barrier();
@@ -993,7 +1005,7 @@ struct Kern {
             const float lg[2] = {__builtin_amdgcn_logf(fabsf(gsv[0])), __builtin_amdgcn_logf(fabsf(gsv[1]))};
             const uint32_t sgn[2] = {gsv[0] < 0.f ? A::kSignBits : 0u, gsv[1] < 0.f ? A::kSignBits : 0u};
             float seg_decay = 0.f;   // lane l: log2 of the segment decay of (state l / 32, feature 32 pw + l % 32)
-            float carry = 0.f;       // lane l: gate sum of that column since the start of the chunk
+            float tot = 0.f;         // lane l: gate sum of that column over the step whose operands come next
             ProdAddr pa(sm, pw, static_cast<uint32_t>(lane));
             pa.preact = a.gate_inv_tau != 0.f;
             pa.unit = pa.preact ? a.gate_inv_tau : kLog2e;
@@ -1023,7 +1035,6 @@ struct Kern {
             RawIO r0, r1;
             RawGates g0, g1;
             ScanOut s0, s1;
-            float decf = 1.f;
             load_gates(g0, src_of(0));
             load_gates(g1, src_of(1));
             load_io(r0, src_of(0));
@@ -1031,14 +1042,17 @@ struct Kern {
             {
                 float t[SGN];
                 scan_b_read(pa, t);
-                scan_b(pa, t, valid_of(0), closes(0), carry, seg_decay, decf);
+                scan_b(pa, t, tot);
+                note_step(pa, tot, seg_decay, a.status);
+                // the caller's states enter the middle frame of step 0
+                lds_st<float>(sm + O_ENT + (pa.dec - (sm + O_DEC)), __builtin_amdgcn_exp2f(0.5f * pa.unit * tot));
             }
             scan_c(pa, s0);
             load_gates(g0, src_of(2));
             {
                 const StepSrc io = src_of(1), gs = src_of(3);
-                produce(pa, 0, r0, s0, valid_of(0), g1, s1, valid_of(1), closes(1), lg, sgn, carry, seg_decay,
-                        decf, NextLoads{r1, io, g1, gs});
+                produce(pa, 0, r0, s0, valid_of(0), g1, s1, valid_of(1), lg, sgn, tot, seg_decay, a.status,
+                        NextLoads{r1, io, g1, gs});
             }
             lds_barrier();   // operands of step 0 are ready
             for (int n = 0; n < nsteps; n += 2) {
@@ -1046,15 +1060,15 @@ struct Kern {
                 if (SETS == 1) lds_barrier();     // one set: wait until step n is consumed
                 {
                     const StepSrc io = src_of(n + 2), gs = src_of(n + 4);
-                    produce(pa, SETS - 1, r1, s1, valid_of(n + 1), g0, s0, valid_of(n + 2), closes(n + 2), lg,
-                            sgn, carry, seg_decay, decf, NextLoads{r0, io, g0, gs});
+                    produce(pa, SETS - 1, r1, s1, valid_of(n + 1), g0, s0, valid_of(n + 2), lg, sgn, tot, seg_decay,
+                            a.status, NextLoads{r0, io, g0, gs});
                 }
                 lds_barrier();
                 if (SETS == 1) lds_barrier();
                 {
                     const StepSrc io = src_of(n + 3), gs = src_of(n + 5);
-                    produce(pa, 0, r0, s0, valid_of(n + 2), g1, s1, valid_of(n + 3), closes(n + 3), lg, sgn,
-                            carry, seg_decay, decf, NextLoads{r1, io, g1, gs});
+                    produce(pa, 0, r0, s0, valid_of(n + 2), g1, s1, valid_of(n + 3), lg, sgn, tot, seg_decay,
+                            a.status, NextLoads{r1, io, g1, gs});
                 }
                 lds_barrier();
             }
@@ -1140,7 +1154,7 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restri
                                                            const int32_t *__restrict__ seq,
                                                            const int32_t *__restrict__ slot,
                                                            const int32_t *__restrict__ seg_first, int H,
-                                                           int64_t seg_tokens)
+                                                           int64_t seg_tokens, int zero_init)
 {
     // one thread per 4 adjacent columns of one (bh, state, row)
     const size_t n4 = static_cast<size_t>(BH) * 2 * D * (D / 4);
@@ -1165,7 +1179,7 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restri
     }
     const size_t sbh = static_cast<size_t>(slot ? slot[b] : b) * H + h;
     const float *src = (i ? S2 : S1) + (sbh * D + row) * D + c4 * 4;
-    float4 s = *reinterpret_cast<const float4 *>(src);
+    float4 s = zero_init ? make_float4(0.f, 0.f, 0.f, 0.f) : *reinterpret_cast<const float4 *>(src);
     const size_t in_slot = (static_cast<size_t>(i) * D + row) * D + c4 * 4;   // this thread's place inside a slot
     if (P <= 1) return;
     *reinterpret_cast<float4 *>(ws_state + slot0 * 2 * D * D + in_slot) = s;
@@ -1213,7 +1227,7 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
             const size_t n4 = static_cast<size_t>(BH) * 2 * D * (D / 4);
             hipLaunchKernelGGL((segment_scan_kernel<D>), dim3(static_cast<unsigned>((n4 + 255) / 256)), dim3(256), 0,
                                stream, a.S1, a.S2, a.ws_state, a.ws_decay, BH, plan.segments, a.cu, a.seq, a.slot,
-                               a.seg_first, a.H, a.seg_tokens);
+                               a.seg_first, a.H, a.seg_tokens, a.zero_init);
             err = hipGetLastError();
         }
         if (err != hipSuccess) return err;
@@ -1364,7 +1378,8 @@ hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T
     a.seg_tokens = plan.segment_tokens;
     a.H = d.H;
     a.P = plan.segments;
-    a.chunk_steps = plan.chunk / 32;
+    a.zero_init = d.zero_init != 0;
+    a.status = d.status;
     a.gamma = d.gamma;
     a.scale = d.scale;
     a.gate_inv_tau = d.gate_mode == DSLA_GATE_PREACT ? 1.0f / d.tau : 0.f;

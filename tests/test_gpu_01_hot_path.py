@@ -50,6 +50,23 @@ def test_carried_states_short_last_segment(io, d, chunk):
         check(f"packed S1[seq {b}]", S1[sl:sl + 1].cpu().numpy(), rS1, TOL[io])
         check(f"packed S2[seq {b}]", S2[sl:sl + 1].cpu().numpy(), rS2, TOL[io])
 
+@pytest.mark.parametrize("io,d,segments,T", [("bf16", 128, 1, 300), ("bf16", 128, 4, 1000), ("f32", 64, 1, 77),
+                                             ("f32", 64, 3, 450)])
+def test_prefill_zero_init_does_not_read_the_states(io, d, segments, T):
+    """desc.zero_init: the states are zero by contract, the call only writes them (dsla_state_init folded in).
+    The state tensors hold NaN on entry, so any read of them would show in the results."""
+    B, H = 2, 3
+    gd = "bf16" if io == "bf16" else "f32"
+    x = wl.layer_inputs(61, B, T, H, d, d, io_dtype=io, gate_dtype=gd, qk_scale=d ** -0.5)
+    layer = GpuLayer(B, H, d, io, gd, gamma=0.3, chunk=64, segments=segments, zero_init=True, init=False)
+    o = layer.prefill(x)
+    S1, S2 = layer.states()
+    ro, rS1, rS2 = orc.recurrent(x["q"], x["k"], x["v"], x["g1"], x["g2"], 0.3)
+    check("o", o, ro, TOL[io])
+    check("S1", S1, rS1, TOL[io])
+    check("S2", S2, rS2, TOL[io])
+
+
 # ---------------------------------------------------------------- prefill, bf16
 
 
@@ -259,13 +276,54 @@ def test_prefill_fp32_d128_chunk64():
                      qk_scale=128 ** -0.5)
 
 
-def test_prefill_fp32_gates_near_the_domain_limit():
-    """tau = 1 gates with pre-activations around 0: |log alpha| averages 0.8 per token, about 50 (at most about 70)
-    per chunk of 64, close to the documented limit of 80; the chunk-local factors then span 30 orders of magnitude."""
-    run_prefill_case(1, 256, 2, 64, "f32", "f32", chunk=64, segments=2, gamma=0.5, tau=1.0, seed=17, init=True,
-                     gate_mean=0.0)
-    run_prefill_case(1, 256, 2, 128, "bf16", "f32", chunk=32, segments=1, gamma=0.5, tau=1.0, seed=19, init=True,
-                     gate_mean=-0.5, qk_scale=128 ** -0.5)
+@pytest.mark.parametrize("io,gd,d", [("f32", "f32", 64), ("bf16", "f32", 128), ("bf16", "bf16", 128), ("f32", "f32", 128)])
+@pytest.mark.parametrize("chunk", [64, 128])
+@pytest.mark.parametrize("gate_mean", [0.0, -2.0])
+def test_prefill_plain_sigmoid_gates(io, gd, d, chunk, gate_mean):
+    """tau = 1 (plain sigmoid) gates with pre-activations z ~ N(0, 1) and z ~ N(-2, 1): |log alpha| averages 0.8 and
+    2.1 per token, 26 and 68 per 32 tokens, 52 and 136 per chunk of 64; the recency state then forgets within a few
+    tokens.  The exponents are referred to the middle of each group of 32 tokens, so neither the chunk length nor the
+    sequence length limits the decay; carried-in states, several segments, a ragged end."""
+    run_prefill_case(2, 5 * chunk + 37, 2, d, io, gd, chunk=chunk, segments=2, gamma=0.5, tau=1.0, seed=17, init=True,
+                     gate_mean=gate_mean, qk_scale=d ** -0.5)
+
+
+def test_prefill_gates_of_any_strength_when_not_sustained():
+    """Single tokens that all but close a gate (log alpha = -100 and -120, alpha = 4e-44 and 8e-53) among ordinary
+    ones: the state is wiped at those tokens, and the sum over their group of 32 stays inside the domain because they
+    are single; another group is filled with as much sustained decay as the domain allows (32 tokens of alpha = 0.0074)."""
+    B, T, H, d = 1, 200, 2, 64
+    x = wl.layer_inputs(71, B, T, H, d, d, io_dtype="f32", gate_dtype="f32", qk_scale=d ** -0.5)
+    x["g1"][:, 40, :, ::3] = np.float32(-100.0)
+    x["g2"][:, 41, :, 1::3] = np.float32(-120.0)
+    x["g1"][:, 96:128, :, 5] = np.float32(-4.9)     # 32 tokens of alpha = 0.0074: 157 over the group
+    from tests.gpu_common import GATE_DOMAIN, step_gate_sums
+    assert 150.0 < step_gate_sums(x) < GATE_DOMAIN
+    import torch
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    layer = GpuLayer(B, H, d, "f32", "f32", gamma=0.4, chunk=64, segments=2, status=status)
+    o = layer.prefill(x)
+    S1, S2 = layer.states()
+    ro, rS1, rS2 = orc.recurrent(x["q"], x["k"], x["v"], x["g1"], x["g2"], 0.4)
+    check("o", o, ro, 1e-4)
+    check("S1", S1, rS1, 1e-4)
+    check("S2", S2, rS2, 1e-4)
+    assert int(status.item()) == 0
+
+
+def test_prefill_reports_gates_outside_the_domain():
+    """Sustained gates of 3e-4 (log alpha = -8 on every token: 256 over 32 tokens) are outside the domain: the kernels
+    say so through the status word instead of returning silently; features that stay inside are still right."""
+    import torch
+    B, T, H, d = 1, 96, 1, 64
+    x = wl.layer_inputs(73, B, T, H, d, d, io_dtype="f32", gate_dtype="f32", qk_scale=d ** -0.5)
+    status = torch.zeros(1, dtype=torch.int32, device="cuda")
+    layer = GpuLayer(B, H, d, "f32", "f32", gamma=0.5, chunk=32, segments=1, status=status)
+    layer.prefill(x)
+    assert int(status.item()) == 0
+    x["g2"][:, 32:64, :, 7] = np.float32(-8.0)
+    layer.prefill(x)
+    assert int(status.item()) == 1
 
 
 def test_prefill_fp32_gamma_extremes():

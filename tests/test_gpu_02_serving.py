@@ -27,8 +27,6 @@ def test_gate_preactivation_mode(io, gate, d, T, tau, tol):
         x[n][:, 11::131, :, ::7] = np.float32(-6.0) if tau > 1 else np.float32(-2.0)
     lg = {n: orc.log_gates_from_preactivations(x[n], tau) for n in ("g1", "g2")}
     C = 64
-    worst = max(float(np.max(-np.add.reduceat(lg[n][:, :T].astype(np.float64), np.arange(0, T, C), axis=1))) for n in lg)
-    assert worst < 80.0, worst
     layer = GpuLayer(B, H, d, io, gate, gamma=0.35, chunk=C, gate_mode=1, tau=tau)
     T1 = 2 * T // 3 + 5
     outs = [layer.prefill(slice_t(x, 0, T1)), layer.prefill(slice_t(x, T1, T))]

@@ -50,7 +50,7 @@ class GpuLayer:
     """One DSLA layer instance on the GPU: owns the states and calls the library."""
 
     def __init__(self, B, H, d, io_dtype, gate_dtype, gamma=0.5, scale=1.0, chunk=0, segments=0,
-                 gamma_per_head=None, gate_mode=0, tau=16.0):
+                 gamma_per_head=None, gate_mode=0, tau=16.0, status=None, zero_init=False, init=True):
         import torch
         self.B, self.H, self.d = B, H, d
         self.io_dtype, self.gate_dtype = io_dtype, gate_dtype
@@ -59,10 +59,12 @@ class GpuLayer:
             self.gph = torch.tensor(np.asarray(gamma_per_head, dtype=np.float32)).cuda()
         self.desc = dsla.make_desc(B, H, d, d, io_dtype=code(io_dtype), gate_dtype=code(gate_dtype), gamma=gamma,
                                    scale=scale, chunk=chunk, segments=segments, gamma_per_head=self.gph,
-                                   gate_mode=gate_mode, tau=tau)
+                                   gate_mode=gate_mode, tau=tau, status=status, zero_init=zero_init)
+        self.status = status
         self.S1 = torch.full((B, H, d, d), float("nan"), device="cuda", dtype=torch.float32)
         self.S2 = torch.full((B, H, d, d), float("nan"), device="cuda", dtype=torch.float32)
-        dsla.dsla_state_init(self.desc, self.S1, self.S2)
+        if init:   # otherwise the states keep their NaN fill (a zero_init prefill must not read them)
+            dsla.dsla_state_init(self.desc, self.S1, self.S2)
 
     def set_states(self, S1, S2):
         import torch
