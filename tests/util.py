@@ -14,10 +14,12 @@ def max_rel_err(x, ref):
     return float(np.max(np.abs(x - ref)) / (den if den > 0 else 1.0))
 
 
-def row_rel_err(x, ref, floor=1e-3):
+def row_rel_err(x, ref, floor=1e-2):
     """The error at the scale of each output row: max over rows (vectors along the last axis) of
     max|x - ref| over the row / max(max|ref| over the row, floor * max|ref| over the tensor).  A quiet row (early
-    tokens, a strongly decayed state row) is held to its own magnitude, not to the loudest row of the tensor."""
+    tokens, a strongly decayed state row) is held to its own magnitude, not to the loudest row of the tensor; rows
+    below 1 % of the tensor maximum are held to that 1 %: such a row is small because its terms cancel (the first
+    token's output is (q.k) v with a 128-term dot product near zero), and its error is that of the terms."""
     x = np.asarray(x, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     top = np.max(np.abs(ref))
