@@ -28,6 +28,13 @@
  * library matmul of tril(QK^T)V, the per-head scalar-gate masked-matmul form,
  * agreement of the recurrence with the unrolled attention-score form, state
  * disabling (gamma in {0,1}, equal gates), linearity and continuation.
+ * dsla_oracle_nstate (N states, outer-product gate, grouped key/value heads): a
+ * hand-computed d=1 example with both gate vectors, bit-equality with
+ * dsla_oracle_recurrent for N = 2 without a beta gate, brute-force loops, the
+ * unrolled form with both gate vectors, the geometric closed form with ratio
+ * alpha_d beta_j, linearity in the blend, grouped heads against repeated heads.
+ * The blend of more than two states is a reading (the paper prints two): that
+ * choice is unpinned by the paper, the function itself is pinned as listed.
  */
 #include <math.h>
 #include <stddef.h>
@@ -146,5 +153,65 @@ void dsla_oracle_unrolled(int B, int T, int H, int dk, int dv,
         }
         free(p1);
         free(p2);
+    }
+}
+
+/*
+ * The recurrence with N states, the general outer-product gate and grouped key/value heads.
+ *
+ * Background section on gated linear attention: the forget gate of a state is a dk x dv matrix formed as the
+ * outer product of two vectors, G_t = alpha_t^T beta_t, applied elementwise to the state:
+ *     S^n_t[d][j] = alpha^n_t[d] * beta^n_t[j] * S^n_{t-1}[d][j] + k_t[d] * v_t[j],     n = 1 .. N.
+ * Section 4.2 ("Why Two States Suffice?") and the ablation over the number of states in Section 5.5 speak of the
+ * same layer with 1, 2, 4 or 8 states, each with its own gate.  The paper prints the blend for two states only
+ * (gamma, 1 - gamma); for N states the reading taken here is one real coefficient per state,
+ *     o_t = scale * q_t * sum_n w_n S^n_t,
+ * of which (gamma, 1 - gamma) is the case N = 2.
+ * Grouped-query shapes (the Llama-3 teacher of Section 5.5): q and the gates have H heads, k and v have Hkv heads,
+ * H a multiple of Hkv; head h reads key/value head h / (H / Hkv).  Every query head keeps its own states.
+ *
+ * Gates are natural logarithms.  galpha: [N][B][T][H][dk]; gbeta: [N][B][T][H][dv] or NULL (beta = 1);
+ * w: [N][H]; S: [N][B][H][dk][dv], initial states on entry, final states on return.
+ */
+void dsla_oracle_nstate(int N, int B, int T, int H, int Hkv, int dk, int dv,
+                        const double *q, const double *k, const double *v,
+                        const double *galpha, const double *gbeta,
+                        const double *w, double scale, double *S, double *o)
+{
+    const int BH = B * H;
+    const int group = H / Hkv;
+    const size_t gstride_a = (size_t)B * T * H * dk, gstride_b = (size_t)B * T * H * dv;
+    const size_t sstride = (size_t)B * H * dk * dv;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bh = 0; bh < BH; ++bh) {
+        const int b = bh / H, h = bh % H, hk = h / group;
+        for (int t = 0; t < T; ++t) {
+            const size_t rq = (((size_t)b * T + t) * H + h) * (size_t)dk;
+            const size_t ro = (((size_t)b * T + t) * H + h) * (size_t)dv;
+            const size_t rk = (((size_t)b * T + t) * Hkv + hk) * (size_t)dk;
+            const size_t rv = (((size_t)b * T + t) * Hkv + hk) * (size_t)dv;
+            for (int n = 0; n < N; ++n) {
+                double *s = S + n * sstride + (size_t)bh * dk * dv;
+                const double *ga = galpha + n * gstride_a + rq;
+                const double *gb = gbeta ? gbeta + n * gstride_b + ro : NULL;
+                for (int d = 0; d < dk; ++d) {
+                    const double a = exp(ga[d]);
+                    for (int j = 0; j < dv; ++j) {
+                        const double bj = gb ? exp(gb[j]) : 1.0;
+                        s[(size_t)d * dv + j] = a * bj * s[(size_t)d * dv + j] + k[rk + d] * v[rv + j];
+                    }
+                }
+            }
+            for (int j = 0; j < dv; ++j) {
+                double acc = 0.0;
+                for (int d = 0; d < dk; ++d) {
+                    double mix = 0.0;
+                    for (int n = 0; n < N; ++n)
+                        mix += w[(size_t)n * H + h] * S[n * sstride + (size_t)bh * dk * dv + (size_t)d * dv + j];
+                    acc += q[rq + d] * mix;
+                }
+                o[ro + j] = scale * acc;
+            }
+        }
     }
 }

@@ -28,6 +28,8 @@ def _load():
         lib.dsla_oracle_recurrent.restype = None
         lib.dsla_oracle_unrolled.argtypes = [ci] * 5 + [dp] * 6 + [ctypes.c_double, dp]
         lib.dsla_oracle_unrolled.restype = None
+        lib.dsla_oracle_nstate.argtypes = [ci] * 7 + [dp] * 6 + [ctypes.c_double, dp, dp]
+        lib.dsla_oracle_nstate.restype = None
         lib.dsla_oracle_threads.argtypes = []
         lib.dsla_oracle_threads.restype = ci
         _lib = lib
@@ -101,3 +103,34 @@ def unrolled(q, k, v, g1, g2, gamma, scale=1.0):
     _load().dsla_oracle_unrolled(B, T, H, dk, dv, _ptr(q), _ptr(k), _ptr(v), _ptr(g1), _ptr(g2),
                                  _ptr(gm), float(scale), _ptr(o))
     return o
+
+
+def nstate(q, k, v, galpha, gbeta=None, w=None, scale=1.0, S=None):
+    """The recurrence with N states, outer-product gates alpha^T beta and grouped key/value heads
+    (oracle/dsla_oracle.c: dsla_oracle_nstate; background section on gated linear attention, Section 4.2,
+    the ablation over the number of states in Section 5.5).
+
+    q [B,T,H,dk]; k [B,T,Hkv,dk]; v [B,T,Hkv,dv]; galpha [N,B,T,H,dk] = log alpha; gbeta [N,B,T,H,dv] = log beta or
+    None (beta = 1); w [N] or [N,H] blend coefficients (default: 1/N each); S [N,B,H,dk,dv] initial states or None
+    (zeros).  Returns (o [B,T,H,dv], S_final [N,B,H,dk,dv]), fp64.
+    """
+    q, k, v, galpha = map(_f64, (q, k, v, galpha))
+    N, B, T, H, dk = galpha.shape
+    Hkv, dv = v.shape[2], v.shape[3]
+    assert q.shape == (B, T, H, dk) and k.shape == (B, T, Hkv, dk) and v.shape == (B, T, Hkv, dv)
+    assert H % Hkv == 0
+    gb = None
+    if gbeta is not None:
+        gb = _f64(gbeta)
+        assert gb.shape == (N, B, T, H, dv)
+    wv = np.full((N, H), 1.0 / N) if w is None else np.asarray(w, dtype=np.float64)
+    if wv.ndim == 1:
+        wv = np.repeat(wv[:, None], H, axis=1)
+    wv = np.ascontiguousarray(wv)
+    assert wv.shape == (N, H)
+    S = np.zeros((N, B, H, dk, dv)) if S is None else _f64(S).copy()
+    assert S.shape == (N, B, H, dk, dv)
+    o = np.zeros((B, T, H, dv))
+    _load().dsla_oracle_nstate(N, B, T, H, Hkv, dk, dv, _ptr(q), _ptr(k), _ptr(v), _ptr(galpha),
+                               _ptr(gb) if gb is not None else None, _ptr(wv), float(scale), _ptr(S), _ptr(o))
+    return o, S

@@ -445,5 +445,119 @@ def test_attention_decode_pins():
     assert abs(-np.sum(a * np.log(a)) - ent.attention_entropy(qq, kq, 0.7)[0, 0]) < 1e-13
 
 
+# ---------------------------------------------------------------- N states, outer-product gate, grouped heads
+def nstate_case(seed, N=3, B=2, T=11, H=4, Hkv=2, dk=5, dv=4, beta=True):
+    q = rnd(seed, B, T, H, dk)
+    k, v = rnd(seed + 1, B, T, Hkv, dk), rnd(seed + 2, B, T, Hkv, dv)
+    ga = -np.random.default_rng(seed + 3).uniform(0.0, 1.0, (N, B, T, H, dk))
+    gb = -np.random.default_rng(seed + 4).uniform(0.0, 0.7, (N, B, T, H, dv)) if beta else None
+    w = np.random.default_rng(seed + 5).uniform(-0.5, 1.0, (N, H))
+    S0 = rnd(seed + 6, N, B, H, dk, dv)
+    return q, k, v, ga, gb, w, S0
+
+
+def test_nstate_hand_example_outer_gate():
+    rows = np.loadtxt(os.path.join(GOLD, "hand_example_outer_gate.txt"))
+    T = rows.shape[0]
+    one = np.ones((1, T, 1, 1))
+    ga = np.log(np.array([0.5, 1.0])).reshape(2, 1, 1, 1, 1) * np.ones((2, 1, T, 1, 1))
+    gb = np.log(np.array([0.5, 0.5])).reshape(2, 1, 1, 1, 1) * np.ones((2, 1, T, 1, 1))
+    o, S = orc.nstate(one, one, one, ga, gb, [0.25, 0.75])
+    np.testing.assert_allclose(o.ravel(), rows[:, 3], atol=1e-15)
+    for t in range(T):
+        _, St = orc.nstate(one[:, :t + 1], one[:, :t + 1], one[:, :t + 1], ga[:, :, :t + 1], gb[:, :, :t + 1], [0.25, 0.75])
+        assert St[0].ravel()[0] == pytest.approx(rows[t, 1], abs=1e-15)
+        assert St[1].ravel()[0] == pytest.approx(rows[t, 2], abs=1e-15)
+
+
+def test_nstate_reduces_to_the_dual_state_recurrence_bit_for_bit():
+    q, k, v, g1, g2 = rand_case(500, B=2, T=17, H=3, dk=6, dv=5)
+    S1, S2 = rnd(501, 2, 3, 6, 5), rnd(502, 2, 3, 6, 5)
+    gamma, scale = 0.3, 0.8
+    ro, rS1, rS2 = orc.recurrent(q, k, v, g1, g2, gamma, scale, S1=S1, S2=S2)
+    for gb in (None, np.zeros((2, 2, 17, 3, 5))):      # no beta gate, and beta = 1 given explicitly
+        o, S = orc.nstate(q, k, v, np.stack([g1, g2]), gb, [gamma, 1.0 - gamma], scale, S=np.stack([S1, S2]))
+        assert np.array_equal(o, ro) and np.array_equal(S[0], rS1) and np.array_equal(S[1], rS2)
+    # one state = the dual-state layer with the second state switched off
+    o1, S = orc.nstate(q, k, v, g1[None], None, [1.0], scale, S=S1[None])
+    ro1, rS1b, _ = orc.recurrent(q, k, v, g1, g2, 1.0, scale, S1=S1, S2=S2)
+    np.testing.assert_allclose(o1, ro1, rtol=0, atol=1e-13)
+    assert np.array_equal(S[0], rS1b)
+
+
+def test_nstate_brute_force_python_loops():
+    N, B, T, H, Hkv, dk, dv = 3, 1, 6, 4, 2, 3, 2
+    q, k, v, ga, gb, w, S0 = nstate_case(520, N, B, T, H, Hkv, dk, dv)
+    o, S = orc.nstate(q, k, v, ga, gb, w, 0.7, S=S0)
+    ref_o = np.zeros((B, T, H, dv))
+    ref_S = S0.copy()
+    for b in range(B):
+        for h in range(H):
+            hk = h // (H // Hkv)
+            for t in range(T):
+                for n in range(N):
+                    for d in range(dk):
+                        for j in range(dv):
+                            ref_S[n, b, h, d, j] = (np.exp(ga[n, b, t, h, d]) * np.exp(gb[n, b, t, h, j]) * ref_S[n, b, h, d, j]
+                                                    + k[b, t, hk, d] * v[b, t, hk, j])
+                for j in range(dv):
+                    ref_o[b, t, h, j] = 0.7 * sum(q[b, t, h, d] * sum(w[n, h] * ref_S[n, b, h, d, j] for n in range(N))
+                                                  for d in range(dk))
+    np.testing.assert_allclose(o, ref_o, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(S, ref_S, rtol=1e-13, atol=1e-13)
+
+
+def test_nstate_unrolled_form_with_both_gate_vectors():
+    """Zero initial states: o_t[j] = scale sum_n w_n sum_{s<=t} (sum_d q_t[d] k_s[d] A^n_ts[d]) B^n_ts[j] v_s[j], with A and B
+    the products of alpha and beta over tau = s+1 .. t, taken here from cumulative sums of the log-gates."""
+    N, B, T, H, Hkv, dk, dv = 2, 1, 9, 2, 1, 4, 3
+    q, k, v, ga, gb, w, _ = nstate_case(530, N, B, T, H, Hkv, dk, dv)
+    o, _ = orc.nstate(q, k, v, ga, gb, w, 1.3)
+    ca, cb = np.cumsum(ga, axis=2), np.cumsum(gb, axis=2)
+    ref = np.zeros_like(o)
+    for h in range(H):
+        for t in range(T):
+            for s_ in range(t + 1):
+                for n in range(N):
+                    A = np.exp(ca[n, 0, t, h] - ca[n, 0, s_, h])
+                    Bv = np.exp(cb[n, 0, t, h] - cb[n, 0, s_, h])
+                    ref[0, t, h] += 1.3 * w[n, h] * np.sum(q[0, t, h] * k[0, s_, 0] * A) * Bv * v[0, s_, 0]
+    np.testing.assert_allclose(o, ref, rtol=1e-12, atol=1e-12)
+
+
+def test_nstate_geometric_closed_form_and_linearity_in_the_blend():
+    N, T, dk, dv = 2, 40, 3, 2
+    a = np.array([[0.9, 0.5, 1.0], [0.7, 0.99, 0.2]])
+    bt = np.array([[0.8, 1.0], [0.6, 0.95]])
+    kk, vv = np.array([0.3, -1.2, 2.0]), np.array([1.5, -0.4])
+    ga = np.log(a).reshape(N, 1, 1, 1, dk) * np.ones((N, 1, T, 1, dk))
+    gb = np.log(bt).reshape(N, 1, 1, 1, dv) * np.ones((N, 1, T, 1, dv))
+    k = kk.reshape(1, 1, 1, dk) * np.ones((1, T, 1, dk))
+    v = vv.reshape(1, 1, 1, dv) * np.ones((1, T, 1, dv))
+    q = rnd(541, 1, T, 1, dk)
+    o, S = orc.nstate(q, k, v, ga, gb, [0.4, 0.6])
+    for n in range(N):
+        r = a[n][:, None] * bt[n][None, :]
+        geo = np.where(r == 1.0, float(T), (1.0 - r ** T) / np.where(r == 1.0, 1.0, 1.0 - r))
+        np.testing.assert_allclose(S[n, 0, 0], geo * np.outer(kk, vv), rtol=1e-12)
+    parts = [orc.nstate(q, k, v, ga, gb, e)[0] for e in ([1.0, 0.0], [0.0, 1.0])]
+    np.testing.assert_allclose(o, 0.4 * parts[0] + 0.6 * parts[1], rtol=1e-12, atol=1e-13)
+
+
+def test_nstate_grouped_heads_equal_repeated_heads_and_planted_mistakes():
+    N, B, T, H, Hkv, dk, dv = 4, 2, 7, 6, 2, 4, 4
+    q, k, v, ga, gb, w, S0 = nstate_case(550, N, B, T, H, Hkv, dk, dv)
+    o, S = orc.nstate(q, k, v, ga, gb, w, 1.0, S=S0)
+    o_rep, S_rep = orc.nstate(q, np.repeat(k, H // Hkv, axis=2), np.repeat(v, H // Hkv, axis=2), ga, gb, w, 1.0, S=S0)
+    assert np.array_equal(o, o_rep) and np.array_equal(S, S_rep)
+    # mistakes that must show: heads interleaved instead of grouped, beta taken for alpha, states swapped in the blend
+    o_bad, _ = orc.nstate(q, np.tile(k, (1, 1, H // Hkv, 1)), np.tile(v, (1, 1, H // Hkv, 1)), ga, gb, w, 1.0, S=S0)
+    assert np.max(np.abs(o_bad - o)) > 1e-3
+    o_bad, _ = orc.nstate(q, k, v, gb, ga, w, 1.0, S=S0)          # dk == dv here, so the swap is well formed
+    assert np.max(np.abs(o_bad - o)) > 1e-3
+    o_bad, _ = orc.nstate(q, k, v, ga, gb, w[::-1].copy(), 1.0, S=S0)
+    assert np.max(np.abs(o_bad - o)) > 1e-3
+
+
 def test_oracle_threads_reported():
     assert orc.threads() >= 1
