@@ -229,6 +229,55 @@ DSLA_API dsla_status dsla_decode_slots(const dsla_desc *desc,
                               float *S1, float *S2, void *o, void *stream);
 
 /*
+ * More than two states, the general outer-product gate, grouped key/value heads.
+ *
+ * The background section on gated linear attention writes the forget gate of a state as a d_k x d_v matrix formed
+ * as the outer product of two vectors, G_t = alpha_t^T beta_t; Section 4.2 ("Why Two States Suffice?") and the
+ * ablation over the number of states in Section 5.5 consider the same layer with 1, 2, 4 or 8 states, each with its
+ * own gate; the Llama-3 teacher of Section 5.5 has grouped key/value heads.  For state n = 0 .. n_states - 1:
+ *     S^n_t[d][j] = alpha^n_t[d] beta^n_t[j] S^n_{t-1}[d][j] + k_t[d] v_t[j]
+ *     o_t         = scale * q_t * sum_n w_n S^n_t
+ * The paper prints the blend for two states only (gamma, 1 - gamma); one real coefficient per state is the reading
+ * taken for N states, and (gamma, 1 - gamma) is its case N = 2.  desc->gamma and desc->gamma_per_head are not used
+ * by these calls; everything else in the descriptor means what it means for dsla_prefill / dsla_decode
+ * (gate_mode applies to alpha and beta alike).
+ *   q, g_alpha[n]     : [B][T][H][d_k]      g_beta[n] : [B][T][H][d_v]      o : [B][T][H][d_v]
+ *   k                 : [B][T][H_kv][d_k]   v         : [B][T][H_kv][d_v]   head h reads key/value head h / (H / H_kv)
+ *   S[n]              : [B][H][d_k][d_v] fp32, one pair of pointers per state, every query head keeps its own states
+ * (decode: the same without the T index).
+ */
+#define DSLA_MAX_STATES 8
+typedef struct {
+    int32_t n_states;              /* 1 .. DSLA_MAX_STATES                                                      */
+    int32_t H_kv;                  /* key/value heads, a divisor of desc->H; 0 = desc->H                        */
+    const void *const *g_alpha;    /* HOST array [n_states] of DEVICE pointers: log alpha^n (or pre-activations) */
+    const void *const *g_beta;     /* HOST array [n_states] of DEVICE pointers (entries may be NULL), or NULL:
+                                      log beta^n; NULL means beta^n = 1                                         */
+    float *const *S;               /* HOST array [n_states] of DEVICE pointers, updated in place                */
+    const float *weights;          /* HOST array [n_states]: blend coefficients w_n of the layer                */
+    const float *weights_per_head; /* optional DEVICE array [n_states][H] overriding weights; or NULL           */
+} dsla_multi;
+
+/*
+ * dsla_decode_multi - one token per sequence for a layer described by desc and multi; every state is read once and
+ * written once.  All of n_states, both gate vectors and H_kv are supported.
+ */
+DSLA_API dsla_status dsla_decode_multi(const dsla_desc *desc, const dsla_multi *multi,
+                              const void *q, const void *k, const void *v, void *o, void *stream);
+
+/*
+ * dsla_prefill_multi - T tokens per sequence for a layer described by desc and multi.  The states are taken two at
+ * a time through the kernels of dsla_prefill (an odd one out runs with an idle partner), the later pairs adding
+ * their share to o; grouped key/value heads are an index map inside the kernels.  A beta gate is not supported by
+ * the prefill (DSLA_ERR_UNSUPPORTED when g_beta names one): a caller that needs it steps through dsla_decode_multi.
+ * workspace: at least dsla_prefill_multi_workspace_bytes(desc, multi, T) bytes, 256-byte aligned.
+ */
+DSLA_API size_t dsla_prefill_multi_workspace_bytes(const dsla_desc *desc, const dsla_multi *multi, int64_t T);
+DSLA_API dsla_status dsla_prefill_multi(const dsla_desc *desc, const dsla_multi *multi, int64_t T,
+                               const void *q, const void *k, const void *v, void *o,
+                               void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * dsla_attention_entropy - the sensitivity signal of Section 4.3 ("Layer Ranking via Sensitivity") for a
  * softmax-attention layer: for every (batch, head), the attention row of the final query over the T keys,
  * A_i = softmax_i(scale * q_T . k_i), and its entropy.  The paper's display shows sum_i A_i log A_i; this returns
@@ -281,7 +330,7 @@ DSLA_API const char *dsla_last_hip_error(void);
  * created by dsla_profile_enable, so the launch path still allocates nothing).
  * Kernel ids: 0 state_init, 1 prefill_segment_state, 2 prefill_segment_scan,
  * 3 prefill_chunk_loop, 4 decode, 5 prefill_segment_list (packed sequences only), 6 attention_entropy,
- * 7 attention_decode (each with its merge kernel).
+ * 7 attention_decode (each with its merge kernel), 8 decode_multi.
  */
 #define DSLA_KERNEL_STATE_INIT 0
 #define DSLA_KERNEL_PREFILL_SEGMENT_STATE 1
@@ -291,7 +340,8 @@ DSLA_API const char *dsla_last_hip_error(void);
 #define DSLA_KERNEL_PREFILL_SEGMENT_LIST 5
 #define DSLA_KERNEL_ATTENTION_ENTROPY 6
 #define DSLA_KERNEL_ATTENTION_DECODE 7
-#define DSLA_KERNEL_COUNT 8
+#define DSLA_KERNEL_DECODE_MULTI 8
+#define DSLA_KERNEL_COUNT 9
 
 /* enable != 0: create the event pool (max_records launches can be recorded between two
  * collects) and start recording; enable == 0: stop and destroy the pool. */

@@ -14,9 +14,10 @@ _lib = None
 
 DSLA_F32, DSLA_BF16 = 0, 1
 KERNEL_NAMES = ("state_init", "prefill_segment_state", "prefill_segment_scan", "prefill_chunk_loop", "decode",
-                "prefill_segment_list", "attention_entropy", "attention_decode")
+                "prefill_segment_list", "attention_entropy", "attention_decode", "decode_multi")
 EXPORTS = ("dsla_state_init", "dsla_prefill_workspace_bytes", "dsla_prefill", "dsla_prefill_static_ws", "dsla_decode",
            "dsla_prefill_varlen_workspace_bytes", "dsla_prefill_varlen", "dsla_decode_slots",
+           "dsla_decode_multi", "dsla_prefill_multi_workspace_bytes", "dsla_prefill_multi",
            "dsla_attention_entropy_workspace_bytes", "dsla_attention_entropy",
            "dsla_attention_decode_workspace_bytes", "dsla_attention_decode",
            "dsla_status_string", "dsla_last_hip_error", "dsla_profile_enable", "dsla_profile_collect")
@@ -29,6 +30,13 @@ class DslaDesc(ctypes.Structure):
                 ("gate_dtype", ctypes.c_int32), ("gate_mode", ctypes.c_int32), ("zero_init", ctypes.c_int32),
                 ("tau", ctypes.c_float), ("gamma", ctypes.c_float), ("scale", ctypes.c_float),
                 ("gamma_per_head", ctypes.c_void_p), ("status", ctypes.c_void_p)]
+
+
+class DslaMulti(ctypes.Structure):
+    """Mirror of `dsla_multi` in include/dsla.h."""
+    _fields_ = [("n_states", ctypes.c_int32), ("H_kv", ctypes.c_int32), ("g_alpha", ctypes.POINTER(ctypes.c_void_p)),
+                ("g_beta", ctypes.POINTER(ctypes.c_void_p)), ("S", ctypes.POINTER(ctypes.c_void_p)),
+                ("weights", ctypes.POINTER(ctypes.c_float)), ("weights_per_head", ctypes.c_void_p)]
 
 
 class DslaError(RuntimeError):
@@ -67,6 +75,13 @@ def load_library():
     lib.dsla_prefill_varlen.restype = ctypes.c_int
     lib.dsla_decode_slots.argtypes = [dp] + [vp] * 11
     lib.dsla_decode_slots.restype = ctypes.c_int
+    mp = ctypes.POINTER(DslaMulti)
+    lib.dsla_decode_multi.argtypes = [dp, mp] + [vp] * 5
+    lib.dsla_decode_multi.restype = ctypes.c_int
+    lib.dsla_prefill_multi_workspace_bytes.argtypes = [dp, mp, ctypes.c_int64]
+    lib.dsla_prefill_multi_workspace_bytes.restype = ctypes.c_size_t
+    lib.dsla_prefill_multi.argtypes = [dp, mp, ctypes.c_int64] + [vp] * 5 + [ctypes.c_size_t, vp]
+    lib.dsla_prefill_multi.restype = ctypes.c_int
     lib.dsla_attention_entropy_workspace_bytes.argtypes = [ctypes.c_int32] * 3 + [ctypes.c_int64]
     lib.dsla_attention_entropy_workspace_bytes.restype = ctypes.c_size_t
     lib.dsla_attention_entropy.argtypes = ([ctypes.c_int32] * 3 + [ctypes.c_int64, ctypes.c_int32, ctypes.c_float]
@@ -175,6 +190,42 @@ def dsla_decode_slots(desc: DslaDesc, q, k, v, g1, g2, state_slot, S1, S2, o, ro
     """One decode step on states picked from a pool (include/dsla.h: dsla_decode_slots)."""
     _check(load_library().dsla_decode_slots(ctypes.byref(desc), _ptr(q), _ptr(k), _ptr(v), _ptr(g1), _ptr(g2),
                                             _ptr(row_index), _ptr(state_slot), _ptr(S1), _ptr(S2), _ptr(o), _stream()))
+
+
+def make_multi(g_alpha, S, weights, *, g_beta=None, H_kv=0, weights_per_head=None) -> DslaMulti:
+    """dsla_multi from lists of GPU tensors (one per state).  The returned structure keeps the host arrays it
+    points to alive (attribute _keep); the caller keeps the tensors alive."""
+    n = len(g_alpha)
+    assert len(S) == n and len(weights) == n and (g_beta is None or len(g_beta) == n)
+    ga = (ctypes.c_void_p * n)(*[t.data_ptr() for t in g_alpha])
+    gb = None
+    if g_beta is not None:
+        gb = (ctypes.c_void_p * n)(*[(t.data_ptr() if t is not None else None) for t in g_beta])
+    Sp = (ctypes.c_void_p * n)(*[t.data_ptr() for t in S])
+    w = (ctypes.c_float * n)(*[float(x) for x in weights])
+    wph = ctypes.c_void_p(weights_per_head.data_ptr()) if weights_per_head is not None else None
+    m = DslaMulti(n, int(H_kv), ctypes.cast(ga, ctypes.POINTER(ctypes.c_void_p)),
+                  ctypes.cast(gb, ctypes.POINTER(ctypes.c_void_p)) if gb is not None else None,
+                  ctypes.cast(Sp, ctypes.POINTER(ctypes.c_void_p)), ctypes.cast(w, ctypes.POINTER(ctypes.c_float)), wph)
+    m._keep = (ga, gb, Sp, w)
+    return m
+
+
+def dsla_decode_multi(desc: DslaDesc, multi: DslaMulti, q, k, v, o):
+    """One decode step of a layer with N states (include/dsla.h: dsla_decode_multi)."""
+    _check(load_library().dsla_decode_multi(ctypes.byref(desc), ctypes.byref(multi), _ptr(q), _ptr(k), _ptr(v), _ptr(o),
+                                            _stream()))
+
+
+def dsla_prefill_multi_workspace_bytes(desc: DslaDesc, multi: DslaMulti, T: int) -> int:
+    return int(load_library().dsla_prefill_multi_workspace_bytes(ctypes.byref(desc), ctypes.byref(multi), int(T)))
+
+
+def dsla_prefill_multi(desc: DslaDesc, multi: DslaMulti, T, q, k, v, o, workspace=None):
+    """Prefill of a layer with N states (include/dsla.h: dsla_prefill_multi)."""
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(load_library().dsla_prefill_multi(ctypes.byref(desc), ctypes.byref(multi), int(T), _ptr(q), _ptr(k), _ptr(v),
+                                             _ptr(o), _ptr(workspace), wbytes, _stream()))
 
 
 def dsla_attention_entropy_workspace_bytes(B: int, H: int, d: int, T: int) -> int:

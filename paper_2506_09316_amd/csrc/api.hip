@@ -246,6 +246,109 @@ dsla_status dsla_decode_slots(const dsla_desc *desc, const void *q, const void *
                                     static_cast<hipStream_t>(stream)));
 }
 
+namespace {
+// Argument checks shared by the calls for N states; fills the by-value pointer block.
+dsla_status check_multi(const dsla_desc *desc, const dsla_multi *m, bool with_beta, MultiStatePtrs *mp, int *Hkv)
+{
+    dsla_status st = check_desc(desc);
+    if (st != DSLA_OK) return st;
+    if (!m || !m->g_alpha || !m->S || !m->weights) return DSLA_ERR_NULL;
+    if (m->n_states < 1 || m->n_states > DSLA_MAX_STATES || m->H_kv < 0) return DSLA_ERR_SHAPE;
+    *Hkv = m->H_kv ? m->H_kv : desc->H;
+    if (*Hkv > desc->H || desc->H % *Hkv != 0) return DSLA_ERR_SHAPE;
+    if (reinterpret_cast<uintptr_t>(m->weights_per_head) & 3u) return DSLA_ERR_SHAPE;
+    for (int n = 0; n < DSLA_MAX_STATES; ++n) {
+        mp->ga[n] = mp->gb[n] = nullptr;
+        mp->S[n] = nullptr;
+        mp->w[n] = 0.f;
+    }
+    for (int n = 0; n < m->n_states; ++n) {
+        if (!m->g_alpha[n] || !m->S[n]) return DSLA_ERR_NULL;
+        const void *gb = m->g_beta ? m->g_beta[n] : nullptr;
+        if (gb && !with_beta) return DSLA_ERR_UNSUPPORTED;
+        if (!aligned16(m->g_alpha[n]) || !aligned16(m->S[n]) || !aligned16(gb)) return DSLA_ERR_SHAPE;
+        for (int n2 = 0; n2 < n; ++n2)
+            if (m->S[n2] == m->S[n]) return DSLA_ERR_SHAPE;   // two states in one buffer
+        mp->ga[n] = m->g_alpha[n];
+        mp->gb[n] = gb;
+        mp->S[n] = m->S[n];
+        mp->w[n] = m->weights[n];
+    }
+    return DSLA_OK;
+}
+}  // namespace
+
+dsla_status dsla_decode_multi(const dsla_desc *desc, const dsla_multi *multi, const void *q, const void *k,
+                              const void *v, void *o, void *stream)
+{
+    MultiStatePtrs mp;
+    int Hkv = 0;
+    dsla_status st = check_multi(desc, multi, true, &mp, &Hkv);
+    if (st != DSLA_OK) return st;
+    if (!q || !k || !v || !o) return DSLA_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return DSLA_ERR_SHAPE;
+    return hip_status(launch_decode_multi(*desc, mp, multi->n_states, Hkv, multi->weights_per_head, q, k, v, nullptr,
+                                          nullptr, o, static_cast<hipStream_t>(stream)));
+}
+
+size_t dsla_prefill_multi_workspace_bytes(const dsla_desc *desc, const dsla_multi *multi, int64_t T)
+{
+    if (check_desc(desc) != DSLA_OK || !multi || multi->n_states < 1 || multi->n_states > DSLA_MAX_STATES || T <= 0)
+        return 0;
+    PrefillPlan plan;
+    if (!prefill_plan(*desc, T, &plan)) return 0;
+    // an odd state out runs beside an idle partner, whose states live behind the plan's own scratch
+    const size_t partner = (multi->n_states & 1) ? plan.state_elems * sizeof(float) : 0;
+    return (plan.ws_total_bytes + 255) / 256 * 256 + partner;
+}
+
+dsla_status dsla_prefill_multi(const dsla_desc *desc, const dsla_multi *multi, int64_t T, const void *q, const void *k,
+                               const void *v, void *o, void *workspace, size_t workspace_bytes, void *stream)
+{
+    MultiStatePtrs mp;
+    int Hkv = 0;
+    dsla_status st = check_multi(desc, multi, false, &mp, &Hkv);
+    if (st != DSLA_OK) return st;
+    if (T < 0 || T > (int64_t(1) << 40)) return DSLA_ERR_SHAPE;
+    if (T == 0) return DSLA_OK;
+    if (!q || !k || !v || !o) return DSLA_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return DSLA_ERR_SHAPE;
+    PrefillPlan plan;
+    if (!prefill_plan(*desc, T, &plan)) return DSLA_ERR_UNSUPPORTED;
+    if (static_cast<int64_t>(desc->B) * desc->H * plan.segments > 0x7fffffffLL) return DSLA_ERR_SHAPE;
+    const size_t need = dsla_prefill_multi_workspace_bytes(desc, multi, T);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return DSLA_ERR_WORKSPACE;
+        if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return DSLA_ERR_SHAPE;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int N = multi->n_states;
+    float *partner = reinterpret_cast<float *>(static_cast<char *>(workspace) + (plan.ws_total_bytes + 255) / 256 * 256);
+    const float *wph = multi->weights_per_head;
+    for (int n = 0; n < N; n += 2) {
+        const bool pair = n + 1 < N;
+        PrefillExt ext;
+        ext.Hkv = Hkv;
+        ext.accumulate = n > 0;
+        ext.wa = mp.w[n];
+        ext.wb = pair ? mp.w[n + 1] : 0.f;
+        ext.wa_per_head = wph ? wph + static_cast<size_t>(n) * desc->H : nullptr;
+        ext.wb_per_head = (wph && pair) ? wph + static_cast<size_t>(n + 1) * desc->H : nullptr;
+        const void *gb = pair ? mp.ga[n + 1] : mp.ga[n];   // the idle partner follows the gates of its neighbour
+        float *Sb = pair ? mp.S[n + 1] : partner;
+        dsla_desc d = *desc;
+        if (!pair && !d.zero_init) {
+            // the idle partner starts from zero and its blend coefficient is zero: it stays finite and adds nothing
+            hipError_t e = launch_state_init(partner, partner + plan.state_elems / 2, plan.state_elems / 2, s);
+            if (e != hipSuccess) return hip_status(e);
+        }
+        hipError_t e = launch_prefill(d, plan, T, nullptr, nullptr, nullptr, q, k, v, mp.ga[n], gb, mp.S[n], Sb, o,
+                                      workspace, s, &ext);
+        if (e != hipSuccess) return hip_status(e);
+    }
+    return DSLA_OK;
+}
+
 size_t dsla_attention_entropy_workspace_bytes(int32_t B, int32_t H, int32_t d, int64_t T)
 {
     EntropyPlan plan;

@@ -117,6 +117,119 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
     }
 }
 
+// The decode step with N states, the outer-product gate and grouped key/value heads (background section on gated
+// linear attention; Section 4.2; the state-count ablation of Section 5.5): per state n
+//     S^n[d][j] <- alpha^n[d] beta^n[j] S^n[d][j] + k[d] v[j],       o[j] = scale sum_d q[d] sum_n w_n S^n[d][j].
+// Same streaming pattern as decode_kernel; the states are taken one after the other, the loads of the next state in
+// flight while the current one is updated, so every state is still read once and written once.
+template <int DK, int DV, int SPLIT, class TIO, class TG>
+__global__ __launch_bounds__(kDecodeThreads) void decode_multi_kernel(
+    const TIO *__restrict__ q, const TIO *__restrict__ k, const TIO *__restrict__ v, MultiStatePtrs mp, int N,
+    const int32_t *__restrict__ row, const int32_t *__restrict__ slot, TIO *__restrict__ o, int H, int Hkv,
+    const float *__restrict__ w_per_head, float scale, float gate_inv_tau)
+{
+    constexpr int COLG = DV / 4 / SPLIT;
+    constexpr int ROWG = kDecodeThreads / COLG;
+    constexpr int ROWS = DK / ROWG;
+    constexpr int ROWF4 = DV / 4;
+    constexpr int NMAX = DSLA_MAX_STATES;
+    __shared__ float s_q[DK], s_k[DK], s_alpha[NMAX][DK], s_beta[NMAX][COLG * 4], s_w[NMAX];
+    __shared__ float4 s_red[kDecodeThreads / 64][COLG];
+
+    const int bh = blockIdx.x / SPLIT;
+    const int part = blockIdx.x % SPLIT;
+    const int tid = threadIdx.x;
+    const int cg = tid % COLG;
+    const int rg = tid / COLG;
+    const int b = bh / H, h = bh % H;
+    const size_t sbase = ((slot ? static_cast<size_t>(slot[b]) : static_cast<size_t>(b)) * H + h) * DK * DV;
+    const size_t c4 = static_cast<size_t>(part) * COLG + cg;   // this thread's float4 inside a state row
+
+    auto load_state = [&](int n, float4 (&x)[ROWS]) {
+        const float4 *p = reinterpret_cast<const float4 *>(mp.S[n] + sbase) + c4;
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) x[j] = p[static_cast<size_t>(rg + j * ROWG) * ROWF4];
+    };
+    float4 cur[ROWS], nxt[ROWS];
+    load_state(0, cur);
+
+    // per-token vectors -> LDS: q, k once, the gates of every state
+    const size_t trow = row ? static_cast<size_t>(row[b]) : static_cast<size_t>(b);
+    const size_t tq = (trow * H + h) * DK;                         // q, alpha gates
+    const size_t tk = (trow * Hkv + h / (H / Hkv)) * DK;           // k: the key/value head of this group
+    auto log_gate = [&](float x) -> float {
+        if (gate_inv_tau != 0.f) x = (fminf(x, 0.f) - log1pf(expf(-fabsf(x)))) * gate_inv_tau;
+        return x;
+    };
+    for (int d = tid; d < DK; d += kDecodeThreads) {
+        s_q[d] = scale * to_f32(q[tq + d]);
+        s_k[d] = to_f32(k[tk + d]);
+    }
+    for (int i = tid; i < N * DK; i += kDecodeThreads) {
+        const int n = i / DK, d = i % DK;
+        s_alpha[n][d] = __expf(log_gate(to_f32(static_cast<const TG *>(mp.ga[n])[tq + d])));
+    }
+    for (int i = tid; i < N * COLG * 4; i += kDecodeThreads) {
+        const int n = i / (COLG * 4), c = i % (COLG * 4);
+        const size_t col = (trow * H + h) * DV + part * COLG * 4 + c;
+        s_beta[n][c] = mp.gb[n] ? __expf(log_gate(to_f32(static_cast<const TG *>(mp.gb[n])[col]))) : 1.0f;
+    }
+    if (tid < N) s_w[tid] = w_per_head ? w_per_head[static_cast<size_t>(tid) * H + h] : mp.w[tid];
+    const TIO *vp = v + (trow * Hkv + h / (H / Hkv)) * DV + c4 * 4;
+    const float v0 = to_f32(vp[0]), v1 = to_f32(vp[1]), v2 = to_f32(vp[2]), v3 = to_f32(vp[3]);
+    __syncthreads();
+
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int n = 0; n < N; ++n) {
+        if (n + 1 < N) load_state(n + 1, nxt);
+        float4 *p = reinterpret_cast<float4 *>(mp.S[n] + sbase) + c4;
+        const float b0 = s_beta[n][cg * 4 + 0], b1 = s_beta[n][cg * 4 + 1], b2 = s_beta[n][cg * 4 + 2],
+                    b3 = s_beta[n][cg * 4 + 3];
+        const float wn = s_w[n];
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) {
+            const int r = rg + j * ROWG;
+            const float a = s_alpha[n][r], kd = s_k[r], qw = s_q[r] * wn;
+            float4 x = cur[j];
+            x.x = fmaf(a * b0, x.x, kd * v0);
+            x.y = fmaf(a * b1, x.y, kd * v1);
+            x.z = fmaf(a * b2, x.z, kd * v2);
+            x.w = fmaf(a * b3, x.w, kd * v3);
+            p[static_cast<size_t>(r) * ROWF4] = x;
+            acc.x = fmaf(qw, x.x, acc.x);
+            acc.y = fmaf(qw, x.y, acc.y);
+            acc.z = fmaf(qw, x.z, acc.z);
+            acc.w = fmaf(qw, x.w, acc.w);
+        }
+#pragma unroll
+        for (int j = 0; j < ROWS; ++j) cur[j] = nxt[j];
+    }
+
+#pragma unroll
+    for (int off = 32; off >= COLG; off >>= 1) {
+        acc.x += __shfl_xor(acc.x, off);
+        acc.y += __shfl_xor(acc.y, off);
+        acc.z += __shfl_xor(acc.z, off);
+        acc.w += __shfl_xor(acc.w, off);
+    }
+    const int wave = tid / 64, lane = tid % 64;
+    if (lane < COLG) s_red[wave][lane] = acc;
+    __syncthreads();
+    if (tid < COLG) {
+        float4 r = s_red[0][tid];
+#pragma unroll
+        for (int w = 1; w < kDecodeThreads / 64; ++w) {
+            const float4 t = s_red[w][tid];
+            r.x += t.x; r.y += t.y; r.z += t.z; r.w += t.w;
+        }
+        TIO *op = o + (trow * H + h) * DV + (part * COLG + tid) * 4;
+        op[0] = from_f32<TIO>(r.x);
+        op[1] = from_f32<TIO>(r.y);
+        op[2] = from_f32<TIO>(r.z);
+        op[3] = from_f32<TIO>(r.w);
+    }
+}
+
 __global__ __launch_bounds__(256) void state_init_kernel(float4 *__restrict__ S1, float4 *__restrict__ S2, size_t n4)
 {
     const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -157,7 +270,41 @@ hipError_t launch_decode_d(const dsla_desc &d, const void *q, const void *k, con
     return launch_decode_t<D, float, float>(d, q, k, v, g1, g2, row, slot, S1, S2, o, stream);
 }
 
+template <int D, class TIO, class TG>
+hipError_t launch_decode_multi_t(const dsla_desc &d, const MultiStatePtrs &mp, int N, int Hkv, const float *w_per_head,
+                                 const void *q, const void *k, const void *v, const int32_t *row, const int32_t *slot,
+                                 void *o, hipStream_t stream)
+{
+    const unsigned grid = static_cast<unsigned>(d.B) * static_cast<unsigned>(d.H) * kDecodeSplit;
+    ProfileScope ps(DSLA_KERNEL_DECODE_MULTI, stream);
+    hipLaunchKernelGGL((decode_multi_kernel<D, D, kDecodeSplit, TIO, TG>), dim3(grid), dim3(kDecodeThreads), 0, stream,
+                       static_cast<const TIO *>(q), static_cast<const TIO *>(k), static_cast<const TIO *>(v), mp, N, row, slot,
+                       static_cast<TIO *>(o), d.H, Hkv, w_per_head, d.scale,
+                       d.gate_mode == DSLA_GATE_PREACT ? 1.0f / d.tau : 0.f);
+    return hipGetLastError();
+}
+
+template <int D>
+hipError_t launch_decode_multi_d(const dsla_desc &d, const MultiStatePtrs &mp, int N, int Hkv, const float *w_per_head,
+                                 const void *q, const void *k, const void *v, const int32_t *row, const int32_t *slot,
+                                 void *o, hipStream_t stream)
+{
+    const bool io16 = d.io_dtype == DSLA_BF16, g16 = d.gate_dtype == DSLA_BF16;
+    if (io16 && g16) return launch_decode_multi_t<D, bf16_t, bf16_t>(d, mp, N, Hkv, w_per_head, q, k, v, row, slot, o, stream);
+    if (io16 && !g16) return launch_decode_multi_t<D, bf16_t, float>(d, mp, N, Hkv, w_per_head, q, k, v, row, slot, o, stream);
+    if (!io16 && g16) return launch_decode_multi_t<D, float, bf16_t>(d, mp, N, Hkv, w_per_head, q, k, v, row, slot, o, stream);
+    return launch_decode_multi_t<D, float, float>(d, mp, N, Hkv, w_per_head, q, k, v, row, slot, o, stream);
+}
+
 }  // namespace
+
+hipError_t launch_decode_multi(const dsla_desc &d, const MultiStatePtrs &mp, int N, int Hkv, const float *w_per_head,
+                               const void *q, const void *k, const void *v, const int32_t *row, const int32_t *slot,
+                               void *o, hipStream_t stream)
+{
+    if (d.d_k == 128) return launch_decode_multi_d<128>(d, mp, N, Hkv, w_per_head, q, k, v, row, slot, o, stream);
+    return launch_decode_multi_d<64>(d, mp, N, Hkv, w_per_head, q, k, v, row, slot, o, stream);
+}
 
 bool decode_supported(const dsla_desc &d) { return d.d_k == d.d_v && (d.d_k == 64 || d.d_k == 128); }
 

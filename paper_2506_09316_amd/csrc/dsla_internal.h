@@ -50,6 +50,17 @@ hipError_t launch_decode(const dsla_desc &d, const void *q, const void *k, const
                          void *o, hipStream_t stream);
 bool decode_supported(const dsla_desc &d);
 
+// The per-state pointers and layer-wide blend coefficients of a call with N states, passed to kernels by value.
+struct MultiStatePtrs {
+    const void *ga[DSLA_MAX_STATES];   // log alpha (or pre-activations) of state n: [..][H][d_k]
+    const void *gb[DSLA_MAX_STATES];   // log beta of state n: [..][H][d_v], or null (beta = 1)
+    float *S[DSLA_MAX_STATES];         // [slots][H][d_k][d_v]
+    float w[DSLA_MAX_STATES];          // blend coefficient of state n
+};
+hipError_t launch_decode_multi(const dsla_desc &d, const MultiStatePtrs &mp, int N, int Hkv, const float *w_per_head,
+                               const void *q, const void *k, const void *v, const int32_t *row_index,
+                               const int32_t *state_slot, void *o, hipStream_t stream);
+
 // Prefill plan: how a sequence is cut into segments and chunks.
 struct PrefillPlan {
     int chunk;               // C
@@ -68,9 +79,18 @@ bool prefill_plan_varlen(const dsla_desc &d, int64_t total_T, int64_t max_T, Pre
 // cu_seqlens == nullptr: B sequences of T tokens each; else packed sequences and T = upper bound of their lengths.
 // seq_index (with cu_seqlens only): which packed sequences take part; nullptr: all, in order.
 // state_slot == nullptr: sequence b owns entry b of S1, S2.
+// ext (or nullptr): a launch for one pair of states of a layer with N states: explicit blend coefficients, key/value
+// heads shared by groups of query heads, and the result added to what o holds.
+struct PrefillExt {
+    int Hkv;
+    int accumulate;
+    float wa, wb;
+    const float *wa_per_head, *wb_per_head;   // optional device arrays [H]
+};
 hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T, const int32_t *cu_seqlens,
                           const int32_t *seq_index, const int32_t *state_slot, const void *q, const void *k, const void *v, const void *g1,
-                          const void *g2, float *S1, float *S2, void *o, void *workspace, hipStream_t stream);
+                          const void *g2, float *S1, float *S2, void *o, void *workspace, hipStream_t stream,
+                          const PrefillExt *ext = nullptr);
 
 // Single-query attention kernels (entropy of the final query, decode attention over a cache): the keys of one
 // (batch, head) are split into `parts` ranges, each leaving a record of floats_per_part floats to merge.

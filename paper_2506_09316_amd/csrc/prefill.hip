@@ -391,6 +391,13 @@ struct PrefillArgs {
     int zero_init;           // nonzero: the states are zero on entry (the caller's S1, S2 are only written)
     int32_t *status;         // optional device word: set to DSLA_STATUS_GATE_DOMAIN by a step whose gates leave the domain
     float gamma, scale;
+    // Extended launches (Kern<.., kExt = true>): explicit blend coefficients of the two states instead of
+    // (gamma, 1 - gamma), key/value heads shared by groups of query heads, and output added to what o holds.
+    int Hkv;                 // key/value heads (k, v are [..][Hkv][D]); == H in ordinary launches
+    int explicit_w;          // nonzero: the blend coefficients are wa, wb (or the per-head arrays)
+    int accumulate;          // nonzero: o += result instead of o = result
+    float wa, wb;
+    const float *wa_per_head, *wb_per_head;   // optional [H]
     float gate_inv_tau;      // 0: g1, g2 are log-gates; else they are pre-activations and this is 1 / tau
 };
 
@@ -414,7 +421,7 @@ struct PrefillArgs {
 //     T <-  diag(2^{-(R + R_next)/2}) T          (R_next = 0 after the last step)
 // Centring halves the largest exponent a step can produce: the factors stay finite while R < 2 * 115, and nothing
 // links the exponents of different steps.
-template <int D, class TIO, class TG, bool kFull>
+template <int D, class TIO, class TG, bool kFull, bool kExt = false>
 struct Kern {
     using A = ArithOf<TIO>;
     using Frag = typename A::Frag;
@@ -483,6 +490,8 @@ struct Kern {
         const TIO *q, *k, *v;   // uniform: first token of the step, this (batch, head)
         const TG *g1, *g2;
         uint32_t off[RPT];      // per lane: element offset of token 2 sg + j, features 32 pw + 8 dgl ..
+        uint32_t offkv[RPT];    // the same inside k and v when they have fewer heads (kExt only)
+        __device__ __forceinline__ uint32_t kv(int j) const { return kExt ? offkv[j] : off[j]; }
     };
     static __device__ __forceinline__ void load_gates(RawGates &g, const StepSrc &s)
     {
@@ -496,9 +505,9 @@ struct Kern {
     {
 #pragma unroll
         for (int j = 0; j < RPT; ++j) {
-            r.k[j].load(s.k, s.off[j]);
+            r.k[j].load(s.k, s.kv(j));
             if (kFull) r.q[j].load(s.q, s.off[j]);
-            r.v[j].load(s.v, s.off[j]);
+            r.v[j].load(s.v, s.kv(j));
         }
     }
     // The loads a producer issues while it prepares step m, one at a time between its stages: q, k, v of step
@@ -517,12 +526,12 @@ struct Kern {
             if (slot == 1) g.g1[1].load(gs.g1, gs.off[1]);
             if (slot == 2) g.g2[0].load(gs.g2, gs.off[0]);
             if (slot == 3) g.g2[1].load(gs.g2, gs.off[1]);
-            if (slot == 4) r.k[0].load(rs.k, rs.off[0]);
-            if (slot == 5) r.k[1].load(rs.k, rs.off[1]);
+            if (slot == 4) r.k[0].load(rs.k, rs.kv(0));
+            if (slot == 5) r.k[1].load(rs.k, rs.kv(1));
             if (slot == 6 && kFull) r.q[0].load(rs.q, rs.off[0]);
             if (slot == 7 && kFull) r.q[1].load(rs.q, rs.off[1]);
-            if (slot == 8) r.v[0].load(rs.v, rs.off[0]);
-            if (slot == 9) r.v[1].load(rs.v, rs.off[1]);
+            if (slot == 8) r.v[0].load(rs.v, rs.kv(0));
+            if (slot == 9) r.v[1].load(rs.v, rs.kv(1));
         }
     };
 
@@ -753,21 +762,30 @@ struct Kern {
     // Staged output rows of one step -> memory.  Consumer wavefront ct writes rows 32/CT * ct ..; a group of NC lanes
     // writes one whole row.
     static __device__ __forceinline__ void flush_rows(uint32_t sm, uint32_t parity, int ct, int lane, TIO *orow, uint32_t rs,
-                                                      int valid)
+                                                      int valid, bool accumulate)
     {
         constexpr int RPI = 64 / NC;   // rows per instruction
 #pragma unroll
         for (int it = 0; it < 2; ++it) {
             const uint32_t r = (S / CT) * ct + RPI * it + static_cast<uint32_t>(lane) / NC, c = static_cast<uint32_t>(lane) % NC;
             const uint32_t a = sm + O_ST + parity * ST_BYTES + r * (D * ESZ) + ((c ^ (r & (NC - 1))) << 4);
-            const u32x4 x = lds_ld<u32x4>(a);
-            if (static_cast<int>(r) < valid)
-                *reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(orow) + (static_cast<size_t>(r) * rs * ESZ + c * 16)) = x;
+            u32x4 x = lds_ld<u32x4>(a);
+            if (static_cast<int>(r) < valid) {
+                u32x4 *dst = reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(orow) + (static_cast<size_t>(r) * rs * ESZ + c * 16));
+                if (kExt && accumulate) {   // staged tiles are 16-bit: add to the eight values already there
+                    const u32x4 old = *dst;
+#pragma unroll
+                    for (int w = 0; w < 4; ++w)
+                        x[w] = ArithBf16::pack2(__uint_as_float(x[w] << 16) + __uint_as_float(old[w] << 16),
+                                                __uint_as_float(x[w] & 0xffff0000u) + __uint_as_float(old[w] & 0xffff0000u));
+                }
+                *dst = x;
+            }
         }
     }
 
     static __device__ __forceinline__ void consume(uint32_t sm, uint32_t set, f32x16 (&acc)[2][DT], int ct, int lane,
-                                                   TIO *orow, uint32_t rs, int valid, uint32_t set_parity)
+                                                   TIO *orow, uint32_t rs, int valid, uint32_t set_parity, bool accumulate)
     {
         const uint32_t lo = opaque(static_cast<uint32_t>(lane));
         const uint32_t ln = lo & 31, g = lo >> 5;
@@ -852,8 +870,16 @@ struct Kern {
         } else if (kFull && static_cast<int>(ln) < valid) {
             TIO *op = orow + static_cast<size_t>(ln) * rs + 32 * ct + 4 * g;
 #pragma unroll
-            for (int jb = 0; jb < 4; ++jb)
-                store4_global(op + 8 * jb, oacc[4 * jb], oacc[4 * jb + 1], oacc[4 * jb + 2], oacc[4 * jb + 3]);
+            for (int jb = 0; jb < 4; ++jb) {
+                float x0 = oacc[4 * jb], x1 = oacc[4 * jb + 1], x2 = oacc[4 * jb + 2], x3 = oacc[4 * jb + 3];
+                if (kExt && accumulate) {
+                    x0 += to_f32(op[8 * jb]);
+                    x1 += to_f32(op[8 * jb + 1]);
+                    x2 += to_f32(op[8 * jb + 2]);
+                    x3 += to_f32(op[8 * jb + 3]);
+                }
+                store4_global(op + 8 * jb, x0, x1, x2, x3);
+            }
         }
 
         // ---- the states move to the middle frame of the next step (after the last step: to their own frame) ----
@@ -961,24 +987,25 @@ struct Kern {
                         for (int j = 0; j < 16; ++j) acc[i][dt][j] = 0.f;
             }
             TIO *orow = static_cast<TIO *>(a.o) + seg0;
+            const bool accum = kExt && a.accumulate;
             lds_barrier();   // operands of step 0 are ready
             if (kFull) rescale(acc, sm + O_ENT + static_cast<uint32_t>(8 * g) * 4);   // into the middle frame of step 0
             for (int n = 0; n < nsteps; n += 2) {
-                if (kStage && n > 0) flush_rows(sm, 1, ct, lane, orow - sstep, rs, S);
-                consume(sm, 0, acc, ct, lane, orow, rs, valid_of(n), 0);
+                if (kStage && n > 0) flush_rows(sm, 1, ct, lane, orow - sstep, rs, S, accum);
+                consume(sm, 0, acc, ct, lane, orow, rs, valid_of(n), 0, accum);
                 orow += sstep;
                 lds_barrier();                    // step n consumed (two sets: and step n+1 ready)
                 if (SETS == 1) lds_barrier();     // one set: step n+1 ready
                 if (n + 1 < nsteps) {
-                    if (kStage) flush_rows(sm, 0, ct, lane, orow - sstep, rs, S);
-                    consume(sm, SETS - 1, acc, ct, lane, orow, rs, valid_of(n + 1), 1);
+                    if (kStage) flush_rows(sm, 0, ct, lane, orow - sstep, rs, S, accum);
+                    consume(sm, SETS - 1, acc, ct, lane, orow, rs, valid_of(n + 1), 1, accum);
                     orow += sstep;
                 }
                 lds_barrier();
                 if (SETS == 1) lds_barrier();
             }
             // the last step (every staged row has passed a barrier)
-            if (kStage) flush_rows(sm, (nsteps - 1) & 1, ct, lane, orow - sstep, rs, valid_of(nsteps - 1));
+            if (kStage) flush_rows(sm, (nsteps - 1) & 1, ct, lane, orow - sstep, rs, valid_of(nsteps - 1), accum);
             // ---- write the states out ----
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
@@ -1001,7 +1028,11 @@ struct Kern {
             // =============================== producer ===============================
             const int pw = wave - CT;
             const float gm = a.gamma_per_head ? a.gamma_per_head[h] : a.gamma;
-            const float gsv[2] = {gm * a.scale, (1.0f - gm) * a.scale};
+            float gsv[2] = {gm * a.scale, (1.0f - gm) * a.scale};
+            if (kExt && a.explicit_w) {
+                gsv[0] = (a.wa_per_head ? a.wa_per_head[h] : a.wa) * a.scale;
+                gsv[1] = (a.wb_per_head ? a.wb_per_head[h] : a.wb) * a.scale;
+            }
             const float lg[2] = {__builtin_amdgcn_logf(fabsf(gsv[0])), __builtin_amdgcn_logf(fabsf(gsv[1]))};
             const uint32_t sgn[2] = {gsv[0] < 0.f ? A::kSignBits : 0u, gsv[1] < 0.f ? A::kSignBits : 0u};
             float seg_decay = 0.f;   // lane l: log2 of the segment decay of (state l / 32, feature 32 pw + l % 32)
@@ -1010,8 +1041,12 @@ struct Kern {
             pa.preact = a.gate_inv_tau != 0.f;
             pa.unit = pa.preact ? a.gate_inv_tau : kLog2e;
 
-            const TIO *q0 = static_cast<const TIO *>(a.q) + seg0, *k0 = static_cast<const TIO *>(a.k) + seg0,
-                      *v0 = static_cast<const TIO *>(a.v) + seg0;
+            // k and v of an extended launch: Hkv heads, head h reads key/value head h / (H / Hkv)
+            const uint32_t rskv = kExt ? static_cast<uint32_t>(a.Hkv) * D : rs;
+            const size_t seg0kv = kExt ? (static_cast<size_t>(seq0 + t0) * a.Hkv + h / (a.H / a.Hkv)) * D : seg0;
+            const size_t sstepkv = static_cast<size_t>(S) * rskv;
+            const TIO *q0 = static_cast<const TIO *>(a.q) + seg0, *k0 = static_cast<const TIO *>(a.k) + seg0kv,
+                      *v0 = static_cast<const TIO *>(a.v) + seg0kv;
             const TG *g10 = static_cast<const TG *>(a.g1) + seg0, *g20 = static_cast<const TG *>(a.g2) + seg0;
             const uint32_t lane_col = 32 * pw + 8 * (lane & 3);
             auto src_of = [&](int n) -> StepSrc {   // step n, or the last step when n is past the end
@@ -1019,12 +1054,14 @@ struct Kern {
                 const size_t so = static_cast<size_t>(m) * sstep;
                 const int vm = valid_of(m);   // >= 1
                 StepSrc s;
-                s.q = q0 + so; s.k = k0 + so; s.v = v0 + so; s.g1 = g10 + so; s.g2 = g20 + so;
+                const size_t sokv = static_cast<size_t>(m) * sstepkv;
+                s.q = q0 + so; s.k = k0 + sokv; s.v = v0 + sokv; s.g1 = g10 + so; s.g2 = g20 + so;
 #pragma unroll
                 for (int j = 0; j < RPT; ++j) {
                     uint32_t row = pa.sg * RPT + j;
                     row = row < static_cast<uint32_t>(vm) ? row : static_cast<uint32_t>(vm - 1);
                     s.off[j] = row * rs + lane_col;
+                    if (kExt) s.offkv[j] = row * rskv + lane_col;
                 }
                 return s;
             };
@@ -1080,10 +1117,10 @@ struct Kern {
     }
 };
 
-template <int D, class TIO, class TG, bool kFull>
+template <int D, class TIO, class TG, bool kFull, bool kExt>
 __global__ __launch_bounds__(4 * D, 2) void prefill_kernel(PrefillArgs a)
 {
-    using K = Kern<D, TIO, TG, kFull>;
+    using K = Kern<D, TIO, TG, kFull, kExt>;
     __shared__ __attribute__((aligned(16))) char smem[K::LDS_BYTES];
     K::run(a, lds_addr_of(smem));
 }
@@ -1196,8 +1233,8 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restri
 }
 
 
-template <int D, class TIO, class TG>
-hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a, hipStream_t stream)
+template <int D, class TIO, class TG, bool kExt>
+hipError_t launch_x(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a, hipStream_t stream)
 {
     const int BH = d.B * d.H;
     // workgroups of the two big kernels: one per (segment, sequence, head); with work lists one per (list entry, head)
@@ -1218,7 +1255,7 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
         }
         if (grid_pre > 0) {
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_STATE, stream);
-            hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, false>), dim3(grid_pre), dim3(4 * D), 0, stream, a);
+            hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, false, kExt>), dim3(grid_pre), dim3(4 * D), 0, stream, a);
             err = hipGetLastError();
         }
         if (err != hipSuccess) return err;
@@ -1234,10 +1271,19 @@ hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
     }
     {
         ProfileScope ps(DSLA_KERNEL_PREFILL_CHUNK_LOOP, stream);
-        hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, true>), dim3(grid_full), dim3(4 * D), 0, stream, a);
+        hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, true, kExt>), dim3(grid_full), dim3(4 * D), 0, stream, a);
     }
     err = hipGetLastError();
     return err;
+}
+
+// Ordinary launches keep the lean kernels; explicit blend coefficients, grouped key/value heads and accumulation
+// into o select the extended ones.
+template <int D, class TIO, class TG>
+hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a, hipStream_t stream)
+{
+    if (a.explicit_w || a.accumulate || a.Hkv != a.H) return launch_x<D, TIO, TG, true>(d, plan, a, stream);
+    return launch_x<D, TIO, TG, false>(d, plan, a, stream);
 }
 
 template <int D, class TIO>
@@ -1348,9 +1394,17 @@ bool prefill_plan_varlen(const dsla_desc &d, int64_t total_T, int64_t max_T, Pre
 
 hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T, const int32_t *cu_seqlens,
                           const int32_t *seq_index, const int32_t *state_slot, const void *q, const void *k, const void *v, const void *g1,
-                          const void *g2, float *S1, float *S2, void *o, void *workspace, hipStream_t stream)
+                          const void *g2, float *S1, float *S2, void *o, void *workspace, hipStream_t stream,
+                          const PrefillExt *ext)
 {
     PrefillArgs a;
+    a.Hkv = ext ? ext->Hkv : d.H;
+    a.explicit_w = ext ? 1 : 0;
+    a.accumulate = ext ? ext->accumulate : 0;
+    a.wa = ext ? ext->wa : 0.f;
+    a.wb = ext ? ext->wb : 0.f;
+    a.wa_per_head = ext ? ext->wa_per_head : nullptr;
+    a.wb_per_head = ext ? ext->wb_per_head : nullptr;
     a.q = q; a.k = k; a.v = v; a.g1 = g1; a.g2 = g2; a.o = o;
     a.S1 = S1; a.S2 = S2;
     a.ws_state = static_cast<float *>(workspace);
