@@ -47,3 +47,25 @@ def attention_decode(q_last, k, v, scale):
             a = e / e.sum()
             out[b, h] = a @ v[b, :, h, :]
     return out
+
+
+def attention_prefill(q, k, v, scale):
+    """Causal softmax attention of a layer that has NOT been converted, over a whole prompt (the Transformer path
+    the paper measures the converted layers against, Section 5.3): for every query position t,
+    o_t = sum_{i <= t} softmax_{i <= t}(scale * q_t . k_i) v_i.  fp64, from the definition: the full score matrix of
+    one (batch, head) through library primitives (matmul, exp, sum), positions after the query set to -inf.
+    q, k: [B, T, H, d]; v: [B, T, H, dv]; returns o: [B, T, H, dv]."""
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    B, T, H, d = q.shape
+    assert k.shape == (B, T, H, d) and v.shape[:3] == (B, T, H)
+    out = np.zeros((B, T, H, v.shape[3]), dtype=np.float64)
+    future = np.triu(np.ones((T, T), dtype=bool), 1)
+    for b in range(B):
+        for h in range(H):
+            s = float(scale) * (q[b, :, h, :] @ k[b, :, h, :].T)
+            s[future] = -np.inf
+            e = np.exp(s - s.max(axis=1, keepdims=True))
+            out[b, :, h, :] = (e / e.sum(axis=1, keepdims=True)) @ v[b, :, h, :]
+    return out

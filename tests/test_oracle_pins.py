@@ -559,5 +559,56 @@ def test_nstate_grouped_heads_equal_repeated_heads_and_planted_mistakes():
     assert np.max(np.abs(o_bad - o)) > 1e-3
 
 
+def test_attention_prefill_pins():
+    """Causal softmax attention over a prompt: the first position returns v_0; zero queries give the running mean of
+    the values; every row equals the single-query oracle on the prefix it may see; a brute-force loop."""
+    from oracle import attention as att
+    B, T, H, d = 2, 19, 3, 8
+    q, k, v = rnd(700, B, T, H, d), rnd(701, B, T, H, d), rnd(702, B, T, H, d)
+    o = att.attention_prefill(q, k, v, 0.6)
+    np.testing.assert_allclose(o[:, 0], v[:, 0], rtol=1e-14)
+    o0 = att.attention_prefill(np.zeros_like(q), k, v, 0.6)
+    np.testing.assert_allclose(o0, np.cumsum(v, axis=1) / np.arange(1, T + 1).reshape(1, T, 1, 1), rtol=1e-12)
+    for t in (0, 5, T - 1):
+        np.testing.assert_allclose(o[:, t], att.attention_decode(q[:, t], k[:, :t + 1], v[:, :t + 1], 0.6), rtol=1e-12)
+    ref = np.zeros_like(o)
+    for b in range(B):
+        for h in range(H):
+            for t in range(T):
+                w = [np.exp(0.6 * float(np.dot(q[b, t, h], k[b, i, h]))) for i in range(t + 1)]
+                ref[b, t, h] = sum(wi * v[b, i, h] for i, wi in enumerate(w)) / sum(w)
+    np.testing.assert_allclose(o, ref, rtol=1e-11)
+    # a key far ahead of the query must not matter: changing the future leaves the past untouched
+    k2, v2 = k.copy(), v.copy()
+    k2[:, 10:] += 3.0
+    v2[:, 10:] -= 5.0
+    np.testing.assert_array_equal(att.attention_prefill(q, k2, v2, 0.6)[:, :10], o[:, :10])
+
+
+def test_controller_oracle_pins():
+    """The conversion logic against the paper's own table and hand-worked cases."""
+    from oracle import controller as ctl
+    table = np.loadtxt(os.path.join(GOLD, "conversion_rate_table.txt"))
+    for lo, hi, pct in table:
+        hi = int(hi) if hi > 0 else 1 << 20
+        for L in (int(lo), (int(lo) + hi) // 2, hi - 1):
+            assert ctl.max_conversion_rate(L) == pct / 100.0, L
+    # the rates of the table on a 32-layer model: 4, 8, 12 and 16 layers
+    assert [int(ctl.max_conversion_rate(L) * 32) for L in (100, 3000, 5000, 20000)] == [4, 8, 12, 16]
+    sens = [0.7, 0.2, 0.9, 0.2, 0.05]
+    assert ctl.rank_layers(sens) == list(np.argsort(np.array(sens), kind="stable")) == [4, 1, 3, 0, 2]
+    # Section 5.3 formula by hand: Llama-2-7B (32 layers, 32 heads of 128) in bf16 at 4096 tokens: 16 KiB per token and
+    # layer, 64 MiB per layer, 2 GiB for the model
+    assert ctl.kv_cache_bytes(1, 1, 1, 32, 128, 2) == 16384
+    assert ctl.kv_cache_bytes(32, 1, 4096, 32, 128, 2) == 2 * 1024 ** 3
+    order = [3, 1, 0, 2]
+    # each conversion frees 12 - 2 = 10: 100 -> 90 -> 80 -> 70
+    assert ctl.conversion_plan(order, 100, 70, 12, 2, 1.0) == ([3, 1, 0], 70, "memory relief")
+    assert ctl.conversion_plan(order, 100, 70, 12, 2, 0.5) == ([3, 1], 80, "quality limit")
+    assert ctl.conversion_plan(order, 60, 70, 12, 2, 1.0) == ([], 60, "no pressure")
+    assert ctl.conversion_plan(order, 100, 10, 12, 2, 1.0) == ([3, 1, 0, 2], 60, "all converted")
+    assert ctl.conversion_plan(order, 100, 99, 12, 2, 0.125) == ([], 100, "quality limit")   # 12.5 % of 4 layers: none
+
+
 def test_oracle_threads_reported():
     assert orc.threads() >= 1
