@@ -318,6 +318,40 @@ DSLA_API dsla_status dsla_attention_decode(int32_t B, int32_t H, int32_t d, int6
                                   const void *q, const void *k, const void *v, const int32_t *seq_lens, void *o,
                                   void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Host-side conversion logic (paper Section 4.3 "Adaptive Layer-wise Conversion").  Plain host functions, HOST
+ * pointers, no device work: they decide which layers of a model run in DSLA form for a request; the calls above
+ * then run those layers (the entropy that ranks them comes from dsla_attention_entropy).
+ *
+ * dsla_rank_layers          - "Layer Ranking via Sensitivity": order[0 .. n_layers) = the layer indices in ascending
+ *                             order of sensitivity (the layer that loses least when converted first); equal scores
+ *                             keep the lower index first.  A NaN score is DSLA_ERR_SHAPE.
+ * dsla_max_conversion_rate  - the table of the trace replay (Section 5.4): the largest fraction of layers converted
+ *                             for a prompt of that many tokens: below 2048 12.5 %, below 4096 25 %, below 8192
+ *                             37.5 %, else 50 % (the paper's "2k", "4k", "8k" read as multiples of 1024).
+ * dsla_kv_cache_bytes       - Section 5.3: 2 * n_layers * batch * context * heads * d_head * bytes_per_element
+ *                             (-1 for a negative argument).
+ * dsla_conversion_plan      - "Adaptive Conversion Logic": when memory_used exceeds memory_threshold, convert layers
+ *                             from the least sensitive end of `order` (a permutation of the layers, as
+ *                             dsla_rank_layers returns it), each conversion trading kv_bytes_per_layer for
+ *                             state_bytes_per_layer, until use falls to the threshold (memory relief) or
+ *                             floor(max_rate * n_layers) layers are converted (the quality limit, as the cap of the
+ *                             trace replay).  converted[layer] (HOST, n_layers bytes) = 1 for a converted layer;
+ *                             *n_converted their number; *memory_after and *reason (DSLA_PLAN_*) optional.
+ */
+#define DSLA_PLAN_NO_PRESSURE 0
+#define DSLA_PLAN_MEMORY_RELIEF 1
+#define DSLA_PLAN_QUALITY_LIMIT 2
+#define DSLA_PLAN_ALL_CONVERTED 3
+DSLA_API dsla_status dsla_rank_layers(int32_t n_layers, const float *sensitivity, int32_t *order);
+DSLA_API float dsla_max_conversion_rate(int64_t prompt_len);
+DSLA_API int64_t dsla_kv_cache_bytes(int32_t n_layers, int64_t batch, int64_t context, int32_t heads, int32_t d_head,
+                            int32_t bytes_per_element);
+DSLA_API dsla_status dsla_conversion_plan(int32_t n_layers, const int32_t *order, int64_t memory_used,
+                                 int64_t memory_threshold, int64_t kv_bytes_per_layer, int64_t state_bytes_per_layer,
+                                 float max_rate, uint8_t *converted, int32_t *n_converted, int64_t *memory_after,
+                                 int32_t *reason);
+
 /* Text for a status code (static storage). */
 DSLA_API const char *dsla_status_string(dsla_status s);
 

@@ -20,6 +20,7 @@ EXPORTS = ("dsla_state_init", "dsla_prefill_workspace_bytes", "dsla_prefill", "d
            "dsla_decode_multi", "dsla_prefill_multi_workspace_bytes", "dsla_prefill_multi",
            "dsla_attention_entropy_workspace_bytes", "dsla_attention_entropy",
            "dsla_attention_decode_workspace_bytes", "dsla_attention_decode",
+           "dsla_rank_layers", "dsla_max_conversion_rate", "dsla_kv_cache_bytes", "dsla_conversion_plan",
            "dsla_status_string", "dsla_last_hip_error", "dsla_profile_enable", "dsla_profile_collect")
 
 
@@ -92,6 +93,16 @@ def load_library():
     lib.dsla_attention_decode.argtypes = ([ctypes.c_int32] * 3 + [ctypes.c_int64, ctypes.c_int32, ctypes.c_float]
                                           + [vp] * 6 + [ctypes.c_size_t, vp])
     lib.dsla_attention_decode.restype = ctypes.c_int
+    lib.dsla_rank_layers.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32)]
+    lib.dsla_rank_layers.restype = ctypes.c_int
+    lib.dsla_max_conversion_rate.argtypes = [ctypes.c_int64]
+    lib.dsla_max_conversion_rate.restype = ctypes.c_float
+    lib.dsla_kv_cache_bytes.argtypes = [ctypes.c_int32, ctypes.c_int64, ctypes.c_int64] + [ctypes.c_int32] * 3
+    lib.dsla_kv_cache_bytes.restype = ctypes.c_int64
+    lib.dsla_conversion_plan.argtypes = ([ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)] + [ctypes.c_int64] * 4
+                                         + [ctypes.c_float, ctypes.POINTER(ctypes.c_uint8), ctypes.POINTER(ctypes.c_int32),
+                                            ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(ctypes.c_int32)])
+    lib.dsla_conversion_plan.restype = ctypes.c_int
     lib.dsla_status_string.argtypes = [ctypes.c_int]
     lib.dsla_status_string.restype = ctypes.c_char_p
     lib.dsla_last_hip_error.argtypes = []
@@ -254,6 +265,42 @@ def dsla_attention_decode(q, k, v, o, scale: float, workspace=None, seq_lens=Non
     _check(load_library().dsla_attention_decode(int(B), int(H), int(d), int(T), _dtype_code(k), float(scale),
                                                 _ptr(q), _ptr(k), _ptr(v), _ptr(seq_lens), _ptr(o), _ptr(workspace), wbytes,
                                                 _stream()))
+
+
+PLAN_REASONS = ("no pressure", "memory relief", "quality limit", "all converted")
+
+
+def dsla_rank_layers(sensitivity) -> list:
+    """Layer indices in ascending order of sensitivity (include/dsla.h: dsla_rank_layers)."""
+    n = len(sensitivity)
+    s = (ctypes.c_float * n)(*[float(x) for x in sensitivity])
+    order = (ctypes.c_int32 * n)()
+    _check(load_library().dsla_rank_layers(n, s, order))
+    return list(order)
+
+
+def dsla_max_conversion_rate(prompt_len: int) -> float:
+    return float(load_library().dsla_max_conversion_rate(int(prompt_len)))
+
+
+def dsla_kv_cache_bytes(n_layers, batch, context, heads, d_head, bytes_per_element) -> int:
+    return int(load_library().dsla_kv_cache_bytes(int(n_layers), int(batch), int(context), int(heads), int(d_head),
+                                                  int(bytes_per_element)))
+
+
+def dsla_conversion_plan(order, memory_used, memory_threshold, kv_bytes_per_layer, state_bytes_per_layer, max_rate):
+    """Returns (converted layer indices in conversion order, memory use afterwards, reason text)
+    (include/dsla.h: dsla_conversion_plan)."""
+    n = len(order)
+    o = (ctypes.c_int32 * n)(*[int(x) for x in order])
+    conv = (ctypes.c_uint8 * n)()
+    cnt, after, why = ctypes.c_int32(), ctypes.c_int64(), ctypes.c_int32()
+    _check(load_library().dsla_conversion_plan(n, o, int(memory_used), int(memory_threshold), int(kv_bytes_per_layer),
+                                               int(state_bytes_per_layer), float(max_rate), conv, ctypes.byref(cnt),
+                                               ctypes.byref(after), ctypes.byref(why)))
+    layers = [l for l in order if conv[l]]
+    assert len(layers) == cnt.value
+    return layers, int(after.value), PLAN_REASONS[why.value]
 
 
 def profile_enable(enable: bool, max_records: int = 4096):

@@ -148,3 +148,31 @@ def test_workspace_plan(lib):
     d = dsla.make_desc(1, 32, 128, 128, io_dtype=1, gate_dtype=1, chunk=64)
     n = lib.dsla_prefill_workspace_bytes(ctypes.byref(d), 16384)
     assert n == 8 * 32 * 2 * 128 * 128 * 4 + 7 * 32 * 2 * 128 * 4
+
+
+def test_conversion_logic_against_its_oracle(lib):
+    """The host-side conversion logic of the library (C++) against the plain Python statement of the same rules:
+    the paper's table, rankings of seeded scores with ties, and conversion plans over a sweep of memory situations."""
+    import numpy as np
+    from oracle import controller as ctl
+    for L in (0, 1, 2047, 2048, 3000, 4095, 4096, 8191, 8192, 100000):
+        assert dsla.dsla_max_conversion_rate(L) == ctl.max_conversion_rate(L)
+    assert dsla.dsla_kv_cache_bytes(32, 8, 8192, 32, 128, 2) == ctl.kv_cache_bytes(32, 8, 8192, 32, 128, 2)
+    rng = np.random.default_rng(11)
+    for n in (1, 4, 32):
+        sens = np.round(rng.uniform(0, 5, n), 1).astype(np.float32)     # rounded: ties occur
+        order = dsla.dsla_rank_layers(sens)
+        assert order == ctl.rank_layers(sens)
+        kv, st = 64 << 20, 4 << 20
+        for used_layers in (0, n // 2, n):
+            for thr_layers in (0, n // 4, n // 2, n):
+                for rate in (0.0, 0.125, 0.25, 0.5, 1.0):
+                    used, thr = 1000 + used_layers * kv, 1000 + thr_layers * kv
+                    assert dsla.dsla_conversion_plan(order, used, thr, kv, st, rate) == \
+                        ctl.conversion_plan(order, used, thr, kv, st, rate)
+    # argument errors
+    bad = (ctypes.c_int32 * 3)(0, 0, 1)
+    conv = (ctypes.c_uint8 * 3)()
+    cnt = ctypes.c_int32()
+    assert lib.dsla_conversion_plan(3, bad, 10, 5, 2, 1, 1.0, conv, ctypes.byref(cnt), None, None) == 2
+    assert lib.dsla_rank_layers(2, (ctypes.c_float * 2)(1.0, float("nan")), (ctypes.c_int32 * 2)()) == 2
