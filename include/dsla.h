@@ -319,6 +319,20 @@ DSLA_API dsla_status dsla_attention_decode(int32_t B, int32_t H, int32_t d, int6
                                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * dsla_attention_prefill - causal softmax attention over a whole prompt: the prefill of a layer that has NOT been
+ * converted, which a partly converted model runs beside its DSLA layers (Section 4.3) and whose quadratic cost the
+ * linear-time DSLA prefill is measured against (Section 5.3):
+ *     o_t = sum_{i <= t} softmax_{i <= t}(scale * q_t . k_i) v_i .
+ *   B, H, d  : batch, heads, head size (d in {64, 128});  T >= 1 tokens per sequence
+ *   io_dtype : DSLA_BF16 only (bf16 operands on MFMA, fp32 accumulation and softmax statistics); DSLA_F32 is
+ *              DSLA_ERR_UNSUPPORTED
+ *   q, k, v  : [B][T][H][d]      o : [B][T][H][d], written
+ * One pass over the keys with a running maximum; no workspace.  Errors and stream semantics as for the other calls.
+ */
+DSLA_API dsla_status dsla_attention_prefill(int32_t B, int32_t H, int32_t d, int64_t T, int32_t io_dtype, float scale,
+                                   const void *q, const void *k, const void *v, void *o, void *stream);
+
+/*
  * Host-side conversion logic (paper Section 4.3 "Adaptive Layer-wise Conversion").  Plain host functions, HOST
  * pointers, no device work: they decide which layers of a model run in DSLA form for a request; the calls above
  * then run those layers (the entropy that ranks them comes from dsla_attention_entropy).
@@ -364,7 +378,7 @@ DSLA_API const char *dsla_last_hip_error(void);
  * created by dsla_profile_enable, so the launch path still allocates nothing).
  * Kernel ids: 0 state_init, 1 prefill_segment_state, 2 prefill_segment_scan,
  * 3 prefill_chunk_loop, 4 decode, 5 prefill_segment_list (packed sequences only), 6 attention_entropy,
- * 7 attention_decode (each with its merge kernel), 8 decode_multi.
+ * 7 attention_decode (each with its merge kernel), 8 decode_multi, 9 attention_prefill.
  */
 #define DSLA_KERNEL_STATE_INIT 0
 #define DSLA_KERNEL_PREFILL_SEGMENT_STATE 1
@@ -375,7 +389,8 @@ DSLA_API const char *dsla_last_hip_error(void);
 #define DSLA_KERNEL_ATTENTION_ENTROPY 6
 #define DSLA_KERNEL_ATTENTION_DECODE 7
 #define DSLA_KERNEL_DECODE_MULTI 8
-#define DSLA_KERNEL_COUNT 9
+#define DSLA_KERNEL_ATTENTION_PREFILL 9
+#define DSLA_KERNEL_COUNT 10
 
 /* enable != 0: create the event pool (max_records launches can be recorded between two
  * collects) and start recording; enable == 0: stop and destroy the pool. */

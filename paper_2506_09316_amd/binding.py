@@ -14,12 +14,12 @@ _lib = None
 
 DSLA_F32, DSLA_BF16 = 0, 1
 KERNEL_NAMES = ("state_init", "prefill_segment_state", "prefill_segment_scan", "prefill_chunk_loop", "decode",
-                "prefill_segment_list", "attention_entropy", "attention_decode", "decode_multi")
+                "prefill_segment_list", "attention_entropy", "attention_decode", "decode_multi", "attention_prefill")
 EXPORTS = ("dsla_state_init", "dsla_prefill_workspace_bytes", "dsla_prefill", "dsla_prefill_static_ws", "dsla_decode",
            "dsla_prefill_varlen_workspace_bytes", "dsla_prefill_varlen", "dsla_decode_slots",
            "dsla_decode_multi", "dsla_prefill_multi_workspace_bytes", "dsla_prefill_multi",
            "dsla_attention_entropy_workspace_bytes", "dsla_attention_entropy",
-           "dsla_attention_decode_workspace_bytes", "dsla_attention_decode",
+           "dsla_attention_decode_workspace_bytes", "dsla_attention_decode", "dsla_attention_prefill",
            "dsla_rank_layers", "dsla_max_conversion_rate", "dsla_kv_cache_bytes", "dsla_conversion_plan",
            "dsla_status_string", "dsla_last_hip_error", "dsla_profile_enable", "dsla_profile_collect")
 
@@ -93,6 +93,8 @@ def load_library():
     lib.dsla_attention_decode.argtypes = ([ctypes.c_int32] * 3 + [ctypes.c_int64, ctypes.c_int32, ctypes.c_float]
                                           + [vp] * 6 + [ctypes.c_size_t, vp])
     lib.dsla_attention_decode.restype = ctypes.c_int
+    lib.dsla_attention_prefill.argtypes = [ctypes.c_int32] * 3 + [ctypes.c_int64, ctypes.c_int32, ctypes.c_float] + [vp] * 5
+    lib.dsla_attention_prefill.restype = ctypes.c_int
     lib.dsla_rank_layers.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32)]
     lib.dsla_rank_layers.restype = ctypes.c_int
     lib.dsla_max_conversion_rate.argtypes = [ctypes.c_int64]
@@ -265,6 +267,13 @@ def dsla_attention_decode(q, k, v, o, scale: float, workspace=None, seq_lens=Non
     _check(load_library().dsla_attention_decode(int(B), int(H), int(d), int(T), _dtype_code(k), float(scale),
                                                 _ptr(q), _ptr(k), _ptr(v), _ptr(seq_lens), _ptr(o), _ptr(workspace), wbytes,
                                                 _stream()))
+
+
+def dsla_attention_prefill(q, k, v, o, scale: float):
+    """Causal softmax attention over a prompt (include/dsla.h: dsla_attention_prefill).  q, k, v, o: [B,T,H,d] bf16."""
+    B, T, H, d = q.shape
+    _check(load_library().dsla_attention_prefill(int(B), int(H), int(d), int(T), _dtype_code(q), float(scale), _ptr(q),
+                                                 _ptr(k), _ptr(v), _ptr(o), _stream()))
 
 
 PLAN_REASONS = ("no pressure", "memory relief", "quality limit", "all converted")

@@ -402,6 +402,17 @@ dsla_status dsla_attention_decode(int32_t B, int32_t H, int32_t d, int64_t T, in
                                          static_cast<hipStream_t>(stream)));
 }
 
+dsla_status dsla_attention_prefill(int32_t B, int32_t H, int32_t d, int64_t T, int32_t io_dtype, float scale,
+                                   const void *q, const void *k, const void *v, void *o, void *stream)
+{
+    if (B <= 0 || H <= 0 || d <= 0 || T <= 0 || T > 0x7fffffffLL) return DSLA_ERR_SHAPE;
+    if (io_dtype != DSLA_BF16 || (d != 64 && d != 128)) return DSLA_ERR_UNSUPPORTED;
+    if (static_cast<int64_t>(B) * H * ((T + 127) / 128) > 0x7fffffffLL) return DSLA_ERR_SHAPE;   // one workgroup per 128 queries
+    if (!q || !k || !v || !o) return DSLA_ERR_NULL;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return DSLA_ERR_SHAPE;
+    return hip_status(launch_attn_prefill(B, H, d, T, scale, q, k, v, o, static_cast<hipStream_t>(stream)));
+}
+
 dsla_status dsla_profile_enable(int enable, int max_records)
 {
     std::lock_guard<std::mutex> lk(g_prof.mu);

@@ -103,6 +103,8 @@ bool entropy_plan(int B, int H, int d, int64_t T, EntropyPlan *plan, int floats_
 hipError_t launch_attn_decode(int B, int H, int d, int64_t T, int io_dtype, const EntropyPlan &plan, float scale,
                               const void *q_last, const void *k, const void *v, const int32_t *seq_lens, void *o,
                               void *workspace, hipStream_t stream);
+hipError_t launch_attn_prefill(int B, int H, int d, int64_t T, float scale, const void *q, const void *k, const void *v,
+                               void *o, hipStream_t stream);
 hipError_t launch_entropy(int B, int H, int d, int64_t T, int io_dtype, const EntropyPlan &plan, float scale,
                           const void *q_last, const void *k, float *entropy, void *workspace, hipStream_t stream);
 

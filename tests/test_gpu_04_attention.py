@@ -150,3 +150,63 @@ def test_attention_decode_mixed_context_lengths():
     for b, L in enumerate(lens):
         ref = ent.attention_decode(q[b:b + 1], k[b:b + 1, :L], v[b:b + 1, :L], d ** -0.5)[0]
         assert np.all(np.abs(got[b] - ref) <= 2.0 ** -8 * np.abs(ref) + 1e-5 * np.max(np.abs(ref))), (b, L)
+
+
+# ---------------------------------------------------------------- causal attention over a prompt
+def _run_attention_prefill(x, scale):
+    import torch
+    t = {n: to_gpu(x[n], "bf16") for n in ("q", "k", "v")}
+    o = torch.full_like(t["v"], float("nan"))
+    dsla.dsla_attention_prefill(t["q"], t["k"], t["v"], o, scale)
+    torch.cuda.synchronize()
+    return o.float().cpu().numpy()
+
+
+@pytest.mark.parametrize("B,T,H,d,spread", [(2, 300, 3, 128, 1.0), (1, 129, 2, 64, 1.0), (1, 1, 2, 128, 1.0), (2, 31, 1, 64, 1.0),
+                                            (1, 1000, 2, 128, 4.0), (3, 128, 2, 128, 1.0), (1, 2500, 1, 64, 2.0)])
+def test_attention_prefill_against_oracle(B, T, H, d, spread):
+    """Every query position of a prompt against the definition (full score matrix, fp64): lengths on and off the
+    boundaries of the 128-query and 32-key blocks, peaked and flat attention rows.  bf16 operands: the scores carry
+    the rounding of scale * q to bf16 and the probabilities that of bf16, so the tolerance is the bf16 one of the
+    DSLA path (2e-2 of the largest output)."""
+    x = wl.layer_inputs(600 + T, B, T, H, d, d, io_dtype="bf16", gate_dtype="f32", qk_scale=1.0)
+    x["q"] = wl.round_to_bf16(x["q"] * np.float32(spread))
+    scale = d ** -0.5
+    got = _run_attention_prefill(x, scale)
+    ref = ent.attention_prefill(x["q"], x["k"], x["v"], scale)
+    assert np.all(np.isfinite(got))
+    err = max_rel_err(got, ref)
+    print(f"    attention prefill B={B} T={T} H={H} d={d}: max rel err {err:.3e}", flush=True)
+    assert err <= 2e-2
+    np.testing.assert_allclose(got[:, 0], x["v"][:, 0], rtol=2 ** -7, atol=1e-6)   # the first position sees itself only
+
+
+def test_attention_prefill_last_row_equals_attention_decode_and_full_size_sample():
+    """B = 2, H = 8, T = 4096 at head size 128: sampled heads against the oracle, and the last query of every head
+    against the single-query kernel on the same keys and values."""
+    import torch
+    B, T, H, d = 2, 4096, 8, 128
+    x = wl.layer_inputs(650, B, T, H, d, d, io_dtype="bf16", gate_dtype="f32", qk_scale=1.0)
+    scale = d ** -0.5
+    got = _run_attention_prefill(x, scale)
+    for b, h in ((0, 0), (1, 5)):
+        xs = {n: x[n][b:b + 1, :, h:h + 1] for n in ("q", "k", "v")}
+        ref = ent.attention_prefill(xs["q"], xs["k"], xs["v"], scale)
+        err = max_rel_err(got[b:b + 1, :, h:h + 1], ref)
+        print(f"    (b={b}, h={h}): max rel err {err:.3e}", flush=True)
+        assert err <= 2e-2
+    t = {n: to_gpu(x[n], "bf16") for n in ("q", "k", "v")}
+    o1 = torch.empty(B, H, d, device="cuda", dtype=torch.bfloat16)
+    n = dsla.dsla_attention_decode_workspace_bytes(B, H, d, T)
+    ws = torch.empty(max(n, 1), dtype=torch.uint8, device="cuda")
+    dsla.dsla_attention_decode(t["q"][:, T - 1].contiguous(), t["k"], t["v"], o1, scale, ws if n else None)
+    torch.cuda.synchronize()
+    assert max_rel_err(got[:, T - 1], o1.float().cpu().numpy()) <= 2e-2
+
+
+def test_attention_prefill_argument_checks():
+    import torch
+    z = torch.zeros(1, 8, 2, 64, device="cuda")
+    with pytest.raises(dsla.DslaError) as e:      # fp32 storage is not built for this call
+        dsla.dsla_attention_prefill(z, z, z, z.clone(), 1.0)
+    assert e.value.status == 3
