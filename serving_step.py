@@ -1,6 +1,7 @@
 """The attention layers of a hybrid serving step, as a usage example and a measurement:
 
     python serving_step.py [--layers 16 --B 8 --T 8192 --decode 128]
+    python serving_step.py --hybrid [--layers 32 --B 8 --T 8192 --decode 128]
     python serving_step.py --packed {equal,pow2,serving,one_long}
     python serving_step.py --entropy [--B 8 --T 8192]
     python serving_step.py --attention-decode [--B 8 --T 8192]
@@ -156,13 +157,131 @@ def attention_decode(B: int, T: int, H: int, d: int):
                       "ratio": round(us_attn / us_dsla, 2)}))
 
 
+def hybrid(n_layers: int, B: int, T: int, H: int, d: int, decode: int):
+    """The attention layers of the hybrid serving configuration as one step: a stack of n_layers attention layers of
+    which the conversion logic picks the ones that run as DSLA layers (entropy of each layer's final query ->
+    ranking -> conversion plan under memory pressure, capped by the prompt-length table), then the prompt through
+    every layer (DSLA prefill or causal softmax attention) and `decode` tokens (DSLA decode step or single-query
+    attention over the growing cache).  Projections and MLPs are not part of this library; inputs are synthetic and
+    shared by the layers.  Prints one JSON line."""
+    import torch
+    import paper_2506_09316_amd as dsla
+    from paper_2506_09316_amd.binding import DSLA_BF16
+
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20250609 + 5000)
+    rnd = lambda *shape: (torch.randn(*shape, device=dev, generator=gen) * d ** -0.5).to(torch.bfloat16)
+
+    def gates(*shape):
+        z = torch.randn(*shape, device=dev, generator=gen) + 2.0
+        return (-torch.nn.functional.softplus(-z) / 16.0).to(torch.bfloat16)
+
+    q, k, v, g1, g2 = rnd(B, T, H, d), rnd(B, T, H, d), rnd(B, T, H, d), gates(B, T, H, d), gates(B, T, H, d)
+    o = torch.empty_like(v)
+
+    # ---- which layers convert: the library's own signal and logic on synthetic per-layer queries ----
+    ent = torch.empty(B, H, device=dev, dtype=torch.float32)
+    ews = torch.empty(max(dsla.dsla_attention_entropy_workspace_bytes(B, H, d, T), 16), dtype=torch.uint8, device=dev)
+    spread = torch.rand(n_layers, generator=torch.Generator().manual_seed(11)) * 14.0 + 1.0   # peaked .. flat layers
+    sens = []
+    for l in range(n_layers):
+        ql = (q[:, -1].float() * float(spread[l]) * d ** 0.5).to(torch.bfloat16).contiguous()
+        dsla.dsla_attention_entropy(ql, k, ent, d ** -0.5, ews)
+        sens.append(float(ent.mean().item()))
+    order = dsla.dsla_rank_layers(sens)
+    kv_layer = dsla.dsla_kv_cache_bytes(1, B, T + decode, H, d, 2)
+    state_layer = B * H * 2 * d * d * 4
+    rate = dsla.dsla_max_conversion_rate(T)
+    used = n_layers * kv_layer
+    converted, after, why = dsla.dsla_conversion_plan(order, used, used // 4, kv_layer, state_layer, rate)
+    conv = set(converted)
+
+    descs = {l: dsla.make_desc(B, H, d, d, io_dtype=DSLA_BF16, gate_dtype=DSLA_BF16, gamma=0.2 + 0.6 * (l % 7) / 6.0,
+                               chunk=64, zero_init=True) for l in conv}
+    S = {l: (torch.empty(B, H, d, d, device=dev), torch.empty(B, H, d, d, device=dev)) for l in conv}
+    nws = dsla.dsla_prefill_workspace_bytes(next(iter(descs.values())), T) if conv else 0
+    ws = torch.empty(max(nws, 256), dtype=torch.uint8, device=dev)
+    cap = T + decode
+    caches = {l: (rnd(B, cap, H, d), rnd(B, cap, H, d)) for l in range(n_layers) if l not in conv}
+    aws = torch.empty(max(dsla.dsla_attention_decode_workspace_bytes(B, H, d, cap), 16), dtype=torch.uint8, device=dev)
+    lens = torch.full((B,), T, dtype=torch.int32, device=dev)
+
+    def prefill(layers):
+        for l in layers:
+            if l in conv:
+                dsla.dsla_prefill(descs[l], T, q, k, v, g1, g2, S[l][0], S[l][1], o, ws if nws else None)
+            else:
+                dsla.dsla_attention_prefill(q, k, v, o, d ** -0.5)
+
+    dq, dk, dv, dg1, dg2 = rnd(B, H, d), rnd(B, H, d), rnd(B, H, d), gates(B, H, d), gates(B, H, d)
+    do = torch.empty_like(dv)
+
+    def decode_step(layers):
+        for l in layers:
+            if l in conv:
+                dsla.dsla_decode(descs[l], dq, dk, dv, dg1, dg2, S[l][0], S[l][1], do)
+            else:
+                dsla.dsla_attention_decode(dq, caches[l][0], caches[l][1], do, d ** -0.5, aws, seq_lens=lens)
+
+    def timed(fn, n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    all_layers = list(range(n_layers))
+    soft = [l for l in all_layers if l not in conv]
+    prefill(all_layers)
+    ms_prefill = timed(lambda: prefill(all_layers), 2)
+    ms_prefill_dsla = timed(lambda: prefill(sorted(conv)), 2) if conv else 0.0
+    ms_prefill_soft = timed(lambda: prefill(soft), 2) if soft else 0.0
+
+    def decode_all():
+        for t in range(decode):
+            lens.fill_(T + t + 1)
+            decode_step(all_layers)
+
+    decode_all()
+    ms_decode = timed(decode_all, 1) / decode
+    lens.fill_(cap)
+    ms_decode_soft_layer = timed(lambda: decode_step(soft[:1]), 20) if soft else 0.0
+    ms_decode_dsla_layer = timed(lambda: decode_step(sorted(conv)[:1]), 20) if conv else 0.0
+    assert bool(torch.isfinite(o.float()).all()) and bool(torch.isfinite(do.float()).all())
+    n_soft = len(soft)
+    print(json.dumps({
+        "workload": f"attention layers of a hybrid step: {n_layers} layers, B={B} H={H} d={d}, prompt T={T}, {decode} decode "
+                    f"tokens, bf16, synthetic inputs; projections and MLPs not included",
+        "converted_layers": sorted(conv), "n_converted": len(conv), "max_conversion_rate": rate, "plan_stopped_by": why,
+        "kv_cache_GB_unconverted_model": round(n_layers * kv_layer / 1e9, 2),
+        "kv_cache_GB_after_conversion": round(n_soft * kv_layer / 1e9, 2),
+        "dsla_states_GB": round(len(conv) * state_layer / 1e9, 3),
+        "prefill_ms_all_layers": round(ms_prefill, 2),
+        "prefill_ms_dsla_layers": round(ms_prefill_dsla, 2), "prefill_ms_softmax_layers": round(ms_prefill_soft, 2),
+        "prefill_ms_if_no_layer_converted": round(ms_prefill_soft / max(n_soft, 1) * n_layers, 2),
+        "softmax_prefill_TFLOPs_causal": round(n_soft * B * H * 2.0 * T * T * d * 2 / 2 / (ms_prefill_soft * 1e-3) / 1e12, 1) if soft else None,
+        "decode_ms_per_token_all_layers": round(ms_decode, 3),
+        "decode_ms_one_softmax_layer_full_cache": round(ms_decode_soft_layer, 4),
+        "decode_ms_one_dsla_layer": round(ms_decode_dsla_layer, 4),
+        "decode_ms_per_token_if_no_layer_converted": round(ms_decode_soft_layer * n_layers, 3),
+        "request_ms_prompt_plus_decode": round(ms_prefill + decode * ms_decode, 1),
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--attention-decode", action="store_true",
                     help="time the decode step of an unconverted softmax layer against the DSLA decode step instead")
     ap.add_argument("--entropy", action="store_true", help="time the attention-entropy kernel on one layer's keys instead")
     ap.add_argument("--packed", choices=sorted(MIXES), help="time one packed mixed-length prefill batch instead")
-    ap.add_argument("--layers", type=int, default=16)
+    ap.add_argument("--hybrid", action="store_true",
+                    help="the whole hybrid configuration: --layers attention layers (default 32), the conversion logic "
+                         "picks the DSLA ones, prompt and decode through every layer")
+    ap.add_argument("--layers", type=int, default=None)
     ap.add_argument("--B", type=int, default=8)
     ap.add_argument("--T", type=int, default=8192)
     ap.add_argument("--H", type=int, default=32)
@@ -170,6 +289,9 @@ def main():
     ap.add_argument("--decode", type=int, default=128)
     ap.add_argument("--repeat", type=int, default=5, help="timed repetitions of the prefill of all layers")
     a = ap.parse_args()
+    if a.hybrid:
+        return hybrid(a.layers or 32, a.B, a.T, a.H, a.d, a.decode)
+    a.layers = a.layers or 16
     if a.packed:
         return packed(a.packed, a.H, a.d)
     if a.entropy:
