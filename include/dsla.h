@@ -319,6 +319,25 @@ DSLA_API dsla_status dsla_attention_decode(int32_t B, int32_t H, int32_t d, int6
                                   void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * dsla_project - the projections in front of a DSLA layer as one MFMA GEMM (Section 5.3: the gates come from single
+ * linear layers; appendix on training details: q, k, v reuse the teacher's projections, the history gate's weight starts
+ * near the identity, the recency gate's from a normal distribution, biases zero).  From the layer input x and the
+ * stacked weights it writes n_out tensors - typically q, k, v and the pre-activations of the two gates - each in the
+ * layout the prefill reads, so that dsla_prefill with gate_mode = DSLA_GATE_PREACT runs on them as they are:
+ *     out_j[m][c] = sum_k x[m][k] W[j * width + c][k] (+ bias[j * width + c]),     j = 0 .. n_out - 1
+ *   M          : rows of x = batch * tokens (>= 1)
+ *   K          : model width, a multiple of 32
+ *   n_out      : 1 .. DSLA_MAX_PROJECTIONS output tensors, each `width` = H * d wide, a multiple of 128
+ *   x          : [M][K] bf16          W : [n_out * width][K] bf16, row-major (a linear layer's weight)
+ *   bias       : [n_out * width] fp32 or NULL
+ *   outs       : HOST array [n_out] of DEVICE pointers, each [M][width] bf16, written
+ * bf16 operands, fp32 accumulation; no workspace.  Errors and stream semantics as for the other calls.
+ */
+#define DSLA_MAX_PROJECTIONS 8
+DSLA_API dsla_status dsla_project(int64_t M, int32_t K, int32_t n_out, int32_t width,
+                         const void *x, const void *W, const float *bias, void *const *outs, void *stream);
+
+/*
  * dsla_attention_prefill - causal softmax attention over a whole prompt: the prefill of a layer that has NOT been
  * converted, which a partly converted model runs beside its DSLA layers (Section 4.3) and whose quadratic cost the
  * linear-time DSLA prefill is measured against (Section 5.3):
@@ -378,7 +397,7 @@ DSLA_API const char *dsla_last_hip_error(void);
  * created by dsla_profile_enable, so the launch path still allocates nothing).
  * Kernel ids: 0 state_init, 1 prefill_segment_state, 2 prefill_segment_scan,
  * 3 prefill_chunk_loop, 4 decode, 5 prefill_segment_list (packed sequences only), 6 attention_entropy,
- * 7 attention_decode (each with its merge kernel), 8 decode_multi, 9 attention_prefill.
+ * 7 attention_decode (each with its merge kernel), 8 decode_multi, 9 attention_prefill, 10 project.
  */
 #define DSLA_KERNEL_STATE_INIT 0
 #define DSLA_KERNEL_PREFILL_SEGMENT_STATE 1
@@ -390,7 +409,8 @@ DSLA_API const char *dsla_last_hip_error(void);
 #define DSLA_KERNEL_ATTENTION_DECODE 7
 #define DSLA_KERNEL_DECODE_MULTI 8
 #define DSLA_KERNEL_ATTENTION_PREFILL 9
-#define DSLA_KERNEL_COUNT 10
+#define DSLA_KERNEL_PROJECT 10
+#define DSLA_KERNEL_COUNT 11
 
 /* enable != 0: create the event pool (max_records launches can be recorded between two
  * collects) and start recording; enable == 0: stop and destroy the pool. */

@@ -5,7 +5,7 @@ kernels); `binding` is a thin ctypes layer with the same entry-point names.  Imp
 the package does not load the library; the first call does, and fails loudly if the
 library has not been built.
 """
-from .binding import (dsla_attention_prefill, dsla_conversion_plan, dsla_kv_cache_bytes, dsla_max_conversion_rate, dsla_rank_layers,  # noqa: F401
+from .binding import (dsla_project, dsla_attention_prefill, dsla_conversion_plan, dsla_kv_cache_bytes, dsla_max_conversion_rate, dsla_rank_layers,  # noqa: F401
                      )
 from .binding import (DslaDesc, DslaError, DslaMulti, dsla_decode_multi, dsla_prefill_multi,  # noqa: F401
                       dsla_prefill_multi_workspace_bytes, make_multi,  # noqa: F401

@@ -14,12 +14,12 @@ _lib = None
 
 DSLA_F32, DSLA_BF16 = 0, 1
 KERNEL_NAMES = ("state_init", "prefill_segment_state", "prefill_segment_scan", "prefill_chunk_loop", "decode",
-                "prefill_segment_list", "attention_entropy", "attention_decode", "decode_multi", "attention_prefill")
+                "prefill_segment_list", "attention_entropy", "attention_decode", "decode_multi", "attention_prefill", "project")
 EXPORTS = ("dsla_state_init", "dsla_prefill_workspace_bytes", "dsla_prefill", "dsla_prefill_static_ws", "dsla_decode",
            "dsla_prefill_varlen_workspace_bytes", "dsla_prefill_varlen", "dsla_decode_slots",
            "dsla_decode_multi", "dsla_prefill_multi_workspace_bytes", "dsla_prefill_multi",
            "dsla_attention_entropy_workspace_bytes", "dsla_attention_entropy",
-           "dsla_attention_decode_workspace_bytes", "dsla_attention_decode", "dsla_attention_prefill",
+           "dsla_attention_decode_workspace_bytes", "dsla_attention_decode", "dsla_attention_prefill", "dsla_project",
            "dsla_rank_layers", "dsla_max_conversion_rate", "dsla_kv_cache_bytes", "dsla_conversion_plan",
            "dsla_status_string", "dsla_last_hip_error", "dsla_profile_enable", "dsla_profile_collect")
 
@@ -93,6 +93,8 @@ def load_library():
     lib.dsla_attention_decode.argtypes = ([ctypes.c_int32] * 3 + [ctypes.c_int64, ctypes.c_int32, ctypes.c_float]
                                           + [vp] * 6 + [ctypes.c_size_t, vp])
     lib.dsla_attention_decode.restype = ctypes.c_int
+    lib.dsla_project.argtypes = [ctypes.c_int64] + [ctypes.c_int32] * 3 + [vp] * 3 + [ctypes.POINTER(ctypes.c_void_p), vp]
+    lib.dsla_project.restype = ctypes.c_int
     lib.dsla_attention_prefill.argtypes = [ctypes.c_int32] * 3 + [ctypes.c_int64, ctypes.c_int32, ctypes.c_float] + [vp] * 5
     lib.dsla_attention_prefill.restype = ctypes.c_int
     lib.dsla_rank_layers.argtypes = [ctypes.c_int32, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32)]
@@ -267,6 +269,19 @@ def dsla_attention_decode(q, k, v, o, scale: float, workspace=None, seq_lens=Non
     _check(load_library().dsla_attention_decode(int(B), int(H), int(d), int(T), _dtype_code(k), float(scale),
                                                 _ptr(q), _ptr(k), _ptr(v), _ptr(seq_lens), _ptr(o), _ptr(workspace), wbytes,
                                                 _stream()))
+
+
+def dsla_project(x, W, outs, bias=None):
+    """The projections in front of a layer as one GEMM (include/dsla.h: dsla_project).  x [M,K] bf16; W [n_out*width,K]
+    bf16; outs: list of n_out bf16 GPU tensors of M*width elements each; bias: fp32 GPU tensor [n_out*width] or None."""
+    M, K = x.shape
+    n_out = len(outs)
+    width = W.shape[0] // n_out
+    assert W.shape == (n_out * width, K) and all(t.numel() == M * width for t in outs)
+    po = (ctypes.c_void_p * n_out)(*[t.data_ptr() for t in outs])
+    for t in outs:
+        assert t.is_cuda and t.is_contiguous()
+    _check(load_library().dsla_project(int(M), int(K), n_out, int(width), _ptr(x), _ptr(W), _ptr(bias), po, _stream()))
 
 
 def dsla_attention_prefill(q, k, v, o, scale: float):

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdsla.so")
-SOURCES = ["api.hip", "decode.hip", "attention.hip", "attention_prefill.hip", "controller.hip", "prefill.hip"]
+SOURCES = ["api.hip", "decode.hip", "attention.hip", "attention_prefill.hip", "controller.hip", "project.hip", "prefill.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -402,6 +402,21 @@ dsla_status dsla_attention_decode(int32_t B, int32_t H, int32_t d, int64_t T, in
                                          static_cast<hipStream_t>(stream)));
 }
 
+dsla_status dsla_project(int64_t M, int32_t K, int32_t n_out, int32_t width, const void *x, const void *W,
+                         const float *bias, void *const *outs, void *stream)
+{
+    if (M <= 0 || K <= 0 || n_out <= 0 || width <= 0) return DSLA_ERR_SHAPE;
+    if (n_out > DSLA_MAX_PROJECTIONS || K % 32 != 0 || width % 128 != 0) return DSLA_ERR_UNSUPPORTED;
+    if ((M + 127) / 128 * (static_cast<int64_t>(n_out) * width / 128) > 0x7ffffff0LL) return DSLA_ERR_SHAPE;
+    if (!x || !W || !outs) return DSLA_ERR_NULL;
+    if (!aligned16(x) || !aligned16(W) || !aligned16(bias)) return DSLA_ERR_SHAPE;
+    for (int j = 0; j < n_out; ++j) {
+        if (!outs[j]) return DSLA_ERR_NULL;
+        if (!aligned16(outs[j])) return DSLA_ERR_SHAPE;
+    }
+    return hip_status(launch_project(M, K, n_out, width, x, W, bias, outs, static_cast<hipStream_t>(stream)));
+}
+
 dsla_status dsla_attention_prefill(int32_t B, int32_t H, int32_t d, int64_t T, int32_t io_dtype, float scale,
                                    const void *q, const void *k, const void *v, void *o, void *stream)
 {

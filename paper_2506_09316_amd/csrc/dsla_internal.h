@@ -103,6 +103,8 @@ bool entropy_plan(int B, int H, int d, int64_t T, EntropyPlan *plan, int floats_
 hipError_t launch_attn_decode(int B, int H, int d, int64_t T, int io_dtype, const EntropyPlan &plan, float scale,
                               const void *q_last, const void *k, const void *v, const int32_t *seq_lens, void *o,
                               void *workspace, hipStream_t stream);
+hipError_t launch_project(int64_t M, int K, int n_out, int width, const void *x, const void *w, const float *bias,
+                          void *const *outs, hipStream_t stream);
 hipError_t launch_attn_prefill(int B, int H, int d, int64_t T, float scale, const void *q, const void *k, const void *v,
                                void *o, hipStream_t stream);
 hipError_t launch_entropy(int B, int H, int d, int64_t T, int io_dtype, const EntropyPlan &plan, float scale,

@@ -210,3 +210,65 @@ def test_varlen_equals_dense_bitwise():
     assert np.array_equal(o.float().cpu().numpy().reshape(B, T, H, d), o_dense)
     assert np.array_equal(S1.cpu().numpy(), S1d) and np.array_equal(S2.cpu().numpy(), S2d)
 
+
+
+# ---------------------------------------------------------------- projections in front of the layer
+def _projection_case(seed, M, K, n_out, width, bias):
+    rng = np.random.default_rng(seed)
+    x = wl.round_to_bf16(rng.standard_normal((M, K), dtype=np.float32))
+    W = wl.round_to_bf16(rng.standard_normal((n_out * width, K), dtype=np.float32) * np.float32(K ** -0.5))
+    b = rng.standard_normal(n_out * width).astype(np.float32) if bias else None
+    return x, W, b
+
+
+@pytest.mark.parametrize("M,K,n_out,width,bias", [(300, 256, 5, 256, False), (128, 64, 1, 128, True), (1000, 512, 3, 384, True),
+                                                  (1, 32, 2, 128, False), (4096, 1024, 5, 1024, False)])
+def test_project_against_library_matmul(M, K, n_out, width, bias):
+    """dsla_project against the definition through a library matmul in fp64 on the same bf16 inputs; the results are
+    stored as bf16, so an element may differ from the exact product by half a bf16 unit of itself plus the fp32
+    accumulation error of K terms."""
+    import torch
+    x, W, b = _projection_case(800 + M, M, K, n_out, width, bias)
+    outs = [torch.full((M, width), float("nan"), device="cuda", dtype=torch.bfloat16) for _ in range(n_out)]
+    dsla.dsla_project(to_gpu(x, "bf16"), to_gpu(W, "bf16"), outs, torch.from_numpy(b).cuda() if bias else None)
+    torch.cuda.synchronize()
+    ref = x.astype(np.float64) @ W.astype(np.float64).T + (b.astype(np.float64) if bias else 0.0)
+    for j in range(n_out):
+        got = outs[j].float().cpu().numpy()
+        r = ref[:, j * width:(j + 1) * width]
+        assert np.all(np.isfinite(got))
+        assert np.max(np.abs(got - r) / (np.abs(r) + 1e-2 * np.max(np.abs(r)))) <= 2 ** -8 * 1.1, f"output {j}"
+
+
+def test_projections_feed_the_prefill():
+    """The layer from its input: x -> one GEMM -> q, k, v and the two gate pre-activations in the prefill's own
+    layout -> dsla_prefill with gate_mode = DSLA_GATE_PREACT.  The oracle takes the same bf16 weights and input
+    through a library matmul (fp64), rounds the five tensors to bf16 as the GPU stores them, maps the gates and runs
+    the recurrence.  The history gate's weight is a scaled identity plus noise, the recency gate's is random, as the
+    paper initialises them."""
+    import torch
+    B, T, H, d, tau = 2, 300, 2, 128, 16.0
+    Dm = H * d
+    rng = np.random.default_rng(820)
+    x = wl.round_to_bf16(rng.standard_normal((B * T, Dm), dtype=np.float32))
+    Wq, Wk, Wv = (rng.standard_normal((Dm, Dm), dtype=np.float32) * np.float32(Dm ** -0.5 * d ** -0.25) for _ in range(3))
+    Wg1 = np.eye(Dm, dtype=np.float32) * 2.0 + rng.standard_normal((Dm, Dm), dtype=np.float32) * np.float32(0.02)
+    Wg2 = rng.standard_normal((Dm, Dm), dtype=np.float32) * np.float32(Dm ** -0.5)
+    W = wl.round_to_bf16(np.concatenate([Wq, Wk, Wv, Wg1, Wg2]))
+    outs = [torch.empty(B, T, H, d, device="cuda", dtype=torch.bfloat16) for _ in range(5)]
+    dsla.dsla_project(to_gpu(x, "bf16"), to_gpu(W, "bf16"), outs)
+    desc = dsla.make_desc(B, H, d, d, io_dtype=code("bf16"), gate_dtype=code("bf16"), gamma=0.4, chunk=64, gate_mode=1, tau=tau,
+                          zero_init=True)
+    S1 = torch.full((B, H, d, d), float("nan"), device="cuda")
+    S2 = torch.full_like(S1, float("nan"))
+    o = torch.full_like(outs[2], float("nan"))
+    nbytes = dsla.dsla_prefill_workspace_bytes(desc, T)
+    ws = torch.empty(max(nbytes, 1), dtype=torch.uint8, device="cuda")
+    dsla.dsla_prefill(desc, T, outs[0], outs[1], outs[2], outs[3], outs[4], S1, S2, o, ws if nbytes else None)
+    torch.cuda.synchronize()
+    y = wl.round_to_bf16((x.astype(np.float64) @ W.astype(np.float64).T).astype(np.float32)).reshape(B, T, 5, H, d)
+    q, k, v, z1, z2 = (y[:, :, j] for j in range(5))
+    ro, rS1, rS2 = orc.recurrent(q, k, v, orc.log_gates_from_preactivations(z1, tau), orc.log_gates_from_preactivations(z2, tau), 0.4)
+    check("o", o.float().cpu().numpy(), ro, 2e-2)
+    check("S1", S1.cpu().numpy(), rS1, 2e-2)
+    check("S2", S2.cpu().numpy(), rS2, 2e-2)
