@@ -2,6 +2,8 @@
 
     python serving_step.py [--layers 16 --B 8 --T 8192 --decode 128]
     python serving_step.py --hybrid [--layers 32 --B 8 --T 8192 --decode 128]
+    python serving_step.py --project [--T 16384 --K 4096]
+    python serving_step.py --multi N [--Hkv 8]
     python serving_step.py --packed {equal,pow2,serving,one_long}
     python serving_step.py --entropy [--B 8 --T 8192]
     python serving_step.py --attention-decode [--B 8 --T 8192]
@@ -272,6 +274,111 @@ def hybrid(n_layers: int, B: int, T: int, H: int, d: int, decode: int):
     }))
 
 
+def project(M: int, K: int, H: int, d: int):
+    """The projections in front of one layer (dsla_project: q, k, v and two gate pre-activations, 5 H d columns) and
+    the prefill that consumes them; one JSON line."""
+    import torch
+    import paper_2506_09316_amd as dsla
+    from paper_2506_09316_amd import binding
+    from paper_2506_09316_amd.binding import DSLA_BF16
+
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20250609)
+    width = H * d
+    x = torch.randn(M, K, device=dev, generator=gen).to(torch.bfloat16)
+    W = (torch.randn(5 * width, K, device=dev, generator=gen) * K ** -0.5).to(torch.bfloat16)
+    outs = [torch.empty(1, M, H, d, device=dev, dtype=torch.bfloat16) for _ in range(5)]
+    desc = dsla.make_desc(1, H, d, d, io_dtype=DSLA_BF16, gate_dtype=DSLA_BF16, gamma=0.5, chunk=64, gate_mode=1, tau=16.0,
+                          zero_init=True)
+    S1, S2 = torch.empty(1, H, d, d, device=dev), torch.empty(1, H, d, d, device=dev)
+    o = torch.empty_like(outs[2])
+    nws = dsla.dsla_prefill_workspace_bytes(desc, M)
+    ws = torch.empty(max(nws, 256), dtype=torch.uint8, device=dev)
+
+    def step():
+        dsla.dsla_project(x, W, outs)
+        dsla.dsla_prefill(desc, M, outs[0], outs[1], outs[2], outs[3], outs[4], S1, S2, o, ws if nws else None)
+
+    for _ in range(5):
+        step()
+    torch.cuda.synchronize()
+    binding.profile_enable(True, 4096)
+    for _ in range(20):
+        step()
+    res = binding.profile_collect()
+    binding.profile_enable(False, 0)
+    ms = {n: res[n][0] / res[n][1] for n in res if res[n][1]}
+    flops = 2.0 * M * K * 5 * width
+    print(json.dumps({"workload": f"projections of one layer: x [{M} x {K}] bf16 -> q, k, v, z1, z2 [{M} x {width}] each, then the "
+                                  f"prefill with gate pre-activations (T = {M}, H = {H}, d = {d})",
+                      "project_ms": round(ms["project"], 4), "project_TFLOPs": round(flops / (ms["project"] * 1e-3) / 1e12, 1),
+                      "project_frac_of_bf16_mfma_peak": round(flops / (ms["project"] * 1e-3) / 1e12 / 2500.0, 4),
+                      "prefill_kernels_ms": {n: round(v, 4) for n, v in ms.items() if n.startswith("prefill")}}))
+
+
+def multi_state(N: int, Hkv: int, B: int, T: int, H: int, d: int):
+    """dsla_decode_multi at the batched-decode shape and dsla_prefill_multi at the long-prompt shape for N states and
+    H_kv key/value heads; one JSON line."""
+    import torch
+    import paper_2506_09316_amd as dsla
+    from paper_2506_09316_amd import binding
+    from paper_2506_09316_amd.binding import DSLA_BF16
+
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20250609)
+    rnd = lambda *shape: (torch.randn(*shape, device=dev, generator=gen) * d ** -0.5).to(torch.bfloat16)
+
+    def gates(*shape):
+        z = torch.randn(*shape, device=dev, generator=gen) + 2.0
+        return (-torch.nn.functional.softplus(-z) / 16.0).to(torch.bfloat16)
+
+    w = [1.0 / N] * N
+    # ---- decode: B = 64 sequences, rotating over several state sets so that the last-level cache cannot hold them
+    Bd, NSETS = 64, max(2, 8 // N)
+    desc = dsla.make_desc(Bd, H, d, d, io_dtype=DSLA_BF16, gate_dtype=DSLA_BF16)
+    sets = [[torch.randn(Bd, H, d, d, device=dev, generator=gen) * 0.05 for _ in range(N)] for _ in range(NSETS)]
+    q, k, v = rnd(Bd, H, d), rnd(Bd, Hkv, d), rnd(Bd, Hkv, d)
+    ga = [gates(Bd, H, d) for _ in range(N)]
+    o = torch.empty_like(q)
+    multis = [dsla.make_multi(ga, s, w, H_kv=Hkv) for s in sets]
+    for i in range(8):
+        dsla.dsla_decode_multi(desc, multis[i % NSETS], q, k, v, o)
+    torch.cuda.synchronize()
+    binding.profile_enable(True, 4096)
+    for i in range(64):
+        dsla.dsla_decode_multi(desc, multis[i % NSETS], q, k, v, o)
+    res = binding.profile_collect()
+    us_dec = 1e3 * res["decode_multi"][0] / res["decode_multi"][1]
+    dec_bytes = Bd * H * N * d * d * 4 * 2
+    del sets, multis
+    # ---- prefill: one long prompt
+    pdesc = dsla.make_desc(B, H, d, d, io_dtype=DSLA_BF16, gate_dtype=DSLA_BF16, chunk=64, zero_init=True)
+    pq, pk, pv = rnd(B, T, H, d), rnd(B, T, Hkv, d), rnd(B, T, Hkv, d)
+    pga = [gates(B, T, H, d) for _ in range(N)]
+    S = [torch.empty(B, H, d, d, device=dev) for _ in range(N)]
+    po = torch.empty_like(pq)
+    pm = dsla.make_multi(pga, S, w, H_kv=Hkv)
+    ws = torch.empty(max(dsla.dsla_prefill_multi_workspace_bytes(pdesc, pm, T), 256), dtype=torch.uint8, device=dev)
+    for _ in range(5):
+        dsla.dsla_prefill_multi(pdesc, pm, T, pq, pk, pv, po, ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(20):
+        dsla.dsla_prefill_multi(pdesc, pm, T, pq, pk, pv, po, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    binding.profile_enable(False, 0)
+    ms_pre = e0.elapsed_time(e1) / 20
+    print(json.dumps({"workload": f"N = {N} states, H = {H} query heads, H_kv = {Hkv}, d = {d}, bf16 io, fp32 states",
+                      "decode_multi_us_B64": round(us_dec, 2), "decode_multi_GBps": round(dec_bytes / us_dec / 1e3, 1),
+                      "decode_multi_frac_of_8TBps": round(dec_bytes / us_dec / 1e3 / 8000, 4),
+                      "prefill_multi_ms": round(ms_pre, 4), "prefill_multi_tokens_per_s": round(B * T / (ms_pre * 1e-3), 1),
+                      "prefill_shape": f"B={B} T={T}"}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--attention-decode", action="store_true",
@@ -281,6 +388,10 @@ def main():
     ap.add_argument("--hybrid", action="store_true",
                     help="the whole hybrid configuration: --layers attention layers (default 32), the conversion logic "
                          "picks the DSLA ones, prompt and decode through every layer")
+    ap.add_argument("--project", action="store_true", help="time the projection GEMM of one layer and the prefill behind it")
+    ap.add_argument("--K", type=int, default=4096, help="--project: model width")
+    ap.add_argument("--multi", type=int, default=0, metavar="N", help="time the N-state decode and prefill calls")
+    ap.add_argument("--Hkv", type=int, default=0, help="--multi: key/value heads (default: H)")
     ap.add_argument("--layers", type=int, default=None)
     ap.add_argument("--B", type=int, default=8)
     ap.add_argument("--T", type=int, default=8192)
@@ -289,6 +400,10 @@ def main():
     ap.add_argument("--decode", type=int, default=128)
     ap.add_argument("--repeat", type=int, default=5, help="timed repetitions of the prefill of all layers")
     a = ap.parse_args()
+    if a.project:
+        return project(16384 if a.T == 8192 else a.T, a.K, a.H, a.d)
+    if a.multi:
+        return multi_state(a.multi, a.Hkv or a.H, 1 if a.B == 8 else a.B, 16384 if a.T == 8192 else a.T, a.H, a.d)
     if a.hybrid:
         return hybrid(a.layers or 32, a.B, a.T, a.H, a.d, a.decode)
     a.layers = a.layers or 16
