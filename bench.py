@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=1024)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--settle-seconds", type=float, default=SETTLE_SECONDS,
+                    help="untimed steps before --warmup (counter runs under rocprofv3 pass 0: every dispatch is slow there)")
     ap.add_argument("--no-calibration-copy", action="store_true",
                     help="skip the plain 256 MiB device copy that gives counter runs a kernel of known traffic")
     args = ap.parse_args()
@@ -101,7 +103,7 @@ def main():
     # (clocks ramp up, code objects and page tables are touched for the first time), so a short --warmup alone
     # would time that transient instead of the steady state.
     t_settle = time.perf_counter()
-    while time.perf_counter() - t_settle < SETTLE_SECONDS:
+    while time.perf_counter() - t_settle < args.settle_seconds:
         for _ in range(20):
             prefill_step()
         torch.cuda.synchronize()
