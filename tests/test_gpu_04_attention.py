@@ -210,3 +210,65 @@ def test_attention_prefill_argument_checks():
     with pytest.raises(dsla.DslaError) as e:      # fp32 storage is not built for this call
         dsla.dsla_attention_prefill(z, z, z, z.clone(), 1.0)
     assert e.value.status == 3
+
+
+def test_hybrid_stack_slice_against_oracles():
+    """The hybrid configuration in miniature, at the real prompt length: 6 attention layers at B = 2, H = 32, d = 128,
+    T = 8192; the library's conversion logic (entropy -> ranking -> plan capped by the prompt-length table) picks the
+    layers that run as DSLA layers; every layer prefills the prompt and decodes 4 tokens (DSLA: prefill + decode
+    step; softmax: causal attention + single-query attention over the growing cache).  One sampled (batch, head) pair
+    per layer is held to the oracle of that layer's form."""
+    import torch
+    from oracle import dsla_oracle as orc
+    B, T, H, d, L, steps = 2, 8192, 32, 128, 6, 4
+    scale = d ** -0.5
+    x = wl.layer_inputs(900, B, T + steps, H, d, d, io_dtype="bf16", gate_dtype="bf16", qk_scale=1.0)
+    t = {n: to_gpu(x[n], "bf16") for n in x}
+    # sensitivities from the entropy kernel on per-layer scaled final queries (peaked .. flat)
+    spreads = [6.0, 0.5, 3.0, 0.1, 9.0, 1.5]
+    ent_out = torch.empty(B, H, device="cuda", dtype=torch.float32)
+    n = dsla.dsla_attention_entropy_workspace_bytes(B, H, d, T)
+    ews = torch.empty(max(n, 1), dtype=torch.uint8, device="cuda")
+    sens = []
+    for l in range(L):
+        ql = wl.round_to_bf16(x["q"][:, T - 1] * np.float32(spreads[l]))
+        dsla.dsla_attention_entropy(to_gpu(ql, "bf16"), t["k"][:, :T].contiguous(), ent_out, scale, ews if n else None)
+        sens.append(float(ent_out.mean().item()))
+    order = dsla.dsla_rank_layers(sens)
+    assert order == sorted(range(L), key=lambda l: -spreads[l])      # the most peaked layer is the least sensitive
+    kv = dsla.dsla_kv_cache_bytes(1, B, T + steps, H, d, 2)
+    conv, _, why = dsla.dsla_conversion_plan(order, L * kv, 0, kv, B * H * 2 * d * d * 4, dsla.dsla_max_conversion_rate(T))
+    assert len(conv) == 3 and why == "quality limit"                  # 50 % of 6 layers at a prompt of 8192 tokens
+    qp, kp, vp = (t[n][:, :T].contiguous() for n in ("q", "k", "v"))
+    g1p, g2p = t["g1"][:, :T].contiguous(), t["g2"][:, :T].contiguous()
+    for l in range(L):
+        b, h = l % B, (5 * l + 3) % H
+        xs = {n: x[n][b:b + 1, :, h:h + 1] for n in x}
+        o = torch.full_like(vp, float("nan"))
+        if l in conv:
+            gamma = 0.2 + 0.1 * l
+            desc = dsla.make_desc(B, H, d, d, io_dtype=1, gate_dtype=1, gamma=gamma, scale=scale, chunk=64, zero_init=True)
+            S1, S2 = torch.empty(B, H, d, d, device="cuda"), torch.empty(B, H, d, d, device="cuda")
+            nb = dsla.dsla_prefill_workspace_bytes(desc, T)
+            ws = torch.empty(max(nb, 1), dtype=torch.uint8, device="cuda")
+            dsla.dsla_prefill(desc, T, qp, kp, vp, g1p, g2p, S1, S2, o, ws if nb else None)
+            od = torch.empty(steps, B, H, d, device="cuda", dtype=torch.bfloat16)
+            for s in range(steps):
+                dsla.dsla_decode(desc, *(t[n][:, T + s].contiguous() for n in ("q", "k", "v", "g1", "g2")), S1, S2, od[s])
+            torch.cuda.synchronize()
+            ro, _, _ = orc.recurrent(xs["q"], xs["k"], xs["v"], xs["g1"], xs["g2"], gamma, scale)
+            got = np.concatenate([o[b, :, h].float().cpu().numpy(), od[:, b, h].float().cpu().numpy()])
+        else:
+            dsla.dsla_attention_prefill(qp, kp, vp, o, scale)
+            nb = dsla.dsla_attention_decode_workspace_bytes(B, H, d, T + steps)
+            ws = torch.empty(max(nb, 1), dtype=torch.uint8, device="cuda")
+            od = torch.empty(steps, B, H, d, device="cuda", dtype=torch.bfloat16)
+            for s in range(steps):
+                lens = torch.full((B,), T + s + 1, dtype=torch.int32, device="cuda")
+                dsla.dsla_attention_decode(t["q"][:, T + s].contiguous(), t["k"], t["v"], od[s], scale, ws if nb else None, seq_lens=lens)
+            torch.cuda.synchronize()
+            ro = ent.attention_prefill(xs["q"], xs["k"], xs["v"], scale)     # causal over prompt + decode tokens
+            got = np.concatenate([o[b, :, h].float().cpu().numpy(), od[:, b, h].float().cpu().numpy()])
+        err = max_rel_err(got, ro[0, :, 0])
+        print(f"    layer {l} ({'DSLA' if l in conv else 'softmax'}), pair (b={b}, h={h}): max rel err {err:.3e}", flush=True)
+        assert np.all(np.isfinite(got)) and err <= 2e-2
