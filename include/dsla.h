@@ -266,10 +266,12 @@ DSLA_API dsla_status dsla_decode_multi(const dsla_desc *desc, const dsla_multi *
                               const void *q, const void *k, const void *v, void *o, void *stream);
 
 /*
- * dsla_prefill_multi - T tokens per sequence for a layer described by desc and multi.  The states are taken two at
- * a time through the kernels of dsla_prefill (an odd one out runs with an idle partner), the later pairs adding
- * their share to o; grouped key/value heads are an index map inside the kernels.  A beta gate is not supported by
- * the prefill (DSLA_ERR_UNSUPPORTED when g_beta names one): a caller that needs it steps through dsla_decode_multi.
+ * dsla_prefill_multi - T tokens per sequence for a layer described by desc and multi.  The states without a beta
+ * gate are taken two at a time through the kernels of dsla_prefill (an odd one out runs with an idle partner); a
+ * state with a beta gate runs on its own in a mode of the same kernels that splits the decay along the columns of
+ * the state between the values on the way in and the output on the way out, as the decay along the rows is split
+ * between keys and queries (the gate domain of dsla_prefill then holds for beta as for alpha).  Every launch after
+ * the first adds its share to o; grouped key/value heads are an index map inside the kernels.
  * workspace: at least dsla_prefill_multi_workspace_bytes(desc, multi, T) bytes, 256-byte aligned.
  */
 DSLA_API size_t dsla_prefill_multi_workspace_bytes(const dsla_desc *desc, const dsla_multi *multi, int64_t T);

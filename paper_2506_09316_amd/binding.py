@@ -209,7 +209,7 @@ def dsla_decode_slots(desc: DslaDesc, q, k, v, g1, g2, state_slot, S1, S2, o, ro
 
 def make_multi(g_alpha, S, weights, *, g_beta=None, H_kv=0, weights_per_head=None) -> DslaMulti:
     """dsla_multi from lists of GPU tensors (one per state).  The returned structure keeps the host arrays it
-    points to alive (attribute _keep); the caller keeps the tensors alive."""
+    points to, and the tensors themselves, alive (attribute _keep)."""
     n = len(g_alpha)
     assert len(S) == n and len(weights) == n and (g_beta is None or len(g_beta) == n)
     ga = (ctypes.c_void_p * n)(*[t.data_ptr() for t in g_alpha])
@@ -222,7 +222,7 @@ def make_multi(g_alpha, S, weights, *, g_beta=None, H_kv=0, weights_per_head=Non
     m = DslaMulti(n, int(H_kv), ctypes.cast(ga, ctypes.POINTER(ctypes.c_void_p)),
                   ctypes.cast(gb, ctypes.POINTER(ctypes.c_void_p)) if gb is not None else None,
                   ctypes.cast(Sp, ctypes.POINTER(ctypes.c_void_p)), ctypes.cast(w, ctypes.POINTER(ctypes.c_float)), wph)
-    m._keep = (ga, gb, Sp, w)
+    m._keep = (ga, gb, Sp, w, list(g_alpha), list(g_beta) if g_beta is not None else None, list(S), weights_per_head)
     return m
 
 

@@ -297,8 +297,9 @@ size_t dsla_prefill_multi_workspace_bytes(const dsla_desc *desc, const dsla_mult
         return 0;
     PrefillPlan plan;
     if (!prefill_plan(*desc, T, &plan)) return 0;
-    // an odd state out runs beside an idle partner, whose states live behind the plan's own scratch
-    const size_t partner = (multi->n_states & 1) ? plan.state_elems * sizeof(float) : 0;
+    // an odd state out runs beside an idle partner, whose states live behind the plan's own scratch (reserved whatever
+    // the parity of the states that pair up: which of them carry a beta gate is not part of the size query's contract)
+    const size_t partner = plan.state_elems * sizeof(float);
     return (plan.ws_total_bytes + 255) / 256 * 256 + partner;
 }
 
@@ -307,7 +308,7 @@ dsla_status dsla_prefill_multi(const dsla_desc *desc, const dsla_multi *multi, i
 {
     MultiStatePtrs mp;
     int Hkv = 0;
-    dsla_status st = check_multi(desc, multi, false, &mp, &Hkv);
+    dsla_status st = check_multi(desc, multi, true, &mp, &Hkv);
     if (st != DSLA_OK) return st;
     if (T < 0 || T > (int64_t(1) << 40)) return DSLA_ERR_SHAPE;
     if (T == 0) return DSLA_OK;
@@ -325,24 +326,43 @@ dsla_status dsla_prefill_multi(const dsla_desc *desc, const dsla_multi *multi, i
     const int N = multi->n_states;
     float *partner = reinterpret_cast<float *>(static_cast<char *>(workspace) + (plan.ws_total_bytes + 255) / 256 * 256);
     const float *wph = multi->weights_per_head;
-    for (int n = 0; n < N; n += 2) {
-        const bool pair = n + 1 < N;
+    // states without a beta gate go through the kernels two at a time, a state with one on its own (beta mode)
+    int plain[DSLA_MAX_STATES], n_plain = 0, gated[DSLA_MAX_STATES], n_gated = 0;
+    for (int n = 0; n < N; ++n) (mp.gb[n] ? gated[n_gated++] : plain[n_plain++]) = n;
+    int launches = 0;
+    for (int at = 0; at < n_plain; at += 2) {
+        const int n = plain[at];
+        const bool pair = at + 1 < n_plain;
+        const int n2 = pair ? plain[at + 1] : n;
         PrefillExt ext;
         ext.Hkv = Hkv;
-        ext.accumulate = n > 0;
+        ext.accumulate = launches++ > 0;
+        ext.beta = 0;
         ext.wa = mp.w[n];
-        ext.wb = pair ? mp.w[n + 1] : 0.f;
+        ext.wb = pair ? mp.w[n2] : 0.f;
         ext.wa_per_head = wph ? wph + static_cast<size_t>(n) * desc->H : nullptr;
-        ext.wb_per_head = (wph && pair) ? wph + static_cast<size_t>(n + 1) * desc->H : nullptr;
-        const void *gb = pair ? mp.ga[n + 1] : mp.ga[n];   // the idle partner follows the gates of its neighbour
-        float *Sb = pair ? mp.S[n + 1] : partner;
-        dsla_desc d = *desc;
-        if (!pair && !d.zero_init) {
+        ext.wb_per_head = (wph && pair) ? wph + static_cast<size_t>(n2) * desc->H : nullptr;
+        float *Sb = pair ? mp.S[n2] : partner;   // the idle partner follows the gates of its neighbour
+        if (!pair && !desc->zero_init) {
             // the idle partner starts from zero and its blend coefficient is zero: it stays finite and adds nothing
             hipError_t e = launch_state_init(partner, partner + plan.state_elems / 2, plan.state_elems / 2, s);
             if (e != hipSuccess) return hip_status(e);
         }
-        hipError_t e = launch_prefill(d, plan, T, nullptr, nullptr, nullptr, q, k, v, mp.ga[n], gb, mp.S[n], Sb, o,
+        hipError_t e = launch_prefill(*desc, plan, T, nullptr, nullptr, nullptr, q, k, v, mp.ga[n], mp.ga[n2], mp.S[n], Sb, o,
+                                      workspace, s, &ext);
+        if (e != hipSuccess) return hip_status(e);
+    }
+    for (int at = 0; at < n_gated; ++at) {
+        const int n = gated[at];
+        PrefillExt ext;
+        ext.Hkv = Hkv;
+        ext.accumulate = launches++ > 0;
+        ext.beta = 1;
+        ext.wa = mp.w[n];
+        ext.wb = 0.f;
+        ext.wa_per_head = wph ? wph + static_cast<size_t>(n) * desc->H : nullptr;
+        ext.wb_per_head = nullptr;
+        hipError_t e = launch_prefill(*desc, plan, T, nullptr, nullptr, nullptr, q, k, v, mp.ga[n], mp.gb[n], mp.S[n], mp.S[n], o,
                                       workspace, s, &ext);
         if (e != hipSuccess) return hip_status(e);
     }

@@ -84,6 +84,7 @@ bool prefill_plan_varlen(const dsla_desc &d, int64_t total_T, int64_t max_T, Pre
 struct PrefillExt {
     int Hkv;
     int accumulate;
+    int beta;   // nonzero: one state with the outer-product gate (g1 = log alpha, g2 = log beta, S1 only, wa only)
     float wa, wb;
     const float *wa_per_head, *wb_per_head;   // optional device arrays [H]
 };

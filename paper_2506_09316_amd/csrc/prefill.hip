@@ -138,6 +138,12 @@ struct ArithBf16 {
     {
         lds_st<u32x2>(a, u32x2{pack2(x0, x1), pack2(x2, x3)});
     }
+    static __device__ __forceinline__ f32x4 load4(uint32_t a)   // four adjacent operand elements
+    {
+        const u32x2 u = lds_ld<u32x2>(a);
+        return f32x4{__uint_as_float(u[0] << 16), __uint_as_float(u[0] & 0xffff0000u), __uint_as_float(u[1] << 16),
+                     __uint_as_float(u[1] & 0xffff0000u)};
+    }
     static __device__ __forceinline__ Frag from_acc(const f32x16 &acc, int half)
     {
         const u32x4 u = {pack2(acc[8 * half + 0], acc[8 * half + 1]), pack2(acc[8 * half + 2], acc[8 * half + 3]),
@@ -199,6 +205,7 @@ struct ArithF32 {
     {
         lds_st<f32x4>(a, f32x4{x0, x1, x2, x3});
     }
+    static __device__ __forceinline__ f32x4 load4(uint32_t a) { return lds_ld<f32x4>(a); }
     static __device__ __forceinline__ Frag from_acc(const f32x16 &acc, int half)
     {
         Frag f;
@@ -396,6 +403,7 @@ struct PrefillArgs {
     int Hkv;                 // key/value heads (k, v are [..][Hkv][D]); == H in ordinary launches
     int explicit_w;          // nonzero: the blend coefficients are wa, wb (or the per-head arrays)
     int accumulate;          // nonzero: o += result instead of o = result
+    int beta;                // nonzero (Kern<.., kBeta = true>): one state with the outer-product gate, see "Beta mode"
     float wa, wb;
     const float *wa_per_head, *wb_per_head;   // optional [H]
     float gate_inv_tau;      // 0: g1, g2 are log-gates; else they are pre-activations and this is 1 / tau
@@ -421,8 +429,19 @@ struct PrefillArgs {
 //     T <-  diag(2^{-(R + R_next)/2}) T          (R_next = 0 after the last step)
 // Centring halves the largest exponent a step can produce: the factors stay finite while R < 2 * 115, and nothing
 // links the exponents of different steps.
-template <int D, class TIO, class TG, bool kFull, bool kExt = false>
+//
+// Beta mode (Kern<.., kBeta = true>, extended launches only): ONE state with the outer-product gate alpha^T beta of the
+// background section on gated linear attention, S[d][j] <- alpha[d] beta[j] S[d][j] + k[d] v[j].  The tensor g1 holds
+// log alpha as usual, g2 holds log beta (one value per token and COLUMN), S1 is the state, S2 is not used.  The decay
+// along the columns is split like the one along the rows: with c' the centred cumulative log2 beta of a step,
+//     V~ = v 2^{-c'}        o = 2^{+c'} . (Q~ T + mask(Q~ K~^T) V~)        T <- T + K~^T V~
+// and T lives in the middle frame of the step for rows and columns alike.  The machinery of the second state carries
+// beta: its gate scan gives c', its Q~ slot in LDS holds the output factors 2^{c'}, its slot of frame changes those of
+// the columns; its K~ and its half of the contractions do not exist.
+template <int D, class TIO, class TG, bool kFull, bool kExt = false, bool kBeta = false>
 struct Kern {
+    static_assert(kExt || !kBeta, "beta mode is an extended launch");
+    static constexpr int NST = kBeta ? 1 : 2;   // states in the contractions
     using A = ArithOf<TIO>;
     using Frag = typename A::Frag;
     using Row8 = typename A::Row8;
@@ -733,6 +752,23 @@ struct Kern {
                 A::template store_tokens<RPT>(pa.kt[(e >> 1) & 1] + so + ((i * D + 8 * (e >> 2) + (e & 3)) * TP) * ESZ, kt, e);
         };
 
+        // beta mode, tokens j: the scaled values V~ (kept for the token-contiguous copy) and the output factors
+        Row8 vs[RPT];
+        auto block_beta = [&](int j, int slot_a, int slot_b) {
+            next.at(slot_a);
+            float vf[8], vh[8], fo[8];
+            r.v[j].unpack(vf);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float c = pa.unit * (sc.pre[1][e] + sc.c[1][j][e]);
+                vh[e] = vf[e] * __builtin_amdgcn_exp2f(-c);
+                fo[e] = __builtin_amdgcn_exp2f(c);
+            }
+            vs[j] = A::pack_row(vh);
+            next.at(slot_b);
+            if (kFull) A::store_row(pa.row + so + O_QS + (j * QP + D) * ESZ, A::pack_row(fo));
+        };
+
         float t[SGN];
         scan_b_read(pa, t);   // the answers arrive while the first block is computed
         block(0, 0, 2, 3);
@@ -746,12 +782,19 @@ struct Kern {
         block(0, 1, 4, 5);
         kt_rows(0);
         scan_c(pa, sn);
-        block(1, 0, 6, 7);
-        block(1, 1, 8, 9);
-        kt_rows(1);
-        // V transposed
+        if constexpr (kBeta) {
+            block_beta(0, 6, 7);
+            block_beta(1, 8, 9);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) store_v_tokens<RPT>(pa.vt[(e >> 1) & 3] + so + e * TP * ESZ, r.v, e);
+            for (int e = 0; e < 8; ++e) A::template store_tokens<RPT>(pa.vt[(e >> 1) & 3] + so + e * TP * ESZ, vs, e);
+        } else {
+            block(1, 0, 6, 7);
+            block(1, 1, 8, 9);
+            kt_rows(1);
+            // V transposed
+#pragma unroll
+            for (int e = 0; e < 8; ++e) store_v_tokens<RPT>(pa.vt[(e >> 1) & 3] + so + e * TP * ESZ, r.v, e);
+        }
     }
 
     // ------------------------------------------------------------------------------------------------------
@@ -814,7 +857,7 @@ struct Kern {
             for (int j = 0; j < 16; ++j) sc[j] = oacc[j] = 0.f;
             {
                 Frag held;   // the Ks fragment of a block waits here for its Qs partner
-                pipelined_steps<2 * NK, 8, A>(
+                pipelined_steps<NST * NK, 8, A>(
                     [&](int s2) -> uint32_t { return ((s2 & 1) ? qs_r : ks_r) + 16 * (s2 >> 1) * ESZ; },
                     [&](int s2, const Frag &f) {
                         if ((s2 & 1) == 0) {
@@ -839,14 +882,14 @@ struct Kern {
 
         // ---- add K~^T V (the output tile finishes in the matrix pipeline meanwhile) ----
         {
-            constexpr int NS = KB * 2 * DT;   // (token block, state, tile)
+            constexpr int NS = KB * NST * DT;   // (token block, state, tile)
             pipelined_steps<NS, 4, A>(
                 [&](int s2) -> uint32_t {
-                    const int kb = s2 / (2 * DT), i = (s2 / DT) % 2, dt = s2 % DT;
+                    const int kb = s2 / (NST * DT), i = (s2 / DT) % NST, dt = s2 % DT;
                     return kt_r[kb] + ((i * D + 32 * dt) * TP) * ESZ;
                 },
                 [&](int s2, const Frag &f) {
-                    const int kb = s2 / (2 * DT), i = (s2 / DT) % 2, dt = s2 % DT;
+                    const int kb = s2 / (NST * DT), i = (s2 / DT) % NST, dt = s2 % DT;
                     A::mma(acc[i][dt], f, vf[kb]);
                 });
             constexpr int RD = ESZ == 2 ? 1 : 2, MM = ESZ == 2 ? 1 : 8;
@@ -860,6 +903,15 @@ struct Kern {
         }
 
         // ---- store: lane (ln, g) holds query ln, columns 32 ct + 8 jb + 4 g .. + 3 ----
+        if constexpr (kBeta && kFull) {   // the output returns from the middle frame of the columns
+            const uint32_t fo_r = setb + O_QS + (ln * QP + D + 32 * ct + 4 * g) * ESZ;
+#pragma unroll
+            for (int jb = 0; jb < 4; ++jb) {
+                const f32x4 fo = A::load4(fo_r + 8 * jb * ESZ);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) oacc[4 * jb + e] *= fo[e];
+            }
+        }
         if constexpr (kStage) {
             // piece (row ln, 16-byte piece c) lives at piece position c ^ (ln mod NC) of its row
             const uint32_t st_w = sm + O_ST + set_parity * ST_BYTES + ln * (D * ESZ) + 8 * g;
@@ -884,14 +936,23 @@ struct Kern {
 
         // ---- the states move to the middle frame of the next step (after the last step: to their own frame) ----
         // (a block of its own for the register allocator: merged into the code above it costs four spilled registers)
-        if (opaque(1u)) rescale(acc, dec_r);
+        if (opaque(1u)) rescale(acc, dec_r, g, 32 * ct + ln);
     }
 
-    // acc[i][dt][j] *= f[i D + feature of register j], f = 2 D floats at LDS address `fac` (+ 8 g floats for this lane)
-    static __device__ __forceinline__ void rescale(f32x16 (&acc)[2][DT], uint32_t fac)
+    // acc[i][dt][j] *= f[i D + feature of register j], f = 2 D floats at LDS address `fac` (+ 8 g floats for this lane);
+    // beta mode: state 0 only, and every register of the lane also by the factor of the lane's column, f[D + column]
+    // (`col` = the lane's column, 32 ct + ln).
+    static __device__ __forceinline__ void rescale(f32x16 (&acc)[2][DT], uint32_t fac, uint32_t g, uint32_t col)
     {
+        if constexpr (kBeta) {
+            const float cf = lds_ld<float>(fac - 8 * g * 4 + (D + col) * 4);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int j = 0; j < 16; ++j) acc[0][dt][j] *= cf;
+        }
+#pragma unroll
+        for (int i = 0; i < NST; ++i) {
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
                 f32x4 dd[4];
@@ -970,7 +1031,7 @@ struct Kern {
             const bool cut = Tb > a.seg_tokens;
             if (kFull && (cut || !a.zero_init)) {
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
+                for (int i = 0; i < NST; ++i) {
                     const float *src = cut ? a.ws_state + ((slot0 + p * slot_step) * 2 + i) * D * D
                                            : (i ? a.S2 : a.S1) + sbh * D * D;
 #pragma unroll
@@ -989,7 +1050,7 @@ struct Kern {
             TIO *orow = static_cast<TIO *>(a.o) + seg0;
             const bool accum = kExt && a.accumulate;
             lds_barrier();   // operands of step 0 are ready
-            if (kFull) rescale(acc, sm + O_ENT + static_cast<uint32_t>(8 * g) * 4);   // into the middle frame of step 0
+            if (kFull) rescale(acc, sm + O_ENT + static_cast<uint32_t>(8 * g) * 4, g, 32 * ct + ln);   // into the middle frame of step 0
             for (int n = 0; n < nsteps; n += 2) {
                 if (kStage && n > 0) flush_rows(sm, 1, ct, lane, orow - sstep, rs, S, accum);
                 consume(sm, 0, acc, ct, lane, orow, rs, valid_of(n), 0, accum);
@@ -1008,7 +1069,7 @@ struct Kern {
             if (kStage) flush_rows(sm, (nsteps - 1) & 1, ct, lane, orow - sstep, rs, valid_of(nsteps - 1), accum);
             // ---- write the states out ----
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < NST; ++i) {
                 float *dst = nullptr;
                 if (kFull) {
                     if (t1 == Tb) dst = (i ? a.S2 : a.S1) + sbh * D * D;   // the segment with the last token
@@ -1117,10 +1178,10 @@ struct Kern {
     }
 };
 
-template <int D, class TIO, class TG, bool kFull, bool kExt>
+template <int D, class TIO, class TG, bool kFull, bool kExt, bool kBeta = false>
 __global__ __launch_bounds__(4 * D, 2) void prefill_kernel(PrefillArgs a)
 {
-    using K = Kern<D, TIO, TG, kFull, kExt>;
+    using K = Kern<D, TIO, TG, kFull, kExt, kBeta>;
     __shared__ __attribute__((aligned(16))) char smem[K::LDS_BYTES];
     K::run(a, lds_addr_of(smem));
 }
@@ -1191,7 +1252,7 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restri
                                                            const int32_t *__restrict__ seq,
                                                            const int32_t *__restrict__ slot,
                                                            const int32_t *__restrict__ seg_first, int H,
-                                                           int64_t seg_tokens, int zero_init)
+                                                           int64_t seg_tokens, int zero_init, int beta)
 {
     // one thread per 4 adjacent columns of one (bh, state, row)
     const size_t n4 = static_cast<size_t>(BH) * 2 * D * (D / 4);
@@ -1202,6 +1263,7 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restri
     const int row = static_cast<int>(r % D);
     const size_t bi = r / D;         // bh*2 + i
     const int i = static_cast<int>(bi & 1);
+    if (beta && i) return;   // beta mode: one state; the second slot of decays holds the log2 decays of its columns
     const size_t bh = bi >> 1;
     const size_t b = bh / H, h = bh % H;
     size_t slot0 = bh, slot_step = BH;
@@ -1221,19 +1283,27 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restri
     if (P <= 1) return;
     *reinterpret_cast<float4 *>(ws_state + slot0 * 2 * D * D + in_slot) = s;
     for (int p = 0; p + 1 < P; ++p) {
-        const float dec = __builtin_amdgcn_exp2f(ws_decay[(slot0 + p * slot_step) * 2 * D + i * D + row]);
+        const float *dslot = ws_decay + (slot0 + p * slot_step) * 2 * D;
+        const float dr = dslot[i * D + row];
+        float4 dec = make_float4(dr, dr, dr, dr);
+        if (beta) {
+            const float4 dc = *reinterpret_cast<const float4 *>(dslot + D + c4 * 4);
+            dec.x += dc.x; dec.y += dc.y; dec.z += dc.z; dec.w += dc.w;
+        }
+        dec.x = __builtin_amdgcn_exp2f(dec.x); dec.y = __builtin_amdgcn_exp2f(dec.y);
+        dec.z = __builtin_amdgcn_exp2f(dec.z); dec.w = __builtin_amdgcn_exp2f(dec.w);
         float4 *u = reinterpret_cast<float4 *>(ws_state + (slot0 + (p + 1) * slot_step) * 2 * D * D + in_slot);
         const float4 x = *u;
-        s.x = fmaf(dec, s.x, x.x);
-        s.y = fmaf(dec, s.y, x.y);
-        s.z = fmaf(dec, s.z, x.z);
-        s.w = fmaf(dec, s.w, x.w);
+        s.x = fmaf(dec.x, s.x, x.x);
+        s.y = fmaf(dec.y, s.y, x.y);
+        s.z = fmaf(dec.z, s.z, x.z);
+        s.w = fmaf(dec.w, s.w, x.w);
         *u = s;
     }
 }
 
 
-template <int D, class TIO, class TG, bool kExt>
+template <int D, class TIO, class TG, bool kExt, bool kBeta = false>
 hipError_t launch_x(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a, hipStream_t stream)
 {
     const int BH = d.B * d.H;
@@ -1255,7 +1325,7 @@ hipError_t launch_x(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
         }
         if (grid_pre > 0) {
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_STATE, stream);
-            hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, false, kExt>), dim3(grid_pre), dim3(4 * D), 0, stream, a);
+            hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, false, kExt, kBeta>), dim3(grid_pre), dim3(4 * D), 0, stream, a);
             err = hipGetLastError();
         }
         if (err != hipSuccess) return err;
@@ -1264,14 +1334,14 @@ hipError_t launch_x(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
             const size_t n4 = static_cast<size_t>(BH) * 2 * D * (D / 4);
             hipLaunchKernelGGL((segment_scan_kernel<D>), dim3(static_cast<unsigned>((n4 + 255) / 256)), dim3(256), 0,
                                stream, a.S1, a.S2, a.ws_state, a.ws_decay, BH, plan.segments, a.cu, a.seq, a.slot,
-                               a.seg_first, a.H, a.seg_tokens, a.zero_init);
+                               a.seg_first, a.H, a.seg_tokens, a.zero_init, kBeta ? 1 : 0);
             err = hipGetLastError();
         }
         if (err != hipSuccess) return err;
     }
     {
         ProfileScope ps(DSLA_KERNEL_PREFILL_CHUNK_LOOP, stream);
-        hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, true, kExt>), dim3(grid_full), dim3(4 * D), 0, stream, a);
+        hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, true, kExt, kBeta>), dim3(grid_full), dim3(4 * D), 0, stream, a);
     }
     err = hipGetLastError();
     return err;
@@ -1282,6 +1352,7 @@ hipError_t launch_x(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
 template <int D, class TIO, class TG>
 hipError_t launch_t(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a, hipStream_t stream)
 {
+    if (a.beta) return launch_x<D, TIO, TG, true, true>(d, plan, a, stream);
     if (a.explicit_w || a.accumulate || a.Hkv != a.H) return launch_x<D, TIO, TG, true>(d, plan, a, stream);
     return launch_x<D, TIO, TG, false>(d, plan, a, stream);
 }
@@ -1401,6 +1472,7 @@ hipError_t launch_prefill(const dsla_desc &d, const PrefillPlan &plan, int64_t T
     a.Hkv = ext ? ext->Hkv : d.H;
     a.explicit_w = ext ? 1 : 0;
     a.accumulate = ext ? ext->accumulate : 0;
+    a.beta = ext ? ext->beta : 0;
     a.wa = ext ? ext->wa : 0.f;
     a.wb = ext ? ext->wb : 0.f;
     a.wa_per_head = ext ? ext->wa_per_head : nullptr;
