@@ -58,6 +58,12 @@ def load_library():
     if not os.path.exists(_LIB_PATH):
         raise FileNotFoundError(f"{_LIB_PATH} is not built; run `python -m paper_2506_09316_amd.build` "
                                 "(or __graft_entry__.build())")
+    # PyTorch ships its own copy of the HIP runtime.  Whichever copy is loaded first serves the whole process, and
+    # tensors and kernels must live in the same one: load PyTorch's before the library pulls in the system's.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(_LIB_PATH)
     vp, dp = ctypes.c_void_p, ctypes.POINTER(DslaDesc)
     lib.dsla_state_init.argtypes = [dp, vp, vp, vp]
