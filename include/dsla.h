@@ -328,7 +328,8 @@ DSLA_API dsla_status dsla_attention_decode(int32_t B, int32_t H, int32_t d, int6
  * layout the prefill reads, so that dsla_prefill with gate_mode = DSLA_GATE_PREACT runs on them as they are:
  *     out_j[m][c] = sum_k x[m][k] W[j * width + c][k] (+ bias[j * width + c]),     j = 0 .. n_out - 1
  *   M          : rows of x = batch * tokens (>= 1)
- *   K          : model width, a multiple of 32
+ *   K          : model width, a multiple of 32 and at most 2^21 (a multiple of 128 takes the faster kernel: 256 x 256
+ *                output tiles instead of 128 x 128)
  *   n_out      : 1 .. DSLA_MAX_PROJECTIONS output tensors, each `width` = H * d wide, a multiple of 128
  *   x          : [M][K] bf16          W : [n_out * width][K] bf16, row-major (a linear layer's weight)
  *   bias       : [n_out * width] fp32 or NULL

@@ -426,7 +426,7 @@ dsla_status dsla_project(int64_t M, int32_t K, int32_t n_out, int32_t width, con
                          const float *bias, void *const *outs, void *stream)
 {
     if (M <= 0 || K <= 0 || n_out <= 0 || width <= 0) return DSLA_ERR_SHAPE;
-    if (n_out > DSLA_MAX_PROJECTIONS || K % 32 != 0 || width % 128 != 0) return DSLA_ERR_UNSUPPORTED;
+    if (n_out > DSLA_MAX_PROJECTIONS || K % 32 != 0 || K > (1 << 21) || width % 128 != 0) return DSLA_ERR_UNSUPPORTED;   // 32-bit byte offsets inside a tile
     if ((M + 127) / 128 * (static_cast<int64_t>(n_out) * width / 128) > 0x7ffffff0LL) return DSLA_ERR_SHAPE;
     if (!x || !W || !outs) return DSLA_ERR_NULL;
     if (!aligned16(x) || !aligned16(W) || !aligned16(bias)) return DSLA_ERR_SHAPE;

@@ -222,7 +222,8 @@ def _projection_case(seed, M, K, n_out, width, bias):
 
 
 @pytest.mark.parametrize("M,K,n_out,width,bias", [(300, 256, 5, 256, False), (128, 64, 1, 128, True), (1000, 512, 3, 384, True),
-                                                  (1, 32, 2, 128, False), (4096, 1024, 5, 1024, False)])
+                                                  (1, 32, 2, 128, False), (4096, 1024, 5, 1024, False),
+                                                  (513, 128, 1, 128, True), (256, 384, 2, 256, True), (700, 96, 2, 128, False)])
 def test_project_against_library_matmul(M, K, n_out, width, bias):
     """dsla_project against the definition through a library matmul in fp64 on the same bf16 inputs; the results are
     stored as bf16, so an element may differ from the exact product by half a bf16 unit of itself plus the fp32

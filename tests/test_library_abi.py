@@ -86,6 +86,21 @@ def test_argument_checks_need_no_gpu(lib):
     assert lib.dsla_prefill(ctypes.byref(d), -1, *([fake] * 8), None, 0, None) == 2
 
 
+def test_projection_argument_checks(lib):
+    fake = ctypes.c_void_p(4096)
+    outs = (ctypes.c_void_p * 2)(4096, 8192)
+    call = lambda M, K, n_out, width, x=fake, W=fake, o=outs: lib.dsla_project(
+        ctypes.c_int64(M), K, n_out, width, x, W, None, o, None)
+    assert call(0, 128, 2, 128) == 2                       # no rows
+    assert call(16, 48, 2, 128) == 3                       # K is not a multiple of 32
+    assert call(16, (1 << 21) + 128, 2, 128) == 3          # K beyond the 32-bit offsets of a tile
+    assert call(16, 128, 2, 192) == 3                      # width is not a multiple of 128
+    assert call(16, 128, 9, 128) == 3                      # more outputs than DSLA_MAX_PROJECTIONS
+    assert call(16, 128, 2, 128, x=None) == 1
+    assert call(16, 128, 2, 128, W=ctypes.c_void_p(4100)) == 2
+    assert call(16, 128, 2, 128, o=(ctypes.c_void_p * 2)(4096, None)) == 1
+
+
 def test_attention_entropy_argument_checks_and_plan(lib):
     fake = ctypes.c_void_p(4096)
     call = lambda B, H, d, T, io, q=fake, k=fake, o=fake, ws=None, n=0: lib.dsla_attention_entropy(
