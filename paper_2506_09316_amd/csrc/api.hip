@@ -440,7 +440,7 @@ dsla_status dsla_project(int64_t M, int32_t K, int32_t n_out, int32_t width, con
 dsla_status dsla_attention_prefill(int32_t B, int32_t H, int32_t d, int64_t T, int32_t io_dtype, float scale,
                                    const void *q, const void *k, const void *v, void *o, void *stream)
 {
-    if (B <= 0 || H <= 0 || d <= 0 || T <= 0 || T > 0x7fffffffLL) return DSLA_ERR_SHAPE;
+    if (B <= 0 || H <= 0 || d <= 0 || T <= 0 || T > 0x7fff0000LL) return DSLA_ERR_SHAPE;   // token indices are 32-bit in the kernel
     if (io_dtype != DSLA_BF16 || (d != 64 && d != 128)) return DSLA_ERR_UNSUPPORTED;
     if (static_cast<int64_t>(B) * H * ((T + 127) / 128) > 0x7fffffffLL) return DSLA_ERR_SHAPE;   // one workgroup per 128 queries
     if (!q || !k || !v || !o) return DSLA_ERR_NULL;
