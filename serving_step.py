@@ -7,6 +7,7 @@
     python serving_step.py --packed {equal,pow2,serving,one_long}
     python serving_step.py --entropy [--B 8 --T 8192]
     python serving_step.py --attention-decode [--B 8 --T 8192]
+    python serving_step.py --attention-prefill [--B 8 --T 8192]
 
 L layer instances (each with its own blend coefficient and its own pair of states per sequence) prefill a
 prompt of T tokens for B sequences and then decode token by token.  The decode step of all layers is captured
@@ -108,6 +109,34 @@ def entropy(B: int, T: int, H: int, d: int):
                       "us_per_call": round(us, 2), "key_bytes": nbytes, "GBps": round(nbytes / us / 1e3, 1),
                       "frac_of_8TBps": round(nbytes / us / 1e3 / 8000, 4),
                       "mean_entropy": round(float(out.mean()), 4)}))
+
+
+def attention_prefill(B: int, T: int, H: int, d: int):
+    """The causal softmax prefill of one unconverted layer (dsla_attention_prefill) over a prompt of T tokens; one
+    JSON line."""
+    import torch
+    import paper_2506_09316_amd as dsla
+
+    dev = torch.device("cuda:0")
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(20250609)
+    rnd = lambda *shape: torch.randn(*shape, device=dev, generator=gen).to(torch.bfloat16)
+    q, k, v = rnd(B, T, H, d), rnd(B, T, H, d), rnd(B, T, H, d)
+    o = torch.empty_like(v)
+    for _ in range(2):
+        dsla.dsla_attention_prefill(q, k, v, o, d ** -0.5)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(5):
+        dsla.dsla_attention_prefill(q, k, v, o, d ** -0.5)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / 5
+    flops = 2.0 * T * T * d * B * H   # Q K^T and P V over the lower triangle
+    print(json.dumps({"workload": f"causal softmax prefill of one layer: B={B} H={H} d={d} T={T}, bf16, synthetic inputs",
+                      "ms": round(ms, 4), "TFLOPs_causal": round(flops / ms / 1e9, 1),
+                      "frac_of_bf16_mfma_peak": round(flops / ms / 1e9 / 2500.0, 4)}))
 
 
 def attention_decode(B: int, T: int, H: int, d: int):
@@ -383,6 +412,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--attention-decode", action="store_true",
                     help="time the decode step of an unconverted softmax layer against the DSLA decode step instead")
+    ap.add_argument("--attention-prefill", action="store_true",
+                    help="time the causal softmax prefill of one unconverted layer instead")
     ap.add_argument("--entropy", action="store_true", help="time the attention-entropy kernel on one layer's keys instead")
     ap.add_argument("--packed", choices=sorted(MIXES), help="time one packed mixed-length prefill batch instead")
     ap.add_argument("--hybrid", action="store_true",
@@ -413,6 +444,8 @@ def main():
         return entropy(a.B, a.T, a.H, a.d)
     if a.attention_decode:
         return attention_decode(a.B, a.T, a.H, a.d)
+    if a.attention_prefill:
+        return attention_prefill(a.B, a.T, a.H, a.d)
 
     import torch
     import paper_2506_09316_amd as dsla
