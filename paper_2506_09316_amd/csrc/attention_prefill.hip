@@ -103,15 +103,23 @@ __global__ __launch_bounds__(256, 2) void attention_prefill_kernel(const bf16_t 
     // ---- staging of a key/value block: thread -> (row, 16-byte pieces), the same for keys and values ----
     constexpr int KPIECES = kKeys * D / 8 / 256;   // 16-byte pieces of K (and of V) per thread (4 at D = 128, 2 at D = 64)
     u32x4 kreg[KPIECES], vreg[KPIECES];
-    // Keys past the end of the sequence re-read the last key: whatever they hold, they lie after every query and are
-    // masked.  (No branch around a load: the loads of a block stay a fixed number of instructions in flight.)
+    // Buffer loads: the descriptors cover this (batch, head)'s keys and values from token 0 to the end of the last
+    // token's row, the per-lane offset of a piece is fixed and the block is the scalar offset: no address arithmetic per
+    // load.  Keys past the end of the sequence read as zero through the range check; they lie after every query and
+    // are masked.  (No branch around a load: the loads of a block stay a fixed number of instructions in flight.)
+    const uint32_t rs2 = static_cast<uint32_t>(rs) * 2;   // bytes between tokens
+    const int kv_bytes = static_cast<int>(static_cast<uint32_t>(T - 1) * rs2 + D * 2);
+    const __amdgpu_buffer_rsrc_t res_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(k + base), 0, kv_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t res_v = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(v + base), 0, kv_bytes, 0x00020000);
+    constexpr int ROWS_PER_PASS = 256 / (D / 8);   // piece i of a thread lies this many rows below piece i - 1
+    const uint32_t voff0 = static_cast<uint32_t>(tid / (D / 8)) * rs2 + 16 * (tid % (D / 8));
     auto load_block = [&](int key0) {
 #pragma unroll
         for (int i = 0; i < KPIECES; ++i) {
-            const int piece = tid + 256 * i, row = piece / (D / 8), c = piece % (D / 8);
-            const int key = key0 + row < T ? key0 + row : T - 1;
-            kreg[i] = *reinterpret_cast<const u32x4 *>(k + base + static_cast<size_t>(key) * rs + 8 * c);
-            vreg[i] = *reinterpret_cast<const u32x4 *>(v + base + static_cast<size_t>(key) * rs + 8 * c);
+            // a row past the last token starts at or beyond kv_bytes: the range check is on this lane offset alone
+            const uint32_t off = static_cast<uint32_t>(key0 + ROWS_PER_PASS * i) * rs2 + voff0;
+            kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(res_k, off, 0, 0);
+            vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(res_v, off, 0, 0);
         }
     };
     auto store_block = [&](int buf) {
