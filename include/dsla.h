@@ -345,7 +345,8 @@ DSLA_API dsla_status dsla_project(int64_t M, int32_t K, int32_t n_out, int32_t w
  * converted, which a partly converted model runs beside its DSLA layers (Section 4.3) and whose quadratic cost the
  * linear-time DSLA prefill is measured against (Section 5.3):
  *     o_t = sum_{i <= t} softmax_{i <= t}(scale * q_t . k_i) v_i .
- *   B, H, d  : batch, heads, head size (d in {64, 128});  T >= 1 tokens per sequence
+ *   B, H, d  : batch, heads, head size (d in {64, 128});  T >= 1 tokens per sequence, one sequence's tensor
+ *              (T * H * d * 2 bytes) below 4 GiB, else DSLA_ERR_SHAPE
  *   io_dtype : DSLA_BF16 only (bf16 operands on MFMA, fp32 accumulation and softmax statistics); DSLA_F32 is
  *              DSLA_ERR_UNSUPPORTED
  *   q, k, v  : [B][T][H][d]      o : [B][T][H][d], written

@@ -442,6 +442,7 @@ dsla_status dsla_attention_prefill(int32_t B, int32_t H, int32_t d, int64_t T, i
 {
     if (B <= 0 || H <= 0 || d <= 0 || T <= 0 || T > 0x7fff0000LL) return DSLA_ERR_SHAPE;   // token indices are 32-bit in the kernel
     if (io_dtype != DSLA_BF16 || (d != 64 && d != 128)) return DSLA_ERR_UNSUPPORTED;
+    if (T * H * d * 2 > 0xffffffffLL) return DSLA_ERR_SHAPE;   // byte offsets inside one sequence are 32-bit (buffer loads)
     if (static_cast<int64_t>(B) * H * ((T + 127) / 128) > 0x7fffffffLL) return DSLA_ERR_SHAPE;   // one workgroup per 128 queries
     if (!q || !k || !v || !o) return DSLA_ERR_NULL;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o)) return DSLA_ERR_SHAPE;

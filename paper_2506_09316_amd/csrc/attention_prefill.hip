@@ -5,14 +5,16 @@
 //
 // One pass over the keys with a running reference maximum (the scores never leave the chip).  A workgroup of four
 // wavefronts takes 128 consecutive queries of one (batch, head); a wavefront owns 32 of them.  Keys and values stream
-// through LDS 64 at a time, shared by the four wavefronts.  Per block of 64 keys a wavefront computes two transposed
-// score tiles S^T[key][query] = K Q^T on MFMA (so that a lane holds the scores of ONE query: the softmax needs one
-// cross-lane exchange), exponentiates against the reference, and adds V^T P^T to its output tiles O^T[column][query].
+// through LDS 64 at a time, shared by the four wavefronts, by buffer loads that go from memory straight to LDS (no
+// staging registers, no LDS store instructions; see AttnTiles for the placement that keeps the reads conflict-free).
+// Per block of 64 keys a wavefront computes two transposed score tiles S^T[key][query] = K Q^T on MFMA (so that a lane
+// holds the scores of ONE query: the softmax needs one cross-lane exchange), exponentiates against the reference, and
+// adds V^T P^T to its output tiles O^T[column][query].
 // The causal mask is applied only in the blocks on the diagonal, and the reference is raised (and the output tiles
-// rescaled) only when a block exceeds it by more than 2^8, which after the first blocks is rare.  Because an MFMA result tile and an MFMA input fragment both index lanes by the tile column, the
-// exponentiated tile is fed back as the input fragment of the second product without passing through LDS; V sits in
-// LDS as its rows were loaded and its transposed fragments come from the transposing LDS read, in the key order the
-// result registers of a score tile have.
+// rescaled) only when a block exceeds it by more than 2^8, which after the first blocks is rare.  Because an MFMA
+// result tile and an MFMA input fragment both index lanes by the tile column, the exponentiated tile is fed back as
+// the input fragment of the second product without passing through LDS; V sits in LDS as its rows arrived and its
+// transposed fragments come from the transposing LDS read, in the key order the result registers of a score tile have.
 // bf16 operands, fp32 accumulation and softmax statistics.
 #include "dsla_internal.h"
 
@@ -39,15 +41,24 @@ __device__ __forceinline__ uint32_t pack2(float a, float b)
     bf16x2 y = __builtin_convertvector(x, bf16x2);
     return __builtin_bit_cast(uint32_t, y);
 }
+// LDS image of a block of 64 keys (and of its values): rows of d elements WITHOUT padding, because the block is
+// written by loads that go from memory straight to LDS (a wavefront's 64 lanes fill 1 KB of consecutive LDS).  Bank
+// conflicts are avoided by WHERE in its row a 16-byte piece is put:
+// - keys: piece c of row r sits at piece position c ^ swz_k(r); the 16 rows that 16 lanes read at one time at the
+//   same logical piece then fall into 16 different groups of four banks;
+// - values: the 64-byte quarter q of row r sits at quarter position q ^ swz_v(r); a pass of the transposing read
+//   takes one quarter from each of 4 consecutive rows, which then fall into the four quarters of the banks.
+// The lane that fills LDS slot (row, position) simply fetches the piece that belongs there.
 template <int D>
 struct AttnTiles {
-    static constexpr int KP = D + 8;                              // pitch of a key row (elements): conflict-free 16-byte reads of 16 rows
-    // Pitch of a value row: a pass of the transposing read takes 64 bytes from each of 4 rows, which fall into
-    // different banks when the rows lie 64 bytes (mod 256) apart.
-    static constexpr int VP = D + 32;
-    static constexpr uint32_t K_BYTES = kKeys * KP * 2;
-    static constexpr uint32_t V_BYTES = kKeys * VP * 2;           // rows as loaded; read back transposed (ds_read_b64_tr_b16)
+    static constexpr int RB = D * 2;                    // bytes per row
+    static constexpr int NC = D / 8;                    // 16-byte pieces per row (16 or 8)
+    static constexpr int NQ = RB / 64;                  // 64-byte quarters per row (4 or 2)
+    static constexpr uint32_t K_BYTES = kKeys * RB;
+    static constexpr uint32_t V_BYTES = kKeys * RB;
     static constexpr uint32_t BUF_BYTES = K_BYTES + V_BYTES;
+    static __device__ __forceinline__ uint32_t swz_k(uint32_t row) { return NC == 16 ? (row & 15u) : ((row >> 1) & 7u); }
+    static __device__ __forceinline__ uint32_t swz_v(uint32_t row) { return NQ == 4 ? (row & 3u) : ((row >> 1) & 1u); }
 };
 
 // Fragment of V^T for a block of 16 keys from V rows in LDS, by two transposing 8-byte reads: the 16 lanes of a group
@@ -72,7 +83,9 @@ __global__ __launch_bounds__(256, 2) void attention_prefill_kernel(const bf16_t 
     using L = AttnTiles<D>;
     constexpr int NKB = D / 16;    // contraction blocks over the features
     constexpr int CT = D / 32;     // output column tiles
-    __shared__ __attribute__((aligned(16))) char smem[2 * L::BUF_BYTES];
+    // two buffers as two objects: the compiler then knows that a load into one does not touch what is read from the other
+    __shared__ __attribute__((aligned(1024))) char buf_a[L::BUF_BYTES];
+    __shared__ __attribute__((aligned(1024))) char buf_b[L::BUF_BYTES];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 31, g = lane >> 5;
@@ -100,40 +113,45 @@ __global__ __launch_bounds__(256, 2) void attention_prefill_kernel(const bf16_t 
         qf[kb] = __builtin_bit_cast(bf16x8, s);
     }
 
-    // ---- staging of a key/value block: thread -> (row, 16-byte pieces), the same for keys and values ----
-    constexpr int KPIECES = kKeys * D / 8 / 256;   // 16-byte pieces of K (and of V) per thread (4 at D = 128, 2 at D = 64)
-    u32x4 kreg[KPIECES], vreg[KPIECES];
-    // Buffer loads: the descriptors cover this (batch, head)'s keys and values from token 0 to the end of the last
-    // token's row, the per-lane offset of a piece is fixed and the block is the scalar offset: no address arithmetic per
-    // load.  Keys past the end of the sequence read as zero through the range check; they lie after every query and
-    // are masked.  (No branch around a load: the loads of a block stay a fixed number of instructions in flight.)
+    // ---- staging of a key/value block: buffer loads with LDS as destination.  One instruction of a wavefront fills
+    // 1 KB = RPI rows; instruction n = wave + 4 i of a block fills rows n RPI .. of the keys (and one more of the
+    // values).  The descriptors cover this (batch, head)'s keys and values from token 0 to the end of the last token's
+    // row: rows past the end of the sequence arrive as zeros (they lie after every query and are masked). ----
+    constexpr int RPI = 1024 / L::RB;                  // rows per instruction (4 or 8)
+    constexpr int NI = kKeys / RPI / 4;                // instructions per wavefront, block and tensor (4 or 2)
     const uint32_t rs2 = static_cast<uint32_t>(rs) * 2;   // bytes between tokens
-    const int kv_bytes = static_cast<int>(static_cast<uint32_t>(T - 1) * rs2 + D * 2);
+    const int kv_bytes = static_cast<int>(static_cast<uint32_t>(T - 1) * rs2 + D * 2);   // an unsigned 32-bit count to the hardware
     const __amdgpu_buffer_rsrc_t res_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(k + base), 0, kv_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t res_v = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(v + base), 0, kv_bytes, 0x00020000);
-    constexpr int ROWS_PER_PASS = 256 / (D / 8);   // piece i of a thread lies this many rows below piece i - 1
-    const uint32_t voff0 = static_cast<uint32_t>(tid / (D / 8)) * rs2 + 16 * (tid % (D / 8));
-    auto load_block = [&](int key0) {
+    const uint32_t uwave = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(wave));
+    // this lane's LDS slot in an instruction: row lr of its RPI rows, piece position lp; the swizzles of the rows an
+    // instruction fills depend on the lane and the wavefront only (RPI n is a multiple of what they look at)
+    const uint32_t lr = static_cast<uint32_t>(lane) / L::NC, lp = static_cast<uint32_t>(lane) % L::NC;
+    const uint32_t row0 = RPI * uwave + lr;            // row of instruction i = 0
+    const uint32_t goff_k = lr * rs2 + 16 * (lp ^ L::swz_k(row0));
+    const uint32_t goff_v = lr * rs2 + 16 * ((((lp >> 2) ^ L::swz_v(row0)) << 2) | (lp & 3u));
+    auto stage_block = [&](char *buf, int key0) {
 #pragma unroll
-        for (int i = 0; i < KPIECES; ++i) {
-            // a row past the last token starts at or beyond kv_bytes: the range check is on this lane offset alone
-            const uint32_t off = static_cast<uint32_t>(key0 + ROWS_PER_PASS * i) * rs2 + voff0;
-            kreg[i] = __builtin_amdgcn_raw_buffer_load_b128(res_k, off, 0, 0);
-            vreg[i] = __builtin_amdgcn_raw_buffer_load_b128(res_v, off, 0, 0);
+        for (int i = 0; i < NI; ++i) {
+            const uint32_t n = uwave + 4 * i;
+            // the range check is on the lane offset alone, so the row goes into it
+            const uint32_t rowoff = (static_cast<uint32_t>(key0) + RPI * n) * rs2;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(res_k, (__attribute__((address_space(3))) void *)(buf + n * 1024), 16,
+                                                     rowoff + goff_k, 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(res_v, (__attribute__((address_space(3))) void *)(buf + L::K_BYTES + n * 1024), 16,
+                                                     rowoff + goff_v, 0, 0, 0);
         }
     };
-    auto store_block = [&](int buf) {
-        char *kb_ = smem + buf * L::BUF_BYTES;
-#pragma unroll
-        for (int i = 0; i < KPIECES; ++i) {
-            const int piece = tid + 256 * i, row = piece / (D / 8), c = piece % (D / 8);
-            *reinterpret_cast<u32x4 *>(kb_ + (row * L::KP + 8 * c) * 2) = kreg[i];
-            *reinterpret_cast<u32x4 *>(kb_ + L::K_BYTES + (row * L::VP + 8 * c) * 2) = vreg[i];
-        }
-    };
-    // transposing reads of V: this lane's address in key block 0, column tile 0
+    // fragment reads.  Keys: row 32 t + ln, logical piece 2 kb + g.  Values (transposing reads): the 16 lanes of a
+    // group address 4 rows x 4 pieces of 4 columns: row 4 g + l16 / 4 of a block of 16 keys (+ 8 for the second read),
+    // columns 32 ct + 16 (lane / 16 % 2) + 4 (l16 % 4), i.e. quarter ct of the row.
+    const uint32_t sk = L::swz_k(ln);                  // (rows 32 t + ln: the swizzle looks at the low bits only)
+    const uint32_t kf_off = ln * L::RB + 16 * ((g ^ sk) & 1u);
+    const uint32_t kf_s1 = sk >> 1;                    // piece pair kb of the row sits at pair position kb ^ kf_s1
     const uint32_t l16 = lane & 15;
-    const uint32_t vt_off = ((4 * g + (l16 >> 2)) * L::VP + 16 * ((lane >> 4) & 1) + 4 * (l16 & 3)) * 2;
+    const uint32_t vrow = 4 * g + (l16 >> 2);
+    const uint32_t sv = L::swz_v(vrow);                // (rows 16 kb2 + 8 h + vrow: low bits only)
+    const uint32_t vt_off = vrow * L::RB + 32 * ((lane >> 4) & 1) + 8 * (l16 & 3);
 
     // keys this workgroup needs: 0 .. min(T, q0 + 128) - 1; this wavefront needs them up to its last query
     const int wg_last_q = (q0 + kQueriesPerWg < T ? q0 + kQueriesPerWg : T) - 1;
@@ -147,15 +165,11 @@ __global__ __launch_bounds__(256, 2) void attention_prefill_kernel(const bf16_t 
         for (int r = 0; r < 16; ++r) oacc[ct][r] = 0.f;
     float m_ref = -1.0e30f, l_run = 0.f;   // reference maximum (log2 domain) and denominator of this lane's query
 
-    load_block(0);
-    store_block(0);
-    for (int jb = 0; jb < nblocks; ++jb) {
-        __syncthreads();   // block jb is in buffer jb & 1; every wavefront is done with block jb - 1
-        if (jb + 1 < nblocks) load_block((jb + 1) * kKeys);
+    auto compute = [&](const char *buf, int jb) {
         const int key0 = jb * kKeys;
         if (key0 <= wave_last_q) {   // else: every key of the block lies after every query of this wavefront
-            const char *kb_ = smem + (jb & 1) * L::BUF_BYTES;
-            const char *vb_ = kb_ + L::K_BYTES;
+            const char *kb_ = buf;
+            const char *vb_ = buf + L::K_BYTES;
             // S^T[key][query], two tiles of 32 keys: lane (ln, g) ends up with keys 32 t + 8 (r / 4) + 4 g + r % 4 of query ln
             f32x16 sc[2];
             const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -163,7 +177,7 @@ __global__ __launch_bounds__(256, 2) void attention_prefill_kernel(const bf16_t 
             for (int kb = 0; kb < NKB; ++kb)
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
-                    const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(kb_ + ((32 * t + ln) * L::KP + 16 * kb + 8 * g) * 2));
+                    const bf16x8 kf = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(kb_ + 32 * t * L::RB + kf_off + 32 * (kb ^ kf_s1)));
                     sc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kb], kb ? sc[t] : zero, 0, 0, 0);
                 }
             // causal mask, only in the blocks that reach past the first query of the wavefront (keys past the end of
@@ -216,11 +230,23 @@ __global__ __launch_bounds__(256, 2) void attention_prefill_kernel(const bf16_t 
             for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
                 for (int kb2 = 0; kb2 < 4; ++kb2) {
-                    const bf16x8 vf = load_vt_frag(vb_ + vt_off + (16 * kb2 * L::VP + 32 * ct) * 2, 8 * L::VP * 2);
+                    const bf16x8 vf = load_vt_frag(vb_ + vt_off + 16 * kb2 * L::RB + 64 * (ct ^ sv), 8 * L::RB);
                     oacc[ct] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[kb2], oacc[ct], 0, 0, 0);
                 }
         }
-        if (jb + 1 < nblocks) store_block((jb + 1) & 1);
+    };
+    // Block j lives in buffer j % 2; its loads are issued one iteration ahead, right after the barrier that frees the
+    // buffer, and the barrier in front of its use waits for them (the loads of every wavefront must have landed).
+    stage_block(buf_a, 0);
+    for (int jb = 0; jb < nblocks; jb += 2) {
+        __syncthreads();   // block jb is in buffer a; every wavefront is done with block jb - 1
+        if (jb + 1 < nblocks) stage_block(buf_b, (jb + 1) * kKeys);
+        compute(buf_a, jb);
+        if (jb + 1 < nblocks) {
+            __syncthreads();   // block jb + 1 is in buffer b; every wavefront is done with block jb
+            if (jb + 2 < nblocks) stage_block(buf_a, (jb + 2) * kKeys);
+            compute(buf_b, jb + 1);
+        }
     }
 
     // ---- o[query][32 ct + 8 (r / 4) + 4 g + r % 4] = O^T / denominator ----

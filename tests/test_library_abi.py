@@ -136,6 +136,18 @@ def test_attention_decode_argument_checks_and_plan(lib):
     assert call(8, 32, 128, 8192, 1) == 4
 
 
+def test_attention_prefill_argument_checks(lib):
+    fake = ctypes.c_void_p(4096)
+    call = lambda B, H, d, T, io, q=fake, k=fake, v=fake, o=fake: lib.dsla_attention_prefill(
+        B, H, d, ctypes.c_int64(T), io, 1.0, q, k, v, o, None)
+    assert call(0, 4, 128, 100, 1) == 2
+    assert call(2, 4, 100, 100, 1) == 3                  # head size
+    assert call(2, 4, 128, 100, 0) == 3                  # fp32 is not built
+    assert call(2, 4, 128, 100, 1, k=None) == 1
+    assert call(2, 4, 128, 100, 1, o=ctypes.c_void_p(4104)) == 2
+    assert call(1, 32, 128, 1 << 19, 1) == 2             # one sequence's tensor reaches 4 GiB: 32-bit byte offsets
+
+
 def test_varlen_workspace_plan(lib):
     up = lambda n: (n + 255) // 256 * 256
     # 8 sequences, 32 heads; total 32768 tokens, longest 16384.  The segment length follows the total (about one
