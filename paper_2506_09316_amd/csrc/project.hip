@@ -11,9 +11,10 @@
 // wavefront per SIMD with a 128 x 128 quadrant = sixteen 32 x 32 MFMA tiles whose 256 accumulator registers live in
 // the accumulation half of the register file.  Per 16 values of K a wavefront reads 4 + 4 fragments from LDS for 16
 // MFMAs - half a 16-byte LDS read per MFMA, a quarter of what a 64 x 64 quadrant needs, which is what keeps the LDS
-// (128 bytes per clock and CU) out of the way.  K in steps of 64 through double-buffered LDS (2 x 64 KB); a row of a
-// tile is 128 bytes, its eight 16-byte pieces stored at piece position c ^ ((row / 2) % 8), so that both the staging
-// stores and the fragment reads of 16 lanes at a time touch every bank once.
+// (128 bytes per clock and CU) out of the way.  K in stages of 32 through a ring of four LDS stages (4 x 32 KB),
+// filled by buffer loads that write LDS directly (no staging registers, no LDS store instructions): a load has two
+// stages to arrive.  A row of a stage is 64 bytes, its four 16-byte pieces stored at piece position c ^ ((row / 4) % 4),
+// so that the fragment reads of 16 lanes at a time touch every bank once.
 //
 // project_kernel (any K that is a multiple of 32): 128 x 128 tile, 64 x 64 quadrants, K in steps of 32.
 //
@@ -91,18 +92,22 @@ __device__ __forceinline__ void store_tile(const f32x16 &acc, const ProjectOuts 
 // ---------------------------------------------------------------------------------------------------------------
 // 256 x 256 tiles
 // ---------------------------------------------------------------------------------------------------------------
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int ROWB = BK * 2;                      // bytes per LDS row (one row of a tile, BK values of K)
-constexpr int OPB = BM * ROWB;                    // bytes per operand tile: 32 KB
-constexpr int STAGEB = 2 * OPB;                   // A tile, then B tile
-constexpr int EPI_PITCH = 128 * 2 + 16;           // bytes per row of a wavefront's 128 x 128 result in LDS (padded)
-constexpr int EPI_BYTES = 4 * 128 * EPI_PITCH;    // four wavefronts
+constexpr int BM = 256, BN = 256;
+constexpr int BK = 32;                            // values of K per stage
+constexpr int ROWB = BK * 2;                     // bytes per LDS row: 64
+constexpr int OPB = BM * ROWB;                  // bytes per operand tile and stage: 16 KB
+constexpr int STAGEB = 2 * OPB;                 // A tile, then B tile: 32 KB
 
 __global__ __launch_bounds__(256) void project_kernel_256(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
-                                                          const float *__restrict__ bias, ProjectOuts outs, long long M,
-                                                          int K, int N, int width, int tiles_m, int tiles_n)
+                                                                 const float *__restrict__ bias, ProjectOuts outs, long long M,
+                                                                 int K, int N, int width, int tiles_m, int tiles_n)
 {
-    __shared__ __attribute__((aligned(16))) char lds[EPI_BYTES > 2 * STAGEB ? EPI_BYTES : 2 * STAGEB];
+    // four stages as four objects: the compiler's wait-count insertion then knows that a load into one stage does not
+    // touch what is read from another
+    __shared__ __attribute__((aligned(1024))) char st0[STAGEB];
+    __shared__ __attribute__((aligned(1024))) char st1[STAGEB];
+    __shared__ __attribute__((aligned(1024))) char st2[STAGEB];
+    __shared__ __attribute__((aligned(1024))) char st3[STAGEB];
     int tm, tn;
     if (!tile_of(tiles_m, tiles_n, tm, tn)) return;
     const long long m0 = static_cast<long long>(tm) * BM;
@@ -111,52 +116,50 @@ __global__ __launch_bounds__(256) void project_kernel_256(const bf16_t *__restri
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int ln = lane & 31, g = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;   // this wavefront's 128 x 128 quadrant
+    const uint32_t uwave = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(wave));
 
-    // staging: 2048 16-byte pieces per operand tile and K-step, eight per thread: piece tid + 256 u is
-    // (row tid / 8 + 32 u, 8 values of K from 8 (tid % 8)).  Buffer loads: the descriptor of an operand starts at the
-    // tile's first row and ends with the last row that exists, so rows past the end of x or W read as zero; the
-    // per-lane offset is 32 bits and the K-step is the scalar offset.
-    const int srow = tid >> 3, sc = tid & 7;
-    uint32_t goff[8];   // byte offset from the first row of the tile: the same in x and W
-#pragma unroll
-    for (int u = 0; u < 8; ++u) goff[u] = (static_cast<uint32_t>(srow + 32 * u) * static_cast<uint32_t>(K) + 8 * sc) * 2u;
+    // Buffer loads with LDS as destination: one instruction of a wavefront fills 1 KB = 16 rows of 64 bytes of a
+    // tile; instruction n = wave + 4 i (i < 4) fills rows 16 n .. 16 n + 15.  A lane fills LDS slot (row lane / 4, piece
+    // position lane % 4) and fetches the piece that belongs there: piece c of row r sits at position c ^ ((r / 4) % 4),
+    // so the 16 rows that 16 lanes read at the same logical piece fall into 16 different groups of four banks.  The
+    // descriptor of an operand starts at the tile's first row and ends with the last row that exists: rows past the
+    // end of x or W arrive as zeros.
     const long long rows_a = M - m0 < BM ? M - m0 : BM, rows_b = N - n0 < BN ? N - n0 : BN;
     const __amdgpu_buffer_rsrc_t res_a = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t *>(x + static_cast<size_t>(m0) * K), 0, static_cast<int>(rows_a * K * 2), 0x00020000);
     const __amdgpu_buffer_rsrc_t res_b = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<bf16_t *>(w + static_cast<size_t>(n0) * K), 0, static_cast<int>(rows_b * K * 2), 0x00020000);
-    // LDS position of this thread's pieces: (row / 2) % 8 is the same for all eight
-    const uint32_t st_off = static_cast<uint32_t>(srow * ROWB + ((sc ^ ((srow >> 1) & 7)) << 4));
-
-    // Two register sets for the staging: K-step j travels through set j % 2.  Its loads are issued at the start of
-    // step j - 2 and it is written to LDS stage j % 2 during step j - 1, so a load has one to two steps (2048 MFMA
-    // cycles each) to arrive.
-    u32x4 ra[2][8], rb[2][8];
-    auto load_tiles = [&](auto set, int k0) {
-        constexpr int s = decltype(set)::value;
+    uint32_t voff[4];   // byte offset of this lane's piece from the first row of the tile (the range check is on it)
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            ra[s][u] = __builtin_amdgcn_raw_buffer_load_b128(res_a, goff[u], k0 * 2, 0);
-            rb[s][u] = __builtin_amdgcn_raw_buffer_load_b128(res_b, goff[u], k0 * 2, 0);
-        }
-    };
-    auto store_tiles = [&](auto set, int u0, int u1) {   // pieces u0 .. u1 - 1 of set s -> LDS stage s
-        constexpr int s = decltype(set)::value;
-        char *base = lds + s * STAGEB + st_off;
+    for (int i = 0; i < 4; ++i)
+        voff[i] = (16 * (uwave + 4 * i) + (static_cast<uint32_t>(lane) >> 2)) * static_cast<uint32_t>(K) * 2u +
+                  16 * ((lane & 3u) ^ ((static_cast<uint32_t>(lane) >> 4) & 3u));
+    const int nk = K / BK;
+    typedef __attribute__((address_space(3))) void *lds_void;
+    auto fetch = [&](char *st, int ks) {   // K-step ks (past the end: the last one again, never used) into a stage
+        const int kbyte = (ks < nk ? ks : nk - 1) * BK * 2;
 #pragma unroll
-        for (int u = u0; u < u1; ++u) {
-            *reinterpret_cast<u32x4 *>(base + u * 32 * ROWB) = ra[s][u];
-            *reinterpret_cast<u32x4 *>(base + OPB + u * 32 * ROWB) = rb[s][u];
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t n = uwave + 4 * i;
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(res_a, (lds_void)(st + n * 1024), 16, voff[i], kbyte, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(res_b, (lds_void)(st + OPB + n * 1024), 16, voff[i], kbyte, 0, 0);
         }
     };
 
-    // fragment reads: row (quadrant + 32 i + ln) of a tile, K block kb: piece 2 kb + g at position (2 kb + g) ^ swz
-    const uint32_t swz = (ln >> 1) & 7;
-    uint32_t fo[BK / 16];
-#pragma unroll
-    for (int kb = 0; kb < BK / 16; ++kb) fo[kb] = ((2 * kb + g) ^ swz) << 4;
+    // fragment reads: row (quadrant + 32 i + ln) of a tile, block kb of 16 values of K: piece 2 kb + g
+    const uint32_t swz = (ln >> 2) & 3;
+    const uint32_t fo0 = ((0 + g) ^ swz) << 4, fo1 = ((2 + g) ^ swz) << 4;
     const uint32_t fa_row = static_cast<uint32_t>((128 * wm + ln) * ROWB);
     const uint32_t fb_row = static_cast<uint32_t>(OPB + (128 * wn + ln) * ROWB);
+    bf16x8 fa[2][4], fb[2][4];   // fragments of two blocks: one in use, one arriving
+    auto read_frags = [&](int buf, const char *st, int kb) {
+        const uint32_t fo = kb ? fo1 : fo0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            fa[buf][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(st + fa_row + i * 32 * ROWB + fo));
+            fb[buf][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(st + fb_row + i * 32 * ROWB + fo));
+        }
+    };
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -166,84 +169,55 @@ __global__ __launch_bounds__(256) void project_kernel_256(const bf16_t *__restri
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    const int nk = K / BK;
-    using P0 = std::integral_constant<int, 0>;
-    using P1 = std::integral_constant<int, 1>;
-    bf16x8 fa[2][4], fb[2][4];   // fragments of two blocks of 16 values of K: one in use, one arriving
-    auto read_frags = [&](int buf, const char *st, int kb) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            fa[buf][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(st + fa_row + i * 32 * ROWB + fo[kb]));
-            fb[buf][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(st + fb_row + i * 32 * ROWB + fo[kb]));
-        }
-    };
-    // One K-step from LDS stage p: four blocks of 16 values of K, each 16 MFMAs with the other work of the block
-    // spread between them one instruction at a time (a burst of LDS reads holds up the MFMA issue of a lone wavefront:
-    // 1.24 against 1.35 PFLOP/s in a loop of nothing else).  The instruction scheduler is held to the order written
-    // here; left alone it moves every fragment read down to just in front of its use.
-    //   block 0: fragments of block 1; first half of K-step ks + 1 from its registers to the other stage; the loads
-    //            of K-step ks + 2 into the registers K-step ks came through
-    //   block 1: fragments of block 2; second half of K-step ks + 1
-    //   barrier: the other stage is complete
-    //   block 2: fragments of block 3
-    //   block 3: fragments of block 0 of K-step ks + 1, from the other stage
-    //   barrier: everybody is done reading this stage; the next step may overwrite it
-    // so no MFMA ever waits for a barrier and the LDS latency behind it.  On entry the fragments of block 0 are there.
     auto block = [&](int kb) {
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kb & 1][j], fa[kb & 1][i], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kb][j], fa[kb][i], acc[i][j], 0, 0, 0);
 #pragma unroll
         for (int t = 0; t < 16; ++t) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                             // 1 MFMA
-            // blocks in front of a barrier (1 and 3) have their LDS work in the first three quarters, so that it is
-            // done when the wavefront arrives there
-            if (kb % 2 == 0 ? t % 2 == 0 : t < 8) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
-            if (kb == 0 ? t % 2 == 1 : (kb == 1 && t >= 4 && t < 12)) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);   // 1 LDS store
-            if (kb == 0) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);                // 1 global load
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                              // 1 MFMA
+            if (t % 2 == 0) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);              // 1 LDS read
+            if (kb == 0 && t % 2 == 1) __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);   // 1 load into LDS
         }
         __builtin_amdgcn_sched_barrier(0);
     };
-    auto step = [&](auto par, int ks) {
-        constexpr int p = decltype(par)::value;
-        using Other = std::integral_constant<int, 1 - p>;
-        const char *st = lds + p * STAGEB, *sn = lds + (1 - p) * STAGEB;
-        read_frags(1, st, 1);
-        store_tiles(Other{}, 0, 4);   // after the last step: the last step again, into a stage nobody reads any more
-        load_tiles(par, (ks + 2 < nk ? ks + 2 : nk - 1) * BK);   // past the end: the last step again, never used
+    // One K-step from stage `cur`.  On entry the fragments of its first block are in registers and stage `nxt` holds
+    // what this wavefront loaded of the next step but one barrier short of being complete for everybody: the barrier
+    // at the start certifies `nxt` (every wavefront has waited for its own loads of it: all but the 8 youngest, which
+    // belong to the stage after) and frees `old` (everybody is done with the step before), which then takes K-step
+    // ks + 3.  So a load has two steps to arrive, and no MFMA waits behind a barrier for LDS latency: the first
+    // fragments of `nxt` are read during the second block.
+    auto step = [&](const char *cur, const char *nxt, char *old, int ks) {
+        asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(old, ks + 3);
+        read_frags(1, cur, 1);
         block(0);
-        read_frags(0, st, 2);
-        store_tiles(Other{}, 4, 8);
+        read_frags(0, nxt, 0);
         block(1);
-        __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);
-        read_frags(1, st, 3);
-        block(2);
-        read_frags(0, sn, 0);
-        block(3);
-        __syncthreads();
-        __builtin_amdgcn_sched_barrier(0);
     };
-    // nk is even (K is a multiple of 2 BK): the loop body has no branch, so the accumulators stay where they are
-    load_tiles(P0{}, 0);
-    load_tiles(P1{}, BK);
-    store_tiles(P0{}, 0, 8);
-    __syncthreads();
-    read_frags(0, lds, 0);
+    // nk is a multiple of 4 (K is a multiple of 128): the loop body has no branch, so the accumulators stay where they are
+    fetch(st0, 0);
+    fetch(st1, 1);
+    fetch(st2, 2);
+    asm volatile("s_waitcnt vmcnt(16)\n\ts_barrier" ::: "memory");   // stage 0 is complete
+    read_frags(0, st0, 0);
     __builtin_amdgcn_sched_barrier(0);
-    for (int ks = 0; ks < nk; ks += 2) {
-        step(P0{}, ks);
-        step(P1{}, ks + 1);
+    for (int ks = 0; ks < nk; ks += 4) {
+        step(st0, st1, st3, ks);
+        step(st1, st2, st0, ks + 1);
+        step(st2, st3, st1, ks + 2);
+        step(st3, st0, st2, ks + 3);
     }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // nothing in flight; everybody is done reading
 
-    // Results: each wavefront turns its quadrant round in LDS (its own 34 KB; the last barrier of the loop has freed the
-    // stages) so that it leaves as whole rows: a lane holds 4 adjacent columns of a row per register group and writes
-    // them as 8 bytes; then 16 lanes read one row of 128 columns as 16 bytes each and store 256 contiguous bytes.
-    // (Stored straight from the registers, 8 bytes at a time into 32 different rows per instruction, the results of a
-    // tile took an eighth of the kernel's time.)
-    char *epi = lds + wave * (128 * EPI_PITCH);
+    // Results: each wavefront turns its quadrant round in LDS - its own stage object, 128 rows of 256 bytes, the 16-byte
+    // piece c of row r at position c ^ (r % 16) - so that it leaves as whole rows: a lane holds 4 adjacent columns of a
+    // row per register group and writes them as 8 bytes; then 16 lanes read one row as 16 bytes each and store 256
+    // contiguous bytes.
+    char *epi = wave == 0 ? st0 : (wave == 1 ? st1 : (wave == 2 ? st2 : st3));
     const int nq = n0 + 128 * wn;   // first column of the quadrant: inside one output tensor (width is a multiple of 128)
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -260,7 +234,8 @@ __global__ __launch_bounds__(256) void project_kernel_256(const bf16_t *__restri
                     c2 += bv[2];
                     c3 += bv[3];
                 }
-                *reinterpret_cast<u32x2 *>(epi + (32 * i + ln) * EPI_PITCH + cq * 2) = u32x2{pack2(c0, c1), pack2(c2, c3)};
+                const int row = 32 * i + ln, piece = cq >> 3;
+                *reinterpret_cast<u32x2 *>(epi + row * 256 + ((piece ^ (row & 15)) << 4) + (cq & 4) * 2) = u32x2{pack2(c0, c1), pack2(c2, c3)};
             }
     if (nq < N) {
         bf16_t *out = static_cast<bf16_t *>(outs.p[nq / width]) + nq % width;
@@ -269,7 +244,7 @@ __global__ __launch_bounds__(256) void project_kernel_256(const bf16_t *__restri
         for (int it = 0; it < 32; ++it) {
             const int row = 4 * it + rsub;
             const long long m = m0 + 128 * wm + row;
-            const u32x4 vrow = *reinterpret_cast<const u32x4 *>(epi + row * EPI_PITCH + piece * 16);
+            const u32x4 vrow = *reinterpret_cast<const u32x4 *>(epi + row * 256 + ((piece ^ (row & 15)) << 4));
             if (m < M) *reinterpret_cast<u32x4 *>(out + static_cast<size_t>(m) * width + piece * 8) = vrow;
         }
     }
@@ -367,7 +342,7 @@ hipError_t launch_project(int64_t M, int K, int n_out, int width, const void *x,
     for (int j = 0; j < DSLA_MAX_PROJECTIONS; ++j) po.p[j] = j < n_out ? outs[j] : nullptr;
     const int N = n_out * width;
     ProfileScope ps(DSLA_KERNEL_PROJECT, stream);
-    if (K % (2 * BK) == 0) {
+    if (K % (4 * BK) == 0) {   // the loop of project_kernel_256 goes four stages at a time
         const int tiles_m = static_cast<int>((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
         const long long ntiles = static_cast<long long>(tiles_m) * tiles_n;
         const unsigned grid = static_cast<unsigned>((ntiles + 7) / 8 * 8);
