@@ -28,7 +28,8 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kQueriesPerWg = 128;   // 4 wavefronts x 32
+constexpr int kWaves = 4;                                 // wavefronts per workgroup
+constexpr int kQueriesPerWg = 32 * kWaves;
 constexpr int kKeys = 64;            // keys per block: two score tiles of 32
 // The running maximum of a query is only raised when a block exceeds it by more than this (log2 units): the
 // exponentials then stay below 2^8 and the output tiles are rescaled once in a long while instead of once per block.
@@ -76,7 +77,7 @@ __device__ __forceinline__ bf16x8 load_vt_frag(const char *a, uint32_t eight_row
 }
 
 template <int D>
-__global__ __launch_bounds__(256, 2) void attention_prefill_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
+__global__ __launch_bounds__(64 * kWaves, 512 / (64 * kWaves)) void attention_prefill_kernel(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
                                                                    const bf16_t *__restrict__ v, bf16_t *__restrict__ o,
                                                                    int H, int T, int blocks_per_seq, float scale_log2e)
 {
@@ -114,11 +115,12 @@ __global__ __launch_bounds__(256, 2) void attention_prefill_kernel(const bf16_t 
     }
 
     // ---- staging of a key/value block: buffer loads with LDS as destination.  One instruction of a wavefront fills
-    // 1 KB = RPI rows; instruction n = wave + 4 i of a block fills rows n RPI .. of the keys (and one more of the
+    // 1 KB = RPI rows; instruction n = wave + kWaves i of a block fills rows n RPI .. of the keys (and one more of the
     // values).  The descriptors cover this (batch, head)'s keys and values from token 0 to the end of the last token's
     // row: rows past the end of the sequence arrive as zeros (they lie after every query and are masked). ----
     constexpr int RPI = 1024 / L::RB;                  // rows per instruction (4 or 8)
-    constexpr int NI = kKeys / RPI / 4;                // instructions per wavefront, block and tensor (4 or 2)
+    constexpr int NI = kKeys / RPI / kWaves;           // instructions per wavefront, block and tensor
+    static_assert(NI >= 1, "every wavefront stages something");
     const uint32_t rs2 = static_cast<uint32_t>(rs) * 2;   // bytes between tokens
     const int kv_bytes = static_cast<int>(static_cast<uint32_t>(T - 1) * rs2 + D * 2);   // an unsigned 32-bit count to the hardware
     const __amdgpu_buffer_rsrc_t res_k = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(k + base), 0, kv_bytes, 0x00020000);
@@ -133,7 +135,7 @@ __global__ __launch_bounds__(256, 2) void attention_prefill_kernel(const bf16_t 
     auto stage_block = [&](char *buf, int key0) {
 #pragma unroll
         for (int i = 0; i < NI; ++i) {
-            const uint32_t n = uwave + 4 * i;
+            const uint32_t n = uwave + kWaves * i;
             // the range check is on the lane offset alone, so the row goes into it
             const uint32_t rowoff = (static_cast<uint32_t>(key0) + RPI * n) * rs2;
             __builtin_amdgcn_raw_ptr_buffer_load_lds(res_k, (__attribute__((address_space(3))) void *)(buf + n * 1024), 16,
@@ -273,11 +275,11 @@ hipError_t launch_attn_prefill(int B, int H, int d, int64_t T, float scale, cons
     const float sl2 = scale * 1.4426950408889634f;
     ProfileScope ps(DSLA_KERNEL_ATTENTION_PREFILL, stream);
     if (d == 128)
-        hipLaunchKernelGGL((attention_prefill_kernel<128>), dim3(grid), dim3(256), 0, stream, static_cast<const bf16_t *>(q),
+        hipLaunchKernelGGL((attention_prefill_kernel<128>), dim3(grid), dim3(64 * kWaves), 0, stream, static_cast<const bf16_t *>(q),
                            static_cast<const bf16_t *>(k), static_cast<const bf16_t *>(v), static_cast<bf16_t *>(o), H,
                            static_cast<int>(T), blocks_per_seq, sl2);
     else
-        hipLaunchKernelGGL((attention_prefill_kernel<64>), dim3(grid), dim3(256), 0, stream, static_cast<const bf16_t *>(q),
+        hipLaunchKernelGGL((attention_prefill_kernel<64>), dim3(grid), dim3(64 * kWaves), 0, stream, static_cast<const bf16_t *>(q),
                            static_cast<const bf16_t *>(k), static_cast<const bf16_t *>(v), static_cast<bf16_t *>(o), H,
                            static_cast<int>(T), blocks_per_seq, sl2);
     return hipGetLastError();
