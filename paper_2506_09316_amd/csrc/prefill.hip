@@ -1178,8 +1178,10 @@ struct Kern {
     }
 };
 
+// Wavefronts per SIMD the register budget is set for: two, except for the fp32 step loop at d = 64, whose one
+// workgroup per compute unit (LDS) is one wavefront per SIMD and whose accumulators do not fit half the register file.
 template <int D, class TIO, class TG, bool kFull, bool kExt, bool kBeta = false>
-__global__ __launch_bounds__(4 * D, 2) void prefill_kernel(PrefillArgs a)
+__global__ __launch_bounds__(4 * D, (D == 64 && sizeof(TIO) == 4 && kFull) ? 1 : 2) void prefill_kernel(PrefillArgs a)
 {
     using K = Kern<D, TIO, TG, kFull, kExt, kBeta>;
     __shared__ __attribute__((aligned(16))) char smem[K::LDS_BYTES];
