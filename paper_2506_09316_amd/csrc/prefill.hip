@@ -102,6 +102,17 @@ struct ArithBf16 {
         f.v = __builtin_bit_cast(bf16x8, lds_ld<u32x4>(a));
         return f;
     }
+    // Two transposing 8-byte reads (see Kern::consume): contraction positions 0..3 from address a, 4..7 from a + step.
+    static __device__ __forceinline__ Frag load_frag_tr(uint32_t a, uint32_t step)
+    {
+        typedef short s16x4 __attribute__((ext_vector_type(4)));
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<s16x4 DSLA_LDS *>(static_cast<uintptr_t>(a)));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<s16x4 DSLA_LDS *>(static_cast<uintptr_t>(a + step)));
+        const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+        Frag f;
+        f.v = __builtin_bit_cast(bf16x8, u32x4{l2[0], l2[1], h2[0], h2[1]});
+        return f;
+    }
     static __device__ __forceinline__ uint32_t pack2(float a, float b)
     {
         f32x2 x = {a, b};
@@ -174,6 +185,7 @@ struct ArithF32 {
         f.v[4] = hi[0]; f.v[5] = hi[1]; f.v[6] = hi[2]; f.v[7] = hi[3];
         return f;
     }
+    static __device__ __forceinline__ Frag load_frag_tr(uint32_t, uint32_t) { return Frag{}; }   // 16-bit storage only
     static __device__ __forceinline__ Row8 pack_row(const float (&x)[8])
     {
         Row8 r;
@@ -334,6 +346,10 @@ __device__ __forceinline__ void store_v_tokens(uint32_t a, const Raw8<float> (&v
         lds_st<f32x2>(a, f32x2{pick(v[0]), pick(v[1])});
 }
 
+// a loaded row piece of V as it is (16-bit storage only)
+__device__ __forceinline__ void store_v_row(uint32_t a, const Raw8<bf16_t> &v) { lds_st<u32x4>(a, v.u); }
+__device__ __forceinline__ void store_v_row(uint32_t, const Raw8<float> &) {}
+
 // four adjacent output elements -> global
 __device__ __forceinline__ void store4_global(bf16_t *p, float a, float b, float c, float d)
 {
@@ -467,7 +483,13 @@ struct Kern {
     static constexpr uint32_t O_QS = 0;                                        // [token][i*D + d]            Q'
     static constexpr uint32_t O_KS = O_QS + (kFull ? S * QP * ESZ : 0);        // [token][i*D + d]            K^
     static constexpr uint32_t O_KT = O_KS + (kFull ? S * QP * ESZ : 0);        // [i*D + rho(d)][rho(token)]  K^
-    static constexpr uint32_t O_VT = O_KT + 2 * D * TP * ESZ;                  // [column][rho(token)]        v
+    // V: 16-bit storage keeps the rows as loaded, [token][column] without padding, the 64-byte quarter q of row r at
+    // quarter position q ^ vswz(r), and the consumers read them with the transposing LDS read, a pass of which takes one
+    // quarter from each of 4 consecutive rows: they fall into different banks.  32-bit storage keeps the
+    // token-contiguous copy [column][rho(token)].  Both take S * D elements.
+    static constexpr bool kTrV = ESZ == 2;
+    static __device__ __forceinline__ uint32_t vswz(uint32_t row) { return D == 128 ? (row & 3u) : ((row >> 1) & 1u); }
+    static constexpr uint32_t O_VT = O_KT + 2 * D * TP * ESZ;
     static constexpr uint32_t O_DEC = O_VT + D * TP * ESZ;                     // float [2D]  frame change after the step
     static constexpr uint32_t SET_BYTES = O_DEC + 2 * D * 4;
     static constexpr uint32_t LDS_MAX = 160 * 1024;                            // LDS of a gfx950 compute unit
@@ -568,6 +590,7 @@ struct Kern {
         uint32_t row;   // row-layout operands: token 2sg, element f0 (token + 1: + QP, state 1: + D elements)
         uint32_t kt[2];   // Kt: row of feature e = 0 of state 0, position of tokens 2sg, 2sg+1; [x]: for features e with (e/2)%2 = x
         uint32_t vt[4];   // Vt: row of column f0, position of tokens 2sg, 2sg+1; [x]: for columns e with (e/2)%4 = x
+        uint32_t vrow[RPT];   // V rows (16-bit storage): token 2sg + j, this lane's 8 columns
         uint32_t sg;
         uint32_t state;   // state of the column this lane scans
         bool preact;      // the gate tensors hold pre-activations, not log-gates (uniform)
@@ -591,6 +614,11 @@ struct Kern {
             // the row of column e is R = 32 pw + 8 dgl + e: (R/2)%4 = (e/2)%4
 #pragma unroll
             for (uint32_t x = 0; x < 4; ++x) vt[x] = sm + O_VT + (f0 * TP + 8 * (piece ^ x) + within) * ESZ;
+#pragma unroll
+            for (uint32_t j = 0; j < RPT; ++j) {
+                const uint32_t r = sg * RPT + j;   // the lane's 8 columns are piece dgl of quarter pw of the row
+                vrow[j] = sm + O_VT + r * (D * ESZ) + 64 * (static_cast<uint32_t>(pw) ^ vswz(r)) + 16 * dgl;
+            }
         }
     };
 
@@ -785,15 +813,24 @@ struct Kern {
         if constexpr (kBeta) {
             block_beta(0, 6, 7);
             block_beta(1, 8, 9);
+            if constexpr (kTrV) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) A::template store_tokens<RPT>(pa.vt[(e >> 1) & 3] + so + e * TP * ESZ, vs, e);
+                for (int j = 0; j < RPT; ++j) A::store_row(pa.vrow[j] + so, vs[j]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) A::template store_tokens<RPT>(pa.vt[(e >> 1) & 3] + so + e * TP * ESZ, vs, e);
+            }
         } else {
             block(1, 0, 6, 7);
             block(1, 1, 8, 9);
             kt_rows(1);
-            // V transposed
+            if constexpr (kTrV) {   // V as loaded
 #pragma unroll
-            for (int e = 0; e < 8; ++e) store_v_tokens<RPT>(pa.vt[(e >> 1) & 3] + so + e * TP * ESZ, r.v, e);
+                for (int j = 0; j < RPT; ++j) store_v_row(pa.vrow[j] + so, r.v[j]);
+            } else {                // V transposed
+#pragma unroll
+                for (int e = 0; e < 8; ++e) store_v_tokens<RPT>(pa.vt[(e >> 1) & 3] + so + e * TP * ESZ, r.v, e);
+            }
         }
     }
 
@@ -840,9 +877,17 @@ struct Kern {
         const uint32_t kt_r[KB] = {setb + O_KT + (ln * TP + p0) * ESZ, setb + O_KT + (ln * TP + p1) * ESZ};
         const uint32_t dec_r = setb + O_DEC + (8 * g) * 4;
 
+        // transposing reads of the V rows: the 16 lanes of a group address 4 tokens x 4 pieces of 4 columns and each
+        // receives 4 tokens of ONE column; lane l ends up with column 32 ct + l % 32 and tokens 16 kb + 4 g + 0..3 (first
+        // read) and 16 kb + 8 + 4 g + 0..3 (second read, 8 rows further): the order of the token-contiguous copies
+        const uint32_t l16 = lo & 15, vr = 4 * g + (l16 >> 2);
+        const uint32_t vs_r = setb + O_VT + vr * (D * ESZ) + 64 * (static_cast<uint32_t>(ct) ^ vswz(vr)) + 32 * ((lo >> 4) & 1) + 8 * (l16 & 3);
         Frag vf[KB];   // V fragments of this wavefront's columns: input of the output and of the update
 #pragma unroll
-        for (int kb = 0; kb < KB; ++kb) vf[kb] = A::load_frag(vt_r[kb]);
+        for (int kb = 0; kb < KB; ++kb) {
+            if constexpr (kTrV) vf[kb] = A::load_frag_tr(vs_r + 16 * kb * (D * ESZ), 8 * (D * ESZ));
+            else vf[kb] = A::load_frag(vt_r[kb]);
+        }
 
         f32x16 oacc;
         if (kFull) {
