@@ -374,16 +374,18 @@ __device__ __forceinline__ void store8_global(float *base, uint32_t elem_off, ui
 
 // Software-pipelined sequence of N steps: the LDS fragment of step s + DEPTH is requested before the
 // MFMA of step s is issued, so that LDS latency overlaps DEPTH matrix instructions.  Fully unrolled.
-template <int N, int DEPTH, class ARITH, class AddrF, class StepF>
-__device__ __forceinline__ void pipelined_steps(AddrF addr, StepF step)
+// kTr: the fragments come from rows by two transposing reads, the second TR_STEP bytes (two row slots) further.
+template <int N, int DEPTH, class ARITH, bool kTr = false, class AddrF, class StepF>
+__device__ __forceinline__ void pipelined_steps(AddrF addr, StepF step, uint32_t tr_step = 0)
 {
+    auto load = [&](int i) { return kTr ? ARITH::load_frag_tr(addr(i), tr_step) : ARITH::load_frag(addr(i)); };
     typename ARITH::Frag buf[DEPTH];
 #pragma unroll
-    for (int i = 0; i < DEPTH && i < N; ++i) buf[i] = ARITH::load_frag(addr(i));
+    for (int i = 0; i < DEPTH && i < N; ++i) buf[i] = load(i);
 #pragma unroll
     for (int s = 0; s < N; ++s) {
         const typename ARITH::Frag cur = buf[s % DEPTH];
-        if (s + DEPTH < N) buf[s % DEPTH] = ARITH::load_frag(addr(s + DEPTH));
+        if (s + DEPTH < N) buf[s % DEPTH] = load(s + DEPTH);
         step(s, cur);
     }
 }
@@ -481,15 +483,26 @@ struct Kern {
 
     // LDS map (bytes).  Two operand sets; per set:
     static constexpr uint32_t O_QS = 0;                                        // [token][i*D + d]            Q'
-    static constexpr uint32_t O_KS = O_QS + (kFull ? S * QP * ESZ : 0);        // [token][i*D + d]            K^
-    static constexpr uint32_t O_KT = O_KS + (kFull ? S * QP * ESZ : 0);        // [i*D + rho(d)][rho(token)]  K^
+    // K~: 16-bit storage keeps ONE copy, in rows [token][i*D + d] of pitch QP; the consumers read it as rows (scores)
+    // and, for the update, transposed with ds_read_b64_tr_b16.  Token t sits in row slot kslot(t): the two low bit pairs
+    // of the token index swapped.  The 16 rows that 16 lanes read at the same feature then lie in 16 different slots
+    // (each slot shifts the banks by 16 bytes: pitch), and the 4 consecutive tokens a pass of the transposing read
+    // takes 64 bytes each from lie 4 slots apart: 64 bytes apart in the banks.  32-bit storage keeps two copies: rows
+    // (step loop only) and the token-contiguous one [i*D + rho(d)][rho(token)].
+    // (Step loop only: in the segment pre-pass, whose consumers have little else to do, the doubled number of LDS read
+    // instructions gets in the way of the producers' gate scan, which is bound by its LDS round trips: 119.6 against
+    // 116.8 us.)
+    static constexpr bool kTrK = ESZ == 2 && kFull;
+    static __device__ __forceinline__ uint32_t kslot(uint32_t t) { return (t & ~15u) | ((t & 3u) << 2) | ((t >> 2) & 3u); }
+    static constexpr uint32_t O_KS = O_QS + (kFull ? S * QP * ESZ : 0);
+    static constexpr uint32_t O_KT = O_KS + ((kFull || kTrK) ? S * QP * ESZ : 0);
     // V: 16-bit storage keeps the rows as loaded, [token][column] without padding, the 64-byte quarter q of row r at
     // quarter position q ^ vswz(r), and the consumers read them with the transposing LDS read, a pass of which takes one
     // quarter from each of 4 consecutive rows: they fall into different banks.  32-bit storage keeps the
     // token-contiguous copy [column][rho(token)].  Both take S * D elements.
     static constexpr bool kTrV = ESZ == 2;
     static __device__ __forceinline__ uint32_t vswz(uint32_t row) { return D == 128 ? (row & 3u) : ((row >> 1) & 1u); }
-    static constexpr uint32_t O_VT = O_KT + 2 * D * TP * ESZ;
+    static constexpr uint32_t O_VT = O_KT + (kTrK ? 0 : 2 * D * TP * ESZ);
     static constexpr uint32_t O_DEC = O_VT + D * TP * ESZ;                     // float [2D]  frame change after the step
     static constexpr uint32_t SET_BYTES = O_DEC + 2 * D * 4;
     static constexpr uint32_t LDS_MAX = 160 * 1024;                            // LDS of a gfx950 compute unit
@@ -591,6 +604,7 @@ struct Kern {
         uint32_t kt[2];   // Kt: row of feature e = 0 of state 0, position of tokens 2sg, 2sg+1; [x]: for features e with (e/2)%2 = x
         uint32_t vt[4];   // Vt: row of column f0, position of tokens 2sg, 2sg+1; [x]: for columns e with (e/2)%4 = x
         uint32_t vrow[RPT];   // V rows (16-bit storage): token 2sg + j, this lane's 8 columns
+        uint32_t krow[RPT];   // K~ rows (16-bit storage): row slot of token 2sg + j, element f0 (state 1: + D elements)
         uint32_t sg;
         uint32_t state;   // state of the column this lane scans
         bool preact;      // the gate tensors hold pre-activations, not log-gates (uniform)
@@ -618,6 +632,7 @@ struct Kern {
             for (uint32_t j = 0; j < RPT; ++j) {
                 const uint32_t r = sg * RPT + j;   // the lane's 8 columns are piece dgl of quarter pw of the row
                 vrow[j] = sm + O_VT + r * (D * ESZ) + 64 * (static_cast<uint32_t>(pw) ^ vswz(r)) + 16 * dgl;
+                krow[j] = sm + O_KS + (kslot(r) * QP + f0) * ESZ;
             }
         }
     };
@@ -762,7 +777,8 @@ struct Kern {
                 for (int e = 0; e < 8; ++e)
                     kh[e] = kf[e] * __builtin_amdgcn_exp2f(-pa.unit * (sc.pre[i][e] + sc.c[i][j][e]));
                 kt[j] = A::pack_row(kh);
-                if (kFull) A::store_row(pa.row + so + O_KS + (j * QP + i * D) * ESZ, kt[j]);
+                if constexpr (kTrK) A::store_row(pa.krow[j] + so + i * D * ESZ, kt[j]);
+                else if (kFull) A::store_row(pa.row + so + O_KS + (j * QP + i * D) * ESZ, kt[j]);
             }
             next.at(slot_q);
             if (kFull) {
@@ -775,6 +791,7 @@ struct Kern {
             }
         };
         auto kt_rows = [&](int i) {
+            if constexpr (kTrK) return;   // the rows are the only copy
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 A::template store_tokens<RPT>(pa.kt[(e >> 1) & 1] + so + ((i * D + 8 * (e >> 2) + (e & 3)) * TP) * ESZ, kt, e);
@@ -875,6 +892,12 @@ struct Kern {
         const uint32_t p0 = 8 * tpiece(g, ln), p1 = 8 * tpiece(g + 2, ln);
         const uint32_t vt_r[KB] = {setb + O_VT + ((32 * ct + ln) * TP + p0) * ESZ, setb + O_VT + ((32 * ct + ln) * TP + p1) * ESZ};
         const uint32_t kt_r[KB] = {setb + O_KT + (ln * TP + p0) * ESZ, setb + O_KT + (ln * TP + p1) * ESZ};
+        // transposing reads of the K~ rows (16-bit storage): lane l must end up with feature rho(l % 32) of a tile of 32
+        // (the row order of the token-contiguous copy: the accumulators are fed back as fragments in it), so the lanes
+        // that address piece s of 4 features point at piece (s swapped in its two bits); tokens as for V: row slots
+        // 4 (l16 / 4) + g of a block of 16, and 2 slots further for the second read
+        const uint32_t l16k = lo & 15, sgm = ((l16k & 1) << 1) | ((l16k >> 1) & 1);
+        const uint32_t ktr_r = setb + O_KS + ((4 * (l16k >> 2) + g) * QP + 16 * ((lo >> 4) & 1) + 4 * sgm) * ESZ;
         const uint32_t dec_r = setb + O_DEC + (8 * g) * 4;
 
         // transposing reads of the V rows: the 16 lanes of a group address 4 tokens x 4 pieces of 4 columns and each
@@ -892,7 +915,7 @@ struct Kern {
         f32x16 oacc;
         if (kFull) {
             const uint32_t qs_r = setb + O_QS + (ln * QP + 8 * g) * ESZ;
-            const uint32_t ks_r = setb + O_KS + (ln * QP + 8 * g) * ESZ;
+            const uint32_t ks_r = setb + O_KS + ((kTrK ? kslot(ln) : ln) * QP + 8 * g) * ESZ;
             // One pass over the 2 d_k features, 16 at a time, with the Q~ fragment shared by two products:
             //   sc[j]   = S^T[key 8(j/4) + 4g + j%4][query ln]        (Q~ K~^T, both states blended)
             //   oacc[j] = o^T[column 8(j/4) + 4g + j%4][query ln]     (carried states: the accumulators themselves
@@ -928,15 +951,17 @@ struct Kern {
         // ---- add K~^T V (the output tile finishes in the matrix pipeline meanwhile) ----
         {
             constexpr int NS = KB * NST * DT;   // (token block, state, tile)
-            pipelined_steps<NS, 4, A>(
+            pipelined_steps<NS, 4, A, kTrK>(
                 [&](int s2) -> uint32_t {
                     const int kb = s2 / (NST * DT), i = (s2 / DT) % NST, dt = s2 % DT;
-                    return kt_r[kb] + ((i * D + 32 * dt) * TP) * ESZ;
+                    if constexpr (kTrK) return ktr_r + (16 * kb * QP + i * D + 32 * dt) * ESZ;
+                    else return kt_r[kb] + ((i * D + 32 * dt) * TP) * ESZ;
                 },
                 [&](int s2, const Frag &f) {
                     const int kb = s2 / (NST * DT), i = (s2 / DT) % NST, dt = s2 % DT;
                     A::mma(acc[i][dt], f, vf[kb]);
-                });
+                },
+                2 * QP * ESZ);
             constexpr int RD = ESZ == 2 ? 1 : 2, MM = ESZ == 2 ? 1 : 8;
             __builtin_amdgcn_sched_group_barrier(0x100, 4 * RD, 0);
 #pragma unroll
