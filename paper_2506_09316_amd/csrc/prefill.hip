@@ -1258,6 +1258,257 @@ __global__ __launch_bounds__(4 * D, (D == 64 && sizeof(TIO) == 4 && kFull) ? 1 :
     K::run(a, lds_addr_of(smem));
 }
 
+// ---------------------------------------------------------------------------------------------
+// Segment pre-pass of its own design for the common case: 16-bit io and gates, d = 128, ordinary launch.
+//
+// The state contribution of a segment of N tokens is U^i = sum_t diag(prod_{s > t} alpha^i_s) k_t^T v_t (Section 4.1,
+// the state update unrolled to the end of the segment).  Walking the segment BACKWARDS, 32 tokens at a time, the
+// exponent of every factor is a running suffix sum of log-gates: never positive, so nothing is centred and the
+// accumulated state is never rescaled:
+//     K~^i_t = k_t 2^{E^i_t},  E^i_t = sum_{s > t} log2 alpha^i_s  (<= 0)        U^i += (K~^i)^T V      per step.
+// Inputs reach LDS as whole rows through loads that write LDS directly (no registers, 2 steps ahead of their use:
+// 64 KB per workgroup in flight).  The suffix sums over the 32 tokens of a step are a product of a constant 0/1
+// matrix with the tile of log-gates: the matrix unit evaluates them, exactly, and hands every lane one feature and 16
+// tokens of it; a transposing LDS read delivers the keys in the same arrangement, and what is left for the vector unit
+// is one fused multiply-add, one exponential, one multiply and half a pack per (token, feature, state): a third of
+// what the producer wavefronts of the step-loop template spend on the same operands.
+//
+// All 8 wavefronts do both jobs: wavefront w prepares state w / 4, features 32 (w % 4) .. + 31, and multiplies
+// state w / 4, columns 32 (w % 4) .. + 31 (64 accumulator registers).  One barrier per step: in interval n every
+// wavefront prepares K~ of step n into one of two K~ buffers and then multiplies step n - 1, so the vector and the
+// matrix work of neighbouring steps overlap across the wavefronts of a SIMD.
+// LDS: 3 slots of (k, g1, g2) rows + 4 slots of v rows + 2 K~ buffers = 72 + 32 + 32 KB.  All rows as loaded, the
+// 64-byte quarter q of row r at quarter position q ^ (r % 4) (every tensor is read transposed); K~ as in the
+// step-loop template: [i D + feature][rho(token)], piece c of row R at c ^ ((R / 2) % 4).
+// ---------------------------------------------------------------------------------------------
+struct SegFast {
+    static constexpr int D = 128, S = 32;
+    static constexpr int NWAVE = 8, NT = 64 * NWAVE;
+    static constexpr int LEAD = 2;                                     // steps between a load and its use
+    static constexpr int KG_SLOTS = LEAD + 1, V_SLOTS = LEAD + 2;      // v lives one interval longer (it is multiplied one later)
+    static constexpr uint32_t ROWB = D * 2, TEN = S * ROWB;            // a row, a tensor of one step (bytes)
+    static constexpr uint32_t KG_BYTES = 3 * TEN;
+    static constexpr uint32_t O_KG = 0, O_V = O_KG + KG_SLOTS * KG_BYTES, O_KT = O_V + V_SLOTS * TEN;
+    static constexpr uint32_t KT_BYTES = 2 * D * S * 2;
+    static constexpr uint32_t LDS_BYTES = O_KT + 2 * KT_BYTES;
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+};
+
+// 16 bytes per lane from `base` (wavefront-uniform) + `voff` (per lane) into LDS at `lds` (uniform) + 16 * lane.
+// The compiler does not know these loads: whoever reads the bytes waits with wait_loads<>() first.
+__device__ __forceinline__ void load_to_lds16(uint32_t lds, uint32_t voff, const char *base)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(base) : "memory");
+}
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier()   // at most N of this wavefront's loads still in flight; then the workgroup meets
+{
+    static_assert(N == 0 || N == 4, "one step of loads is 4 instructions per wavefront");
+    __builtin_amdgcn_sched_barrier(0);
+    if constexpr (N == 4) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+__device__ __forceinline__ const char *uniform_ptr(const void *p)   // the same pointer, held in scalar registers
+{
+    const uint64_t x = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(x)));
+    const uint32_t hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<uint32_t>(x >> 32)));
+    return reinterpret_cast<const char *>((static_cast<uint64_t>(hi) << 32) | lo);
+}
+__global__ __launch_bounds__(SegFast::NT, 2) void segment_state_fast_kernel(PrefillArgs a)
+{
+    using F = SegFast;
+    using A = ArithBf16;
+    constexpr int D = F::D, S = F::S;
+    __shared__ __attribute__((aligned(1024))) char smem[F::LDS_BYTES];
+    const uint32_t sm = lds_addr_of(smem);
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x >> 6)));
+
+    // the work item: as Kern::run with kFull = false
+    int bidx, h, p;
+    size_t slot0, slot_step;
+    if (a.list_full) {
+        const int it = blockIdx.x / a.H;
+        if (it >= a.seg_count[1]) return;
+        const int2 e = a.list_pre[it];
+        bidx = e.x;
+        p = e.y;
+        h = blockIdx.x % a.H;
+        slot0 = static_cast<size_t>(a.seg_first[bidx]) * a.H + h;
+        slot_step = a.H;
+    } else {
+        const int nseg = a.P - 1;
+        const int bh = blockIdx.x / nseg;
+        p = blockIdx.x % nseg;
+        bidx = bh / a.H;
+        h = bh % a.H;
+        slot0 = bh;
+        slot_step = gridDim.x / nseg;
+    }
+    const int sq = (a.cu && a.seq) ? a.seq[bidx] : bidx;
+    const int64_t seq0 = a.cu ? static_cast<int64_t>(a.cu[sq]) : static_cast<int64_t>(bidx) * a.T;
+    const int64_t Tb = a.cu ? static_cast<int64_t>(a.cu[sq + 1]) - seq0 : a.T;
+    const int64_t t0 = static_cast<int64_t>(p) * a.seg_tokens;
+    if (t0 + a.seg_tokens >= Tb) return;   // no segment follows: nobody needs this one's contribution (uniform exit)
+    const int nsteps = static_cast<int>(a.seg_tokens / S);   // a segment with a successor is whole: a multiple of the chunk
+    const uint32_t rs2 = static_cast<uint32_t>(a.H) * D * 2;   // bytes between consecutive tokens
+    const size_t seg0 = (static_cast<size_t>(seq0 + t0) * a.H + h) * D * 2;
+    const size_t step_bytes = static_cast<size_t>(S) * rs2;
+    const char *pk = uniform_ptr(static_cast<const char *>(a.k) + seg0), *pv = uniform_ptr(static_cast<const char *>(a.v) + seg0),
+               *pg1 = uniform_ptr(static_cast<const char *>(a.g1) + seg0), *pg2 = uniform_ptr(static_cast<const char *>(a.g2) + seg0);
+
+    // ---- loading: wavefront w brings rows 4 w .. 4 w + 3 of every tensor of a step, lane l piece position l % 16 of row l / 16 ----
+    const uint32_t drow = 4 * wave + (lane >> 4), dpos = lane & 15;
+    const uint32_t voff = drow * rs2 + (((((dpos >> 2) ^ (drow & 3u)) << 2) | (dpos & 3u)) << 4);
+    auto issue = [&](uint32_t kg_slot, uint32_t v_slot, int n) {   // step n of the walk = step nsteps - 1 - n of the segment
+        const size_t off = static_cast<size_t>(nsteps - 1 - n) * step_bytes;
+        const uint32_t kgb = sm + F::O_KG + kg_slot * F::KG_BYTES + wave * 1024;
+        load_to_lds16(kgb, voff, pk + off);
+        load_to_lds16(kgb + F::TEN, voff, pg1 + off);
+        load_to_lds16(kgb + 2 * F::TEN, voff, pg2 + off);
+        load_to_lds16(sm + F::O_V + v_slot * F::TEN + wave * 1024, voff, pv + off);
+    };
+
+    // Both jobs of wavefront w concern state st = w / 4 and the 32-tile ct = w % 4: features 32 ct .. of the keys and gates
+    // when preparing, columns 32 ct .. of the values when multiplying.  A transposing read of staged rows hands lane
+    // (ln, g) column 32 ct + ln and, for token block kb, the 8 tokens tau(kb, g, e) = 16 kb + 8 (e / 4) + 4 g + e % 4 --
+    // an MFMA input fragment whose contraction index runs over the tokens in that order.
+    const uint32_t st = wave >> 2, ct = wave & 3, ln = lane & 31, g = lane >> 5, l16 = lane & 15, vr = 4 * g + (l16 >> 2);
+    const uint32_t tr_r = vr * F::ROWB + 64 * (ct ^ (vr & 3u)) + 32 * ((lane >> 4) & 1u) + 8 * (l16 & 3u);   // inside a staged tensor
+    auto rows_frag = [&](uint32_t tensor, int kb) { return A::load_frag_tr(tensor + tr_r + 16 * kb * F::ROWB, 8 * F::ROWB); };
+    // K~ rows: lane (ln, g) writes (preparing) and reads (multiplying) piece g + 2 kb of row st D + 32 tile + ln
+    const uint32_t kt_r = sm + F::O_KT + (st * D + ln) * 64;
+    const uint32_t kt_p[2] = {(g ^ ((ln >> 1) & 3u)) << 4, ((g + 2) ^ ((ln >> 1) & 3u)) << 4};
+
+    // ---- preparing ----
+    // The exponents of a step are suffix sums of its log-gates over the tokens: E[t][f] = sum_{t' > t} g[t'][f], a product
+    // of a constant 0/1 matrix with the gate tile, which the matrix unit evaluates exactly (bf16 gates times 0 or 1, fp32
+    // sums): tri[kb] is row ln of that matrix as the fragment whose contraction index runs over tau(kb, g, .).  The result
+    // tile hands lane (ln, g) feature 32 ct + ln and, in register j, token 8 (j / 4) + 4 g + j % 4 = tau(j / 8, g, j % 8): the
+    // order in which a transposing read delivers the keys, and 8 consecutive positions of a K~ row.
+    A::Frag tri[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+        u32x4 u;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const uint32_t t_lo = 16 * kb + 8 * ((2 * w) >> 2) + 4 * g + ((2 * w) & 3), t_hi = t_lo + 1;
+            u[w] = (t_lo > ln ? 0x3f80u : 0u) | (t_hi > ln ? 0x3f800000u : 0u);   // bf16 1.0 = 0x3f80
+        }
+        tri[kb].v = __builtin_bit_cast(bf16x8, u);
+    }
+    const bool preact = a.gate_inv_tau != 0.f;
+    const float unit = preact ? a.gate_inv_tau : kLog2e;   // gate sums times this = log2 of a decay
+    float carry = 0.f;   // gate sum over all later steps of the segment, feature 32 ct + ln of state st (the same in both lane groups)
+
+    auto prepare = [&](uint32_t kg_slot, uint32_t kt_buf) {
+        const uint32_t kbase = sm + F::O_KG + kg_slot * F::KG_BYTES, gbase = kbase + (1 + st) * F::TEN;
+        A::Frag gf[2], kf[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) gf[kb] = rows_frag(gbase, kb);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) kf[kb] = rows_frag(kbase, kb);
+        f32x16 E;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) E[j] = 0.f;
+        float g_first;   // the gate of token tau(0, g, 0) = 4 g
+        if (!preact) {
+            A::mma(E, tri[0], gf[0]);
+            A::mma(E, tri[1], gf[1]);
+            g_first = __uint_as_float(__builtin_bit_cast(u32x4, gf[0].v)[0] << 16);
+        } else {
+            // pre-activations z -> tau log2 alpha (as Kern::activate); the result is not a bf16 number: it enters the
+            // matrix unit as the sum of two (hi + lo: 16 mantissa bits)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const u32x4 zw = __builtin_bit_cast(u32x4, gf[kb].v);
+                u32x4 hi, lo;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    float x[2] = {__uint_as_float(zw[w] << 16), __uint_as_float(zw[w] & 0xffff0000u)};
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const float y = x[e] * kLog2e;
+                        x[e] = fminf(y, 0.f) - __builtin_amdgcn_logf(1.0f + __builtin_amdgcn_exp2f(-__builtin_fabsf(y)));
+                    }
+                    if (kb == 0 && w == 0) g_first = x[0];
+                    hi[w] = A::pack2(x[0], x[1]);
+                    lo[w] = A::pack2(x[0] - __uint_as_float(hi[w] << 16), x[1] - __uint_as_float(hi[w] & 0xffff0000u));
+                }
+                A::Frag fh, fl;
+                fh.v = __builtin_bit_cast(bf16x8, hi);
+                fl.v = __builtin_bit_cast(bf16x8, lo);
+                A::mma(E, tri[kb], fh);
+                A::mma(E, tri[kb], fl);
+            }
+        }
+        // gate sum of the whole step = E[token 0] + g[token 0]: lane group 0 has it, group 1 fetches it
+        const float tot = __int_as_float(__builtin_amdgcn_ds_bpermute(static_cast<int>(ln << 2), __float_as_int(E[0] + g_first)));
+        const float cu = carry * unit;
+        carry += tot;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            const u32x4 kw = __builtin_bit_cast(u32x4, kf[kb].v);
+            u32x4 out;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const float k0 = __uint_as_float(kw[w] << 16), k1 = __uint_as_float(kw[w] & 0xffff0000u);
+                out[w] = A::pack2(k0 * __builtin_amdgcn_exp2f(fmaf(E[8 * kb + 2 * w], unit, cu)),
+                                  k1 * __builtin_amdgcn_exp2f(fmaf(E[8 * kb + 2 * w + 1], unit, cu)));
+            }
+            lds_st<u32x4>(kt_r + kt_buf * F::KT_BYTES + 32 * ct * 64 + kt_p[kb], out);
+        }
+    };
+
+    // ---- multiplying: U[st][:, 32 ct ..] += K~^T V ----
+    f32x16 acc[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[dt][j] = 0.f;
+    auto multiply = [&](uint32_t v_slot, uint32_t kt_buf) {
+        A::Frag vf[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) vf[kb] = rows_frag(sm + F::O_V + v_slot * F::TEN, kb);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+                A::mma(acc[dt], A::load_frag(kt_r + kt_buf * F::KT_BYTES + 32 * dt * 64 + kt_p[kb]), vf[kb]);
+    };
+
+    // ---- the walk: interval n prepares step n and multiplies step n - 1 ----
+    issue(0, 0, 0);
+    if (nsteps > 1) issue(1, 1, 1);
+    uint32_t kg_n = 0, v_n = 0;          // slots of step n
+    uint32_t kg_i = 2, v_i = 2;          // slots of step n + LEAD
+    for (int n = 0; n <= nsteps; ++n) {
+        // step n has landed (the loads of step n + 1 may still be in flight); K~ of step n - 1 is complete; the slots
+        // and the K~ buffer that this interval overwrites have been read by everyone
+        if (n + 1 < nsteps) wait_loads_and_barrier<4>();
+        else wait_loads_and_barrier<0>();
+        if (n + F::LEAD < nsteps) issue(kg_i, v_i, n + F::LEAD);
+        if (n < nsteps) prepare(kg_n, static_cast<uint32_t>(n) & 1u);
+        if (n >= 1) multiply(v_n == 0 ? F::V_SLOTS - 1 : v_n - 1, static_cast<uint32_t>(n - 1) & 1u);
+        kg_n = kg_n + 1 == F::KG_SLOTS ? 0 : kg_n + 1;
+        v_n = v_n + 1 == F::V_SLOTS ? 0 : v_n + 1;
+        kg_i = kg_i + 1 == F::KG_SLOTS ? 0 : kg_i + 1;
+        v_i = v_i + 1 == F::V_SLOTS ? 0 : v_i + 1;
+    }
+
+    // ---- contribution of segment p -> state slot p + 1; its log2 decay -> decay slot p ----
+    {
+        float *dst = a.ws_state + ((slot0 + (p + 1) * slot_step) * 2 + st) * D * D + (4 * g) * D + 32 * ct + ln;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int j = 0; j < 16; ++j) dst[(32 * dt + 8 * (j >> 2) + (j & 3)) * D] = acc[dt][j];
+        if (g == 0) a.ws_decay[(slot0 + p * slot_step) * 2 * D + st * D + 32 * ct + ln] = carry * unit;
+    }
+}
+
 // Work lists for packed sequences (one workgroup): sequence b has ceil(T_b / seg_tokens) segments;
 // seg_first = exclusive prefix sum of that over the sequences, list_full = every (sequence, segment),
 // list_pre = those with a successor.  Thread t takes a contiguous run of sequences.
@@ -1397,7 +1648,12 @@ hipError_t launch_x(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
         }
         if (grid_pre > 0) {
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_STATE, stream);
-            hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, false, kExt, kBeta>), dim3(grid_pre), dim3(4 * D), 0, stream, a);
+            // the pre-pass of its own design where it is built; its per-lane offsets inside a step are 32-bit
+            constexpr bool kFast = D == SegFast::D && std::is_same<TIO, bf16_t>::value && std::is_same<TG, bf16_t>::value && !kExt && !kBeta;
+            if (kFast && static_cast<int64_t>(d.H) * D * 2 * SegFast::S < (int64_t{1} << 31))
+                hipLaunchKernelGGL(segment_state_fast_kernel, dim3(grid_pre), dim3(SegFast::NT), 0, stream, a);
+            else
+                hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, false, kExt, kBeta>), dim3(grid_pre), dim3(4 * D), 0, stream, a);
             err = hipGetLastError();
         }
         if (err != hipSuccess) return err;

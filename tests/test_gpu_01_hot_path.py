@@ -78,6 +78,18 @@ def test_prefill_bf16_shapes(d, chunk, segments, T, gd):
                      qk_scale=d ** -0.5)
 
 
+@pytest.mark.parametrize("chunk,segments,T,tau,gate_mean", [(32, 8, 256, 16.0, 2.0), (32, 3, 200, 16.0, 2.0),
+                                                            (64, 2, 1000, 16.0, 2.0), (64, 5, 1601, 16.0, 2.0),
+                                                            (64, 2, 900, 1.0, -2.0), (128, 3, 2500, 4.0, 0.0)])
+def test_prefill_segment_states_walked_backwards(chunk, segments, T, tau, gate_mean):
+    """bf16 io and gates at d = 128: the state contribution of every segment but the last comes from the kernel that
+    walks the segment backwards with suffix sums of the log-gates as exponents.  Segments of 1, 3, 16, 5 and 14 steps of
+    32 tokens, a ragged last segment, carried-in states; weak gates and gates so strong (68 per 32 tokens) that the
+    factors of the early tokens of a segment underflow to zero, as their true weights do."""
+    run_prefill_case(2, T, 3, 128, "bf16", "bf16", chunk=chunk, segments=segments, gamma=0.55, tau=tau, seed=27, init=True,
+                     gate_mean=gate_mean, qk_scale=128 ** -0.5)
+
+
 @pytest.mark.parametrize("io,d,segments,T", [("bf16", 128, 2, 700), ("bf16", 128, 0, 4096), ("f32", 64, 3, 450)])
 def test_prefill_chunk128(io, d, segments, T):
     run_prefill_case(1, T, 2, d, io, "f32" if io == "f32" else "bf16", chunk=128, segments=segments, gamma=0.45, seed=23,
