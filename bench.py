@@ -6,7 +6,9 @@
 Prints ONE JSON line.  Headline (`value`): prefill throughput in tokens/s of one
 Llama-2-7B-shaped DSLA layer (B=1, H=32, d_k=d_v=128, bf16 I/O, fp32 states, chunk 64)
 at T=16384; a step is one dsla_prefill over the whole sequence from zero states (the state
-initialisation is part of the call: desc.zero_init) with the inputs already resident in HBM.  The same line carries the batched-decode measurement
+initialisation is part of the call: desc.zero_init) with the inputs already resident in HBM; the steps rotate
+over three input sets (2.4 GB), so that no step finds parts of its inputs in the 256 MB last-level cache only because
+the step before it read the same tensors.  The same line carries the batched-decode measurement
 (B=64, 256 single-token steps rotating over 8 independent state sets so that the
 256 MB last-level cache cannot hold the states), the roofline objects of the dominant
 kernels (durations from HIP events recorded by the library around each kernel launch,
@@ -53,6 +55,10 @@ def main():
     ap.add_argument("--segments", type=int, default=0)
     ap.add_argument("--chunk", type=int, default=64)
     ap.add_argument("--decode-steps", type=int, default=1024)
+    ap.add_argument("--input-sets", type=int, default=3,
+                    help="prefill input sets the steps rotate over, so that no step finds its inputs in the 256 MB "
+                         "last-level cache because the step before it read the same tensors (1: one set, as a loop "
+                         "over one layer's tensors would)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--settle-seconds", type=float, default=SETTLE_SECONDS,
@@ -90,25 +96,29 @@ def main():
     xg = {n: torch.from_numpy(a).to(dev).to(torch.bfloat16).contiguous() for n, a in x.items()}
     desc = dsla.make_desc(B, H, D, D, io_dtype=DSLA_BF16, gate_dtype=DSLA_BF16, gamma=0.5, scale=1.0,
                           chunk=args.chunk, segments=args.segments, zero_init=True)
+    # further input sets: the same sequences shifted cyclically along the token axis (same statistics, other memory)
+    sets = [xg] + [{n: t.roll(shifts=1 + 4099 * s, dims=1).contiguous() for n, t in xg.items()}
+                   for s in range(1, max(1, args.input_sets))]
     S1 = torch.empty(B, H, D, D, device=dev, dtype=torch.float32)
     S2 = torch.empty_like(S1)
     o = torch.empty_like(xg["v"])
     nws = dsla.dsla_prefill_workspace_bytes(desc, T)
     ws = torch.empty(max(nws, 256), dtype=torch.uint8, device=dev)
 
-    def prefill_step():
-        dsla.dsla_prefill(desc, T, xg["q"], xg["k"], xg["v"], xg["g1"], xg["g2"], S1, S2, o, ws if nws else None)
+    def prefill_step(i):
+        xs = sets[i % len(sets)]
+        dsla.dsla_prefill(desc, T, xs["q"], xs["k"], xs["v"], xs["g1"], xs["g2"], S1, S2, o, ws if nws else None)
 
     # Settle phase, fixed and untimed, before the caller's warm-up: the first launches after start-up run slower
     # (clocks ramp up, code objects and page tables are touched for the first time), so a short --warmup alone
     # would time that transient instead of the steady state.
     t_settle = time.perf_counter()
     while time.perf_counter() - t_settle < args.settle_seconds:
-        for _ in range(20):
-            prefill_step()
+        for i in range(20):
+            prefill_step(i)
         torch.cuda.synchronize()
-    for _ in range(args.warmup):
-        prefill_step()
+    for i in range(args.warmup):
+        prefill_step(i)
     torch.cuda.synchronize()
     # Kernel durations come from HIP events the library records around its launches, on the launch stream, inside
     # the timed region.  An event record between two dependent kernels costs a few microseconds of stream time
@@ -118,8 +128,8 @@ def main():
     dsla.profile_enable(True, 4 * ev_steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        prefill_step()
+    for i in range(args.steps):
+        prefill_step(args.steps - 1 - i)   # the last step runs on set 0, whose results the oracle checks below
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     prof = dsla.profile_collect()
@@ -152,7 +162,7 @@ def main():
         "config": {"workload": "value = prefill tokens/s of cfg3: B=1 H=32 d_k=d_v=128 T=%d chunk=%d bf16 io, bf16 "
                                "log-gates, fp32 states; step = one prefill call from zero states; the decode part of the "
                                "metric (cfg4, B=64) is under \"decode\"" % (T, C),
-                   "segments": args.segments, "kernel_events": "all launches of the first 1/%d of each timed region" % EVENT_SHARE, "workspace_bytes": nws},
+                   "segments": args.segments, "input_sets": len(sets), "kernel_events": "all launches of the first 1/%d of each timed region" % EVENT_SHARE, "workspace_bytes": nws},
         "roofline": roofline,
         "kernel_ms": {k: v for k, v in kern_ms.items() if v is not None},
         "end_to_end_hbm_frac": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -170,7 +180,7 @@ def main():
         got = (o.float().cpu().numpy(), S1.cpu().numpy(), S2.cpu().numpy())
 
     # ------------------------------------------------------------------ batched decode
-    del xg, o, ws
+    del xg, sets, o, ws
     if not args.no_decode:
         c4 = wl.CONFIGS["cfg4"]
         Bd, Hd, Dd, Tp = c4["B"], c4["H"], c4["dk"], c4["T"]
