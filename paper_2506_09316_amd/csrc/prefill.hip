@@ -1259,7 +1259,7 @@ __global__ __launch_bounds__(4 * D, (D == 64 && sizeof(TIO) == 4 && kFull) ? 1 :
 }
 
 // ---------------------------------------------------------------------------------------------
-// Segment pre-pass of its own design for the common case: 16-bit io and gates, d = 128, ordinary launch.
+// Segment pre-pass of its own design for the common case: 16-bit io and gates, d = 128, two states.
 //
 // The state contribution of a segment of N tokens is U^i = sum_t diag(prod_{s > t} alpha^i_s) k_t^T v_t (Section 4.1,
 // the state update unrolled to the end of the segment).  Walking the segment BACKWARDS, 32 tokens at a time, the
@@ -1356,19 +1356,24 @@ __global__ __launch_bounds__(SegFast::NT, 2) void segment_state_fast_kernel(Pref
     const uint32_t rs2 = static_cast<uint32_t>(a.H) * D * 2;   // bytes between consecutive tokens
     const size_t seg0 = (static_cast<size_t>(seq0 + t0) * a.H + h) * D * 2;
     const size_t step_bytes = static_cast<size_t>(S) * rs2;
-    const char *pk = uniform_ptr(static_cast<const char *>(a.k) + seg0), *pv = uniform_ptr(static_cast<const char *>(a.v) + seg0),
+    // k and v may have fewer heads (extended launches): head h reads key/value head h / (H / Hkv)
+    const uint32_t rs2kv = static_cast<uint32_t>(a.Hkv) * D * 2;
+    const size_t seg0kv = (static_cast<size_t>(seq0 + t0) * a.Hkv + h / (a.H / a.Hkv)) * D * 2;
+    const size_t step_bytes_kv = static_cast<size_t>(S) * rs2kv;
+    const char *pk = uniform_ptr(static_cast<const char *>(a.k) + seg0kv), *pv = uniform_ptr(static_cast<const char *>(a.v) + seg0kv),
                *pg1 = uniform_ptr(static_cast<const char *>(a.g1) + seg0), *pg2 = uniform_ptr(static_cast<const char *>(a.g2) + seg0);
 
     // ---- loading: wavefront w brings rows 4 w .. 4 w + 3 of every tensor of a step, lane l piece position l % 16 of row l / 16 ----
     const uint32_t drow = 4 * wave + (lane >> 4), dpos = lane & 15;
-    const uint32_t voff = drow * rs2 + (((((dpos >> 2) ^ (drow & 3u)) << 2) | (dpos & 3u)) << 4);
+    const uint32_t dpiece = ((((dpos >> 2) ^ (drow & 3u)) << 2) | (dpos & 3u)) << 4;
+    const uint32_t voff = drow * rs2 + dpiece, voff_kv = drow * rs2kv + dpiece;
     auto issue = [&](uint32_t kg_slot, uint32_t v_slot, int n) {   // step n of the walk = step nsteps - 1 - n of the segment
-        const size_t off = static_cast<size_t>(nsteps - 1 - n) * step_bytes;
+        const size_t off = static_cast<size_t>(nsteps - 1 - n) * step_bytes, off_kv = static_cast<size_t>(nsteps - 1 - n) * step_bytes_kv;
         const uint32_t kgb = sm + F::O_KG + kg_slot * F::KG_BYTES + wave * 1024;
-        load_to_lds16(kgb, voff, pk + off);
+        load_to_lds16(kgb, voff_kv, pk + off_kv);
         load_to_lds16(kgb + F::TEN, voff, pg1 + off);
         load_to_lds16(kgb + 2 * F::TEN, voff, pg2 + off);
-        load_to_lds16(sm + F::O_V + v_slot * F::TEN + wave * 1024, voff, pv + off);
+        load_to_lds16(sm + F::O_V + v_slot * F::TEN + wave * 1024, voff_kv, pv + off_kv);
     };
 
     // Both jobs of wavefront w concern state st = w / 4 and the 32-tile ct = w % 4: features 32 ct .. of the keys and gates
@@ -1649,7 +1654,7 @@ hipError_t launch_x(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
         if (grid_pre > 0) {
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_STATE, stream);
             // the pre-pass of its own design where it is built; its per-lane offsets inside a step are 32-bit
-            constexpr bool kFast = D == SegFast::D && std::is_same<TIO, bf16_t>::value && std::is_same<TG, bf16_t>::value && !kExt && !kBeta;
+            constexpr bool kFast = D == SegFast::D && std::is_same<TIO, bf16_t>::value && std::is_same<TG, bf16_t>::value && !kBeta;
             if (kFast && static_cast<int64_t>(d.H) * D * 2 * SegFast::S < (int64_t{1} << 31))
                 hipLaunchKernelGGL(segment_state_fast_kernel, dim3(grid_pre), dim3(SegFast::NT), 0, stream, a);
             else
