@@ -1296,10 +1296,14 @@ struct SegFast {
 
 // 16 bytes per lane from `base` (wavefront-uniform) + `voff` (per lane) into LDS at `lds` (uniform) + 16 * lane.
 // The compiler does not know these loads: whoever reads the bytes waits with wait_loads<>() first.
+// (M0 holds the LDS address; the compiler reserves that register for instructions of this kind and is told that it changes.)
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void load_to_lds16(uint32_t lds, uint32_t voff, const char *base)
 {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(base) : "memory");
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(base) : "m0", "memory");
 }
+#pragma clang diagnostic pop
 template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier()   // at most N of this wavefront's loads still in flight; then the workgroup meets
 {
