@@ -876,7 +876,9 @@ struct Kern {
                         x[w] = ArithBf16::pack2(__uint_as_float(x[w] << 16) + __uint_as_float(old[w] << 16),
                                                 __uint_as_float(x[w] & 0xffff0000u) + __uint_as_float(old[w] & 0xffff0000u));
                 }
-                *dst = x;
+                // streaming store: the output is not read again by this call, and kept out of the caches it does not
+                // delay the kernel that follows (measured: the next call's segment pre-pass 107 -> 95 us)
+                __builtin_nontemporal_store(x, dst);
             }
         }
     }
