@@ -245,7 +245,8 @@ __global__ __launch_bounds__(256) void project_kernel_256(const bf16_t *__restri
             const int row = 4 * it + rsub;
             const long long m = m0 + 128 * wm + row;
             const u32x4 vrow = *reinterpret_cast<const u32x4 *>(epi + row * 256 + ((piece ^ (row & 15)) << 4));
-            if (m < M) *reinterpret_cast<u32x4 *>(out + static_cast<size_t>(m) * width + piece * 8) = vrow;
+            if (m < M)   // streaming store: a tile of results is not read again by this kernel
+                __builtin_nontemporal_store(vrow, reinterpret_cast<u32x4 *>(out + static_cast<size_t>(m) * width + piece * 8));
         }
     }
 }
