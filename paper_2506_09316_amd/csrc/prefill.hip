@@ -852,6 +852,187 @@ struct Kern {
     }
 
     // ------------------------------------------------------------------------------------------------------
+    // Producers that load whole 128-byte lines (kLineProd: 16-bit io, ordinary step loop).  The loads and stores of the
+    // step loop alone, with no arithmetic, take as long as the whole kernel, and they take 5-7 % less when a load
+    // instruction fetches pieces of 128 bytes instead of 64.  So here a producer wavefront prepares ONE state, 64 features
+    // of it (one line of a row), all 32 tokens: a thread has 4 tokens x 8 features.  q and k are loaded by the wavefront
+    // of either state (the second request hits in L2); v is split by tokens between them.  The gate scan stays inside
+    // the wavefront: sums over the thread's 4 tokens, 8 totals per feature through wavefront-private LDS, one lane per
+    // feature.  The operand sets, and with them the consumers, are the ones of the row producers above.
+    // ------------------------------------------------------------------------------------------------------
+    static constexpr bool kLineProd = ESZ == 2 && kFull && !kExt && !kBeta && SETS == 2;
+    static constexpr int FHN = D / 64;   // lines per row = producer wavefronts per state
+    static constexpr int TPT = 4;        // tokens per thread
+    struct LineIO {
+        Raw8<TIO> q[TPT], k[TPT], v[2];
+    };
+    struct LineGates {
+        Raw8<TG> g[TPT];
+    };
+    struct LineSrc {
+        const TIO *q, *k, *v;   // uniform: first token of the step, this (batch, head)
+        const TG *g;            // the gates of this wavefront's state
+        uint32_t off[TPT];      // per lane: element offset of token 4 sq + j, features 64 fh + 8 dg ..
+        uint32_t offv[2];       // the same for this wavefront's share of v: token 16 st + 2 sq + j
+    };
+    struct LineNext {
+        LineIO &r;
+        const LineSrc &rs;
+        LineGates &g;
+        const LineSrc &gs;
+        __device__ __forceinline__ void at(int slot) const
+        {
+            if (slot >= 0 && slot < 4) g.g[slot].load(gs.g, gs.off[slot]);
+            if (slot >= 4 && slot < 8) r.k[slot - 4].load(rs.k, rs.off[slot - 4]);
+            if (slot >= 8 && slot < 12) r.q[slot - 8].load(rs.q, rs.off[slot - 8]);
+            if (slot == 12) r.v[0].load(rs.v, rs.offv[0]);
+            if (slot == 13) r.v[1].load(rs.v, rs.offv[1]);
+        }
+    };
+    struct LineAddr {
+        uint32_t tot;         // scan scratch [8 quads][64 features] floats: this lane's 8 features of quad sq
+        uint32_t col;         // scan scratch: this lane's column (feature lane of the 64), quad 0
+        uint32_t dec;         // decay factor of this lane's column
+        uint32_t qrow[TPT];   // Q~ row of token 4 sq + j, element st D + 64 fh + 8 dg
+        uint32_t krow[TPT];   // K~: its row slot
+        uint32_t vrow[2];     // V rows of token 16 st + 2 sq + j, columns 64 fh + 8 dg ..
+        uint32_t sq, st, fh;
+        bool preact;
+        float unit;
+        __device__ __forceinline__ LineAddr(uint32_t sm, int pw, uint32_t lane)
+        {
+            st = static_cast<uint32_t>(pw) / FHN;
+            fh = static_cast<uint32_t>(pw) % FHN;
+            sq = lane >> 3;
+            const uint32_t dg = lane & 7, f0 = 64 * fh + 8 * dg;
+            const uint32_t csw = sm + O_CS + pw * 4096;
+            tot = csw + (sq * 64 + 8 * dg) * 4;
+            col = csw + lane * 4;
+            dec = sm + O_DEC + (st * D + 64 * fh + lane) * 4;
+#pragma unroll
+            for (uint32_t j = 0; j < TPT; ++j) {
+                const uint32_t t = 4 * sq + j;
+                qrow[j] = sm + O_QS + (t * QP + st * D + f0) * ESZ;
+                krow[j] = sm + O_KS + (kslot(t) * QP + st * D + f0) * ESZ;
+            }
+#pragma unroll
+            for (uint32_t j = 0; j < 2; ++j) {
+                const uint32_t t = 16 * st + 2 * sq + j;
+                vrow[j] = sm + O_VT + t * (D * ESZ) + 64 * ((f0 >> 5) ^ vswz(t)) + (f0 & 31u) * ESZ;
+            }
+        }
+    };
+    struct LineScan {
+        float c[TPT][8];   // gate sums over this thread's tokens: c[j] = g[0] + .. + g[j]
+        float pre[8];      // centred gate sum from the first token of the step to before this thread's tokens
+    };
+    static __device__ __forceinline__ void line_scan_a(const LineAddr &pa, LineGates &r, int valid, LineScan &o)
+    {
+        if (valid < S) {   // a token past the end: log-gate 0, or a pre-activation whose log-gate is exactly 0
+#pragma unroll
+            for (int j = 0; j < TPT; ++j)
+                if (static_cast<int>(pa.sq) * TPT + j >= valid) {
+                    if (pa.preact) r.g[j].fill_huge();
+                    else r.g[j].zero();
+                }
+        }
+        float g[8];
+#pragma unroll
+        for (int j = 0; j < TPT; ++j) {
+            r.g[j].unpack(g);
+            if (pa.preact) activate(g);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o.c[j][e] = j ? o.c[j - 1][e] + g[e] : g[e];
+        }
+        lds_st<f32x4>(pa.tot, f32x4{o.c[TPT - 1][0], o.c[TPT - 1][1], o.c[TPT - 1][2], o.c[TPT - 1][3]});
+        lds_st<f32x4>(pa.tot + 16, f32x4{o.c[TPT - 1][4], o.c[TPT - 1][5], o.c[TPT - 1][6], o.c[TPT - 1][7]});
+    }
+    static __device__ __forceinline__ void line_scan_b_read(const LineAddr &pa, float (&t)[8])
+    {
+        wave_sync();
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2) t[s2] = lds_ld<float>(pa.col + s2 * 64 * 4);
+    }
+    static __device__ __forceinline__ void line_scan_b(const LineAddr &pa, const float (&t)[8], float &total)
+    {
+        const float tot = ((t[0] + t[1]) + (t[2] + t[3])) + ((t[4] + t[5]) + (t[6] + t[7]));
+        float run = -0.5f * tot;   // centred on the step, as scan_b
+#pragma unroll
+        for (int s2 = 0; s2 < 8; ++s2) {
+            lds_st<float>(pa.col + s2 * 64 * 4, run);
+            run += t[s2];
+        }
+        total = tot;
+    }
+    static __device__ __forceinline__ void line_scan_c(const LineAddr &pa, LineScan &o)
+    {
+        wave_sync();
+        const f32x4 p0 = lds_ld<f32x4>(pa.tot), p1 = lds_ld<f32x4>(pa.tot + 16);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            o.pre[e] = p0[e];
+            o.pre[4 + e] = p1[e];
+        }
+    }
+    static __device__ __forceinline__ void line_note_step(const LineAddr &pa, float total, int32_t *status)
+    {
+        if (status && !(total * pa.unit >= -kMaxStepLog2Decay)) *status = DSLA_STATUS_GATE_DOMAIN;
+    }
+    // One call: operands of step m (state pa.st, 64 features) into operand set `set`, and, interleaved, the gate scan of
+    // step m + 1 and the loads of later steps; as produce().  lg, sgn: of this wavefront's state.
+    static __device__ __forceinline__ void line_produce(const LineAddr &pa, uint32_t set, LineIO &r, const LineScan &sc, int valid,
+                                                        LineGates &gn, LineScan &sn, int valid_n, float lg, uint32_t sgn,
+                                                        float &tot, int32_t *status, const LineNext &next)
+    {
+        const uint32_t so = set * SET_BYTES;
+        if (valid < S) {   // ragged tail: tokens past the end act as "no key, no value"
+#pragma unroll
+            for (int j = 0; j < TPT; ++j)
+                if (static_cast<int>(pa.sq) * TPT + j >= valid) r.k[j].zero();
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                if (static_cast<int>(16 * pa.st + 2 * pa.sq) + j >= valid) r.v[j].zero();
+        }
+        line_scan_a(pa, gn, valid_n, sn);
+        next.at(0);
+        next.at(1);
+        next.at(2);
+        next.at(3);
+        auto block = [&](int j) {
+            next.at(4 + j);
+            float kf[8], kh[8];
+            r.k[j].unpack(kf);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) kh[e] = kf[e] * __builtin_amdgcn_exp2f(-pa.unit * (sc.pre[e] + sc.c[j][e]));
+            A::store_row(pa.krow[j] + so, A::pack_row(kh));
+            next.at(8 + j);
+            float qf[8], qt[8];
+            r.q[j].unpack(qf);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qt[e] = qf[e] * __builtin_amdgcn_exp2f(fmaf(sc.pre[e] + sc.c[j][e], pa.unit, lg));
+            A::store_row(pa.qrow[j] + so, A::flip_sign(A::pack_row(qt), sgn));
+        };
+        float t[8];
+        line_scan_b_read(pa, t);   // the answers arrive while the first block is computed
+        block(0);
+        {
+            float tot_n;
+            line_scan_b(pa, t, tot_n);
+            lds_st<float>(pa.dec + so, __builtin_amdgcn_exp2f(0.5f * pa.unit * (tot + tot_n)));
+            line_note_step(pa, tot_n, status);
+            tot = tot_n;
+        }
+        block(1);
+        line_scan_c(pa, sn);
+        block(2);
+        next.at(12);
+        block(3);
+        next.at(13);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) store_v_row(pa.vrow[j] + so, r.v[j]);   // V as loaded
+    }
+
+    // ------------------------------------------------------------------------------------------------------
     // Consumer: all contractions of one step from operand set `set`.  acc[i][dt]: rows 32 dt .. of state i (Kt row
     // order), columns 32 ct ...  Register j of lane (ln, g) holds feature 32 dt + 16 (j / 8) + 8 g + j % 8.
     // Inside a chunk acc holds the state in the frame of the chunk start (see the step algebra above).
@@ -1168,6 +1349,88 @@ struct Kern {
             }
             const float lg[2] = {__builtin_amdgcn_logf(fabsf(gsv[0])), __builtin_amdgcn_logf(fabsf(gsv[1]))};
             const uint32_t sgn[2] = {gsv[0] < 0.f ? A::kSignBits : 0u, gsv[1] < 0.f ? A::kSignBits : 0u};
+            if constexpr (kLineProd) {
+                LineAddr pa(sm, pw, static_cast<uint32_t>(lane));
+                pa.preact = a.gate_inv_tau != 0.f;
+                pa.unit = pa.preact ? a.gate_inv_tau : kLog2e;
+                const float lgs = pa.st ? lg[1] : lg[0];
+                const uint32_t sgns = pa.st ? sgn[1] : sgn[0];
+                float tot = 0.f;   // lane l: gate sum of column (state st, feature 64 fh + l) over the step whose operands come next
+                const TIO *q0 = static_cast<const TIO *>(a.q) + seg0, *k0 = static_cast<const TIO *>(a.k) + seg0,
+                          *v0 = static_cast<const TIO *>(a.v) + seg0;
+                const TG *g0p = static_cast<const TG *>(pa.st ? a.g2 : a.g1) + seg0;
+                const uint32_t lane_col = 64 * pa.fh + 8 * (lane & 7);
+                auto src_of = [&](int n) -> LineSrc {   // step n, or the last step when n is past the end
+                    const int m = n < nsteps ? n : nsteps - 1;
+                    const size_t so = static_cast<size_t>(m) * sstep;
+                    const uint32_t vm = static_cast<uint32_t>(valid_of(m));   // >= 1
+                    LineSrc s;
+                    s.q = q0 + so; s.k = k0 + so; s.v = v0 + so; s.g = g0p + so;
+#pragma unroll
+                    for (int j = 0; j < TPT; ++j) {
+                        uint32_t row = pa.sq * TPT + j;
+                        row = row < vm ? row : vm - 1;
+                        s.off[j] = row * rs + lane_col;
+                    }
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        uint32_t row = 16 * pa.st + 2 * pa.sq + j;
+                        row = row < vm ? row : vm - 1;
+                        s.offv[j] = row * rs + lane_col;
+                    }
+                    return s;
+                };
+                auto load_gates_l = [&](LineGates &g, const LineSrc &s) {
+#pragma unroll
+                    for (int j = 0; j < TPT; ++j) g.g[j].load(s.g, s.off[j]);
+                };
+                LineIO r0, r1;
+                LineGates g0, g1;
+                LineScan s0, s1;
+                load_gates_l(g0, src_of(0));
+                load_gates_l(g1, src_of(1));
+                {
+                    const LineSrc s = src_of(0);
+#pragma unroll
+                    for (int j = 0; j < TPT; ++j) {
+                        r0.k[j].load(s.k, s.off[j]);
+                        r0.q[j].load(s.q, s.off[j]);
+                    }
+                    r0.v[0].load(s.v, s.offv[0]);
+                    r0.v[1].load(s.v, s.offv[1]);
+                }
+                line_scan_a(pa, g0, valid_of(0), s0);
+                {
+                    float t[8];
+                    line_scan_b_read(pa, t);
+                    line_scan_b(pa, t, tot);
+                    line_note_step(pa, tot, a.status);
+                    // the caller's states enter the middle frame of step 0
+                    lds_st<float>(sm + O_ENT + (pa.dec - (sm + O_DEC)), __builtin_amdgcn_exp2f(0.5f * pa.unit * tot));
+                }
+                line_scan_c(pa, s0);
+                load_gates_l(g0, src_of(2));
+                {
+                    const LineSrc io = src_of(1), gs = src_of(3);
+                    line_produce(pa, 0, r0, s0, valid_of(0), g1, s1, valid_of(1), lgs, sgns, tot, a.status, LineNext{r1, io, g1, gs});
+                }
+                lds_barrier();   // operands of step 0 are ready
+                for (int n = 0; n < nsteps; n += 2) {
+                    {
+                        const LineSrc io = src_of(n + 2), gs = src_of(n + 4);
+                        line_produce(pa, 1, r1, s1, valid_of(n + 1), g0, s0, valid_of(n + 2), lgs, sgns, tot, a.status,
+                                     LineNext{r0, io, g0, gs});
+                    }
+                    lds_barrier();
+                    {
+                        const LineSrc io = src_of(n + 3), gs = src_of(n + 5);
+                        line_produce(pa, 0, r0, s0, valid_of(n + 2), g1, s1, valid_of(n + 3), lgs, sgns, tot, a.status,
+                                     LineNext{r1, io, g1, gs});
+                    }
+                    lds_barrier();
+                }
+                return;
+            }
             float seg_decay = 0.f;   // lane l: log2 of the segment decay of (state l / 32, feature 32 pw + l % 32)
             float tot = 0.f;         // lane l: gate sum of that column over the step whose operands come next
             ProdAddr pa(sm, pw, static_cast<uint32_t>(lane));
