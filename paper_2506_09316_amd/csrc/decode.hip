@@ -15,6 +15,16 @@ namespace {
 
 constexpr int kDecodeThreads = 256;
 
+// A state row piece as a streaming (non-temporal) load: a state is read once per step and written back, and the
+// next read of it is a whole batch later; kept out of the caches' allocation the reads run 2 % faster
+// (106.6 -> 104.3 us per step at B = 64).  The stores stay ordinary: streaming stores measured slower.
+__device__ __forceinline__ float4 load_streaming(const float4 *p)
+{
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const f4 x = __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p));
+    return make_float4(x[0], x[1], x[2], x[3]);
+}
+
 template <int DK, int DV, int SPLIT, class TIO, class TG>
 __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
     const TIO *__restrict__ q, const TIO *__restrict__ k, const TIO *__restrict__ v, const TG *__restrict__ g1,
@@ -46,8 +56,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_kernel(
 #pragma unroll
     for (int j = 0; j < ROWS; ++j) {
         const int row = rg + j * ROWG;
-        a[j] = p1[static_cast<size_t>(row) * ROWF4];
-        b[j] = p2[static_cast<size_t>(row) * ROWF4];
+        a[j] = load_streaming(&p1[static_cast<size_t>(row) * ROWF4]);
+        b[j] = load_streaming(&p2[static_cast<size_t>(row) * ROWF4]);
     }
 
     // 2. per-token vectors -> LDS (gates exponentiated once per row)
@@ -148,7 +158,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_multi_kernel(
     auto load_state = [&](int n, float4 (&x)[ROWS]) {
         const float4 *p = reinterpret_cast<const float4 *>(mp.S[n] + sbase) + c4;
 #pragma unroll
-        for (int j = 0; j < ROWS; ++j) x[j] = p[static_cast<size_t>(rg + j * ROWG) * ROWF4];
+        for (int j = 0; j < ROWS; ++j) x[j] = load_streaming(&p[static_cast<size_t>(rg + j * ROWG) * ROWF4]);
     };
     float4 cur[ROWS], nxt[ROWS];
     load_state(0, cur);
