@@ -11,7 +11,7 @@ over three input sets (2.4 GB), so that no step finds parts of its inputs in the
 the step before it read the same tensors.  The same line carries the batched-decode measurement
 (B=64, 256 single-token steps rotating over 8 independent state sets so that the
 256 MB last-level cache cannot hold the states), the roofline objects of the dominant
-kernels (durations from HIP events recorded by the library around each kernel launch,
+kernels (durations from HIP events that the library attaches to each kernel launch,
 inside the timed region) and the CPU oracle timed on the host cores as a baseline.
 """
 import argparse
@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
-EVENT_SHARE = 8                 # kernel events bracket every launch of the first 1/EVENT_SHARE of a timed region
+EVENT_SHARE = 8                 # kernel events time every launch of the first 1/EVENT_SHARE of a timed region
 EVENT_MIN_STEPS = 8             # ... and of at least this many steps
 SETTLE_SECONDS = 0.5            # untimed steps before --warmup
 
@@ -59,6 +59,9 @@ def main():
                     help="prefill input sets the steps rotate over, so that no step finds its inputs in the 256 MB "
                          "last-level cache because the step before it read the same tensors (1: one set, as a loop "
                          "over one layer's tensors would)")
+    ap.add_argument("--event-steps", type=int, default=0,
+                    help="kernel events time the launches of this many steps at the start of each timed region "
+                         "(0: an eighth of the region, at least 8 steps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--settle-seconds", type=float, default=SETTLE_SECONDS,
@@ -120,11 +123,13 @@ def main():
     for i in range(args.warmup):
         prefill_step(i)
     torch.cuda.synchronize()
-    # Kernel durations come from HIP events the library records around its launches, on the launch stream, inside
-    # the timed region.  An event record between two dependent kernels costs a few microseconds of stream time
-    # (21 us per step when every launch is bracketed), so only the launches of the first eighth of the region are
-    # bracketed, all of them: a kernel whose predecessor is not bracketed as well reads 10 us too long.
-    ev_steps = min(args.steps, max(EVENT_MIN_STEPS, args.steps // EVENT_SHARE))
+    # Kernel durations come from HIP events inside the timed region, on the launch stream: the library attaches a
+    # pair of events to each of its launches (hipExtLaunchKernelGGL: the dispatch itself stamps the start and the
+    # end of the kernel, no event packets of their own enter the stream).  A timed step still costs about 8 us
+    # (measured: 500 timed steps of 500 against 62: 0.3065 against 0.2993 ms per step), so the launches of the first
+    # eighth of the region are timed, all of them.
+    ev_steps = args.event_steps if args.event_steps > 0 else max(EVENT_MIN_STEPS, args.steps // EVENT_SHARE)
+    ev_steps = max(1, min(args.steps, ev_steps))
     dsla.profile_enable(True, 4 * ev_steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -162,7 +167,7 @@ def main():
         "config": {"workload": "value = prefill tokens/s of cfg3: B=1 H=32 d_k=d_v=128 T=%d chunk=%d bf16 io, bf16 "
                                "log-gates, fp32 states; step = one prefill call from zero states; the decode part of the "
                                "metric (cfg4, B=64) is under \"decode\"" % (T, C),
-                   "segments": args.segments, "input_sets": len(sets), "kernel_events": "all launches of the first 1/%d of each timed region" % EVENT_SHARE, "workspace_bytes": nws},
+                   "segments": args.segments, "input_sets": len(sets), "kernel_events": "all launches of the first %d steps of the timed region, events attached to the dispatches" % ev_steps, "workspace_bytes": nws},
         "roofline": roofline,
         "kernel_ms": {k: v for k, v in kern_ms.items() if v is not None},
         "end_to_end_hbm_frac": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -233,7 +238,7 @@ def main():
         decode_steps(64)
         torch.cuda.synchronize()
         nd = args.decode_steps
-        dsla.profile_enable(True, max(1, nd // EVENT_SHARE))
+        dsla.profile_enable(True, max(1, min(nd, args.event_steps if args.event_steps > 0 else nd // EVENT_SHARE)))
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         decode_steps(nd)

@@ -396,9 +396,11 @@ DSLA_API const char *dsla_status_string(dsla_status s);
 DSLA_API const char *dsla_last_hip_error(void);
 
 /*
- * Kernel timing for benchmarks.  While enabled, every kernel the library launches is
- * bracketed by two HIP events recorded on the launch stream (events come from a pool
- * created by dsla_profile_enable, so the launch path still allocates nothing).
+ * Kernel timing for benchmarks.  While enabled, every kernel the library launches carries
+ * two HIP events in its dispatch (hipExtLaunchKernelGGL: the start and the end of the kernel
+ * are stamped by the dispatch itself, on the launch stream, and no event packet of its own
+ * delays the launch that follows; events come from a pool created by dsla_profile_enable,
+ * so the launch path still allocates nothing).
  * Kernel ids: 0 state_init, 1 prefill_segment_state, 2 prefill_segment_scan,
  * 3 prefill_chunk_loop, 4 decode, 5 prefill_segment_list (packed sequences only), 6 attention_entropy,
  * 7 attention_decode (each with its merge kernel), 8 decode_multi, 9 attention_prefill, 10 project.

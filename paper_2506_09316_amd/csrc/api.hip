@@ -41,30 +41,19 @@ struct Profiler {
     std::vector<hipEvent_t> ev;  // 2 per record
     std::vector<int> ids;
     int max_records = 0;
-    bool open = false;  // a "before" without its "after"
 } g_prof;
 
 }  // namespace
 
-void profile_before(int kernel_id, hipStream_t stream)
+void profile_reserve(int kernel_id, hipEvent_t *start, hipEvent_t *stop)
 {
     if (!g_prof.enabled) return;
     std::lock_guard<std::mutex> lk(g_prof.mu);
     if (static_cast<int>(g_prof.ids.size()) >= g_prof.max_records) return;
     const size_t r = g_prof.ids.size();
-    (void)hipEventRecord(g_prof.ev[2 * r], stream);
+    *start = g_prof.ev[2 * r];
+    *stop = g_prof.ev[2 * r + 1];
     g_prof.ids.push_back(kernel_id);
-    g_prof.open = true;
-}
-
-void profile_after(int, hipStream_t stream)
-{
-    if (!g_prof.enabled) return;
-    std::lock_guard<std::mutex> lk(g_prof.mu);
-    if (!g_prof.open) return;
-    const size_t r = g_prof.ids.size() - 1;
-    (void)hipEventRecord(g_prof.ev[2 * r + 1], stream);
-    g_prof.open = false;
 }
 
 }  // namespace dsla
@@ -456,7 +445,6 @@ dsla_status dsla_profile_enable(int enable, int max_records)
     g_prof.ev.clear();
     g_prof.ids.clear();
     g_prof.enabled = false;
-    g_prof.open = false;
     g_prof.max_records = 0;
     if (!enable) return DSLA_OK;
     if (max_records <= 0) return DSLA_ERR_SHAPE;
@@ -479,7 +467,7 @@ dsla_status dsla_profile_collect(double *total_ms, int64_t *launches)
         total_ms[i] = 0.0;
         launches[i] = 0;
     }
-    const size_t n = g_prof.ids.size() - (g_prof.open ? 1 : 0);
+    const size_t n = g_prof.ids.size();
     for (size_t r = 0; r < n; ++r) {
         hipError_t err = hipEventSynchronize(g_prof.ev[2 * r + 1]);
         if (err != hipSuccess) return hip_status(err);
@@ -493,7 +481,6 @@ dsla_status dsla_profile_collect(double *total_ms, int64_t *launches)
         }
     }
     g_prof.ids.clear();
-    g_prof.open = false;
     return DSLA_OK;
 }
 

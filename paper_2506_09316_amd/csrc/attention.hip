@@ -308,13 +308,14 @@ hipError_t launch_attn_decode_t(int B, int H, int64_t T, const EntropyPlan &plan
 {
     const int BH = B * H;
     ProfileScope ps(DSLA_KERNEL_ATTENTION_DECODE, stream);
-    hipLaunchKernelGGL((attn_decode_kernel<D, TIO>), dim3(static_cast<unsigned>(BH) * plan.parts), dim3(kEntThreads), 0,
+    if (plan.parts == 1) ps.e1_first = ps.e1;   // no merge kernel follows: the first launch closes the record too
+    DSLA_LAUNCH_FIRST(ps, (attn_decode_kernel<D, TIO>), dim3(static_cast<unsigned>(BH) * plan.parts), dim3(kEntThreads), 0,
                        stream, static_cast<const TIO *>(q_last), static_cast<const TIO *>(k), static_cast<const TIO *>(v),
                        seq_lens, scale, H, static_cast<long long>(T), plan.parts, static_cast<long long>(plan.rows_per_part),
                        static_cast<float *>(workspace), static_cast<TIO *>(o));
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || plan.parts == 1) return err;
-    hipLaunchKernelGGL((attn_decode_merge_kernel<D, TIO>), dim3(BH), dim3(D), 0, stream,
+    DSLA_LAUNCH_LAST(ps, (attn_decode_merge_kernel<D, TIO>), dim3(BH), dim3(D), 0, stream,
                        static_cast<const float *>(workspace), plan.parts, static_cast<TIO *>(o));
     return hipGetLastError();
 }
@@ -325,12 +326,13 @@ hipError_t launch_entropy_t(int B, int H, int64_t T, const EntropyPlan &plan, fl
 {
     const int BH = B * H;
     ProfileScope ps(DSLA_KERNEL_ATTENTION_ENTROPY, stream);
-    hipLaunchKernelGGL((entropy_kernel<D, TIO>), dim3(static_cast<unsigned>(BH) * plan.parts), dim3(kEntThreads), 0, stream,
+    if (plan.parts == 1) ps.e1_first = ps.e1;   // no merge kernel follows: the first launch closes the record too
+    DSLA_LAUNCH_FIRST(ps, (entropy_kernel<D, TIO>), dim3(static_cast<unsigned>(BH) * plan.parts), dim3(kEntThreads), 0, stream,
                        static_cast<const TIO *>(q_last), static_cast<const TIO *>(k), scale, H, static_cast<long long>(T),
                        plan.parts, static_cast<long long>(plan.rows_per_part), static_cast<float *>(workspace), entropy);
     hipError_t err = hipGetLastError();
     if (err != hipSuccess || plan.parts == 1) return err;
-    hipLaunchKernelGGL(entropy_merge_kernel, dim3((BH + 255) / 256), dim3(256), 0, stream,
+    DSLA_LAUNCH_LAST(ps, entropy_merge_kernel, dim3((BH + 255) / 256), dim3(256), 0, stream,
                        static_cast<const float *>(workspace), BH, plan.parts, entropy);
     return hipGetLastError();
 }

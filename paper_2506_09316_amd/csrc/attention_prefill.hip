@@ -275,11 +275,11 @@ hipError_t launch_attn_prefill(int B, int H, int d, int64_t T, float scale, cons
     const float sl2 = scale * 1.4426950408889634f;
     ProfileScope ps(DSLA_KERNEL_ATTENTION_PREFILL, stream);
     if (d == 128)
-        hipLaunchKernelGGL((attention_prefill_kernel<128>), dim3(grid), dim3(64 * kWaves), 0, stream, static_cast<const bf16_t *>(q),
+        DSLA_LAUNCH(ps, (attention_prefill_kernel<128>), dim3(grid), dim3(64 * kWaves), 0, stream, static_cast<const bf16_t *>(q),
                            static_cast<const bf16_t *>(k), static_cast<const bf16_t *>(v), static_cast<bf16_t *>(o), H,
                            static_cast<int>(T), blocks_per_seq, sl2);
     else
-        hipLaunchKernelGGL((attention_prefill_kernel<64>), dim3(grid), dim3(64 * kWaves), 0, stream, static_cast<const bf16_t *>(q),
+        DSLA_LAUNCH(ps, (attention_prefill_kernel<64>), dim3(grid), dim3(64 * kWaves), 0, stream, static_cast<const bf16_t *>(q),
                            static_cast<const bf16_t *>(k), static_cast<const bf16_t *>(v), static_cast<bf16_t *>(o), H,
                            static_cast<int>(T), blocks_per_seq, sl2);
     return hipGetLastError();

@@ -261,7 +261,7 @@ hipError_t launch_decode_t(const dsla_desc &d, const void *q, const void *k, con
 {
     const unsigned grid = static_cast<unsigned>(d.B) * static_cast<unsigned>(d.H) * kDecodeSplit;
     ProfileScope ps(DSLA_KERNEL_DECODE, stream);
-    hipLaunchKernelGGL((decode_kernel<D, D, kDecodeSplit, TIO, TG>), dim3(grid), dim3(kDecodeThreads), 0, stream,
+    DSLA_LAUNCH(ps, (decode_kernel<D, D, kDecodeSplit, TIO, TG>), dim3(grid), dim3(kDecodeThreads), 0, stream,
                        static_cast<const TIO *>(q), static_cast<const TIO *>(k), static_cast<const TIO *>(v),
                        static_cast<const TG *>(g1), static_cast<const TG *>(g2), row, slot, S1, S2, static_cast<TIO *>(o), d.H,
                        d.gamma, d.gamma_per_head, d.scale, d.gate_mode == DSLA_GATE_PREACT ? 1.0f / d.tau : 0.f);
@@ -287,7 +287,7 @@ hipError_t launch_decode_multi_t(const dsla_desc &d, const MultiStatePtrs &mp, i
 {
     const unsigned grid = static_cast<unsigned>(d.B) * static_cast<unsigned>(d.H) * kDecodeSplit;
     ProfileScope ps(DSLA_KERNEL_DECODE_MULTI, stream);
-    hipLaunchKernelGGL((decode_multi_kernel<D, D, kDecodeSplit, TIO, TG>), dim3(grid), dim3(kDecodeThreads), 0, stream,
+    DSLA_LAUNCH(ps, (decode_multi_kernel<D, D, kDecodeSplit, TIO, TG>), dim3(grid), dim3(kDecodeThreads), 0, stream,
                        static_cast<const TIO *>(q), static_cast<const TIO *>(k), static_cast<const TIO *>(v), mp, N, row, slot,
                        static_cast<TIO *>(o), d.H, Hkv, w_per_head, d.scale,
                        d.gate_mode == DSLA_GATE_PREACT ? 1.0f / d.tau : 0.f);
@@ -333,7 +333,7 @@ hipError_t launch_state_init(float *S1, float *S2, size_t elems_per_state, hipSt
     if (blocks > 256 * 16) blocks = 256 * 16;
     if (blocks == 0) blocks = 1;
     ProfileScope ps(DSLA_KERNEL_STATE_INIT, stream);
-    hipLaunchKernelGGL(state_init_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream,
+    DSLA_LAUNCH(ps, state_init_kernel, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream,
                        reinterpret_cast<float4 *>(S1), reinterpret_cast<float4 *>(S2), n4);
     return hipGetLastError();
 }

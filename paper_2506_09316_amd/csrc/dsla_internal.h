@@ -1,6 +1,7 @@
 // Internal declarations shared by the translation units of libdsla (not part of the ABI).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -31,15 +32,33 @@ template <>
 __device__ __forceinline__ bf16_t from_f32<bf16_t>(float f) { return bf16_t{f32_to_bf16_bits(f)}; }
 
 // ---- profiling hooks (api.hip) -----------------------------------------------------------
-void profile_before(int kernel_id, hipStream_t stream);
-void profile_after(int kernel_id, hipStream_t stream);
+// Kernel timing (dsla_profile_enable): a scope reserves a pair of events and the launches inside it carry them in
+// the dispatch itself (hipExtLaunchKernelGGL: the start and the end of the kernel are stamped by the dispatch, no
+// event packets of their own enter the stream, so timing a launch does not delay the one behind it).  Null events:
+// an ordinary launch.
+void profile_reserve(int kernel_id, hipEvent_t *start, hipEvent_t *stop);
 
 struct ProfileScope {
-    int id;
-    hipStream_t s;
-    ProfileScope(int kernel_id, hipStream_t stream) : id(kernel_id), s(stream) { profile_before(id, s); }
-    ~ProfileScope() { profile_after(id, s); }
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipEvent_t e1_first = nullptr;   // the stop event of the first of two launches (set when the second is not issued)
+    ProfileScope(int kernel_id, hipStream_t) { profile_reserve(kernel_id, &e0, &e1); }
 };
+// the only launch of a scope / the first and the last of a scope with two launches
+#define DSLA_LAUNCH(ps, kernel, grid, block, shmem, stream, ...)                                                     \
+    do {                                                                                                             \
+        if ((ps).e0) hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, (ps).e0, (ps).e1, 0, __VA_ARGS__);    \
+        else hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);                                    \
+    } while (0)
+#define DSLA_LAUNCH_FIRST(ps, kernel, grid, block, shmem, stream, ...)                                               \
+    do {                                                                                                             \
+        if ((ps).e0) hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, (ps).e0, (ps).e1_first, 0, __VA_ARGS__); \
+        else hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);                                    \
+    } while (0)
+#define DSLA_LAUNCH_LAST(ps, kernel, grid, block, shmem, stream, ...)                                                \
+    do {                                                                                                             \
+        if ((ps).e1) hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, nullptr, (ps).e1, 0, __VA_ARGS__);    \
+        else hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);                                    \
+    } while (0)
 
 // ---- launchers (one per kernel family; each returns the launch error) ------------------------
 hipError_t launch_state_init(float *S1, float *S2, size_t elems_per_state, hipStream_t stream);

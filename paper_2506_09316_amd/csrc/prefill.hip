@@ -1913,7 +1913,7 @@ hipError_t launch_x(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
     if (plan.segments > 1) {
         if (a.list_full) {
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_LIST, stream);
-            hipLaunchKernelGGL(segment_list_kernel, dim3(1), dim3(256), 0, stream, a.cu, a.seq, d.B, a.seg_tokens,
+            DSLA_LAUNCH(ps, segment_list_kernel, dim3(1), dim3(256), 0, stream, a.cu, a.seq, d.B, a.seg_tokens,
                                const_cast<int32_t *>(a.seg_first), const_cast<int32_t *>(a.seg_count),
                                const_cast<int2 *>(a.list_full), const_cast<int2 *>(a.list_pre),
                                static_cast<int>(plan.max_items), static_cast<int>(plan.max_pre_items));
@@ -1925,16 +1925,16 @@ hipError_t launch_x(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
             // the pre-pass of its own design where it is built; its per-lane offsets inside a step are 32-bit
             constexpr bool kFast = D == SegFast::D && std::is_same<TIO, bf16_t>::value && std::is_same<TG, bf16_t>::value && !kBeta;
             if (kFast && static_cast<int64_t>(d.H) * D * 2 * SegFast::S < (int64_t{1} << 31))
-                hipLaunchKernelGGL(segment_state_fast_kernel, dim3(grid_pre), dim3(SegFast::NT), 0, stream, a);
+                DSLA_LAUNCH(ps, segment_state_fast_kernel, dim3(grid_pre), dim3(SegFast::NT), 0, stream, a);
             else
-                hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, false, kExt, kBeta>), dim3(grid_pre), dim3(4 * D), 0, stream, a);
+                DSLA_LAUNCH(ps, (prefill_kernel<D, TIO, TG, false, kExt, kBeta>), dim3(grid_pre), dim3(4 * D), 0, stream, a);
             err = hipGetLastError();
         }
         if (err != hipSuccess) return err;
         {
             ProfileScope ps(DSLA_KERNEL_PREFILL_SEGMENT_SCAN, stream);
             const size_t n4 = static_cast<size_t>(BH) * 2 * D * (D / 4);
-            hipLaunchKernelGGL((segment_scan_kernel<D>), dim3(static_cast<unsigned>((n4 + 255) / 256)), dim3(256), 0,
+            DSLA_LAUNCH(ps, (segment_scan_kernel<D>), dim3(static_cast<unsigned>((n4 + 255) / 256)), dim3(256), 0,
                                stream, a.S1, a.S2, a.ws_state, a.ws_decay, BH, plan.segments, a.cu, a.seq, a.slot,
                                a.seg_first, a.H, a.seg_tokens, a.zero_init, kBeta ? 1 : 0);
             err = hipGetLastError();
@@ -1943,7 +1943,7 @@ hipError_t launch_x(const dsla_desc &d, const PrefillPlan &plan, PrefillArgs &a,
     }
     {
         ProfileScope ps(DSLA_KERNEL_PREFILL_CHUNK_LOOP, stream);
-        hipLaunchKernelGGL((prefill_kernel<D, TIO, TG, true, kExt, kBeta>), dim3(grid_full), dim3(4 * D), 0, stream, a);
+        DSLA_LAUNCH(ps, (prefill_kernel<D, TIO, TG, true, kExt, kBeta>), dim3(grid_full), dim3(4 * D), 0, stream, a);
     }
     err = hipGetLastError();
     return err;

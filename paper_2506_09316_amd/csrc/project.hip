@@ -347,13 +347,13 @@ hipError_t launch_project(int64_t M, int K, int n_out, int width, const void *x,
         const int tiles_m = static_cast<int>((M + BM - 1) / BM), tiles_n = (N + BN - 1) / BN;
         const long long ntiles = static_cast<long long>(tiles_m) * tiles_n;
         const unsigned grid = static_cast<unsigned>((ntiles + 7) / 8 * 8);
-        hipLaunchKernelGGL(project_kernel_256, dim3(grid), dim3(256), 0, stream, static_cast<const bf16_t *>(x),
+        DSLA_LAUNCH(ps, project_kernel_256, dim3(grid), dim3(256), 0, stream, static_cast<const bf16_t *>(x),
                            static_cast<const bf16_t *>(w), bias, po, static_cast<long long>(M), K, N, width, tiles_m, tiles_n);
     } else {
         const int tiles_m = static_cast<int>((M + TM - 1) / TM), tiles_n = N / TN;
         const long long ntiles = static_cast<long long>(tiles_m) * tiles_n;
         const unsigned grid = static_cast<unsigned>((ntiles + 7) / 8 * 8);
-        hipLaunchKernelGGL(project_kernel, dim3(grid), dim3(256), 0, stream, static_cast<const bf16_t *>(x),
+        DSLA_LAUNCH(ps, project_kernel, dim3(grid), dim3(256), 0, stream, static_cast<const bf16_t *>(x),
                            static_cast<const bf16_t *>(w), bias, po, static_cast<long long>(M), K, width, tiles_m, tiles_n);
     }
     return hipGetLastError();
