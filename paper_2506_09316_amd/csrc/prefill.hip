@@ -348,7 +348,6 @@ __device__ __forceinline__ void store_v_tokens(uint32_t a, const Raw8<float> (&v
 
 // a loaded row piece of V as it is (16-bit storage only)
 __device__ __forceinline__ void store_v_row(uint32_t a, const Raw8<bf16_t> &v) { lds_st<u32x4>(a, v.u); }
-__device__ __forceinline__ void store_v_row(uint32_t, const Raw8<float> &) {}
 
 // four adjacent output elements -> global
 __device__ __forceinline__ void store4_global(bf16_t *p, float a, float b, float c, float d)
@@ -358,18 +357,6 @@ __device__ __forceinline__ void store4_global(bf16_t *p, float a, float b, float
 __device__ __forceinline__ void store4_global(float *p, float a, float b, float c, float d)
 {
     *reinterpret_cast<f32x4 *>(p) = f32x4{a, b, c, d};
-}
-
-// staged output row (8 elements in LDS) -> global, uniform base + 32-bit lane offset
-__device__ __forceinline__ void store8_global(bf16_t *base, uint32_t elem_off, uint32_t lds8)
-{
-    *reinterpret_cast<u32x4 *>(reinterpret_cast<char *>(base) + elem_off * 2u) = lds_ld<u32x4>(lds8);
-}
-__device__ __forceinline__ void store8_global(float *base, uint32_t elem_off, uint32_t lds8)
-{
-    char *p = reinterpret_cast<char *>(base) + elem_off * 4u;
-    *reinterpret_cast<f32x4 *>(p) = lds_ld<f32x4>(lds8);
-    *reinterpret_cast<f32x4 *>(p + 16) = lds_ld<f32x4>(lds8 + 16);
 }
 
 // Software-pipelined sequence of N steps: the LDS fragment of step s + DEPTH is requested before the
