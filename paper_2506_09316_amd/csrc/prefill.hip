@@ -1347,6 +1347,12 @@ struct Kern {
                           *v0 = static_cast<const TIO *>(a.v) + seg0;
                 const TG *g0p = static_cast<const TG *>(pa.st ? a.g2 : a.g1) + seg0;
                 const uint32_t lane_col = 64 * pa.fh + 8 * (lane & 7);
+                // the lane offsets of a whole step never change; only a ragged last step clamps its rows
+                uint32_t off_whole[TPT], offv_whole[2];
+#pragma unroll
+                for (int j = 0; j < TPT; ++j) off_whole[j] = (pa.sq * TPT + j) * rs + lane_col;
+#pragma unroll
+                for (int j = 0; j < 2; ++j) offv_whole[j] = (16 * pa.st + 2 * pa.sq + j) * rs + lane_col;
                 auto src_of = [&](int n) -> LineSrc {   // step n, or the last step when n is past the end
                     const int m = n < nsteps ? n : nsteps - 1;
                     const size_t so = static_cast<size_t>(m) * sstep;
@@ -1354,16 +1360,20 @@ struct Kern {
                     LineSrc s;
                     s.q = q0 + so; s.k = k0 + so; s.v = v0 + so; s.g = g0p + so;
 #pragma unroll
-                    for (int j = 0; j < TPT; ++j) {
-                        uint32_t row = pa.sq * TPT + j;
-                        row = row < vm ? row : vm - 1;
-                        s.off[j] = row * rs + lane_col;
-                    }
+                    for (int j = 0; j < TPT; ++j) s.off[j] = off_whole[j];
 #pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        uint32_t row = 16 * pa.st + 2 * pa.sq + j;
-                        row = row < vm ? row : vm - 1;
-                        s.offv[j] = row * rs + lane_col;
+                    for (int j = 0; j < 2; ++j) s.offv[j] = offv_whole[j];
+                    if (vm < static_cast<uint32_t>(S)) {   // uniform
+#pragma unroll
+                        for (int j = 0; j < TPT; ++j) {
+                            const uint32_t row = pa.sq * TPT + j;
+                            s.off[j] = (row < vm ? row : vm - 1) * rs + lane_col;
+                        }
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            const uint32_t row = 16 * pa.st + 2 * pa.sq + j;
+                            s.offv[j] = (row < vm ? row : vm - 1) * rs + lane_col;
+                        }
                     }
                     return s;
                 };
