@@ -99,3 +99,61 @@ def test_prefill_with_segments_replayed():
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(o, eo) and torch.equal(S1, eS1) and torch.equal(S2, eS2), f"seed {seed}"
+
+
+def test_kernel_timing_leaves_results_alone_and_counts_every_launch():
+    """dsla_profile_enable attaches a pair of events to every launch (the dispatches carry them).  A segmented
+    prefill, decode steps and the two attention passes -- with one part per pair (no merge kernel) and with several --
+    give bit-identical results with and without the timing, every launch is counted once, and every duration is
+    positive and plausible."""
+    import numpy as np
+    import torch
+    import workloads as wl
+    import paper_2506_09316_amd as dsla
+    from paper_2506_09316_amd import binding
+    from tests.util import GpuLayer, slice_t, to_gpu
+
+    B, T, H, d, steps = 1, 1024, 2, 128, 3
+    x = wl.layer_inputs(505, B, T + steps, H, d, d, io_dtype="bf16", gate_dtype="bf16", qk_scale=d ** -0.5)
+
+    def layer_run():
+        layer = GpuLayer(B, H, d, "bf16", "bf16", gamma=0.4, chunk=64, segments=4)
+        outs = [layer.prefill(slice_t(x, 0, T))]
+        for t in range(T, T + steps):
+            outs.append(layer.decode(slice_t(x, t, t + 1)))
+        return np.concatenate(outs, 1), layer.states()
+
+    def attention_run(Ta):
+        k = to_gpu(x["k"][:, :Ta], "bf16")
+        v = to_gpu(x["v"][:, :Ta], "bf16")
+        q = to_gpu(x["q"][:, Ta], "bf16")
+        o = torch.full_like(q, float("nan"))
+        e = torch.full((B, H), float("nan"), device="cuda", dtype=torch.float32)
+        n = dsla.dsla_attention_decode_workspace_bytes(B, H, d, Ta)
+        ws = torch.empty(max(n, 1), dtype=torch.uint8, device="cuda")
+        dsla.dsla_attention_decode(q, k, v, o, d ** -0.5, ws if n else None)
+        n = dsla.dsla_attention_entropy_workspace_bytes(B, H, d, Ta)
+        ws2 = torch.empty(max(n, 1), dtype=torch.uint8, device="cuda")
+        dsla.dsla_attention_entropy(q, k, e, d ** -0.5, ws2 if n else None)
+        torch.cuda.synchronize()
+        return o.float().cpu().numpy(), e.cpu().numpy()
+
+    plain = (layer_run(), attention_run(17), attention_run(1000))
+    binding.profile_enable(True, 64)
+    try:
+        timed = (layer_run(), attention_run(17), attention_run(1000))
+        torch.cuda.synchronize()
+        res = binding.profile_collect()
+    finally:
+        binding.profile_enable(False, 0)
+    (o0, (a0, b0)), (o1, (a1, b1)) = plain[0], timed[0]
+    assert np.array_equal(o0, o1) and np.array_equal(a0, a1) and np.array_equal(b0, b1)
+    for p, t in zip(plain[1:], timed[1:]):
+        assert np.array_equal(p[0], t[0]) and np.array_equal(p[1], t[1])
+    print("  kernel timing:", {k: (round(ms * 1e3, 1), n) for k, (ms, n) in res.items() if n}, flush=True)
+    expected = {"prefill_segment_state": 1, "prefill_segment_scan": 1, "prefill_chunk_loop": 1, "decode": steps,
+                "attention_decode": 2, "attention_entropy": 2}
+    for name, count in expected.items():
+        ms, n = res[name]
+        assert n == count, (name, n)
+        assert 0.0 < ms / n < 5.0, (name, ms)      # microseconds to a few milliseconds per launch
