@@ -1269,7 +1269,8 @@ struct Kern {
             // launch, so no workgroup of such a sequence may read them here.  A sequence of one segment reads the
             // caller's states itself (it is also the only one that writes them), unless they are zero by contract.
             const bool cut = Tb > a.seg_tokens;
-            if (kFull && (cut || !a.zero_init)) {
+            // (with states that are zero by contract the first segment has nothing to read: the scan leaves its slot unwritten)
+            if (kFull && (!a.zero_init || (cut && p > 0))) {
 #pragma unroll
                 for (int i = 0; i < NST; ++i) {
                     const float *src = cut ? a.ws_state + ((slot0 + p * slot_step) * 2 + i) * D * D
@@ -1875,7 +1876,7 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restri
     float4 s = zero_init ? make_float4(0.f, 0.f, 0.f, 0.f) : *reinterpret_cast<const float4 *>(src);
     const size_t in_slot = (static_cast<size_t>(i) * D + row) * D + c4 * 4;   // this thread's place inside a slot
     if (P <= 1) return;
-    *reinterpret_cast<float4 *>(ws_state + slot0 * 2 * D * D + in_slot) = s;
+    if (!zero_init) *reinterpret_cast<float4 *>(ws_state + slot0 * 2 * D * D + in_slot) = s;   // zero states: segment 0 starts from registers set to zero
     for (int p = 0; p + 1 < P; ++p) {
         const float *dslot = ws_decay + (slot0 + p * slot_step) * 2 * D;
         const float dr = dslot[i * D + row];
