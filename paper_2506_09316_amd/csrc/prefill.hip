@@ -11,7 +11,8 @@
 // contribution U and its total log-decay.  (2) segment_scan: an elementwise scan over segments
 // turns these into the true state entering each segment.  (3) chunk_loop: every segment runs the
 // fused step loop from its true initial state and writes o; the last segment writes the final
-// states.  P = 1 runs (3) alone.  (1) and (3) are one kernel template.
+// states.  P = 1 runs (3) alone.  (1) and (3) are one kernel template; for 16-bit inputs and gates at d = 128, (1) has a
+// kernel of its own that walks a segment backwards (segment_state_fast_kernel, below the template).
 // Packed sequences of different lengths share one segment length; a one-workgroup kernel (segment_list) turns
 // their offsets into the lists of (sequence, segment) pairs that (1) and (3) take their work from, so that no
 // workgroup is launched for a segment that does not exist.  Sequences may be a subset of the packed batch and
