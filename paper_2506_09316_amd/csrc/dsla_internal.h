@@ -85,9 +85,10 @@ struct PrefillPlan {
     int chunk;               // C
     int segments;            // P >= 1
     int64_t segment_tokens;  // tokens per segment (multiple of C), last segment may be shorter
+    int pre_split;           // R in {1, 2}: the pre-pass and the scan work on R pieces per segment (every segment but the last)
     size_t state_elems;      // B*H*d_k*d_v
-    size_t ws_state_bytes;   // one slot of both states (fp32) per (segment, sequence, head) when P > 1
-    size_t ws_decay_bytes;   // one slot of both segment decays (fp32 log2) per (segment, sequence, head) when P > 1
+    size_t ws_state_bytes;   // one slot of both states (fp32) per (piece, sequence, head) when P > 1: R (P - 1) + 1 pieces
+    size_t ws_decay_bytes;   // one slot of both decays (fp32 log2) per (piece, sequence, head) when P > 1
     int64_t max_items;       // packed sequences with P > 1: capacity of the list of all segments (else 0)
     int64_t max_pre_items;   //   and of the list of segments that have a successor
     size_t ws_lists_bytes;   //   and the bytes of the lists

@@ -175,6 +175,12 @@ def test_workspace_plan(lib):
     d = dsla.make_desc(1, 32, 128, 128, io_dtype=1, gate_dtype=1, chunk=64)
     n = lib.dsla_prefill_workspace_bytes(ctypes.byref(d), 16384)
     assert n == 8 * 32 * 2 * 128 * 128 * 4 + 7 * 32 * 2 * 128 * 4
+    # B*H = 128: two segments, and the pre-pass on the two halves of the first one (3 slots, 2 decay vectors);
+    # a caller who asks for two segments gets two slots
+    d = dsla.make_desc(4, 32, 128, 128, io_dtype=1, gate_dtype=1, chunk=64)
+    assert lib.dsla_prefill_workspace_bytes(ctypes.byref(d), 16384) == 3 * 128 * 2 * 128 * 128 * 4 + 2 * 128 * 2 * 128 * 4
+    d = dsla.make_desc(4, 32, 128, 128, io_dtype=1, gate_dtype=1, chunk=64, segments=2)
+    assert lib.dsla_prefill_workspace_bytes(ctypes.byref(d), 16384) == 2 * 128 * 2 * 128 * 128 * 4 + 1 * 128 * 2 * 128 * 4
 
 
 def test_conversion_logic_against_its_oracle(lib):

@@ -23,7 +23,7 @@ def _both_ways(B, T, H, d, io, gd, seed, segments, tol):
     desc = dsla.make_desc(B, H, d, d, io_dtype=code(io), gate_dtype=code(gd), gamma=0.4, chunk=64, segments=segments)
     t = {n: to_gpu(x[n], io if n in ("q", "k", "v") else gd) for n in x}
     nbytes = dsla.dsla_prefill_workspace_bytes(desc, T)
-    assert 0 < nbytes <= 48 << 20, "the case must use the scratch buffer and fit the built-in one"
+    assert 0 < nbytes <= 64 << 20, "the case must use the scratch buffer and fit the built-in one"
     ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     res = []
     for static in (False, True):
@@ -52,7 +52,7 @@ def test_static_ws_prefill_rejects_oversize_plan():
     import torch
     B, H, d, T = 4, 32, 128, 8192
     desc = dsla.make_desc(B, H, d, d, io_dtype=code("bf16"), gate_dtype=code("bf16"), segments=8)
-    assert dsla.dsla_prefill_workspace_bytes(desc, T) > 48 << 20
+    assert dsla.dsla_prefill_workspace_bytes(desc, T) > 64 << 20
     S1 = torch.ones(B, H, d, d, device="cuda")
     S2 = torch.ones_like(S1)
     q = torch.zeros(B, T, H, d, device="cuda", dtype=torch.bfloat16)
