@@ -1999,11 +1999,13 @@ void finish_plan(const dsla_desc &d, int C, int64_t P, int64_t nchunks, bool may
     plan->state_elems = static_cast<size_t>(BH) * D * D;
     plan->max_items = plan->max_pre_items = 0;
     plan->ws_lists_bytes = 0;
-    // The pre-pass has one workgroup per (segment but the last, sequence, head).  Where that leaves half of the
-    // compute units without one (two segments and 65 .. 128 heads in all; short sequences), it works on half
-    // segments and the scan combines the halves: measured at B H = 128, T = 16384 the pre-pass streams at 3.6 TB/s
-    // from 128 workgroups and at 5.6 TB/s from 224.  A caller who names the number of segments gets exactly those.
-    plan->pre_split = (may_split && P > 1 && cps % 2 == 0 && BH * (P - 1) * 2 <= ((D == 64) ? 512 : 256)) ? 2 : 1;
+    // The pre-pass has one workgroup per (segment but the last, sequence, head).  With two segments that is at most
+    // half of the compute units (65 .. 128 heads in all; short sequences): it then works on the two halves of the first
+    // segment and the scan combines them: measured at B H = 128, T = 16384 the pre-pass streams at 3.7 TB/s from 128
+    // workgroups and at 5.7 TB/s from 256.  With more segments the longer scan costs what the shorter pieces gain
+    // (B H = 32, T = 1024, four segments: pre-pass - 2 us, scan + 5 us).  A caller who names the number of segments
+    // gets exactly those.
+    plan->pre_split = (may_split && P == 2 && cps % 2 == 0 && cps * C >= 256 && BH * 2 <= ((D == 64) ? 512 : 256)) ? 2 : 1;
     if (P > 1) {
         const int64_t pieces = plan->pre_split * (P - 1) + 1;
         plan->ws_state_bytes = static_cast<size_t>(pieces) * plan->state_elems * 2 * sizeof(float);

@@ -50,19 +50,19 @@ def test_carried_states_short_last_segment(io, d, chunk):
         check(f"packed S1[seq {b}]", S1[sl:sl + 1].cpu().numpy(), rS1, TOL[io])
         check(f"packed S2[seq {b}]", S2[sl:sl + 1].cpu().numpy(), rS2, TOL[io])
 
-@pytest.mark.parametrize("io,d,B,H,T,chunk,P,init", [("bf16", 128, 4, 32, 1024, 0, 2, False), ("bf16", 128, 3, 32, 1500, 64, 2, True),
-                                                     ("f32", 64, 2, 4, 512, 64, 2, True), ("f32", 128, 1, 2, 2048, 64, 8, True),
-                                                     ("bf16", 128, 2, 2, 2040, 32, 16, False)])
-def test_prefill_pre_pass_on_half_segments(io, d, B, H, T, chunk, P, init):
-    """Plans the library makes itself (no segment count given) in which the pre-pass would leave half of the compute
-    units without a workgroup: it then works on half segments, the scan combines the halves and segment p of the
-    chunk loop starts from slot 2 p.  The workspace size shows that the case is one of those (2 (P - 1) + 1 slots and
-    2 (P - 1) decay vectors per (sequence, head)); the results are held to the oracle like any other."""
+@pytest.mark.parametrize("io,d,B,H,T,chunk,init", [("bf16", 128, 4, 32, 1024, 0, False), ("bf16", 128, 3, 32, 1500, 64, True),
+                                                   ("f32", 64, 2, 4, 512, 64, True), ("f32", 128, 1, 2, 700, 64, True),
+                                                   ("bf16", 128, 2, 2, 1400, 128, False)])
+def test_prefill_pre_pass_on_half_segments(io, d, B, H, T, chunk, init):
+    """Plans of two segments that the library makes itself (no segment count given): the pre-pass, which would have a
+    workgroup for at most half of the compute units, works on the two halves of the first segment, the scan combines
+    them and the second segment of the chunk loop starts from slot 2.  The workspace size shows that the case is one
+    of those (3 state slots and 2 decay vectors per (sequence, head)); the results are held to the oracle like any
+    other."""
     gd = "bf16" if io == "bf16" else "f32"
     desc = dsla.make_desc(B, H, d, d, io_dtype=code(io), gate_dtype=code(gd), chunk=chunk)
-    pieces = 2 * (P - 1) + 1
-    decay = (pieces - 1) * B * H * 2 * d * 4
-    assert dsla.dsla_prefill_workspace_bytes(desc, T) == pieces * B * H * 2 * d * d * 4 + (decay + 255) // 256 * 256
+    decay = 2 * B * H * 2 * d * 4
+    assert dsla.dsla_prefill_workspace_bytes(desc, T) == 3 * B * H * 2 * d * d * 4 + (decay + 255) // 256 * 256
     run_prefill_case(B, T, H, d, io, gd, chunk=chunk, segments=0, gamma=0.35, seed=91, init=init, qk_scale=d ** -0.5)
 
 
