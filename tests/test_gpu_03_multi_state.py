@@ -73,7 +73,9 @@ def test_decode_multi_equals_decode_for_two_states():
     (1, 2, "f32", "f32", 64, 200, 2, ()), (2, 1, "bf16", "bf16", 128, 700, 3, ()), (3, 4, "f32", "f32", 64, 333, 1, ()),
     (4, 2, "bf16", "bf16", 128, 1100, 0, ()), (4, 4, "f32", "bf16", 128, 150, 2, ()), (8, 2, "bf16", "f32", 64, 450, 2, ()),
     (1, 4, "f32", "f32", 64, 300, 2, (0,)), (1, 4, "bf16", "bf16", 128, 500, 3, (0,)), (2, 2, "f32", "f32", 128, 170, 1, (0, 1)),
-    (3, 1, "bf16", "bf16", 128, 900, 2, (1,)), (4, 4, "bf16", "f32", 64, 257, 2, (0, 3)), (2, 4, "f32", "f32", 64, 31, 1, (1,))])
+    (3, 1, "bf16", "bf16", 128, 900, 2, (1,)), (4, 4, "bf16", "f32", 64, 257, 2, (0, 3)), (2, 4, "f32", "f32", 64, 31, 1, (1,)),
+    # plans of the library's own with two segments: the pre-pass works on the halves of the first one
+    (3, 2, "bf16", "bf16", 128, 700, 0, (1,)), (2, 4, "f32", "f32", 64, 700, 0, (0,))])
 def test_prefill_multi(N, Hkv, io, gd, d, T, segments, beta):
     """N states through the prefill kernels (two at a time without a beta gate, one at a time with one), grouped
     key/value heads, carried-in states, then a decode step on the same states.  `beta` lists the states that have a
