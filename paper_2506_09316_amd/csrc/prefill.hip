@@ -1896,7 +1896,7 @@ __global__ __launch_bounds__(256) void segment_scan_kernel(const float *__restri
         s.y = fmaf(dec.y, s.y, x.y);
         s.z = fmaf(dec.z, s.z, x.z);
         s.w = fmaf(dec.w, s.w, x.w);
-        *u = s;
+        if (!(zero_init && p == 0)) *u = s;   // from zero states the first slot already holds its result
     }
 }
 
